@@ -1,0 +1,297 @@
+"""Float64 CPU oracle for the RAP decode hot path.  TEST INFRASTRUCTURE ONLY.
+
+This module is the slow, plain definition of what the decode-time path of RAP
+(RoPE-Aligned Pruning) computes.  It exists to check the HIP library; it shares
+no code with it, imports nothing from it, and must only be imported by the
+tests, the smoke entry and the CPU-baseline leg of the benchmark.
+
+Everything is NumPy float64.  bf16 storage is handled as raw uint16 bit
+patterns; the two converters below are written from the IEEE-754 layout
+(1 sign, 8 exponent, 7 fraction bits = the top half of a binary32).
+
+Passages of the paper each function follows:
+
+  inv_freq, rope_full      Sec. "Motivation: RoPE Incompatibility", Eq. (rope):
+                           pair (j, j') rotated by R(t, theta_j),
+                           theta_j = theta_base^(-2j/D), half-apart pairing
+                           (x, x + D/2).
+  rope_compact             Sec. "RAP", index-aware rotation on the compressed
+                           matrices (original indices of the retained pairs);
+                           App. "Method", Eq. (selection-rope-intertwine),
+                           block R_{t,S}.
+  append_ref               Sec. "Background" (each new K_t, V_t is written into
+                           a cache) + Sec. "Step 3: RAP Construction"
+                           (the cache holds K_latent = RoPE(X W~_k), width 2m).
+  attn_ref                 Eq. (attn) with the GQA remark under it;
+                           Eq. (latent-score).
+  attn_full_masked_ref     App. "Method", Eq. (masked-logit-equivalence): the
+                           full-width right-hand side with removed pairs zeroed.
+  merge_partials_ref       log-sum-exp combination of row-partitioned softmax
+                           partials (algebraic identity of Eq. (attn); the paper
+                           itself has no split kernel).
+  kept_pairs, kv_bytes_*   App. "Cost model" (Cache = rho * 2SD) and the
+                           rounding of a budget to whole pairs; Tab. (effsweep),
+                           Tab. (serving).
+
+Parity pins (tests/test_oracle_*.py): rho=1 reduction to textbook RoPE attention,
+zero-mask identity, intertwining identity, relative-position invariance, closed
+forms, brute force with scalar math, and the paper's printed cost-table values.
+Every function here has at least one such pin; nothing is "parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+# --------------------------------------------------------------------------
+# bf16 <-> float64, from the bit layout
+# --------------------------------------------------------------------------
+
+
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Exact value of bf16 bit patterns (uint16) as float64.
+
+    A bf16 is the upper 16 bits of an IEEE binary32, so widening is a shift.
+    """
+    b = np.asarray(bits)
+    if b.dtype != np.uint16:
+        raise TypeError("bf16 bit patterns must be uint16")
+    with np.errstate(invalid="ignore"):      # signalling-NaN patterns are fine to widen
+        return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def f64_to_bf16_bits_rne(x: np.ndarray) -> np.ndarray:
+    """Round float64 to bf16, nearest-even, in ONE rounding (no float32 detour).
+
+    bf16 has 8 significant bits, exponent range of binary32 (normal minimum
+    2^-126, subnormal quantum 2^-133, largest finite (2 - 2^-7) * 2^127).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    out = np.zeros(x.shape, dtype=np.uint16)
+    sign = np.signbit(x)
+    a = np.abs(x)
+
+    nan = np.isnan(x)
+    inf = np.isinf(x)
+    fin = ~(nan | inf)
+
+    af = np.where(fin, a, 0.0)
+    m, e = np.frexp(af)                     # af = m * 2^e, m in [0.5, 1)
+    # quantum of the target binade: 8 significant bits -> 2^(e-8); never finer
+    # than the subnormal quantum 2^-133.
+    qexp = np.maximum(e - 8, -133)
+    scaled = np.ldexp(af, -qexp)            # exact (power-of-two scaling)
+    n = np.rint(scaled)                     # ties to even
+    val = np.ldexp(n, qexp)                 # the rounded magnitude, exact in f64
+
+    # encode val (exactly representable in bf16, or overflowed past max finite)
+    m2, e2 = np.frexp(val)                  # val = m2 * 2^e2
+    biased = e2 - 1 + 127                   # exponent field if normal
+    normal = (val > 0) & (biased >= 1)
+    frac_n = np.rint(np.ldexp(m2, 8)).astype(np.int64) - 128      # 7 fraction bits
+    with np.errstate(invalid="ignore", over="ignore"):            # lanes not taken by the selects below
+        sub_n = np.rint(np.ldexp(np.minimum(val, 1.0), 133)).astype(np.int64)   # subnormal count
+    mag = np.where(normal, (biased.astype(np.int64) << 7) | frac_n, sub_n)
+    mag = np.where(biased >= 255, 0x7F80, mag)                     # overflow -> inf
+    mag = np.where(val == 0, 0, mag)
+
+    mag = np.where(inf, 0x7F80, mag)
+    mag = np.where(nan, 0x7FC0, mag)
+    out = (mag.astype(np.uint16) | (sign.astype(np.uint16) << np.uint16(15))).astype(np.uint16)
+    out = np.where(nan, np.uint16(0x7FC0), out).astype(np.uint16)
+    return out
+
+
+# --------------------------------------------------------------------------
+# RoPE
+# --------------------------------------------------------------------------
+
+
+def inv_freq(theta_base: float, d_head: int) -> np.ndarray:
+    """theta_j = theta_base^(-2j/D), j = 0 .. D/2-1 (0-based pair index)."""
+    j = np.arange(d_head // 2, dtype=np.float64)
+    return np.float64(theta_base) ** (-2.0 * j / np.float64(d_head))
+
+
+def rope_full(x: np.ndarray, t, theta_base: float) -> np.ndarray:
+    """Full-width rotation of x[..., D] at position(s) t (broadcast over ...).
+
+    Pair j couples dims (j, j + D/2); the 2x2 block is
+    [[cos, -sin], [sin, cos]] with angle t * theta_j.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    d = x.shape[-1]
+    half = d // 2
+    phi = np.asarray(t, dtype=np.float64)[..., None] * inv_freq(theta_base, d)
+    c, s = np.cos(phi), np.sin(phi)
+    a, b = x[..., :half], x[..., half:]
+    return np.concatenate([a * c - b * s, a * s + b * c], axis=-1)
+
+
+def rope_compact(x: np.ndarray, t, keep: np.ndarray, theta_base: float, d_head: int) -> np.ndarray:
+    """Index-aware rotation of a compact row x[..., 2P].
+
+    Compact order: element c (< P) is original dim keep[c], element c + P is
+    original dim keep[c] + D/2.  Pair c rotates at the ORIGINAL frequency index
+    keep[c], not at c.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    keep = np.asarray(keep)
+    p = keep.shape[-1]
+    if x.shape[-1] != 2 * p:
+        raise ValueError("row width must be 2 * number of kept pairs")
+    f = inv_freq(theta_base, d_head)[keep]                      # [..., P]
+    phi = np.asarray(t, dtype=np.float64)[..., None] * f
+    c, s = np.cos(phi), np.sin(phi)
+    a, b = x[..., :p], x[..., p:]
+    return np.concatenate([a * c - b * s, a * s + b * c], axis=-1)
+
+
+def select_pairs(x_full: np.ndarray, keep: np.ndarray) -> np.ndarray:
+    """E_k applied to a full-width row: gather dims keep and keep + D/2."""
+    d = x_full.shape[-1]
+    keep = np.asarray(keep)
+    idx = np.concatenate([keep, keep + d // 2])
+    return np.asarray(x_full)[..., idx]
+
+
+# --------------------------------------------------------------------------
+# Cache append
+# --------------------------------------------------------------------------
+
+
+def append_ref(k_new, v_new, pos, keep, k_cache, v_cache, theta_base, d_head):
+    """Rotate each new compact K row at its position and store K, V rows.
+
+    k_new   uint16 [B, n_new, H_kv, 2P]  bf16 bits, before rotation
+    v_new   uint16 [B, n_new, H_kv, d_v] bf16 bits
+    pos     int    [B, n_new]            position == destination row
+    keep    int    [H_kv, P]             original pair index per KV head
+    k_cache uint16 [B, H_kv, cap, 2P]    modified in place
+    v_cache uint16 [B, H_kv, cap, d_v]   modified in place
+
+    The rotated row is rounded to bf16 once, nearest-even, from float64;
+    V is a bit copy.
+    """
+    k_new = np.asarray(k_new)
+    v_new = np.asarray(v_new)
+    pos = np.asarray(pos)
+    keep = np.asarray(keep)
+    bsz, n_new, n_kv, _ = k_new.shape
+    kf = bf16_bits_to_f64(k_new)
+    for b in range(bsz):
+        for n in range(n_new):
+            t = int(pos[b, n])
+            for h in range(n_kv):
+                rot = rope_compact(kf[b, n, h], np.float64(t), keep[h], theta_base, d_head)
+                k_cache[b, h, t, :] = f64_to_bf16_bits_rne(rot)
+                v_cache[b, h, t, :] = v_new[b, n, h, :]
+
+
+# --------------------------------------------------------------------------
+# Attention
+# --------------------------------------------------------------------------
+
+
+def softmax_ref(s: np.ndarray) -> np.ndarray:
+    """softmax over the last axis, max-shifted."""
+    s = np.asarray(s, dtype=np.float64)
+    e = np.exp(s - np.max(s, axis=-1, keepdims=True))
+    return e / np.sum(e, axis=-1, keepdims=True)
+
+
+def attn_rows_ref(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float) -> np.ndarray:
+    """One KV head: q [G, d_k], k [S, d_k], v [S, d_v] (float64) -> [G, d_v]."""
+    if k.shape[0] == 0:
+        return np.zeros((q.shape[0], v.shape[1]), dtype=np.float64)
+    s = (q @ k.T) * np.float64(scale)
+    return softmax_ref(s) @ v
+
+
+def attn_ref(q, k_cache, v_cache, seq_lens, scale) -> np.ndarray:
+    """GQA decode attention over the compact cache.
+
+    q        uint16 [B, H_q, d_k]        bf16 bits, pruned and already rotated
+    k_cache  uint16 [B, H_kv, cap, d_k]
+    v_cache  uint16 [B, H_kv, cap, d_v]
+    seq_lens int    [B]                  rows [0, len) are attended
+    returns  float64 [B, H_q, d_v]; a sequence of length 0 gives zeros.
+
+    Query head a reads KV head a // G (contiguous groups).
+    """
+    q = np.asarray(q)
+    bsz, n_q, _ = q.shape
+    n_kv = k_cache.shape[1]
+    g = n_q // n_kv
+    if g * n_kv != n_q:
+        raise ValueError("n_q_heads must be a multiple of n_kv_heads")
+    d_v = v_cache.shape[3]
+    out = np.zeros((bsz, n_q, d_v), dtype=np.float64)
+    qf = bf16_bits_to_f64(q)
+    for b in range(bsz):
+        n = int(seq_lens[b])
+        for h in range(n_kv):
+            kf = bf16_bits_to_f64(k_cache[b, h, :n])
+            vf = bf16_bits_to_f64(v_cache[b, h, :n])
+            out[b, h * g:(h + 1) * g] = attn_rows_ref(qf[b, h * g:(h + 1) * g], kf, vf, scale)
+    return out
+
+
+def attn_full_masked_ref(q_full, k_full, v_full, pos_q, pos_k, keep, keep_v, theta_base, scale):
+    """Full-width attention with the removed pairs / channels zeroed.
+
+    q_full float64 [G, D] and k_full [S, D] are UNROTATED full-width rows of one
+    KV head; they are rotated here with rope_full at pos_q / pos_k[S], then the
+    dims outside the kept pairs are zeroed in q and k, and the channels outside
+    keep_v are zeroed in v_full [S, D].  Returns [G, D] (zeros in removed
+    channels).
+    """
+    q_full = np.asarray(q_full, dtype=np.float64)
+    k_full = np.asarray(k_full, dtype=np.float64)
+    v_full = np.asarray(v_full, dtype=np.float64)
+    d = q_full.shape[-1]
+    mask = np.zeros(d)
+    mask[np.asarray(keep)] = 1.0
+    mask[np.asarray(keep) + d // 2] = 1.0
+    vmask = np.zeros(d)
+    vmask[np.asarray(keep_v)] = 1.0
+    qr = rope_full(q_full, np.full(q_full.shape[:-1], pos_q, dtype=np.float64), theta_base) * mask
+    kr = rope_full(k_full, np.asarray(pos_k, dtype=np.float64), theta_base) * mask
+    return attn_rows_ref(qr, kr, v_full * vmask, scale)
+
+
+def partial_ref(q, k, v, scale):
+    """Un-normalised softmax partial of one row range: (m [G], l [G], acc [G, d_v])."""
+    s = (q @ k.T) * np.float64(scale)
+    m = np.max(s, axis=-1)
+    e = np.exp(s - m[:, None])
+    return m, np.sum(e, axis=-1), e @ v
+
+
+def merge_partials_ref(ms, ls, accs):
+    """Combine row-partitioned partials: out = sum_s e^{m_s-m*} acc_s / sum_s e^{m_s-m*} l_s."""
+    ms = np.stack(ms)            # [n, G]
+    ls = np.stack(ls)            # [n, G]
+    accs = np.stack(accs)        # [n, G, d_v]
+    mstar = np.max(ms, axis=0)
+    w = np.exp(ms - mstar)
+    return np.einsum("ng,ngd->gd", w, accs) / np.sum(w * ls, axis=0)[:, None]
+
+
+# --------------------------------------------------------------------------
+# Cost model (byte accounting)
+# --------------------------------------------------------------------------
+
+
+def kept_pairs(rho: float, d_head: int) -> int:
+    """Budget rounded to whole pairs: m = round(rho * D / 2)."""
+    return int(np.floor(rho * d_head / 2.0 + 0.5))
+
+
+def kv_bytes_per_token(n_layers: int, n_kv_heads: int, d_k: int, d_v: int, bytes_per_el: int = 2) -> int:
+    """Resident KV state per token: layers * KV heads * (d_k + d_v) * element size."""
+    return n_layers * n_kv_heads * (d_k + d_v) * bytes_per_el
+
+
+def decode_kv_bytes(seq_lens, n_kv_heads: int, d_k: int, d_v: int, bytes_per_el: int = 2) -> int:
+    """Bytes of K and V that one decode step must read once: sum_b H_kv * len_b * (d_k + d_v) * size."""
+    return int(sum(int(n) for n in seq_lens)) * n_kv_heads * (d_k + d_v) * bytes_per_el

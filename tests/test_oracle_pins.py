@@ -1,0 +1,462 @@
+"""Pins for the float64 oracle: everything here runs on the CPU and checks oracle/
+against facts fixed by the paper or by mathematics, never against the HIP path.
+
+Each test names the passage it comes from and the mistake it is meant to catch.
+"""
+import cmath
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import rap_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+# ---------------------------------------------------------------- bf16 conversion
+
+
+def _all_finite_bf16():
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    vals = O.bf16_bits_to_f64(bits)
+    ok = np.isfinite(vals)
+    return bits[ok], vals[ok]
+
+
+def test_bf16_decode_against_bit_layout():
+    """Value of a bf16 from its fields: (-1)^s 2^(e-127) (1 + f/128), subnormal 2^-126 f/128."""
+    for bits in [0x0000, 0x8000, 0x3F80, 0xBF80, 0x4000, 0x3F00, 0x0001, 0x007F, 0x0080, 0x7F7F, 0x4049, 0xC2F7]:
+        s, e, f = bits >> 15, (bits >> 7) & 0xFF, bits & 0x7F
+        want = (f / 128.0) * 2.0 ** -126 if e == 0 else (1 + f / 128.0) * 2.0 ** (e - 127)
+        want = -want if s else want
+        got = O.bf16_bits_to_f64(np.array([bits], dtype=np.uint16))[0]
+        assert got == want
+    assert np.isinf(O.bf16_bits_to_f64(np.array([0x7F80], dtype=np.uint16))[0])
+    assert np.isnan(O.bf16_bits_to_f64(np.array([0x7FC1], dtype=np.uint16))[0])
+
+
+def test_bf16_round_trip_every_pattern():
+    bits, vals = _all_finite_bf16()
+    back = O.f64_to_bf16_bits_rne(vals)
+    # -0.0 and +0.0 keep their sign bit as well
+    assert np.array_equal(back, bits)
+
+
+def test_bf16_rne_against_exhaustive_nearest_search():
+    """Nearest-even by brute force over the sorted list of all finite bf16 values, in exact
+    rational arithmetic.  Catches truncation, round-half-up, wrong subnormal quantum."""
+    bits, vals = _all_finite_bf16()
+    pos = vals >= 0
+    pbits, pvals = bits[pos & (bits < 0x8000)], vals[pos & (bits < 0x8000)]
+    order = np.argsort(pvals, kind="stable")
+    pbits, pvals = pbits[order], pvals[order]
+    rng = _rng(7)
+    xs = list(np.abs(rng.standard_normal(300)) * 10.0 ** rng.integers(-42, 38, 300))
+    # exact ties and near-ties between neighbours, normal and subnormal
+    for i in [1, 2, 3, 126, 127, 128, 129, 5000, 16255, 16256, 16257, 20000, len(pvals) - 2]:
+        lo, hi = Fraction(float(pvals[i])), Fraction(float(pvals[i + 1]))
+        mid = (lo + hi) / 2
+        xs += [float(mid), float(np.nextafter(float(mid), 0.0)), float(np.nextafter(float(mid), np.inf))]
+    for x in xs:
+        if x > float(pvals[-1]):
+            continue
+        i = int(np.searchsorted(pvals, x, side="right")) - 1
+        i = max(i, 0)
+        cands = [i] if i + 1 >= len(pvals) else [i, i + 1]
+        fx = Fraction(x)
+        best = min(cands, key=lambda c: (abs(Fraction(float(pvals[c])) - fx), int(pbits[c]) & 1))
+        got = O.f64_to_bf16_bits_rne(np.array([x, -x]))
+        assert got[0] == pbits[best], (x, hex(got[0]), hex(pbits[best]))
+        assert got[1] == (pbits[best] | 0x8000)
+
+
+def test_bf16_rne_matches_torch_cast_from_float32():
+    """Library routine as a second opinion: torch's float32 -> bfloat16 cast is RNE."""
+    rng = _rng(11)
+    x32 = (rng.standard_normal(200000) * 10.0 ** rng.integers(-30, 30, 200000)).astype(np.float32)
+    x32 = np.concatenate([x32, np.array([0.0, -0.0, 1.0, 1.00390625, 1.01171875, 3.3895314e38, 1e-40, 6e-41], dtype=np.float32)])
+    want = torch.from_numpy(x32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = O.f64_to_bf16_bits_rne(x32.astype(np.float64))
+    assert np.array_equal(got, want)
+
+
+def test_bf16_overflow_inf_nan():
+    got = O.f64_to_bf16_bits_rne(np.array([1e39, -1e39, np.inf, -np.inf, 3.3961775292304601e38]))
+    assert list(got[:4]) == [0x7F80, 0xFF80, 0x7F80, 0xFF80]
+    assert got[4] == 0x7F80  # halfway between max finite and 2^128 rounds to even = inf
+    assert O.f64_to_bf16_bits_rne(np.array([np.nan]))[0] & 0x7FFF > 0x7F80
+
+
+# ---------------------------------------------------------------- RoPE
+
+
+def test_inv_freq_values():
+    """theta_j = theta_base^(-2j/D), 0-based j: pair 0 has frequency 1, the last pair
+    theta_base^(-(D-2)/D).  Catches 1-based j or an exponent of j/D."""
+    f = O.inv_freq(5.0e5, 128)
+    assert f.shape == (64,)
+    assert f[0] == 1.0
+    assert math.isclose(f[63], 5.0e5 ** (-126.0 / 128.0), rel_tol=1e-15)
+    assert math.isclose(f[32], 5.0e5 ** -0.5, rel_tol=1e-15)
+    assert np.all(np.diff(f) < 0)
+
+
+def test_rope_full_equals_complex_rotation():
+    """Eq. (rope): the 2x2 block is multiplication of (x_j + i x_{j+D/2}) by e^{i t theta_j}.
+    Written with cmath, one pair at a time.  Catches a flipped sine sign, adjacent pairing,
+    swapped halves."""
+    rng = _rng(3)
+    d, theta = 16, 1.0e4
+    x = rng.standard_normal(d)
+    for t in [0, 1, 7, 1000, 131071]:
+        y = O.rope_full(x, np.float64(t), theta)
+        for j in range(d // 2):
+            z = complex(x[j], x[j + d // 2]) * cmath.exp(1j * t * theta ** (-2.0 * j / d))
+            assert math.isclose(y[j], z.real, rel_tol=0, abs_tol=1e-12)
+            assert math.isclose(y[j + d // 2], z.imag, rel_tol=0, abs_tol=1e-12)
+
+
+def test_rope_matrix_entries_one_pair():
+    """The printed matrix [[cos, -sin], [sin, cos]] at t*theta_j = pi/2 maps (1, 0) to (0, 1)."""
+    d, theta = 4, 1.0e4
+    # pair 0 has frequency 1: t = pi/2 is not an integer position, so use the function with a float t
+    y = O.rope_full(np.array([1.0, 0.0, 0.0, 0.0]), np.float64(math.pi / 2), theta)
+    assert abs(y[0]) < 1e-15 and abs(y[2] - 1.0) < 1e-15
+
+
+def test_rho1_compact_is_full_bit_for_bit():
+    """E_k = I: index-aware rotation with keep = 0..D/2-1 is the standard rotation."""
+    rng = _rng(4)
+    x = rng.standard_normal((5, 128))
+    t = np.array([0, 1, 17, 4097, 131071], dtype=np.float64)
+    a = O.rope_full(x, t, 5.0e5)
+    b = O.rope_compact(x, t, np.arange(64), 5.0e5, 128)
+    assert np.array_equal(a, b)
+
+
+def test_intertwining_identity():
+    """App. Method, Eq. (selection-rope-intertwine): E_k R_t = R_{t,S} E_k.
+    Catches rotating pair c at frequency c instead of keep[c]."""
+    rng = _rng(5)
+    d, p = 128, 45
+    for trial in range(5):
+        keep = np.sort(rng.choice(d // 2, p, replace=False))
+        x = rng.standard_normal((3, d))
+        t = rng.integers(0, 131072, 3).astype(np.float64)
+        lhs = O.select_pairs(O.rope_full(x, t, 1.0e6), keep)
+        rhs = O.rope_compact(O.select_pairs(x, keep), t, keep, 1.0e6, d)
+        assert np.array_equal(lhs, rhs)
+    # and it is NOT what a contiguous re-indexing would give
+    wrong = O.rope_compact(O.select_pairs(x, keep), t, np.arange(p), 1.0e6, d)
+    assert np.max(np.abs(wrong - rhs)) > 1e-3
+
+
+def test_selection_matrix_facts():
+    """App. Method: E_k E_k^T = I_2m; M_S = E_k^T E_k is a 0/1 diagonal mask; expanding the
+    reduced row gives the masked row.  select_pairs is E_k."""
+    rng = _rng(6)
+    d, p = 16, 3
+    keep = np.sort(rng.choice(d // 2, p, replace=False))
+    E = O.select_pairs(np.eye(d), keep).T            # [2p, d]: row i picks original dim RAPIndex[i]
+    assert np.array_equal(E @ E.T, np.eye(2 * p))
+    M = E.T @ E
+    assert np.array_equal(M, np.diag(np.diag(M))) and set(np.diag(M)) <= {0.0, 1.0}
+    assert int(np.trace(M)) == 2 * p
+    x = rng.standard_normal(d)
+    assert np.array_equal(O.select_pairs(x, keep) @ E, x * np.diag(M))
+    # R_t M_S = M_S R_t
+    t = np.float64(37)
+    assert np.allclose(O.rope_full(x * np.diag(M), t, 1e4), O.rope_full(x, t, 1e4) * np.diag(M), atol=0)
+
+
+def test_relative_position_invariance():
+    """R(t)^T R(u) = R(u - t): the score depends on the offset only, also on the compact row."""
+    rng = _rng(8)
+    d, p, theta = 128, 45, 5.0e5
+    keep = np.sort(rng.choice(d // 2, p, replace=False))
+    q = rng.standard_normal(2 * p)
+    k = rng.standard_normal(2 * p)
+    def score(t, u):
+        return float(O.rope_compact(q, np.float64(t), keep, theta, d) @ O.rope_compact(k, np.float64(u), keep, theta, d))
+    base = score(900, 123)
+    for delta in [1, 64, 4096, 100000]:
+        assert abs(score(900 + delta, 123 + delta) - base) < 1e-9
+    assert abs(score(901, 123) - base) > 1e-6      # and it does depend on the offset
+
+
+def test_closed_form_single_pair_score():
+    """q-pair = k-pair = (r, 0) on kept pair c only: score = r^2 cos((t-u) theta_keep[c])."""
+    d, theta = 128, 1.0e6
+    keep = np.array([3, 10, 41])
+    r, t, u = 1.75, 5000, 4211
+    for c in range(3):
+        x = np.zeros(6)
+        x[c] = r
+        s = float(O.rope_compact(x, np.float64(t), keep, theta, d) @ O.rope_compact(x, np.float64(u), keep, theta, d))
+        want = r * r * math.cos((t - u) * theta ** (-2.0 * keep[c] / d))
+        assert abs(s - want) < 1e-10
+
+
+def test_rotation_preserves_pair_norm_and_pos0_is_identity():
+    rng = _rng(9)
+    keep = np.array([0, 5, 9, 63])
+    x = rng.standard_normal(8)
+    y = O.rope_compact(x, np.float64(77777), keep, 5e5, 128)
+    assert np.allclose(x[:4] ** 2 + x[4:] ** 2, y[:4] ** 2 + y[4:] ** 2, rtol=1e-14)
+    assert np.array_equal(O.rope_compact(x, np.float64(0), keep, 5e5, 128), x)
+
+
+# ---------------------------------------------------------------- append
+
+
+def _bf16_of(x):
+    return O.f64_to_bf16_bits_rne(np.asarray(x, dtype=np.float64))
+
+
+def test_append_writes_only_its_rows_and_copies_v():
+    rng = _rng(10)
+    B, n_new, H, P, dv, cap, D = 2, 3, 2, 3, 5, 16, 16
+    keep = np.stack([np.sort(rng.choice(D // 2, P, replace=False)) for _ in range(H)])
+    k_new = _bf16_of(rng.standard_normal((B, n_new, H, 2 * P)))
+    v_new = _bf16_of(rng.standard_normal((B, n_new, H, dv)))
+    pos = np.array([[4, 5, 6], [0, 9, 15]])
+    kc = _bf16_of(rng.standard_normal((B, H, cap, 2 * P)))
+    vc = _bf16_of(rng.standard_normal((B, H, cap, dv)))
+    kc0, vc0 = kc.copy(), vc.copy()
+    O.append_ref(k_new, v_new, pos, keep, kc, vc, 1e4, D)
+    for b in range(B):
+        touched = set(pos[b].tolist())
+        for r in range(cap):
+            if r in touched:
+                n = pos[b].tolist().index(r)
+                assert np.array_equal(vc[b, :, r], v_new[b, n])
+                for h in range(H):
+                    want = O.rope_compact(O.bf16_bits_to_f64(k_new[b, n, h]), np.float64(r), keep[h], 1e4, D)
+                    assert np.array_equal(kc[b, h, r], _bf16_of(want))
+            else:
+                assert np.array_equal(kc[b, :, r], kc0[b, :, r]) and np.array_equal(vc[b, :, r], vc0[b, :, r])
+    # position 0 rotates by nothing: the stored row is the input row, bit for bit
+    assert np.array_equal(kc[1, :, 0], k_new[1, 0])
+
+
+# ---------------------------------------------------------------- attention
+
+
+def test_attention_equals_torch_sdpa_float64_with_gqa():
+    """Eq. (attn) + GQA remark: a library routine (torch SDPA, float64, CPU) on explicitly
+    repeat-interleaved KV heads.  Catches a//G vs a%H_kv, a transposed matmul, a missing scale."""
+    rng = _rng(12)
+    B, Hq, Hkv, dk, dv, S = 2, 6, 2, 10, 7, 33
+    q = _bf16_of(rng.standard_normal((B, Hq, dk)))
+    kc = _bf16_of(rng.standard_normal((B, Hkv, S, dk)))
+    vc = _bf16_of(rng.standard_normal((B, Hkv, S, dv)))
+    scale = 0.37
+    got = O.attn_ref(q, kc, vc, np.array([S, S]), scale)
+    tq = torch.from_numpy(O.bf16_bits_to_f64(q))[:, :, None, :]
+    tk = torch.from_numpy(O.bf16_bits_to_f64(kc)).repeat_interleave(Hq // Hkv, dim=1)
+    tv = torch.from_numpy(O.bf16_bits_to_f64(vc)).repeat_interleave(Hq // Hkv, dim=1)
+    want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, scale=scale)[:, :, 0, :].numpy()
+    assert np.max(np.abs(got - want)) < 1e-13
+
+
+def test_attention_respects_seq_lens():
+    """Rows at and beyond len must not matter, whatever they hold; len = 1 returns V[0];
+    len = 0 returns zeros."""
+    rng = _rng(13)
+    B, Hq, Hkv, dk, dv, cap = 3, 4, 2, 6, 5, 12
+    q = _bf16_of(rng.standard_normal((B, Hq, dk)))
+    kc = _bf16_of(rng.standard_normal((B, Hkv, cap, dk)))
+    vc = _bf16_of(rng.standard_normal((B, Hkv, cap, dv)))
+    lens = np.array([1, 7, 0])
+    a = O.attn_ref(q, kc, vc, lens, 0.5)
+    kc2, vc2 = kc.copy(), vc.copy()
+    for b in range(B):
+        kc2[b, :, lens[b]:] = 0x7F00   # huge finite
+        vc2[b, :, lens[b]:] = 0xFF00
+    assert np.array_equal(a, O.attn_ref(q, kc2, vc2, lens, 0.5))
+    for a_h in range(Hq):
+        assert np.array_equal(a[0, a_h], O.bf16_bits_to_f64(vc[0, a_h // 2, 0]))
+    assert np.all(a[2] == 0)
+
+
+def test_softmax_invariants():
+    rng = _rng(14)
+    s = rng.standard_normal((4, 1000)) * 20
+    p = O.softmax_ref(s)
+    assert np.max(np.abs(p.sum(-1) - 1)) < 1e-14
+    assert np.all(p >= 0)
+    assert np.max(np.abs(O.softmax_ref(s + 123.0) - p)) < 1e-12
+    # equal keys -> mean of V; output inside the per-channel hull of V; row permutation invariance
+    q = rng.standard_normal((3, 8))
+    k = np.tile(rng.standard_normal(8), (50, 1))
+    v = rng.standard_normal((50, 5))
+    assert np.max(np.abs(O.attn_rows_ref(q, k, v, 0.3) - v.mean(0))) < 1e-13
+    k = rng.standard_normal((50, 8))
+    o = O.attn_rows_ref(q, k, v, 0.3)
+    assert np.all(o <= v.max(0) + 1e-12) and np.all(o >= v.min(0) - 1e-12)
+    perm = rng.permutation(50)
+    assert np.max(np.abs(O.attn_rows_ref(q, k[perm], v[perm], 0.3) - o)) < 1e-13
+
+
+def test_zero_mask_identity():
+    """App. Method, Eq. (masked-logit-equivalence): reduced attention == full-width attention
+    with removed pairs zeroed in q and k and removed channels zeroed in v, at the same scale."""
+    rng = _rng(15)
+    D, P, dv, G, S, theta = 128, 45, 90, 4, 40, 5.0e5
+    keep = np.sort(rng.choice(D // 2, P, replace=False))
+    keep_v = np.sort(rng.choice(D, dv, replace=False))
+    qf = rng.standard_normal((G, D))
+    kf = rng.standard_normal((S, D))
+    vf = rng.standard_normal((S, D))
+    pos_k = np.arange(S, dtype=np.float64) + 1000
+    pos_q = 1000 + S - 1
+    for scale in [1 / math.sqrt(D), 1 / math.sqrt(2 * P)]:
+        full = O.attn_full_masked_ref(qf, kf, vf, pos_q, pos_k, keep, keep_v, theta, scale)
+        qc = O.rope_compact(O.select_pairs(qf, keep), np.full(G, pos_q, dtype=np.float64), keep, theta, D)
+        kc = O.rope_compact(O.select_pairs(kf, keep), pos_k, keep, theta, D)
+        red = O.attn_rows_ref(qc, kc, vf[:, keep_v], scale)
+        assert np.max(np.abs(full[:, keep_v] - red)) < 1e-12
+        dropped = np.setdiff1d(np.arange(D), keep_v)
+        assert np.all(full[:, dropped] == 0)
+    # masking only q (or only k) already gives the same logits: M_S is idempotent
+    mask = np.zeros(D)
+    mask[keep] = 1
+    mask[keep + D // 2] = 1
+    qr = O.rope_full(qf, np.full(G, pos_q, dtype=np.float64), theta)
+    kr = O.rope_full(kf, pos_k, theta)
+    assert np.max(np.abs((qr * mask) @ kr.T - (qr * mask) @ (kr * mask).T)) < 1e-12
+    assert np.max(np.abs(qr @ (kr * mask).T - qc @ kc.T)) < 1e-12
+
+
+def test_rho1_attention_is_standard_rope_attention():
+    """rho = 1: the whole chain (rotate K rows with all pairs, attend) equals textbook RoPE
+    attention computed by SDPA on complex-rotated rows."""
+    rng = _rng(16)
+    D, G, S, theta = 16, 2, 9, 1.0e4
+    qf, kf, vf = rng.standard_normal((G, D)), rng.standard_normal((S, D)), rng.standard_normal((S, D))
+    keep = np.arange(D // 2)
+    pos_k = np.arange(S, dtype=np.float64)
+    qc = O.rope_compact(qf, np.full(G, S - 1.0), keep, theta, D)
+    kc = O.rope_compact(kf, pos_k, keep, theta, D)
+    got = O.attn_rows_ref(qc, kc, vf, 1 / math.sqrt(D))
+
+    def crot(x, t):
+        out = np.empty(D)
+        for j in range(D // 2):
+            z = complex(x[j], x[j + D // 2]) * cmath.exp(1j * t * theta ** (-2.0 * j / D))
+            out[j], out[j + D // 2] = z.real, z.imag
+        return out
+    tq = torch.tensor(np.stack([crot(qf[g], S - 1) for g in range(G)]))[None, :, None, :]
+    tk = torch.tensor(np.stack([crot(kf[i], i) for i in range(S)]))[None, None].expand(1, G, S, D)
+    tv = torch.tensor(vf)[None, None].expand(1, G, S, D)
+    want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv)[0, :, 0, :].numpy()
+    assert np.max(np.abs(got - want)) < 1e-13
+
+
+def _brute_force(k_new_vals, v_vals, q_vals, keep, theta, D, scale, G):
+    """Whole path with scalar math only: rotate, round to bf16 by nearest search, attend."""
+    bits_all = np.arange(0x7F80, dtype=np.uint32).astype(np.uint16)
+    vals_all = O.bf16_bits_to_f64(bits_all).tolist()      # ascending non-negative finite values
+
+    def rne(x):
+        a = abs(x)
+        import bisect
+        i = max(bisect.bisect_right(vals_all, a) - 1, 0)
+        cands = [i, i + 1] if i + 1 < len(vals_all) else [i]
+        best = min(cands, key=lambda c: (abs(Fraction(vals_all[c]) - Fraction(a)), c & 1))
+        return math.copysign(vals_all[best], x)
+
+    S, H, P = len(k_new_vals), len(keep), len(keep[0])
+    kc = [[[0.0] * (2 * P) for _ in range(S)] for _ in range(H)]
+    for t in range(S):
+        for h in range(H):
+            for c in range(P):
+                phi = t * theta ** (-2.0 * keep[h][c] / D)
+                a, b = k_new_vals[t][h][c], k_new_vals[t][h][c + P]
+                kc[h][t][c] = rne(a * math.cos(phi) - b * math.sin(phi))
+                kc[h][t][c + P] = rne(a * math.sin(phi) + b * math.cos(phi))
+    dv = len(v_vals[0][0])
+    out = [[0.0] * dv for _ in range(H * G)]
+    for a_h in range(H * G):
+        h = a_h // G
+        s = [scale * sum(q_vals[a_h][c] * kc[h][t][c] for c in range(2 * P)) for t in range(S)]
+        mx = max(s)
+        e = [math.exp(x - mx) for x in s]
+        z = sum(e)
+        for c in range(dv):
+            out[a_h][c] = sum(e[t] * v_vals[t][h][c] for t in range(S)) / z
+    return kc, out
+
+
+@pytest.mark.parametrize("P,dv,G,S", [(1, 1, 1, 1), (2, 3, 3, 5), (3, 1, 1, 4), (3, 3, 3, 2), (2, 1, 3, 3)])
+def test_brute_force_tiny(P, dv, G, S):
+    """D = 8: explicit Python loops with math.cos/sin/exp against append_ref + attn_ref."""
+    rng = _rng(100 + P * 31 + dv * 7 + G * 3 + S)
+    D, H, theta, scale = 8, 2, 1.0e4, 0.6
+    keep = np.stack([np.sort(rng.choice(D // 2, P, replace=False)) for _ in range(H)])
+    k_new = _bf16_of(rng.standard_normal((1, S, H, 2 * P)) * 2)
+    v_new = _bf16_of(rng.standard_normal((1, S, H, dv)))
+    q = _bf16_of(rng.standard_normal((1, H * G, 2 * P)))
+    kc = np.zeros((1, H, S + 3, 2 * P), dtype=np.uint16)
+    vc = np.zeros((1, H, S + 3, dv), dtype=np.uint16)
+    O.append_ref(k_new, v_new, np.arange(S)[None, :], keep, kc, vc, theta, D)
+    got = O.attn_ref(q, kc, vc, np.array([S]), scale)[0]
+    bk, bo = _brute_force(O.bf16_bits_to_f64(k_new[0]).tolist(), O.bf16_bits_to_f64(v_new[0]).tolist(),
+                          O.bf16_bits_to_f64(q[0]).tolist(), keep.tolist(), theta, D, scale, G)
+    assert np.array_equal(O.bf16_bits_to_f64(kc[0, :, :S]), np.array(bk))
+    assert np.max(np.abs(got - np.array(bo))) < 1e-14
+
+
+def test_split_merge_identity():
+    """Merging (m, l, acc) partials over any partition of the rows gives the unsplit result."""
+    rng = _rng(17)
+    G, dk, dv, S = 4, 12, 9, 101
+    q, k, v = rng.standard_normal((G, dk)), rng.standard_normal((S, dk)) * 4, rng.standard_normal((S, dv))
+    whole = O.attn_rows_ref(q, k, v, 0.4)
+    for cuts in [[0, S], [0, 1, S], [0, 32, 64, 96, S], [0, 7, 8, 50, 99, 100, S]]:
+        parts = [O.partial_ref(q, k[a:b], v[a:b], 0.4) for a, b in zip(cuts[:-1], cuts[1:])]
+        merged = O.merge_partials_ref(*zip(*parts))
+        assert np.max(np.abs(merged - whole)) < 1e-13
+
+
+# ---------------------------------------------------------------- byte accounting
+
+
+def _read_table(name):
+    rows = []
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                rows.append(line.split())
+    return rows
+
+
+def test_kept_pairs_reproduces_counted_fractions():
+    """Tab. (effsweep): with D = 128 the counted RAP fraction equals kept_pairs/64 to the three
+    printed digits at every retain ratio, which fixes m = round(rho D / 2)."""
+    for rho_s, frac_s in _read_table("effsweep.txt"):
+        m = O.kept_pairs(float(rho_s), 128)
+        assert abs(m / 64.0 - float(frac_s)) < 5.1e-4, (rho_s, m)
+    assert [O.kept_pairs(r, 128) for r in (0.9, 0.7, 0.5, 1.0)] == [58, 45, 32, 64]
+
+
+def test_kv_bytes_per_token_against_serving_table():
+    """Tab. (serving): dense Llama-3-8B keeps 128 KiB per token; RAP 0.7 keeps 89.5 KiB, which the
+    uniform 45-pair / 90-channel layout (90.0 KiB) matches to 1 % (the deployed budgets are
+    layer-adaptive)."""
+    t = dict((k, float(v)) for k, v in _read_table("serving.txt"))
+    assert O.kv_bytes_per_token(32, 8, 128, 128) == t["dense"] * 1024
+    rap = O.kv_bytes_per_token(32, 8, 90, 90) / 1024.0
+    assert abs(rap - t["rap0.7"]) / t["rap0.7"] < 0.01
+    # cache scales as rho: Cache = rho * 2SD
+    assert O.decode_kv_bytes([8192] * 16, 8, 90, 90) == 16 * 8 * 8192 * 180 * 2
+    assert abs(O.decode_kv_bytes([100], 8, 90, 90) / O.decode_kv_bytes([100], 8, 128, 128) - 45 / 64) < 1e-15
