@@ -1,0 +1,250 @@
+#!/usr/bin/env python3
+"""Benchmark of the librap hot path on one MI355X.
+
+A step is one pass of the whole path over one batch: rap_rope_append of one new token per
+sequence, then rap_decode_attn over the compact cache.  Workload: the Llama-3.1-8B-shaped
+configuration at rho = 0.7 (batch 16, 32/8 heads, 8192 rows, d_k = d_v = 90, 1 % of K rows x8),
+seeded synthetic bf16 data already resident in HBM.  Successive steps rotate over several
+distinct copies of the cache so that the working set exceeds L2 + Infinity Cache and the bytes
+really come from HBM.
+
+Prints ONE JSON line: whole-job throughput in algorithmic GB/s (K and V bytes that a decode step
+must read once, divided by the step time), the roofline object of the dominant kernel measured
+with HIP events on the launch stream, the float64 oracle timed on the host cores, and the
+rho = 1.0 control from the same code.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+class HipEvents:
+    """hipEvent_t handles through the HIP runtime's own C API (torch events are tied to torch's
+    current stream; these are recorded by librap on the stream it launches on)."""
+
+    def __init__(self):
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [C.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+
+    def create(self) -> C.c_void_p:
+        ev = C.c_void_p()
+        rc = self.hip.hipEventCreate(C.byref(ev))
+        if rc != 0:
+            raise RuntimeError("hipEventCreate failed: %d" % rc)
+        return ev
+
+    def elapsed_ms(self, a, b) -> float:
+        self.hip.hipEventSynchronize(b)
+        ms = C.c_float()
+        rc = self.hip.hipEventElapsedTime(C.byref(ms), a, b)
+        if rc != 0:
+            raise RuntimeError("hipEventElapsedTime failed: %d" % rc)
+        return float(ms.value)
+
+    def destroy(self, ev):
+        self.hip.hipEventDestroy(ev)
+
+
+def kv_bytes(w, seq_lens) -> int:
+    """Algorithmic bytes of one decode step: every K and V row of every KV head once."""
+    return int(np.sum(seq_lens)) * w.n_kv_heads * (w.d_k + w.d_v) * 2
+
+
+class Job:
+    """One workload with n_buf distinct cache copies, ready to step."""
+
+    def __init__(self, rap, I, name, n_buf, device):
+        import torch
+        self.torch = torch
+        self.rap = rap
+        self.w = I.WORKLOADS[name]
+        self.cases = [I.make_case(I.scaled(self.w, seed=self.w.seed + 100 * i), device=device) for i in range(n_buf)]
+        c0 = self.cases[0]
+        w = self.w
+        self.shape = rap.shape(w.batch, w.n_q_heads, w.n_kv_heads, w.d_head, w.n_pairs, w.d_v, c0.cap, w.rope_theta)
+        self.max_len = int(max(int(c.seq_lens.max().item()) for c in self.cases))
+        self.ws = rap.new_workspace(self.shape, self.max_len, None, device=device)
+        self.out = torch.empty((w.batch, w.n_q_heads, w.d_v), dtype=torch.float32, device=device)
+        self.bytes_per_step = float(np.mean([kv_bytes(w, c.seq_lens.cpu().numpy()) for c in self.cases]))
+        self.i = 0
+
+    def step(self, tuning=None):
+        c = self.cases[self.i % len(self.cases)]
+        self.i += 1
+        w = self.w
+        self.rap.rap_rope_append(self.shape, w.n_new, c.k_new, c.v_new, c.pos, c.keep, c.k_cache, c.v_cache)
+        self.rap.rap_decode_attn(self.shape, c.q, c.k_cache, c.v_cache, c.seq_lens, self.max_len, self.out,
+                                 float(w.scale), self.ws, tuning)
+
+    def timed(self, steps, warmup):
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    def kernel_ms(self, steps, ev):
+        """Average duration of the partial-attention kernel alone, HIP events recorded by librap
+        around that launch on the launch stream."""
+        pairs = [(ev.create(), ev.create()) for _ in range(steps)]
+        for a, b in pairs:
+            self.step(self.rap.tuning(ev_main_start=a, ev_main_stop=b))
+        self.torch.cuda.synchronize()
+        ms = [ev.elapsed_ms(a, b) for a, b in pairs]
+        for a, b in pairs:
+            ev.destroy(a)
+            ev.destroy(b)
+        return float(np.mean(ms)), float(np.min(ms))
+
+
+def cpu_baseline(I, case, min_seconds=10.0):
+    """The oracle as it stands, on the host cores, over whole decode steps of the same workload
+    (append of the new token + attention), repeated until min_seconds have passed."""
+    from oracle import rap_oracle as O
+    w = case.w
+    q, kc, vc = I.bits(case.q), I.bits(case.k_cache), I.bits(case.v_cache)
+    k_new, v_new = I.bits(case.k_new), I.bits(case.v_new)
+    pos, keep, lens = case.pos.cpu().numpy(), case.keep.cpu().numpy(), case.seq_lens.cpu().numpy()
+    n = 0
+    t0 = time.perf_counter()
+    while True:
+        O.append_ref(k_new, v_new, pos, keep, kc, vc, w.rope_theta, w.d_head)
+        O.attn_ref(q, kc, vc, lens, w.scale)
+        n += 1
+        dt = time.perf_counter() - t0
+        if dt >= min_seconds or n >= 50:
+            break
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    threads = min(threads, len(os.sched_getaffinity(0)))
+    return {"value": round(kv_bytes(w, lens) * n / dt / 1e9, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+            "sample": "%d whole steps of the same workload (append + attention, %d sequences x %d KV heads x %d rows), "
+                      "NumPy float64, %.1f s" % (n, w.batch, w.n_kv_heads, w.ctx, dt),
+            "tokens_per_s": round(w.batch * n / dt, 3), "host_cpus": len(os.sched_getaffinity(0))}
+
+
+def read_traffic(path):
+    """HBM bytes per launch of the dominant kernel from the committed counter summary, if present."""
+    try:
+        kv = {}
+        with open(path) as f:
+            for line in f:
+                if "=" in line and not line.lstrip().startswith("#"):
+                    k, v = line.split("=", 1)
+                    kv[k.strip()] = v.strip()
+        return float(kv["hbm_bytes_per_launch"])
+    except Exception:
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--buffers", type=int, default=4, help="distinct cache copies rotated through")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--no-control", action="store_true", help="skip the rho = 1.0 control")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (every box here has one); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2602_02599_amd as pkg
+    from paper_2602_02599_amd import inputs as I
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    rap = pkg.load()
+    ev = HipEvents()
+
+    job = Job(rap, I, args.workload, args.buffers, dev)
+    w = job.w
+    sec = job.timed(args.steps, args.warmup)
+    gbps = job.bytes_per_step / sec / 1e9
+    k_mean_ms, k_min_ms = job.kernel_ms(args.steps, ev)
+    achieved = job.bytes_per_step / (k_mean_ms * 1e-3) / 1e9
+
+    # what a trivial read-only kernel reaches over the same bytes, same run
+    flat = torch.cat([c.k_cache.view(-1) for c in job.cases] + [c.v_cache.view(-1) for c in job.cases])
+    nflat = flat.numel() * 2 // 16 * 16
+    flat_u8 = flat.view(torch.uint8)[:nflat]
+    sink = torch.zeros(16, dtype=torch.uint8, device=dev)
+    for _ in range(3):
+        rap.rap_stream_read(flat_u8, sink)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(10):
+        rap.rap_stream_read(flat_u8, sink)
+    torch.cuda.synchronize()
+    stream_gbps = nflat * 10 / (time.perf_counter() - t0) / 1e9
+    del flat, flat_u8
+
+    result = {
+        "metric": "decode-attention HBM GB/s (fraction of peak) and tokens/s at rho=0.7, 1 MI355X",
+        "value": round(gbps, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 storage, f32 accumulate", "data": "synthetic",
+        "config": {"workload": "%s: B=%d, %d/%d heads, ctx=%d, d_k=%d, d_v=%d, rho=%.1f, one layer; step = rope_append(1 token/seq) + decode_attn"
+                               % (w.name, w.batch, w.n_q_heads, w.n_kv_heads, w.ctx, w.d_k, w.d_v, w.n_pairs / (w.d_head / 2)),
+                   "cache_copies_rotated": args.buffers, "kv_bytes_per_step": int(job.bytes_per_step)},
+        "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
+        "tokens_per_s": round(w.batch / sec, 1),
+        "stream_read_GBps": round(stream_gbps, 1),
+        "roofline": {"bound": "hbm", "kernel": "decode_mfma_kernel", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": read_traffic(os.path.join(ROOT, "profiles", "traffic_decode_mfma_%s.txt" % w.name)),
+                     "kernel_ms_mean": round(k_mean_ms, 5), "kernel_ms_min": round(k_min_ms, 5),
+                     "algorithmic_bytes_per_launch": int(job.bytes_per_step)},
+    }
+
+    if not args.no_control and (args.workload + "_rho1") in I.WORKLOADS:
+        case0 = job.cases[0]
+        del job.cases[1:]
+        ctl = Job(rap, I, args.workload + "_rho1", args.buffers, dev)
+        csec = ctl.timed(args.steps, args.warmup)
+        result["rho1_control"] = {"value": round(ctl.bytes_per_step / csec / 1e9, 2), "unit": "GB/s",
+                                  "ms_per_step": round(csec * 1e3, 5), "kv_bytes_per_step": int(ctl.bytes_per_step),
+                                  "speedup_of_pruned": round(csec / sec, 4),
+                                  "kv_byte_ratio": round(ctl.bytes_per_step / job.bytes_per_step, 4)}
+        del ctl
+        torch.cuda.empty_cache()
+    else:
+        case0 = job.cases[0]
+
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(I, case0)
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

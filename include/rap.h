@@ -1,0 +1,153 @@
+/* librap - decode-time attention over a RoPE-aligned-pruned KV cache, for AMD MI355X (gfx950).
+ *
+ * RAP (RoPE-Aligned Pruning) removes whole RoPE pairs from the key projection and whole channels
+ * from the value projection, fuses the selection into W_q and W_o offline, and so leaves a KV
+ * cache whose K rows have width d_k = 2 * P (P kept pairs) and whose V rows have width d_v.
+ * This library is the online half: write a new token into that compact cache, and attend over it.
+ *
+ * All pointers marked "dev" are device (HBM) addresses valid on the current HIP device; "host"
+ * pointers are ordinary process memory.  The caller owns every buffer.  The library allocates
+ * nothing, keeps no state between calls, never synchronises the device and never throws: each
+ * entry point validates what can be validated on the host, enqueues its kernels on `stream`
+ * (a hipStream_t passed as void*, NULL = the default stream) and returns a status.  When a status
+ * other than RAP_OK is returned, no kernel has been enqueued by that call (except RAP_ERR_HIP,
+ * which reports a launch failure of the HIP runtime).
+ *
+ * Element type of q, k_new, v_new and both caches is bfloat16 (upper half of an IEEE binary32),
+ * arithmetic is fp32 (fp64 for the rotation angle), `out` is fp32.
+ */
+#ifndef RAP_H_
+#define RAP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum rap_status {
+  RAP_OK = 0,
+  RAP_ERR_NULL = 1,        /* a required pointer is NULL                                        */
+  RAP_ERR_SHAPE = 2,       /* inconsistent shape: G not integral, P > D/2, cap % 8 != 0, ...    */
+  RAP_ERR_UNSUPPORTED = 3, /* consistent, but outside what the kernels are built for            */
+  RAP_ERR_CAPACITY = 4,    /* max_seq_len exceeds cache_cap                                     */
+  RAP_ERR_WORKSPACE = 5,   /* workspace missing or smaller than rap_decode_attn_workspace_bytes */
+  RAP_ERR_HIP = 6          /* the HIP runtime refused a launch                                  */
+} rap_status_t;
+
+/* Geometry of one attention layer and its compact cache.  Plain data, passed by const pointer.
+ *
+ * Layouts (row-major, innermost last, no padding anywhere):
+ *   k_cache  bf16 [batch, n_kv_heads, cache_cap, 2 * n_pairs]
+ *   v_cache  bf16 [batch, n_kv_heads, cache_cap, d_v]
+ * A compact K (or q) row holds, for kept pair c in [0, P): element c = original dim
+ * keep_pair_idx[h][c], element c + P = original dim keep_pair_idx[h][c] + d_head / 2
+ * (the half-apart pairing of Eq. (rope), restricted to the kept pairs: the row order of the
+ * selection matrix E_k of Eq. (pruned-decomposition)).
+ * Limits: 1 <= n_pairs <= d_head / 2, n_pairs <= 64, 1 <= d_v <= 128, G = n_q_heads / n_kv_heads
+ * integral and <= 8, cache_cap a positive multiple of 8 (keeps every 8-row group of either
+ * cache 16-byte aligned, whatever the row width).
+ */
+typedef struct rap_shape {
+  int32_t batch;
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t d_head;     /* original head dim D: fixes theta_j = rope_theta^(-2j/D) */
+  int32_t n_pairs;    /* P kept RoPE pairs; d_k = 2P                             */
+  int32_t d_v;        /* kept V channels                                         */
+  int64_t cache_cap;  /* rows per (batch, kv head) in both caches                */
+  double rope_theta;  /* theta_base                                              */
+} rap_shape_t;
+
+/* Optional knobs for rap_decode_attn; NULL or all-zero means "choose for me". */
+typedef struct rap_tuning {
+  int32_t kernel;          /* 0 auto, 1 plain vector-ALU kernel, 2 matrix-core (MFMA) kernel      */
+  int32_t rows_per_split;  /* rows of one sequence handled by one workgroup; 0 auto; else a
+                              positive multiple of 128                                            */
+  int32_t reserved0;
+  int32_t reserved1;
+  void* ev_main_start;     /* host: optional hipEvent_t recorded on `stream` right before ...     */
+  void* ev_main_stop;      /* ... and right after the partial-attention kernel (measurement aid) */
+} rap_tuning_t;
+
+/* Per-token cache append.
+ *
+ * Paper: Sec. "Background" (each new K_t, V_t is written into the cache); Sec. "RAP"
+ * (index-aware rotation that uses the original indices of the retained pairs); Eq. (rope)
+ * (block [[cos,-sin],[sin,cos]], angle t * theta_base^(-2j/D), pairing (j, j + D/2));
+ * Eq. (latent-score) (the cache holds K_latent = RoPE(X W~_k), width 2m).
+ *
+ * For every b < batch, n < n_new, h < n_kv_heads, with t = pos[b][n] and j_c = keep_pair_idx[h][c]:
+ *   phi = t * theta^(-2 j_c / D)                                  (fp64)
+ *   k_cache[b][h][t][c]     = bf16( k_new[b][n][h][c] cos phi - k_new[b][n][h][c+P] sin phi )
+ *   k_cache[b][h][t][c + P] = bf16( k_new[b][n][h][c] sin phi + k_new[b][n][h][c+P] cos phi )
+ *   v_cache[b][h][t][:]     = v_new[b][n][h][:]                   (bit copy)
+ * with one round-to-nearest-even to bf16.  Rows not named by pos are left untouched.
+ *
+ *   k_new          dev  bf16  [batch, n_new, n_kv_heads, 2P]  un-rotated, compact order
+ *   v_new          dev  bf16  [batch, n_new, n_kv_heads, d_v]
+ *   pos            dev  int32 [batch, n_new]   position of the token == destination row
+ *   keep_pair_idx  dev  int32 [n_kv_heads, P]  original pair index in [0, D/2)
+ *   k_cache/v_cache dev, updated in place
+ * A token whose pos lies outside [0, cache_cap), and a pair whose index lies outside [0, D/2),
+ * is skipped on the device (nothing is written for it); the host cannot see either.
+ * n_new == 0 or batch == 0 is a no-op returning RAP_OK.
+ */
+rap_status_t rap_rope_append(const rap_shape_t* shape, int32_t n_new,
+                             const void* k_new, const void* v_new,
+                             const int32_t* pos, const int32_t* keep_pair_idx,
+                             void* k_cache, void* v_cache, void* stream);
+
+/* Bytes of device scratch rap_decode_attn needs for sequences up to max_seq_len rows with the
+ * given tuning (NULL = auto).  Returns 0 for an invalid shape.  Never more than a few MB. */
+size_t rap_decode_attn_workspace_bytes(const rap_shape_t* shape, int64_t max_seq_len,
+                                       const rap_tuning_t* tuning);
+
+/* GQA decode attention of one new token per sequence over the compact cache.
+ *
+ * Paper: Eq. (attn) and the GQA remark under it; Eq. (latent-score) (scores are taken between
+ * the pruned, rotated query and K_latent); Sec. "Step 3" (the caller chooses the softmax scale;
+ * the paper keeps 1/sqrt(D)).
+ *
+ * For every b, query head a (KV head h = a / G), over rows i < seq_lens[b]:
+ *   s_i = scale * sum_c q[b][a][c] * k_cache[b][h][i][c]
+ *   out[b][a][:] = sum_i softmax(s)_i * v_cache[b][h][i][:]
+ * Long sequences are cut into row ranges handled by different workgroups (running max / sum /
+ * accumulator per range) and combined by a second kernel; the result does not depend on the cut
+ * beyond fp32 rounding.
+ *
+ *   q          dev  bf16  [batch, n_q_heads, 2P]  pruned and already rotated at its position
+ *   seq_lens   dev  int32 [batch]  rows attended, includes the token just appended;
+ *                                   0 gives a zero output row; values above max_seq_len are
+ *                                   clamped to max_seq_len on the device
+ *   max_seq_len host: upper bound on seq_lens, sizes the grid; 1 <= max_seq_len <= cache_cap
+ *   out        dev  fp32  [batch, n_q_heads, d_v]
+ *   workspace  dev, at least rap_decode_attn_workspace_bytes(shape, max_seq_len, tuning) bytes,
+ *              256-byte aligned; contents before and after the call are unspecified
+ * Cache rows at or beyond seq_lens[b] are never used in the result, whatever bits they hold.
+ */
+rap_status_t rap_decode_attn(const rap_shape_t* shape, const void* q,
+                             const void* k_cache, const void* v_cache,
+                             const int32_t* seq_lens, int64_t max_seq_len,
+                             void* out, float scale,
+                             void* workspace, size_t workspace_bytes,
+                             const rap_tuning_t* tuning, void* stream);
+
+/* Measurement aids (not part of the method): a read-only streaming pass over `bytes` bytes of
+ * `src` (16-byte aligned, bytes % 16 == 0) that folds everything into 16 bytes at `sink`, and a
+ * plain copy of `bytes` bytes.  They give the bandwidth a trivial kernel reaches on the same
+ * device and calibrate hardware byte counters.  Both are dev pointers. */
+rap_status_t rap_stream_read(const void* src, size_t bytes, void* sink, void* stream);
+rap_status_t rap_stream_copy(void* dst, const void* src, size_t bytes, void* stream);
+
+/* Static string for a status code. */
+const char* rap_status_str(rap_status_t status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int32_t rap_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAP_H_ */

@@ -1,0 +1,161 @@
+"""ctypes binding of librap.so (argument marshalling only; see include/rap.h for the contract)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "librap.so")
+
+
+class RapError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__("librap: %s (status %d)" % (text, status))
+        self.status = status
+
+
+class RapShape(C.Structure):
+    """Mirror of rap_shape_t."""
+    _fields_ = [
+        ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("d_head", C.c_int32),
+        ("n_pairs", C.c_int32), ("d_v", C.c_int32), ("cache_cap", C.c_int64), ("rope_theta", C.c_double),
+    ]
+
+
+class RapTuning(C.Structure):
+    """Mirror of rap_tuning_t."""
+    _fields_ = [
+        ("kernel", C.c_int32), ("rows_per_split", C.c_int32), ("reserved0", C.c_int32), ("reserved1", C.c_int32),
+        ("ev_main_start", C.c_void_p), ("ev_main_stop", C.c_void_p),
+    ]
+
+
+KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
+
+STATUS = {0: "RAP_OK", 1: "RAP_ERR_NULL", 2: "RAP_ERR_SHAPE", 3: "RAP_ERR_UNSUPPORTED", 4: "RAP_ERR_CAPACITY",
+          5: "RAP_ERR_WORKSPACE", 6: "RAP_ERR_HIP"}
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None, name="tensor") -> C.c_void_p:
+    if t is None:
+        return C.c_void_p(0)
+    if not t.is_cuda:
+        raise ValueError("%s must live on the GPU" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        if not torch.cuda.is_available():     # host-only argument checks: nothing will be launched
+            return C.c_void_p(0)
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+class Rap:
+    """The loaded library.  Method names are the C entry points."""
+
+    def __init__(self, path: Optional[str] = None):
+        path = path or library_path()
+        if not os.path.exists(path):
+            raise RapError(-1, "%s is missing: build it with `python -m paper_2602_02599_amd.build` "
+                               "(or __graft_entry__.build()); there is no fallback path" % path)
+        self.path = path
+        self.lib = C.CDLL(path)
+        L = self.lib
+        L.rap_rope_append.restype = C.c_int
+        L.rap_rope_append.argtypes = [C.POINTER(RapShape), C.c_int32] + [C.c_void_p] * 7
+        L.rap_decode_attn_workspace_bytes.restype = C.c_size_t
+        L.rap_decode_attn_workspace_bytes.argtypes = [C.POINTER(RapShape), C.c_int64, C.POINTER(RapTuning)]
+        L.rap_decode_attn.restype = C.c_int
+        L.rap_decode_attn.argtypes = [C.POINTER(RapShape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                      C.c_void_p, C.c_float, C.c_void_p, C.c_size_t, C.POINTER(RapTuning), C.c_void_p]
+        L.rap_stream_read.restype = C.c_int
+        L.rap_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        L.rap_stream_copy.restype = C.c_int
+        L.rap_stream_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.rap_status_str.restype = C.c_char_p
+        L.rap_status_str.argtypes = [C.c_int]
+        L.rap_version.restype = C.c_int32
+        L.rap_version.argtypes = []
+
+    # -- helpers
+    def _check(self, status: int):
+        if status != 0:
+            raise RapError(status, self.lib.rap_status_str(status).decode())
+
+    def rap_status_str(self, status: int) -> str:
+        return self.lib.rap_status_str(status).decode()
+
+    def rap_version(self) -> int:
+        return int(self.lib.rap_version())
+
+    @staticmethod
+    def shape(batch, n_q_heads, n_kv_heads, d_head, n_pairs, d_v, cache_cap, rope_theta) -> RapShape:
+        return RapShape(batch, n_q_heads, n_kv_heads, d_head, n_pairs, d_v, cache_cap, rope_theta)
+
+    @staticmethod
+    def tuning(kernel=0, rows_per_split=0, ev_main_start=None, ev_main_stop=None) -> RapTuning:
+        return RapTuning(kernel, rows_per_split, 0, 0, ev_main_start, ev_main_stop)
+
+    # -- entry points
+    def rap_rope_append(self, shape: RapShape, n_new: int, k_new, v_new, pos, keep_pair_idx, k_cache, v_cache,
+                        stream=None, check=True) -> int:
+        st = self.lib.rap_rope_append(C.byref(shape), n_new, _ptr(k_new, torch.bfloat16, "k_new"),
+                                      _ptr(v_new, torch.bfloat16, "v_new"), _ptr(pos, torch.int32, "pos"),
+                                      _ptr(keep_pair_idx, torch.int32, "keep_pair_idx"),
+                                      _ptr(k_cache, torch.bfloat16, "k_cache"), _ptr(v_cache, torch.bfloat16, "v_cache"),
+                                      _stream(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def rap_decode_attn_workspace_bytes(self, shape: RapShape, max_seq_len: int, tuning: Optional[RapTuning] = None) -> int:
+        return int(self.lib.rap_decode_attn_workspace_bytes(C.byref(shape), max_seq_len,
+                                                            C.byref(tuning) if tuning is not None else None))
+
+    def rap_decode_attn(self, shape: RapShape, q, k_cache, v_cache, seq_lens, max_seq_len: int, out, scale: float,
+                        workspace=None, tuning: Optional[RapTuning] = None, stream=None, check=True) -> int:
+        st = self.lib.rap_decode_attn(C.byref(shape), _ptr(q, torch.bfloat16, "q"), _ptr(k_cache, torch.bfloat16, "k_cache"),
+                                      _ptr(v_cache, torch.bfloat16, "v_cache"), _ptr(seq_lens, torch.int32, "seq_lens"),
+                                      max_seq_len, _ptr(out, torch.float32, "out"), scale,
+                                      _ptr(workspace, None, "workspace"),
+                                      0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                      C.byref(tuning) if tuning is not None else None, _stream(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def rap_stream_read(self, src, sink, stream=None):
+        self._check(self.lib.rap_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream)))
+
+    def rap_stream_copy(self, dst, src, stream=None):
+        self._check(self.lib.rap_stream_copy(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream(stream)))
+
+    # -- convenience on top of the entry points (allocation of scratch and output only)
+    def new_workspace(self, shape: RapShape, max_seq_len: int, tuning=None, device="cuda") -> torch.Tensor:
+        n = self.rap_decode_attn_workspace_bytes(shape, max_seq_len, tuning)
+        if n == 0:
+            raise RapError(2, "workspace query rejected the shape")
+        return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+_LOADED: Optional[Rap] = None
+
+
+def load(path: Optional[str] = None) -> Rap:
+    """Load librap.so (once).  Raises RapError if it has not been built."""
+    global _LOADED
+    if _LOADED is None or (path is not None and path != _LOADED.path):
+        _LOADED = Rap(path)
+    return _LOADED

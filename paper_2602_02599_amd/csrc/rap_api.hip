@@ -1,0 +1,200 @@
+// C ABI of librap: host-side validation, split planning and kernel dispatch.  See include/rap.h
+// for the contract of every entry point.
+#include <math.h>
+#include <string.h>
+
+#include "../../include/rap.h"
+#include "rap_device.h"
+
+namespace rap {
+hipError_t launch_append(const AppendArgs& a, hipStream_t stream);
+hipError_t launch_decode_valu(const DecodeArgs& a, hipStream_t stream);
+hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t stream);
+hipError_t launch_merge(const DecodeArgs& a, hipStream_t stream);
+hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t stream);
+hipError_t launch_stream_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
+int mfma_lds_wave_bytes(int d_k, int d_v);
+int mfma_fast_rows(int d_k, int d_v);
+}  // namespace rap
+
+namespace {
+
+constexpr int kCUs = 256;   // MI355X
+
+rap_status_t check_shape(const rap_shape_t* s) {
+  if (!s) return RAP_ERR_NULL;
+  if (s->batch < 0 || s->n_q_heads <= 0 || s->n_kv_heads <= 0 || s->d_head <= 0 || (s->d_head & 1) ||
+      s->n_pairs <= 0 || s->d_v <= 0 || s->cache_cap <= 0 || !(s->rope_theta > 0.0))
+    return RAP_ERR_SHAPE;
+  if (s->n_q_heads % s->n_kv_heads != 0) return RAP_ERR_SHAPE;
+  if (s->n_pairs > s->d_head / 2) return RAP_ERR_SHAPE;
+  if (s->cache_cap % 8 != 0) return RAP_ERR_SHAPE;
+  if (s->n_pairs > rap::kMaxPairs || s->d_v > rap::kMaxDv || s->n_q_heads / s->n_kv_heads > rap::kMaxGroup)
+    return RAP_ERR_UNSUPPORTED;
+  if (s->cache_cap > 0x7fffffffLL - 1024 || s->batch > 65535 || s->n_kv_heads > 65535) return RAP_ERR_UNSUPPORTED;
+  return RAP_OK;
+}
+
+struct Plan {
+  int rows_per_split;
+  int n_split;
+  int kernel;   // 1 vector ALU, 2 matrix core
+};
+
+// Row range per workgroup.  The grid is (n_split, H_kv, B); a workgroup whose range starts at or
+// beyond its sequence's length exits at once, so ragged batches cost only empty launches.  The
+// automatic choice aims at a few workgroups per compute unit in total, and never cuts finer than
+// kSplitQuantum rows.
+rap_status_t make_plan(const rap_shape_t* s, int64_t max_seq_len, const rap_tuning_t* t, Plan* p) {
+  int rps = t ? t->rows_per_split : 0;
+  if (rps < 0 || (rps % rap::kSplitQuantum) != 0) return RAP_ERR_SHAPE;
+  const int kernel = t ? t->kernel : 0;
+  if (kernel < 0 || kernel > 2) return RAP_ERR_SHAPE;
+  if (rps == 0) {
+    const int64_t slabs = static_cast<int64_t>(s->batch) * s->n_kv_heads;
+    const int64_t want_wgs = 8LL * kCUs;                               // target workgroups in flight
+    int64_t per_slab = slabs > 0 ? (want_wgs + slabs - 1) / slabs : 1;  // splits per (b, h)
+    if (per_slab < 1) per_slab = 1;
+    int64_t r = (max_seq_len + per_slab - 1) / per_slab;
+    r = (r + rap::kSplitQuantum - 1) / rap::kSplitQuantum * rap::kSplitQuantum;
+    if (r < 512) r = 512;                                               // at least 4 tiles per wavefront
+    rps = static_cast<int>(r);
+  }
+  p->rows_per_split = rps;
+  p->n_split = static_cast<int>((max_seq_len + rps - 1) / rps);
+  p->kernel = kernel == 0 ? 2 : kernel;
+  return RAP_OK;
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+size_t part_acc_bytes(const rap_shape_t* s, const Plan& p) {
+  return align_up(static_cast<size_t>(s->batch) * s->n_q_heads * p.n_split * s->d_v * sizeof(float), 256);
+}
+size_t part_ml_bytes(const rap_shape_t* s, const Plan& p) {
+  return align_up(static_cast<size_t>(s->batch) * s->n_q_heads * p.n_split * 2 * sizeof(float), 256);
+}
+
+}  // namespace
+
+extern "C" {
+
+rap_status_t rap_rope_append(const rap_shape_t* shape, int32_t n_new, const void* k_new, const void* v_new,
+                             const int32_t* pos, const int32_t* keep_pair_idx, void* k_cache, void* v_cache,
+                             void* stream) {
+  rap_status_t st = check_shape(shape);
+  if (st != RAP_OK) return st;
+  if (n_new < 0) return RAP_ERR_SHAPE;
+  if (n_new == 0 || shape->batch == 0) return RAP_OK;
+  if (!k_new || !v_new || !pos || !keep_pair_idx || !k_cache || !v_cache) return RAP_ERR_NULL;
+  if (static_cast<int64_t>(shape->batch) * n_new > 0x7fffffffLL) return RAP_ERR_UNSUPPORTED;
+  rap::AppendArgs a;
+  a.k_new = static_cast<const uint16_t*>(k_new);
+  a.v_new = static_cast<const uint16_t*>(v_new);
+  a.pos = pos;
+  a.keep = keep_pair_idx;
+  a.k_cache = static_cast<uint16_t*>(k_cache);
+  a.v_cache = static_cast<uint16_t*>(v_cache);
+  a.batch = shape->batch;
+  a.n_new = n_new;
+  a.n_kv = shape->n_kv_heads;
+  a.d_head = shape->d_head;
+  a.n_pairs = shape->n_pairs;
+  a.d_v = shape->d_v;
+  a.cap = shape->cache_cap;
+  a.theta = shape->rope_theta;
+  return rap::launch_append(a, static_cast<hipStream_t>(stream)) == hipSuccess ? RAP_OK : RAP_ERR_HIP;
+}
+
+size_t rap_decode_attn_workspace_bytes(const rap_shape_t* shape, int64_t max_seq_len, const rap_tuning_t* tuning) {
+  if (check_shape(shape) != RAP_OK || max_seq_len < 1 || max_seq_len > shape->cache_cap) return 0;
+  Plan p;
+  if (make_plan(shape, max_seq_len, tuning, &p) != RAP_OK) return 0;
+  return part_acc_bytes(shape, p) + part_ml_bytes(shape, p) + 256;
+}
+
+rap_status_t rap_decode_attn(const rap_shape_t* shape, const void* q, const void* k_cache, const void* v_cache,
+                             const int32_t* seq_lens, int64_t max_seq_len, void* out, float scale, void* workspace,
+                             size_t workspace_bytes, const rap_tuning_t* tuning, void* stream) {
+  rap_status_t st = check_shape(shape);
+  if (st != RAP_OK) return st;
+  if (max_seq_len < 1) return RAP_ERR_SHAPE;
+  if (max_seq_len > shape->cache_cap) return RAP_ERR_CAPACITY;
+  if (shape->batch == 0) return RAP_OK;
+  if (!q || !k_cache || !v_cache || !seq_lens || !out) return RAP_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(k_cache) & 15) || (reinterpret_cast<uintptr_t>(v_cache) & 15) ||
+      (reinterpret_cast<uintptr_t>(q) & 3) || (reinterpret_cast<uintptr_t>(out) & 3))
+    return RAP_ERR_SHAPE;
+  Plan p;
+  st = make_plan(shape, max_seq_len, tuning, &p);
+  if (st != RAP_OK) return st;
+  const size_t need = part_acc_bytes(shape, p) + part_ml_bytes(shape, p) + 256;
+  if (p.n_split > 1) {
+    if (!workspace || workspace_bytes < need) return RAP_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255) return RAP_ERR_WORKSPACE;
+  }
+  if (p.n_split > 65535) return RAP_ERR_UNSUPPORTED;
+
+  rap::DecodeArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = static_cast<const uint16_t*>(q);
+  a.k_cache = static_cast<const uint16_t*>(k_cache);
+  a.v_cache = static_cast<const uint16_t*>(v_cache);
+  a.seq_lens = seq_lens;
+  a.out = static_cast<float*>(out);
+  a.part_acc = static_cast<float*>(workspace);
+  a.part_ml = workspace ? reinterpret_cast<float*>(static_cast<char*>(workspace) + part_acc_bytes(shape, p)) : nullptr;
+  a.batch = shape->batch;
+  a.n_q = shape->n_q_heads;
+  a.n_kv = shape->n_kv_heads;
+  a.group = shape->n_q_heads / shape->n_kv_heads;
+  a.n_pairs = shape->n_pairs;
+  a.d_k = 2 * shape->n_pairs;
+  a.d_v = shape->d_v;
+  a.max_len = static_cast<int32_t>(max_seq_len);
+  a.rows_per_split = p.rows_per_split;
+  a.n_split = p.n_split;
+  a.cap = shape->cache_cap;
+  a.scale_log2e = scale * 1.4426950408889634f;
+  a.lds_wave_bytes = rap::mfma_lds_wave_bytes(a.d_k, a.d_v);
+  a.fast_rows = rap::mfma_fast_rows(a.d_k, a.d_v);
+
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (tuning && tuning->ev_main_start && hipEventRecord(static_cast<hipEvent_t>(tuning->ev_main_start), s) != hipSuccess)
+    return RAP_ERR_HIP;
+  hipError_t e = p.kernel == 1 ? rap::launch_decode_valu(a, s) : rap::launch_decode_mfma(a, s);
+  if (e != hipSuccess) return RAP_ERR_HIP;
+  if (tuning && tuning->ev_main_stop && hipEventRecord(static_cast<hipEvent_t>(tuning->ev_main_stop), s) != hipSuccess)
+    return RAP_ERR_HIP;
+  if (p.n_split > 1 && rap::launch_merge(a, s) != hipSuccess) return RAP_ERR_HIP;
+  return RAP_OK;
+}
+
+rap_status_t rap_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
+  if (!src || !sink) return RAP_ERR_NULL;
+  if ((bytes & 15) || (reinterpret_cast<uintptr_t>(src) & 15) || (reinterpret_cast<uintptr_t>(sink) & 15)) return RAP_ERR_SHAPE;
+  return rap::launch_stream_read(src, bytes, sink, static_cast<hipStream_t>(stream)) == hipSuccess ? RAP_OK : RAP_ERR_HIP;
+}
+
+rap_status_t rap_stream_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!src || !dst) return RAP_ERR_NULL;
+  if ((bytes & 15) || (reinterpret_cast<uintptr_t>(src) & 15) || (reinterpret_cast<uintptr_t>(dst) & 15)) return RAP_ERR_SHAPE;
+  return rap::launch_stream_copy(dst, src, bytes, static_cast<hipStream_t>(stream)) == hipSuccess ? RAP_OK : RAP_ERR_HIP;
+}
+
+const char* rap_status_str(rap_status_t status) {
+  switch (status) {
+    case RAP_OK: return "ok";
+    case RAP_ERR_NULL: return "null pointer";
+    case RAP_ERR_SHAPE: return "inconsistent shape or argument";
+    case RAP_ERR_UNSUPPORTED: return "shape outside the supported range";
+    case RAP_ERR_CAPACITY: return "max_seq_len exceeds cache capacity";
+    case RAP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case RAP_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+int32_t rap_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,340 @@
+// Matrix-core decode attention over the compact cache: the default kernel of rap_decode_attn.
+//
+// Eq. (attn) with the GQA remark, evaluated as online softmax over tiles of 32 cache rows.
+// The path is bound by HBM: every K and V byte is needed exactly once per decode step, and the
+// arithmetic (G flop per cache byte) is small.  The design therefore serves one goal, keeping many
+// large, perfectly coalesced reads in flight per compute unit with as few instructions as possible
+// around them:
+//
+//  * Each wavefront is autonomous.  It owns every fourth 32-row tile of its workgroup's row range,
+//    streams the tile's K bytes and V bytes as two flat, 16-byte-aligned runs (row widths such as
+//    180, 232 or 230 bytes are not multiples of 16, but 8 rows of any width are), holds the next
+//    tile in registers while it works on the current one, and parks the current one in its private
+//    slice of LDS.  There is no barrier in the main loop.
+//  * Scores: S^T[row][g] = K_tile[row][:] . q[g][:] on v_mfma_f32_16x16x32_bf16 with the K tile as
+//    the A operand (a lane reads 16 bytes of one row from LDS) and the G query rows, zero-padded to
+//    16, resident in registers as the B operand.  bf16 products are exact in fp32.
+//  * The result layout of that instruction (lane = query head, 4 registers = 4 rows per 16-lane
+//    group) is exactly the A-operand layout of v_mfma_f32_16x16x4_f32, so after the exponential
+//    the probabilities feed P.V without any data movement, in fp32.  The V element each lane needs
+//    (row = contraction index, channel = lane) is a 2-byte LDS read: the "transpose" that a
+//    row-major V needs for a matrix instruction costs nothing but LDS address bits.
+//  * The vector ALU only scales, exponentiates and sums eight scores per lane per tile; the
+//    accumulators are rescaled only when a running maximum actually moves.
+//
+// Garbage safety: rows at or beyond the sequence length may hold any bits.  Their scores are
+// replaced by -inf (a select, not arithmetic), their V reads are redirected to the last valid row
+// of the tile, and the part of a K fragment beyond d_k is masked to zero, so nothing read outside
+// the valid rows can reach a result.
+#include "rap_device.h"
+
+namespace rap {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int kTileRows = 32;
+
+__device__ __forceinline__ void wave_lds_sync() {
+  // LDS operations of one wavefront execute in order; this only stops the compiler from moving
+  // LDS accesses of different lanes across the hand-over point.
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int KCH, int NT>
+__global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeArgs a) {
+  constexpr int NLD_K = 2 * KCH;   // 1 KB wave-loads covering a K tile (d_k <= 32 KCH)
+  constexpr int NLD_V = NT;        // same for a V tile (d_v <= 16 NT)
+  extern __shared__ __align__(16) unsigned char smem[];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int l16 = lane & 15;
+  const int lg = lane >> 4;
+  const int split = blockIdx.x;
+  const int h = blockIdx.y;
+  const int b = blockIdx.z;
+
+  int len = a.seq_lens[b];
+  len = len < 0 ? 0 : (len > a.max_len ? a.max_len : len);
+  const int r0 = split * a.rows_per_split;
+  if (r0 >= len && !(split == 0 && a.n_split == 1)) return;
+  const int r1 = min(r0 + a.rows_per_split, len);
+  const int len8 = (len + 7) & ~7;                 // <= cache_cap: rows below it are readable
+
+  const int G = a.group;
+  const int dk = a.d_k, dv = a.d_v;
+  const int pitch_k = 2 * dk, pitch_v = 2 * dv;    // bytes
+  // LDS slice of this wavefront: K area and V area, each a whole number of 1 KB wave-stores
+  unsigned char* kt = smem + wave * a.lds_wave_bytes;
+  unsigned char* vt = kt + 1024 * NLD_K;
+
+  const long long slab = static_cast<long long>(b) * a.n_kv + h;
+  const unsigned char* kslab = reinterpret_cast<const unsigned char*>(a.k_cache) + slab * a.cap * pitch_k;
+  const unsigned char* vslab = reinterpret_cast<const unsigned char*>(a.v_cache) + slab * a.cap * pitch_v;
+
+  // ---- query rows as the B operand: lane (l16 = head slot, lg = k sub-chunk)
+  bf16x8 qf[KCH];
+  {
+    const uint32_t* qrow = reinterpret_cast<const uint32_t*>(a.q) +
+                           (static_cast<long long>(b) * a.n_q + h * G + (l16 < G ? l16 : 0)) * a.n_pairs;
+#pragma unroll
+    for (int kk = 0; kk < KCH; ++kk) {
+      uint32_t w[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int e = 32 * kk + 8 * lg + 2 * i;
+        w[i] = (l16 < G && e < dk) ? qrow[e >> 1] : 0u;
+      }
+      qf[kk] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+    }
+  }
+  // mask of the last K fragment (elements at or beyond d_k belong to the next row)
+  uint32_t kmask[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) kmask[i] = (32 * (KCH - 1) + 8 * lg + 2 * i) < dk ? 0xffffffffu : 0u;
+
+  // LDS byte offsets of this lane's operands inside a tile
+  int koff[2];
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt) koff[rt] = (16 * rt + l16) * pitch_k + 16 * lg;
+  int voff[2][4];
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) voff[rt][r] = (16 * rt + 4 * lg + r) * pitch_v + 2 * l16;
+
+  f32x4 acc[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY;
+  float l_run = 0.f;
+
+  uint4 kst[NLD_K], vst[NLD_V];
+#pragma unroll
+  for (int j = 0; j < NLD_K; ++j) kst[j] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+  for (int j = 0; j < NLD_V; ++j) vst[j] = make_uint4(0, 0, 0, 0);
+
+  auto issue_loads = [&](int base) {
+    const unsigned char* kg = kslab + static_cast<long long>(base) * pitch_k + 16 * lane;
+    const unsigned char* vg = vslab + static_cast<long long>(base) * pitch_v + 16 * lane;
+    if (base + a.fast_rows <= len8) {
+      // common case: the whole 1 KB-granular run, including what spills past the tile's last
+      // row (fewer than 1024 bytes), lies below row len8 and is readable
+#pragma unroll
+      for (int j = 0; j < NLD_K; ++j) kst[j] = *reinterpret_cast<const uint4*>(kg + 1024 * j);
+#pragma unroll
+      for (int j = 0; j < NLD_V; ++j) vst[j] = *reinterpret_cast<const uint4*>(vg + 1024 * j);
+    } else {
+      // last tiles of a sequence: read only rows [base, len8), chunk by chunk
+      const int rows = min(kTileRows, len8 - base);   // multiple of 8
+      const int kval = rows * pitch_k, vval = rows * pitch_v;
+#pragma unroll
+      for (int j = 0; j < NLD_K; ++j)
+        if (1024 * j + 16 * lane < kval) kst[j] = *reinterpret_cast<const uint4*>(kg + 1024 * j);
+#pragma unroll
+      for (int j = 0; j < NLD_V; ++j)
+        if (1024 * j + 16 * lane < vval) vst[j] = *reinterpret_cast<const uint4*>(vg + 1024 * j);
+    }
+  };
+
+  const int first = r0 + kTileRows * wave;
+  if (first < r1) issue_loads(first);
+
+  for (int base = first; base < r1; base += 4 * kTileRows) {
+    // ---- park the staged tile in LDS, start fetching the next one
+    wave_lds_sync();
+#pragma unroll
+    for (int j = 0; j < NLD_K; ++j) *reinterpret_cast<uint4*>(kt + 1024 * j + 16 * lane) = kst[j];
+#pragma unroll
+    for (int j = 0; j < NLD_V; ++j) *reinterpret_cast<uint4*>(vt + 1024 * j + 16 * lane) = vst[j];
+    wave_lds_sync();
+    if (base + 4 * kTileRows < r1) issue_loads(base + 4 * kTileRows);
+
+    // ---- scores: sc[rt][r] = q[g = l16] . K[base + 16 rt + 4 lg + r]
+    f32x4 sc[2];
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) {
+      sc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < KCH; ++kk) {
+        const uint32_t* p = reinterpret_cast<const uint32_t*>(kt + koff[rt] + 64 * kk);
+        uint4 w = make_uint4(p[0], p[1], p[2], p[3]);
+        if (kk == KCH - 1) {
+          w.x &= kmask[0];
+          w.y &= kmask[1];
+          w.z &= kmask[2];
+          w.w &= kmask[3];
+        }
+        sc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), qf[kk], sc[rt], 0, 0, 0);
+      }
+    }
+
+    // ---- online softmax (log2 units)
+    const int nv = min(kTileRows, r1 - base);       // valid rows in this tile, >= 1
+    float x[2][4];
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float s = sc[rt][r] * a.scale_log2e;
+        x[rt][r] = (16 * rt + 4 * lg + r) < nv ? s : -INFINITY;
+        tmax = fmaxf(tmax, x[rt][r]);
+      }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+    const float m_new = fmaxf(m_run, tmax);
+    if (__any(m_new > m_run)) {
+      const float alpha = exp2f(m_run - m_new);      // first tile: 2^-inf = 0
+      l_run *= alpha;
+#pragma unroll
+      for (int reg = 0; reg < 4; ++reg) {
+        const float at = __shfl(alpha, 4 * lg + reg);   // the head this accumulator register holds
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[nt][reg] *= at;
+      }
+      m_run = m_new;
+    }
+    float pr[2][4];
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        pr[rt][r] = exp2f(x[rt][r] - m_run);
+        l_run += pr[rt][r];
+      }
+
+    // ---- P.V: acc[nt][reg] (head 4 lg + reg, channel 16 nt + l16) += p . V
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int row = min(16 * rt + 4 * lg + r, nv - 1);
+        const unsigned char* vp = vt + (nv == kTileRows ? voff[rt][r] : row * pitch_v + 2 * l16);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          const uint32_t raw = *reinterpret_cast<const uint16_t*>(vp + 32 * nt);
+          acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(pr[rt][r], __uint_as_float(raw << 16), acc[nt], 0, 0, 0);
+        }
+      }
+  }
+
+  // ---- fold lane groups, then the four wavefronts, through LDS
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+  __syncthreads();                                   // every wavefront is done with its tile area
+  float* wm = reinterpret_cast<float*>(smem + wave * a.lds_wave_bytes);   // [16] max, [16] sum, [8][16 NT] acc
+  if (lg == 0) {
+    wm[l16] = m_run;
+    wm[16 + l16] = l_run;
+  }
+#pragma unroll
+  for (int reg = 0; reg < 4; ++reg) {
+    const int g = 4 * lg + reg;
+    if (g < kMaxGroup) {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) wm[32 + g * (16 * NT) + 16 * nt + l16] = acc[nt][reg];
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < G * dv; e += 256) {
+    const int g = e / dv, c = e - g * dv;
+    float mw[4], mstar = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      mw[w] = reinterpret_cast<const float*>(smem + w * a.lds_wave_bytes)[g];
+      mstar = fmaxf(mstar, mw[w]);
+    }
+    float num = 0.f, den = 0.f;
+    if (mstar > -INFINITY) {
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float* pw = reinterpret_cast<const float*>(smem + w * a.lds_wave_bytes);
+        const float wt = exp2f(mw[w] - mstar);
+        den = fmaf(wt, pw[16 + g], den);
+        num = fmaf(wt, pw[32 + g * (16 * NT) + c], num);
+      }
+    }
+    const long long hq = static_cast<long long>(b) * a.n_q + h * G + g;
+    if (a.n_split == 1) {
+      a.out[hq * dv + c] = den > 0.f ? num / den : 0.f;
+    } else {
+      a.part_acc[(hq * a.n_split + split) * dv + c] = num;
+      if (c == 0) {
+        a.part_ml[(hq * a.n_split + split) * 2 + 0] = mstar;
+        a.part_ml[(hq * a.n_split + split) * 2 + 1] = den;
+      }
+    }
+  }
+}
+
+template <int KCH, int NT>
+hipError_t launch_inst(const DecodeArgs& a, hipStream_t stream) {
+  dim3 grid(a.n_split, a.n_kv, a.batch), block(256);
+  const size_t lds = 4 * static_cast<size_t>(a.lds_wave_bytes);
+  if (lds > 64 * 1024) {
+    // more than the default dynamic-LDS limit: raise it once per kernel (gfx950 has 160 KB per CU)
+    static int raised_to = 0;
+    if (raised_to < static_cast<int>(lds)) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_mfma_kernel<KCH, NT>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+      if (e != hipSuccess) return e;
+      raised_to = static_cast<int>(lds);
+    }
+  }
+  hipLaunchKernelGGL((decode_mfma_kernel<KCH, NT>), grid, block, lds, stream, a);
+  return hipGetLastError();
+}
+
+template <int KCH>
+hipError_t launch_k(const DecodeArgs& a, hipStream_t stream) {
+  switch ((a.d_v + 15) / 16) {
+    case 1: return launch_inst<KCH, 1>(a, stream);
+    case 2: return launch_inst<KCH, 2>(a, stream);
+    case 3: return launch_inst<KCH, 3>(a, stream);
+    case 4: return launch_inst<KCH, 4>(a, stream);
+    case 5: return launch_inst<KCH, 5>(a, stream);
+    case 6: return launch_inst<KCH, 6>(a, stream);
+    case 7: return launch_inst<KCH, 7>(a, stream);
+    case 8: return launch_inst<KCH, 8>(a, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+// LDS bytes one wavefront needs: its K tile, its V tile and slack for the fragment reads that run
+// past the last row, or the hand-over area of the final fold, whichever is larger.
+int mfma_lds_wave_bytes(int d_k, int d_v) {
+  const int nt = (d_v + 15) / 16;
+  const int tiles = 1024 * (2 * ((d_k + 31) / 32) + nt) + 128;
+  const int fold = (32 + kMaxGroup * 16 * nt) * 4;
+  const int need = tiles > fold ? tiles : fold;
+  return (need + 127) / 128 * 128;
+}
+
+// Rows, counted from a tile's first row, that the whole-KB loads of a tile reach into.
+int mfma_fast_rows(int d_k, int d_v) {
+  const int kb = 1024 * 2 * ((d_k + 31) / 32), vb = 1024 * ((d_v + 15) / 16);
+  const int kr = (kb + 2 * d_k - 1) / (2 * d_k), vr = (vb + 2 * d_v - 1) / (2 * d_v);
+  return kr > vr ? kr : vr;
+}
+
+hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t stream) {
+  switch ((a.d_k + 31) / 32) {
+    case 1: return launch_k<1>(a, stream);
+    case 2: return launch_k<2>(a, stream);
+    case 3: return launch_k<3>(a, stream);
+    case 4: return launch_k<4>(a, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace rap

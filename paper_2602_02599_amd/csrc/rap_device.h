@@ -1,0 +1,63 @@
+// Shared device-side helpers and the argument blocks of the librap kernels (gfx950 only).
+#ifndef RAP_DEVICE_H_
+#define RAP_DEVICE_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rap {
+
+constexpr int kWave = 64;            // CDNA wavefront width
+constexpr int kMaxPairs = 64;        // P <= 64  (d_k <= 128)
+constexpr int kMaxDv = 128;
+constexpr int kMaxGroup = 8;
+constexpr int kSplitQuantum = 128;   // rows_per_split granularity
+
+// bf16 bit pattern -> fp32 (a bf16 is the upper half of a binary32)
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
+
+// fp64 -> bf16 with a single round-to-nearest-even: truncate to fp32 keeping a sticky bit
+// (round-to-odd), then round the fp32 to its upper 16 bits.
+__device__ __forceinline__ uint16_t f64_to_bf16_rne(double x) {
+  float f = __double2float_rz(x);
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7f800000u) == 0x7f800000u) {                 // inf / nan pass through
+    return static_cast<uint16_t>((u >> 16) | ((u & 0xffffu) ? 0x40u : 0u));
+  }
+  if (static_cast<double>(f) != x) u |= 1u;                // sticky
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<uint16_t>(u >> 16);
+}
+
+struct AppendArgs {
+  const uint16_t* k_new;
+  const uint16_t* v_new;
+  const int32_t* pos;
+  const int32_t* keep;
+  uint16_t* k_cache;
+  uint16_t* v_cache;
+  int32_t batch, n_new, n_kv, d_head, n_pairs, d_v;
+  int64_t cap;
+  double theta;
+};
+
+struct DecodeArgs {
+  const uint16_t* q;
+  const uint16_t* k_cache;
+  const uint16_t* v_cache;
+  const int32_t* seq_lens;
+  float* out;          // [B, H_q, d_v]
+  float* part_acc;     // [B, H_q, n_split, d_v]   un-normalised accumulators
+  float* part_ml;      // [B, H_q, n_split, 2]     (running max in log2 units, running sum)
+  int32_t batch, n_q, n_kv, group, n_pairs, d_k, d_v;
+  int32_t max_len, rows_per_split, n_split;
+  int32_t lds_wave_bytes;   // matrix-core kernel: LDS slice of one wavefront
+  int32_t fast_rows;        // matrix-core kernel: rows from a tile's base that its 1 KB-granular loads touch
+  int64_t cap;
+  float scale_log2e;   // softmax scale * log2(e): exponentials are taken as exp2
+};
+
+}  // namespace rap
+#endif  // RAP_DEVICE_H_

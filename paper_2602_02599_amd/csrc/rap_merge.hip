@@ -1,0 +1,39 @@
+// Second stage of split decode attention: combine the per-range partials of one query head.
+//
+// A range s leaves (m_s, l_s, acc_s[d_v]) with m_s the running maximum of the scaled scores in
+// log2 units, l_s = sum_i 2^(x_i - m_s) and acc_s = sum_i 2^(x_i - m_s) V[i].  Softmax over the
+// whole sequence is then
+//   out = sum_s 2^(m_s - m*) acc_s / sum_s 2^(m_s - m*) l_s,   m* = max_s m_s,
+// which is Eq. (attn) regrouped by row ranges.  Only the ranges that hold rows of this sequence
+// (ceil(len / rows_per_split) of them) were written by the first stage and only those are read.
+#include "rap_device.h"
+
+namespace rap {
+
+__global__ __launch_bounds__(128) void merge_kernel(DecodeArgs a) {
+  const long long hq = blockIdx.x;                 // b * n_q + query head
+  const int b = static_cast<int>(hq / a.n_q);
+  const int c = threadIdx.x;
+  int len = a.seq_lens[b];
+  len = len < 0 ? 0 : (len > a.max_len ? a.max_len : len);
+  const int n = (len + a.rows_per_split - 1) / a.rows_per_split;
+  const float* ml = a.part_ml + hq * a.n_split * 2;
+  const float* acc = a.part_acc + hq * a.n_split * a.d_v;
+  float mstar = -INFINITY;
+  for (int s = 0; s < n; ++s) mstar = fmaxf(mstar, ml[2 * s]);
+  float den = 0.f, num = 0.f;
+  for (int s = 0; s < n; ++s) {
+    const float w = exp2f(ml[2 * s] - mstar);
+    den = fmaf(w, ml[2 * s + 1], den);
+    if (c < a.d_v) num = fmaf(w, acc[static_cast<long long>(s) * a.d_v + c], num);
+  }
+  if (c < a.d_v) a.out[hq * a.d_v + c] = n > 0 ? num / den : 0.f;
+}
+
+hipError_t launch_merge(const DecodeArgs& a, hipStream_t stream) {
+  dim3 grid(static_cast<unsigned>(a.batch) * a.n_q), block(128);
+  hipLaunchKernelGGL(merge_kernel, grid, block, 0, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace rap

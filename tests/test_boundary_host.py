@@ -1,0 +1,83 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared symbol, and rejects
+bad arguments before launching anything.  No kernel runs here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2602_02599_amd as pkg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def rap():
+    if not os.path.exists(pkg.library_path()):
+        import __graft_entry__
+        __graft_entry__.build()
+    return pkg.load()
+
+
+def test_every_declared_symbol_is_exported(rap):
+    text = open(os.path.join(ROOT, "include", "rap.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(rap_[a-z_0-9]+)\s*\(", text))
+    assert {"rap_rope_append", "rap_decode_attn", "rap_decode_attn_workspace_bytes", "rap_status_str"} <= names
+    for n in names:
+        assert hasattr(rap.lib, n), n
+
+
+def test_struct_layout_matches_header():
+    assert C.sizeof(pkg.RapShape) == 40
+    assert pkg.RapShape.cache_cap.offset == 24 and pkg.RapShape.rope_theta.offset == 32
+    assert C.sizeof(pkg.RapTuning) == 32 and pkg.RapTuning.ev_main_start.offset == 16
+
+
+def test_status_strings(rap):
+    assert rap.rap_status_str(0) == "ok"
+    assert len({rap.rap_status_str(i) for i in range(7)}) == 7
+    assert rap.rap_version() >= 100
+
+
+def _shape(rap, **kw):
+    d = dict(batch=2, n_q_heads=8, n_kv_heads=2, d_head=128, n_pairs=45, d_v=90, cache_cap=512, rope_theta=5e5)
+    d.update(kw)
+    return rap.shape(**d)
+
+
+def test_append_rejects_bad_arguments(rap):
+    f = lambda shp, n=1: rap.rap_rope_append(shp, n, None, None, None, None, None, None, check=False)
+    assert f(_shape(rap)) == 1                                   # null pointers
+    assert f(_shape(rap), n=0) == 0                              # nothing to do
+    assert f(_shape(rap, batch=0)) == 0
+    assert f(_shape(rap, n_q_heads=7)) == 2                      # G not integral
+    assert f(_shape(rap, n_pairs=65)) == 2                       # P > D/2
+    assert f(_shape(rap, cache_cap=510)) == 2                    # cap % 8
+    assert f(_shape(rap, rope_theta=0.0)) == 2
+    assert f(_shape(rap, d_head=256, n_pairs=100)) == 3          # consistent but not built
+    assert f(_shape(rap, d_v=200)) == 3
+    assert f(_shape(rap, n_q_heads=32, n_kv_heads=2)) == 3       # G = 16
+    assert f(_shape(rap), n=-1) == 2
+
+
+def test_decode_rejects_bad_arguments(rap):
+    f = lambda shp, msl=512, tun=None: rap.rap_decode_attn(shp, None, None, None, None, msl, None, 0.1, None, tun, check=False)
+    assert f(_shape(rap)) == 1
+    assert f(_shape(rap), msl=513) == 4                          # beyond capacity
+    assert f(_shape(rap), msl=0) == 2
+    assert f(_shape(rap, n_q_heads=7)) == 2
+    assert f(_shape(rap, batch=0)) == 0
+    assert rap.rap_decode_attn_workspace_bytes(_shape(rap), 512) > 0
+    assert rap.rap_decode_attn_workspace_bytes(_shape(rap), 513) == 0
+    assert rap.rap_decode_attn_workspace_bytes(_shape(rap, cache_cap=7), 4) == 0
+    assert rap.rap_decode_attn_workspace_bytes(_shape(rap), 512, rap.tuning(rows_per_split=100)) == 0
+    # workspace grows with the number of row ranges
+    a = rap.rap_decode_attn_workspace_bytes(_shape(rap), 512, rap.tuning(rows_per_split=128))
+    b = rap.rap_decode_attn_workspace_bytes(_shape(rap), 512, rap.tuning(rows_per_split=256))
+    assert a > b
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    with pytest.raises(pkg.RapError):
+        pkg.Rap(str(tmp_path / "librap.so"))

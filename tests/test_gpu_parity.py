@@ -1,0 +1,258 @@
+"""GPU parity: librap (through its C ABI) against the float64 oracle on the same seeded inputs.
+
+Bars: appended K rows within 1 bf16 ulp of the oracle's single-rounded row (V rows bit-exact);
+attention outputs max-abs <= 1e-2 and mean-relative (mean |diff| / mean |ref|) <= 1e-3.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rap_oracle as O
+from paper_2602_02599_amd import inputs as I
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+VALU, MFMA = 1, 2
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ append
+
+
+def _check_append(rap, case, what):
+    kc, vc = I.bits(case.k_cache), I.bits(case.v_cache)       # before: filler
+    H.run_append(rap, case)
+    torch.cuda.synchronize()
+    H.oracle_append(case, kc, vc)
+    gk, gv = I.bits(case.k_cache), I.bits(case.v_cache)
+    assert np.array_equal(gv, vc), what + ": V cache differs"
+    dist = H.bf16_ulp_distance(gk, kc)
+    assert dist.max() <= 1, "%s: K row off by %d ulp" % (what, dist.max())
+    return int((dist != 0).sum()), dist.size
+
+
+@pytest.mark.parametrize("P,dv,H_kv,n_new,B", [(45, 90, 8, 5, 3), (58, 115, 2, 1, 2), (32, 64, 8, 4, 1),
+                                              (64, 128, 4, 7, 2), (1, 1, 1, 1, 1), (3, 5, 2, 9, 2)])
+def test_append_small(rap, P, dv, H_kv, n_new, B):
+    w = I.scaled(I.WORKLOADS["cfg2"], batch=B, n_q_heads=H_kv * 2, n_kv_heads=H_kv, n_pairs=P, d_v=dv,
+                 ctx=100 + n_new, n_new=n_new, peaky_frac=0.0, seed=40 + P)
+    _say("append small P=%d dv=%d" % (P, dv))
+    case = I.make_case(w, device=DEV)
+    off, n = _check_append(rap, case, "small")
+    assert off <= n // 1000 + 1          # single rounding from fp64: essentially bit-exact
+
+
+def test_append_cfg1_whole_cache(rap):
+    """cfg1: all 2048 positions of the cache are written through the append call."""
+    _say("append cfg1")
+    case = I.make_case(I.WORKLOADS["cfg1"], device=DEV)
+    off, n = _check_append(rap, case, "cfg1")
+    _say("cfg1 append: %d of %d elements differ (by 1 ulp)" % (off, n))
+    assert off <= n // 1000 + 1
+
+
+@pytest.mark.parametrize("theta", [5.0e5, 1.0e6, 1.0e4])
+def test_append_far_positions(rap, theta):
+    """Positions up to 131071: the angle needs fp64 to stay inside one bf16 ulp."""
+    w = I.scaled(I.WORKLOADS["cfg4"], batch=2, ctx=131072, n_new=6, rope_theta=theta, seed=77)
+    _say("append far theta=%g" % theta)
+    case = I.make_case(w, device=DEV)
+    pos = torch.tensor([[131071, 131066, 99999, 65536, 1, 0], [131070, 77777, 4097, 4096, 12345, 2]], dtype=torch.int32, device=DEV)
+    case.pos = pos
+    off, n = _check_append(rap, case, "far")
+    assert off <= n // 1000 + 1
+
+
+def test_append_skips_out_of_range(rap):
+    w = I.scaled(I.WORKLOADS["cfg2"], batch=1, ctx=64, n_new=3, peaky_frac=0.0, seed=5)
+    case = I.make_case(w, device=DEV)
+    before_k, before_v = I.bits(case.k_cache).copy(), I.bits(case.v_cache).copy()
+    case.pos = torch.tensor([[-1, case.cap, 10]], dtype=torch.int32, device=DEV)
+    H.run_append(rap, case)
+    torch.cuda.synchronize()
+    gk, gv = I.bits(case.k_cache), I.bits(case.v_cache)
+    changed = np.where((gk != before_k).any(axis=(0, 1, 3)))[0]
+    assert list(changed) == [10]
+    assert np.array_equal(np.delete(gv, 10, axis=2), np.delete(before_v, 10, axis=2))
+
+
+# ------------------------------------------------------------------ decode, small shapes
+
+
+def _oracle_out(case):
+    return O.attn_ref(I.bits(case.q), I.bits(case.k_cache), I.bits(case.v_cache), case.seq_lens.cpu().numpy(), case.w.scale)
+
+
+SMALL = [
+    # P, dv, Hq, Hkv, ctx  (several 32-row tiles and a ragged tail)
+    (45, 90, 8, 2, 333), (58, 115, 8, 2, 289), (32, 64, 10, 2, 1000), (64, 128, 8, 2, 515),
+    (45, 90, 6, 2, 31), (45, 90, 2, 2, 1), (3, 5, 3, 1, 77), (10, 7, 16, 2, 130), (51, 102, 4, 1, 257),
+    (38, 77, 12, 2, 640), (64, 128, 1, 1, 96), (17, 33, 7, 1, 200),
+]
+
+
+@pytest.mark.parametrize("kernel", [VALU, MFMA])
+@pytest.mark.parametrize("P,dv,Hq,Hkv,ctx", SMALL)
+def test_decode_small(rap, kernel, P, dv, Hq, Hkv, ctx):
+    w = I.scaled(I.WORKLOADS["cfg2"], batch=3, n_q_heads=Hq, n_kv_heads=Hkv, n_pairs=P, d_v=dv, ctx=ctx, n_new=1,
+                 ragged_min=max(1, ctx // 3), peaky_frac=0.0, seed=900 + P + ctx)
+    _say("decode small kernel=%d P=%d dv=%d Hq=%d Hkv=%d ctx=%d" % (kernel, P, dv, Hq, Hkv, ctx))
+    case = I.make_case(w, device=DEV)
+    ref = _oracle_out(case)
+    for rps in (0, 128, 256):
+        got = H.run_decode(rap, case, kernel=kernel, rows_per_split=rps).cpu().numpy()
+        H.assert_attn_close(got, ref, "rps=%d" % rps)
+
+
+@pytest.mark.parametrize("kernel", [VALU, MFMA])
+def test_decode_peaky_and_scales(rap, kernel):
+    """1 % of K rows x8 (softmax dominated by a few rows), both softmax scales."""
+    for scale in (1 / np.sqrt(128.0), 1 / np.sqrt(90.0), 0.5):
+        w = I.scaled(I.WORKLOADS["cfg2"], batch=2, ctx=1500, scale=scale, seed=321)
+        _say("decode peaky kernel=%d scale=%.4f" % (kernel, scale))
+        case = I.make_case(w, device=DEV)
+        ref = _oracle_out(case)
+        for rps in (0, 128, 384):
+            got = H.run_decode(rap, case, kernel=kernel, rows_per_split=rps).cpu().numpy()
+            H.assert_attn_close(got, ref, "scale=%g rps=%d" % (scale, rps))
+
+
+@pytest.mark.parametrize("kernel", [VALU, MFMA])
+def test_decode_ignores_rows_beyond_len(rap, kernel):
+    """Rows at and beyond seq_lens hold NaN / Inf / huge patterns: the result must not change."""
+    w = I.scaled(I.WORKLOADS["cfg3"], batch=4, ctx=300, ragged_min=5, seed=11)
+    _say("decode garbage kernel=%d" % kernel)
+    case = I.make_case(w, device=DEV)
+    lens = case.seq_lens.cpu().numpy()
+    ref = _oracle_out(case)
+    poison = torch.tensor([0x7FC0, 0x7F80, 0xFF80, 0x7F7F, 0xFFFF], dtype=torch.int32).to(torch.int16).view(torch.bfloat16).to(DEV)
+    for b in range(w.batch):
+        n = case.cap - int(lens[b])
+        if n > 0:
+            idx = torch.arange(n * w.d_k, device=DEV) % 5
+            case.k_cache[b, :, int(lens[b]):] = poison[idx].view(n, w.d_k)
+            idx = torch.arange(n * w.d_v, device=DEV) % 5
+            case.v_cache[b, :, int(lens[b]):] = poison[idx].view(n, w.d_v)
+    for rps in (0, 128):
+        got = H.run_decode(rap, case, kernel=kernel, rows_per_split=rps).cpu().numpy()
+        H.assert_attn_close(got, ref, "poisoned tail rps=%d" % rps)
+
+
+@pytest.mark.parametrize("kernel", [VALU, MFMA])
+def test_decode_zero_length_and_clamp(rap, kernel):
+    w = I.scaled(I.WORKLOADS["cfg2"], batch=3, ctx=200, peaky_frac=0.0, seed=12)
+    case = I.make_case(w, device=DEV)
+    case.seq_lens = torch.tensor([0, 200, 1], dtype=torch.int32, device=DEV)
+    ref = _oracle_out(case)
+    for rps in (0, 128):
+        got = H.run_decode(rap, case, kernel=kernel, rows_per_split=rps, max_seq_len=200).cpu().numpy()
+        assert np.all(got[0] == 0)
+        H.assert_attn_close(got, ref, "zero-length rps=%d" % rps)
+    # seq_lens above max_seq_len is clamped on the device
+    case.seq_lens = torch.tensor([150, 999, 7], dtype=torch.int32, device=DEV)
+    got = H.run_decode(rap, case, kernel=kernel, max_seq_len=160).cpu().numpy()
+    case.seq_lens = torch.tensor([150, 160, 7], dtype=torch.int32, device=DEV)
+    H.assert_attn_close(got, _oracle_out(case), "clamped")
+
+
+def test_split_invariance(rap):
+    """1 range vs many: same result up to fp32 rounding (merge identity on the GPU side)."""
+    w = I.scaled(I.WORKLOADS["cfg2"], batch=2, ctx=4000, seed=13)
+    case = I.make_case(w, device=DEV)
+    base = H.run_decode(rap, case, kernel=MFMA, rows_per_split=4096).cpu().numpy()
+    for kernel in (VALU, MFMA):
+        for rps in (128, 640, 2048, 4096):
+            got = H.run_decode(rap, case, kernel=kernel, rows_per_split=rps).cpu().numpy()
+            rel = np.abs(got - base).max() / np.abs(base).max()
+            assert rel <= 1e-5, (kernel, rps, rel)
+
+
+# ------------------------------------------------------------------ the five configurations at full size
+
+
+def _append_then_decode(rap, case, kernels=(MFMA,), sample=None, rng=None):
+    """Append the new tokens with librap, check those rows, then decode and compare (all of it, or
+    the (b, kv head) slabs in `sample`) with the oracle fed from the cache librap produced."""
+    w = case.w
+    pos = case.pos.cpu().numpy()
+    lens = case.seq_lens.cpu().numpy()
+    # rows the append will touch, before (filler) -> oracle result
+    H.run_append(rap, case)
+    torch.cuda.synchronize()
+    slabs = sample if sample is not None else [(b, h) for b in range(w.batch) for h in range(w.n_kv_heads)]
+    keep = case.keep.cpu().numpy()
+    k_new, v_new = I.bits(case.k_new), I.bits(case.v_new)
+    worst = 0
+    for b, h in slabs:
+        rows = pos[b]
+        got_k = I.bits(case.k_cache[b, h, rows.tolist()])
+        got_v = I.bits(case.v_cache[b, h, rows.tolist()])
+        kf = O.bf16_bits_to_f64(k_new[b, :, h])
+        want_k = O.f64_to_bf16_bits_rne(O.rope_compact(kf, rows.astype(np.float64), keep[h], w.rope_theta, w.d_head))
+        assert np.array_equal(got_v, v_new[b, :, h])
+        worst = max(worst, int(H.bf16_ulp_distance(got_k, want_k).max()))
+    assert worst <= 1
+    outs = {k: H.run_decode(rap, case, kernel=k).cpu().numpy() for k in kernels}
+    qb = I.bits(case.q)
+    g = w.group
+    for b, h in slabs:
+        n = int(lens[b])
+        kf = O.bf16_bits_to_f64(I.bits(case.k_cache[b, h, :n]))
+        vf = O.bf16_bits_to_f64(I.bits(case.v_cache[b, h, :n]))
+        ref = O.attn_rows_ref(O.bf16_bits_to_f64(qb[b, h * g:(h + 1) * g]), kf, vf, w.scale)
+        for k, out in outs.items():
+            H.assert_attn_close(out[b, h * g:(h + 1) * g], ref, "%s b=%d h=%d kernel=%d" % (w.name, b, h, k))
+    for out in outs.values():
+        assert np.all(np.isfinite(out))
+    return outs
+
+
+def test_cfg1_full(rap):
+    _say("cfg1 full")
+    case = I.make_case(I.WORKLOADS["cfg1"], device=DEV)
+    _append_then_decode(rap, case, kernels=(VALU, MFMA))
+
+
+def test_cfg2_full(rap):
+    _say("cfg2 full")
+    case = I.make_case(I.WORKLOADS["cfg2"], device=DEV)
+    _append_then_decode(rap, case, kernels=(VALU, MFMA))
+
+
+def _sampled(w, n, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    picks = set()
+    while len(picks) < n:
+        picks.add((int(rng.integers(w.batch)), int(rng.integers(w.n_kv_heads))))
+    return sorted(picks)
+
+
+def test_cfg3_sampled(rap):
+    _say("cfg3 sampled")
+    w = I.WORKLOADS["cfg3"]
+    case = I.make_case(w, device=DEV)
+    _append_then_decode(rap, case, sample=_sampled(w, 6, 3) + [(0, 0), (w.batch - 1, w.n_kv_heads - 1)])
+
+
+def test_cfg4_sampled(rap):
+    _say("cfg4 sampled")
+    w = I.WORKLOADS["cfg4"]
+    case = I.make_case(w, device=DEV)
+    _append_then_decode(rap, case, sample=_sampled(w, 4, 4) + [(0, 0), (w.batch - 1, w.n_kv_heads - 1)])
+
+
+@pytest.mark.parametrize("name", ["cfg5", "cfg5_rho1"])
+def test_cfg5_sampled(rap, name):
+    _say(name + " sampled")
+    w = I.WORKLOADS[name]
+    case = I.make_case(w, device=DEV)
+    lens = case.seq_lens.cpu().numpy()
+    shortest, longest = int(np.argmin(lens)), int(np.argmax(lens))
+    sample = _sampled(w, 4, 5) + [(shortest, 0), (longest, w.n_kv_heads - 1)]
+    outs = _append_then_decode(rap, case, sample=sample)
+    del case
+    torch.cuda.empty_cache()
