@@ -99,7 +99,7 @@ SMALL = [
 @pytest.mark.parametrize("P,dv,Hq,Hkv,ctx", SMALL)
 def test_decode_small(rap, kernel, P, dv, Hq, Hkv, ctx):
     w = I.scaled(I.WORKLOADS["cfg2"], batch=3, n_q_heads=Hq, n_kv_heads=Hkv, n_pairs=P, d_v=dv, ctx=ctx, n_new=1,
-                 ragged_min=max(1, ctx // 3), peaky_frac=0.0, seed=900 + P + ctx)
+                 ragged_min=(max(1, ctx // 3) if ctx >= 4 else None), peaky_frac=0.0, seed=900 + P + ctx)
     _say("decode small kernel=%d P=%d dv=%d Hq=%d Hkv=%d ctx=%d" % (kernel, P, dv, Hq, Hkv, ctx))
     case = I.make_case(w, device=DEV)
     ref = _oracle_out(case)
