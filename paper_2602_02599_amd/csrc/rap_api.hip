@@ -42,9 +42,12 @@ struct Plan {
 };
 
 // Row range per workgroup.  The grid is (n_split, H_kv, B); a workgroup whose range starts at or
-// beyond its sequence's length exits at once, so ragged batches cost only empty launches.  The
-// automatic choice aims at a few workgroups per compute unit in total, and never cuts finer than
-// kSplitQuantum rows.
+// beyond its sequence's length exits at once, so ragged batches cost only empty launches.
+// Measured on MI355X: a workgroup should stream for a long time (its fixed cost is a few
+// microseconds), and when the whole job fits in one round of resident workgroups their number
+// should be a multiple of the 256 compute units.  So: about 512 workgroups when the (b, h) count
+// allows it, ranges never shorter than 512 rows nor longer than 4096 (longer ranges only lengthen
+// the tail of a ragged batch).
 rap_status_t make_plan(const rap_shape_t* s, int64_t max_seq_len, const rap_tuning_t* t, Plan* p) {
   int rps = t ? t->rows_per_split : 0;
   if (rps < 0 || (rps % rap::kSplitQuantum) != 0) return RAP_ERR_SHAPE;
@@ -52,12 +55,12 @@ rap_status_t make_plan(const rap_shape_t* s, int64_t max_seq_len, const rap_tuni
   if (kernel < 0 || kernel > 2) return RAP_ERR_SHAPE;
   if (rps == 0) {
     const int64_t slabs = static_cast<int64_t>(s->batch) * s->n_kv_heads;
-    const int64_t want_wgs = 8LL * kCUs;                               // target workgroups in flight
-    int64_t per_slab = slabs > 0 ? (want_wgs + slabs - 1) / slabs : 1;  // splits per (b, h)
+    int64_t per_slab = slabs > 0 ? (2LL * kCUs) / slabs : 1;            // ranges per (b, h)
     if (per_slab < 1) per_slab = 1;
     int64_t r = (max_seq_len + per_slab - 1) / per_slab;
     r = (r + rap::kSplitQuantum - 1) / rap::kSplitQuantum * rap::kSplitQuantum;
-    if (r < 512) r = 512;                                               // at least 4 tiles per wavefront
+    if (r < 512) r = 512;
+    if (r > 4096) r = 4096;
     rps = static_cast<int>(r);
   }
   p->rows_per_split = rps;

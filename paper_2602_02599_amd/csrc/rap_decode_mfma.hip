@@ -45,15 +45,22 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int KCH, int NT>
-__global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeArgs a) {
+// Headroom, in log2 units, by which a score may exceed the reference of its running softmax
+// before the accumulators are rescaled: 2^64 * (rows of a range) * |v| stays far below fp32 max.
+constexpr float kHeadroom = 64.f;
+
+// KCH = ceil(d_k / 32) score k-steps, NT = 16-channel output tiles.  VPAIR (even d_v): a lane
+// reads two adjacent V channels with one 4-byte LDS read and tile nt holds channels
+// 32 (nt / 2) + 2 l16 + (nt & 1); otherwise 2-byte reads and tile nt holds channels 16 nt + l16.
+template <int KCH, int NT, bool VPAIR>
+__global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(DecodeArgs a) {
   constexpr int NLD_K = 2 * KCH;   // 1 KB wave-loads covering a K tile (d_k <= 32 KCH)
   constexpr int NLD_V = NT;        // same for a V tile (d_v <= 16 NT)
   extern __shared__ __align__(16) unsigned char smem[];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction
   const int l16 = lane & 15;
   const int lg = lane >> 4;
   const int split = blockIdx.x;
@@ -63,7 +70,14 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeArgs a) {
   int len = a.seq_lens[b];
   len = len < 0 ? 0 : (len > a.max_len ? a.max_len : len);
   const int r0 = split * a.rows_per_split;
-  if (r0 >= len && !(split == 0 && a.n_split == 1)) return;
+  if (r0 >= len) {
+    // no rows for this workgroup.  With a single range nobody else writes the output row of an
+    // empty sequence; with several ranges the combining kernel does.
+    if (a.n_split == 1)
+      for (int e = tid; e < a.group * a.d_v; e += 256)
+        a.out[(static_cast<long long>(b) * a.n_q + h * a.group) * a.d_v + e] = 0.f;
+    return;
+  }
   const int r1 = min(r0 + a.rows_per_split, len);
   const int len8 = (len + 7) & ~7;                 // <= cache_cap: rows below it are readable
 
@@ -77,37 +91,6 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeArgs a) {
   const long long slab = static_cast<long long>(b) * a.n_kv + h;
   const unsigned char* kslab = reinterpret_cast<const unsigned char*>(a.k_cache) + slab * a.cap * pitch_k;
   const unsigned char* vslab = reinterpret_cast<const unsigned char*>(a.v_cache) + slab * a.cap * pitch_v;
-
-  // ---- query rows as the B operand: lane (l16 = head slot, lg = k sub-chunk)
-  bf16x8 qf[KCH];
-  {
-    const uint32_t* qrow = reinterpret_cast<const uint32_t*>(a.q) +
-                           (static_cast<long long>(b) * a.n_q + h * G + (l16 < G ? l16 : 0)) * a.n_pairs;
-#pragma unroll
-    for (int kk = 0; kk < KCH; ++kk) {
-      uint32_t w[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int e = 32 * kk + 8 * lg + 2 * i;
-        w[i] = (l16 < G && e < dk) ? qrow[e >> 1] : 0u;
-      }
-      qf[kk] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
-    }
-  }
-  // mask of the last K fragment (elements at or beyond d_k belong to the next row)
-  uint32_t kmask[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) kmask[i] = (32 * (KCH - 1) + 8 * lg + 2 * i) < dk ? 0xffffffffu : 0u;
-
-  // LDS byte offsets of this lane's operands inside a tile
-  int koff[2];
-#pragma unroll
-  for (int rt = 0; rt < 2; ++rt) koff[rt] = (16 * rt + l16) * pitch_k + 16 * lg;
-  int voff[2][4];
-#pragma unroll
-  for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) voff[rt][r] = (16 * rt + 4 * lg + r) * pitch_v + 2 * l16;
 
   f32x4 acc[NT];
 #pragma unroll
@@ -144,8 +127,41 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeArgs a) {
     }
   };
 
+  // first tile on its way before anything else is fetched
   const int first = r0 + kTileRows * wave;
   if (first < r1) issue_loads(first);
+
+  // ---- query rows as the B operand: lane (l16 = head slot, lg = k sub-chunk)
+  bf16x8 qf[KCH];
+  {
+    const uint32_t* qrow = reinterpret_cast<const uint32_t*>(a.q) +
+                           (static_cast<long long>(b) * a.n_q + h * G + (l16 < G ? l16 : 0)) * a.n_pairs;
+#pragma unroll
+    for (int kk = 0; kk < KCH; ++kk) {
+      uint32_t w[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int e = 32 * kk + 8 * lg + 2 * i;
+        w[i] = (l16 < G && e < dk) ? qrow[e >> 1] : 0u;
+      }
+      qf[kk] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+    }
+  }
+  // mask of the last K fragment (elements at or beyond d_k belong to the next row)
+  uint32_t kmask[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) kmask[i] = (32 * (KCH - 1) + 8 * lg + 2 * i) < dk ? 0xffffffffu : 0u;
+
+  // LDS byte offsets of this lane's operands inside a tile
+  int koff[2];
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt) koff[rt] = (16 * rt + l16) * pitch_k + 16 * lg;
+  int voff[2][4];
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) voff[rt][r] = (16 * rt + 4 * lg + r) * pitch_v + (VPAIR ? 4 : 2) * l16;
+
 
   for (int base = first; base < r1; base += 4 * kTileRows) {
     // ---- park the staged tile in LDS, start fetching the next one
@@ -176,7 +192,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeArgs a) {
       }
     }
 
-    // ---- online softmax (log2 units)
+    // ---- softmax numerators against a reference that rarely moves (log2 units)
     const int nv = min(kTileRows, r1 - base);       // valid rows in this tile, >= 1
     float x[2][4];
     float tmax = -INFINITY;
@@ -188,11 +204,13 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeArgs a) {
         x[rt][r] = (16 * rt + 4 * lg + r) < nv ? s : -INFINITY;
         tmax = fmaxf(tmax, x[rt][r]);
       }
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-    const float m_new = fmaxf(m_run, tmax);
-    if (__any(m_new > m_run)) {
-      const float alpha = exp2f(m_run - m_new);      // first tile: 2^-inf = 0
+    if (__any(tmax > m_run + kHeadroom)) {
+      // first tile of the wavefront (m_run = -inf), or a score far above the reference: take
+      // the true maximum over the four lane groups and rescale what has been accumulated
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+      const float m_new = fmaxf(m_run, tmax);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);      // first tile: 2^-inf = 0
       l_run *= alpha;
 #pragma unroll
       for (int reg = 0; reg < 4; ++reg) {
@@ -207,21 +225,30 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeArgs a) {
     for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        pr[rt][r] = exp2f(x[rt][r] - m_run);
+        pr[rt][r] = __builtin_amdgcn_exp2f(x[rt][r] - m_run);
         l_run += pr[rt][r];
       }
 
-    // ---- P.V: acc[nt][reg] (head 4 lg + reg, channel 16 nt + l16) += p . V
+    // ---- P.V: acc[nt][reg] (head 4 lg + reg, channel slot l16 of tile nt) += p . V
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int row = min(16 * rt + 4 * lg + r, nv - 1);
-        const unsigned char* vp = vt + (nv == kTileRows ? voff[rt][r] : row * pitch_v + 2 * l16);
+        const unsigned char* vp = vt + (nv == kTileRows ? voff[rt][r] : row * pitch_v + (VPAIR ? 4 : 2) * l16);
+        if constexpr (VPAIR) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          const uint32_t raw = *reinterpret_cast<const uint16_t*>(vp + 32 * nt);
-          acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(pr[rt][r], __uint_as_float(raw << 16), acc[nt], 0, 0, 0);
+          for (int np = 0; np < NT / 2; ++np) {
+            const uint32_t raw = *reinterpret_cast<const uint32_t*>(vp + 64 * np);
+            acc[2 * np] = __builtin_amdgcn_mfma_f32_16x16x4f32(pr[rt][r], bf16_lo(raw), acc[2 * np], 0, 0, 0);
+            acc[2 * np + 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(pr[rt][r], bf16_hi(raw), acc[2 * np + 1], 0, 0, 0);
+          }
+        } else {
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            const uint32_t raw = *reinterpret_cast<const uint16_t*>(vp + 32 * nt);
+            acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(pr[rt][r], __uint_as_float(raw << 16), acc[nt], 0, 0, 0);
+          }
         }
       }
   }
@@ -240,7 +267,8 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeArgs a) {
     const int g = 4 * lg + reg;
     if (g < kMaxGroup) {
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) wm[32 + g * (16 * NT) + 16 * nt + l16] = acc[nt][reg];
+      for (int nt = 0; nt < NT; ++nt)
+        wm[32 + g * (16 * NT) + (VPAIR ? 32 * (nt >> 1) + 2 * l16 + (nt & 1) : 16 * nt + l16)] = acc[nt][reg];
     }
   }
   __syncthreads();
@@ -275,7 +303,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeArgs a) {
   }
 }
 
-template <int KCH, int NT>
+template <int KCH, int NT, bool VPAIR>
 hipError_t launch_inst(const DecodeArgs& a, hipStream_t stream) {
   dim3 grid(a.n_split, a.n_kv, a.batch), block(256);
   const size_t lds = 4 * static_cast<size_t>(a.lds_wave_bytes);
@@ -283,27 +311,37 @@ hipError_t launch_inst(const DecodeArgs& a, hipStream_t stream) {
     // more than the default dynamic-LDS limit: raise it once per kernel (gfx950 has 160 KB per CU)
     static int raised_to = 0;
     if (raised_to < static_cast<int>(lds)) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_mfma_kernel<KCH, NT>),
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_mfma_kernel<KCH, NT, VPAIR>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
       if (e != hipSuccess) return e;
       raised_to = static_cast<int>(lds);
     }
   }
-  hipLaunchKernelGGL((decode_mfma_kernel<KCH, NT>), grid, block, lds, stream, a);
+  hipLaunchKernelGGL((decode_mfma_kernel<KCH, NT, VPAIR>), grid, block, lds, stream, a);
   return hipGetLastError();
 }
 
 template <int KCH>
 hipError_t launch_k(const DecodeArgs& a, hipStream_t stream) {
-  switch ((a.d_v + 15) / 16) {
-    case 1: return launch_inst<KCH, 1>(a, stream);
-    case 2: return launch_inst<KCH, 2>(a, stream);
-    case 3: return launch_inst<KCH, 3>(a, stream);
-    case 4: return launch_inst<KCH, 4>(a, stream);
-    case 5: return launch_inst<KCH, 5>(a, stream);
-    case 6: return launch_inst<KCH, 6>(a, stream);
-    case 7: return launch_inst<KCH, 7>(a, stream);
-    case 8: return launch_inst<KCH, 8>(a, stream);
+  const int nt = (a.d_v + 15) / 16;
+  if ((a.d_v & 1) == 0 && (nt & 1) == 0) {   // paired 4-byte V reads
+    switch (nt) {
+      case 2: return launch_inst<KCH, 2, true>(a, stream);
+      case 4: return launch_inst<KCH, 4, true>(a, stream);
+      case 6: return launch_inst<KCH, 6, true>(a, stream);
+      case 8: return launch_inst<KCH, 8, true>(a, stream);
+      default: return hipErrorInvalidValue;
+    }
+  }
+  switch (nt) {
+    case 1: return launch_inst<KCH, 1, false>(a, stream);
+    case 2: return launch_inst<KCH, 2, false>(a, stream);
+    case 3: return launch_inst<KCH, 3, false>(a, stream);
+    case 4: return launch_inst<KCH, 4, false>(a, stream);
+    case 5: return launch_inst<KCH, 5, false>(a, stream);
+    case 6: return launch_inst<KCH, 6, false>(a, stream);
+    case 7: return launch_inst<KCH, 7, false>(a, stream);
+    case 8: return launch_inst<KCH, 8, false>(a, stream);
     default: return hipErrorInvalidValue;
   }
 }

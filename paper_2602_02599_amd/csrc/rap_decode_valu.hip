@@ -36,7 +36,14 @@ __global__ __launch_bounds__(256) void decode_valu_kernel(DecodeArgs a) {
   int len = a.seq_lens[b];
   len = len < 0 ? 0 : (len > a.max_len ? a.max_len : len);
   const int r0 = split * a.rows_per_split;
-  if (r0 >= len && !(split == 0 && a.n_split == 1)) return;   // nothing to do for this range
+  if (r0 >= len) {
+    // no rows for this workgroup.  With a single range nobody else writes the output row of an
+    // empty sequence; with several ranges the combining kernel does.
+    if (a.n_split == 1)
+      for (int e = tid; e < G * a.d_v; e += 256)
+        a.out[(static_cast<long long>(b) * a.n_q + h * G) * a.d_v + e] = 0.f;
+    return;
+  }
   const int r1 = min(r0 + a.rows_per_split, len);
 
   const int P = a.n_pairs;

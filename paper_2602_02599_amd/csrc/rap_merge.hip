@@ -19,15 +19,39 @@ __global__ __launch_bounds__(128) void merge_kernel(DecodeArgs a) {
   const int n = (len + a.rows_per_split - 1) / a.rows_per_split;
   const float* ml = a.part_ml + hq * a.n_split * 2;
   const float* acc = a.part_acc + hq * a.n_split * a.d_v;
+  // two passes over the n partials, four independent loads in flight per step
   float mstar = -INFINITY;
-  for (int s = 0; s < n; ++s) mstar = fmaxf(mstar, ml[2 * s]);
+  int s = 0;
+  for (; s + 4 <= n; s += 4) {
+    const float m0 = ml[2 * s], m1 = ml[2 * s + 2], m2 = ml[2 * s + 4], m3 = ml[2 * s + 6];
+    mstar = fmaxf(fmaxf(mstar, fmaxf(m0, m1)), fmaxf(m2, m3));
+  }
+  for (; s < n; ++s) mstar = fmaxf(mstar, ml[2 * s]);
   float den = 0.f, num = 0.f;
-  for (int s = 0; s < n; ++s) {
+  const bool live = c < a.d_v;
+  const float* accc = acc + (live ? c : 0);
+  s = 0;
+  for (; s + 4 <= n; s += 4) {
+    float m[4], l[4], v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      m[u] = ml[2 * (s + u)];
+      l[u] = ml[2 * (s + u) + 1];
+      v[u] = accc[static_cast<long long>(s + u) * a.d_v];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float w = exp2f(m[u] - mstar);
+      den = fmaf(w, l[u], den);
+      num = fmaf(w, v[u], num);
+    }
+  }
+  for (; s < n; ++s) {
     const float w = exp2f(ml[2 * s] - mstar);
     den = fmaf(w, ml[2 * s + 1], den);
-    if (c < a.d_v) num = fmaf(w, acc[static_cast<long long>(s) * a.d_v + c], num);
+    num = fmaf(w, accc[static_cast<long long>(s) * a.d_v], num);
   }
-  if (c < a.d_v) a.out[hq * a.d_v + c] = n > 0 ? num / den : 0.f;
+  if (live) a.out[hq * a.d_v + c] = den > 0.f ? num / den : 0.f;
 }
 
 hipError_t launch_merge(const DecodeArgs& a, hipStream_t stream) {

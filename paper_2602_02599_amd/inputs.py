@@ -104,27 +104,29 @@ def _randn_bf16(shape, gen: torch.Generator, device) -> torch.Tensor:
     return torch.randn(shape, generator=gen, device=device, dtype=torch.float32).to(torch.bfloat16)
 
 
-def make_case(w: Workload, device="cpu", fill_unused: bool = True) -> Case:
+def make_case(w: Workload, device="cpu", fill_unused: bool = True, cap_extra: int = 0) -> Case:
     """Draw every tensor of a workload.
 
     Cache rows [0, prefill_len_b) hold N(0,1) bf16 values taken as already
     rotated keys (a rotation of an isotropic Gaussian row has the same law).
     Rows from prefill_len_b on are what the append call will write; until then,
     and up to cap, they hold a finite filler (also N(0,1)) when fill_unused is
-    set, zeros otherwise.  Order of draws is fixed: keep, keep_v, lengths (NumPy
+    set, zeros otherwise.  Order of draws is fixed: lengths, keep, keep_v (NumPy
     PCG64), then K, V per batch element, q, k_new, v_new (torch generator).
     """
     dev = torch.device(device)
     rng = np.random.Generator(np.random.PCG64(w.seed))
-    keep = draw_keep(rng, w.n_kv_heads, w.d_head // 2, w.n_pairs)
-    keep_v = draw_keep(rng, w.n_kv_heads, w.d_head, w.d_v)
+    # lengths first, so that they depend on the seed alone (a rho = 1 control with the same seed
+    # gets the identical length mix)
     if w.ragged_min is not None:
         hi = w.ctx - w.n_new
         prefill = rng.integers(w.ragged_min, hi + 1, size=w.batch).astype(np.int64)
     else:
         prefill = np.full(w.batch, w.ctx - w.n_new, dtype=np.int64)
+    keep = draw_keep(rng, w.n_kv_heads, w.d_head // 2, w.n_pairs)
+    keep_v = draw_keep(rng, w.n_kv_heads, w.d_head, w.d_v)
     seq_lens = prefill + w.n_new
-    cap = round_up(int(seq_lens.max()), 8)
+    cap = round_up(int(seq_lens.max()) + cap_extra, 8)     # cap_extra: spare rows a serving stack would keep
 
     gen = torch.Generator(device=dev)
     gen.manual_seed(w.seed)
