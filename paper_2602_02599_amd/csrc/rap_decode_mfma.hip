@@ -14,13 +14,15 @@
 //  * Scores: S^T[row][g] = K_tile[row][:] . q[g][:] on v_mfma_f32_16x16x32_bf16 with the K tile as
 //    the A operand (a lane reads 16 bytes of one row from LDS) and the G query rows, zero-padded to
 //    16, resident in registers as the B operand.  bf16 products are exact in fp32.
-//  * The result layout of that instruction (lane = query head, 4 registers = 4 rows per 16-lane
-//    group) is exactly the A-operand layout of v_mfma_f32_16x16x4_f32, so after the exponential
-//    the probabilities feed P.V without any data movement, in fp32.  The V element each lane needs
-//    (row = contraction index, channel = lane) is a 2-byte LDS read: the "transpose" that a
-//    row-major V needs for a matrix instruction costs nothing but LDS address bits.
-//  * The vector ALU only scales, exponentiates and sums eight scores per lane per tile; the
-//    accumulators are rescaled only when a running maximum actually moves.
+//  * In the result layout of that instruction a lane (query head g, lane group lg) holds the scores
+//    of eight rows of the tile.  P.V runs on the same instruction with the contraction slots
+//    numbered so that a lane's eight slots are exactly those eight rows: the probabilities go from
+//    the exponential into the A operand without leaving the lane, as a bf16 head plus a bf16
+//    remainder (16 significant bits).  The V operand a lane needs (its channel, eight rows) is
+//    gathered from LDS with 4-byte reads of two adjacent channels and a byte permute per row pair:
+//    the "transpose" a row-major V needs costs LDS address bits and one ALU instruction per pair.
+//  * The vector ALU only scales, exponentiates, sums and packs eight scores per lane per tile;
+//    the accumulators are rescaled only when a score outgrows the reference by 2^64.
 //
 // Garbage safety: rows at or beyond the sequence length may hold any bits.  Their scores are
 // replaced by -inf (a select, not arithmetic), their V reads are redirected to the last valid row
@@ -35,7 +37,16 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
 constexpr int kTileRows = 32;
+
+// two fp32 -> two bf16 (round to nearest even) in one dword, first argument in the low half
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
 
 __device__ __forceinline__ void wave_lds_sync() {
   // LDS operations of one wavefront execute in order; this only stops the compiler from moving
@@ -229,28 +240,63 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
         l_run += pr[rt][r];
       }
 
-    // ---- P.V: acc[nt][reg] (head 4 lg + reg, channel slot l16 of tile nt) += p . V
+    // ---- P.V on the bf16 matrix instruction: acc[nt][reg] (head 4 lg + reg, channel slot l16 of
+    // tile nt) += sum over the tile's 32 rows.  Contraction slot k = 8 lg + j of that instruction
+    // is row 16 (j / 4) + 4 lg + (j % 4): exactly the rows whose probabilities this lane already
+    // holds (j = 4 rt + r), so the A operand is built in-lane.  p is split into a bf16 head and a
+    // bf16 remainder (two instructions), which keeps 16 significant bits of every probability.
+    uint4 p_hi, p_lo;
+    {
+      uint32_t* ph = reinterpret_cast<uint32_t*>(&p_hi);
+      uint32_t* pl = reinterpret_cast<uint32_t*>(&p_lo);
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int row = min(16 * rt + 4 * lg + r, nv - 1);
-        const unsigned char* vp = vt + (nv == kTileRows ? voff[rt][r] : row * pitch_v + (VPAIR ? 4 : 2) * l16);
-        if constexpr (VPAIR) {
-#pragma unroll
-          for (int np = 0; np < NT / 2; ++np) {
-            const uint32_t raw = *reinterpret_cast<const uint32_t*>(vp + 64 * np);
-            acc[2 * np] = __builtin_amdgcn_mfma_f32_16x16x4f32(pr[rt][r], bf16_lo(raw), acc[2 * np], 0, 0, 0);
-            acc[2 * np + 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(pr[rt][r], bf16_hi(raw), acc[2 * np + 1], 0, 0, 0);
-          }
-        } else {
-#pragma unroll
-          for (int nt = 0; nt < NT; ++nt) {
-            const uint32_t raw = *reinterpret_cast<const uint16_t*>(vp + 32 * nt);
-            acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(pr[rt][r], __uint_as_float(raw << 16), acc[nt], 0, 0, 0);
-          }
-        }
+      for (int d = 0; d < 4; ++d) {
+        const float a0 = pr[d >> 1][2 * (d & 1)], a1 = pr[d >> 1][2 * (d & 1) + 1];
+        const uint32_t h = pack_bf16(a0, a1);
+        ph[d] = h;
+        pl[d] = pack_bf16(a0 - bf16_lo(h), a1 - bf16_hi(h));
       }
+    }
+    const bf16x8 pa_hi = __builtin_bit_cast(bf16x8, p_hi), pa_lo = __builtin_bit_cast(bf16x8, p_lo);
+    int vo[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int row = min(16 * (j >> 2) + 4 * lg + (j & 3), nv - 1);
+      vo[j] = nv == kTileRows ? voff[j >> 2][j & 3] : row * pitch_v + (VPAIR ? 4 : 2) * l16;
+    }
+    if constexpr (VPAIR) {
+#pragma unroll
+      for (int np = 0; np < NT / 2; ++np) {
+        uint32_t w[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) w[j] = *reinterpret_cast<const uint32_t*>(vt + vo[j] + 64 * np);
+        uint4 be, bo;   // even / odd channel of the pair, rows packed two by two
+        be.x = __builtin_amdgcn_perm(w[1], w[0], 0x05040100u);
+        be.y = __builtin_amdgcn_perm(w[3], w[2], 0x05040100u);
+        be.z = __builtin_amdgcn_perm(w[5], w[4], 0x05040100u);
+        be.w = __builtin_amdgcn_perm(w[7], w[6], 0x05040100u);
+        bo.x = __builtin_amdgcn_perm(w[1], w[0], 0x07060302u);
+        bo.y = __builtin_amdgcn_perm(w[3], w[2], 0x07060302u);
+        bo.z = __builtin_amdgcn_perm(w[5], w[4], 0x07060302u);
+        bo.w = __builtin_amdgcn_perm(w[7], w[6], 0x07060302u);
+        const bf16x8 vbe = __builtin_bit_cast(bf16x8, be), vbo = __builtin_bit_cast(bf16x8, bo);
+        acc[2 * np] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi, vbe, acc[2 * np], 0, 0, 0);
+        acc[2 * np + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi, vbo, acc[2 * np + 1], 0, 0, 0);
+        acc[2 * np] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_lo, vbe, acc[2 * np], 0, 0, 0);
+        acc[2 * np + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_lo, vbo, acc[2 * np + 1], 0, 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        uint32_t u[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) u[j] = *reinterpret_cast<const uint16_t*>(vt + vo[j] + 32 * nt);
+        const uint4 bv = make_uint4(u[0] | (u[1] << 16), u[2] | (u[3] << 16), u[4] | (u[5] << 16), u[6] | (u[7] << 16));
+        const bf16x8 vb = __builtin_bit_cast(bf16x8, bv);
+        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi, vb, acc[nt], 0, 0, 0);
+        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_lo, vb, acc[nt], 0, 0, 0);
+      }
+    }
   }
 
   // ---- fold lane groups, then the four wavefronts, through LDS
