@@ -169,6 +169,8 @@ def main():
     ap.add_argument("--buffers", type=int, default=4, help="distinct cache copies rotated through")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-control", action="store_true", help="skip the rho = 1.0 control")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain copies of 256 MiB (known-size reference for hardware byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (every box here has one); run with --gpus 1", file=sys.stderr)
@@ -206,6 +208,14 @@ def main():
     torch.cuda.synchronize()
     stream_gbps = nflat * 10 / (time.perf_counter() - t0) / 1e9
     del flat, flat_u8
+
+    if args.copy_calibration:
+        csrc = torch.full((256 << 20,), 3, dtype=torch.uint8, device=dev)
+        cdst = torch.empty_like(csrc)
+        for _ in range(3):
+            rap.rap_stream_copy(cdst, csrc)
+        torch.cuda.synchronize()
+        del csrc, cdst
 
     result = {
         "metric": "decode-attention HBM GB/s (fraction of peak) and tokens/s at rho=0.7, 1 MI355X",

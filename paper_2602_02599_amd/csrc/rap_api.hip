@@ -14,7 +14,6 @@ hipError_t launch_merge(const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t stream);
 hipError_t launch_stream_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 int mfma_lds_wave_bytes(int d_k, int d_v);
-int mfma_fast_rows(int d_k, int d_v);
 }  // namespace rap
 
 namespace {
@@ -160,7 +159,6 @@ rap_status_t rap_decode_attn(const rap_shape_t* shape, const void* q, const void
   a.cap = shape->cache_cap;
   a.scale_log2e = scale * 1.4426950408889634f;
   a.lds_wave_bytes = rap::mfma_lds_wave_bytes(a.d_k, a.d_v);
-  a.fast_rows = rap::mfma_fast_rows(a.d_k, a.d_v);
 
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (tuning && tuning->ev_main_start && hipEventRecord(static_cast<hipEvent_t>(tuning->ev_main_start), s) != hipSuccess)

@@ -115,16 +115,21 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
 #pragma unroll
   for (int j = 0; j < NLD_V; ++j) vst[j] = make_uint4(0, 0, 0, 0);
 
+  // does this lane's share of the last whole-KB load belong to the tile?
+  const bool k_last = 1024 * (NLD_K - 1) + 16 * lane < kTileRows * pitch_k;
+  const bool v_last = 1024 * (NLD_V - 1) + 16 * lane < kTileRows * pitch_v;
   auto issue_loads = [&](int base) {
     const unsigned char* kg = kslab + static_cast<long long>(base) * pitch_k + 16 * lane;
     const unsigned char* vg = vslab + static_cast<long long>(base) * pitch_v + 16 * lane;
-    if (base + a.fast_rows <= len8) {
-      // common case: the whole 1 KB-granular run, including what spills past the tile's last
-      // row (fewer than 1024 bytes), lies below row len8 and is readable
+    if (base + kTileRows <= len8) {
+      // common case, a full tile: whole-KB loads, the last one of each run trimmed to the tile's
+      // own bytes so that nothing is fetched twice and nothing beyond row len8 is touched
 #pragma unroll
-      for (int j = 0; j < NLD_K; ++j) kst[j] = *reinterpret_cast<const uint4*>(kg + 1024 * j);
+      for (int j = 0; j < NLD_K - 1; ++j) kst[j] = *reinterpret_cast<const uint4*>(kg + 1024 * j);
+      if (k_last) kst[NLD_K - 1] = *reinterpret_cast<const uint4*>(kg + 1024 * (NLD_K - 1));
 #pragma unroll
-      for (int j = 0; j < NLD_V; ++j) vst[j] = *reinterpret_cast<const uint4*>(vg + 1024 * j);
+      for (int j = 0; j < NLD_V - 1; ++j) vst[j] = *reinterpret_cast<const uint4*>(vg + 1024 * j);
+      if (v_last) vst[NLD_V - 1] = *reinterpret_cast<const uint4*>(vg + 1024 * (NLD_V - 1));
     } else {
       // last tiles of a sequence: read only rows [base, len8), chunk by chunk
       const int rows = min(kTileRows, len8 - base);   // multiple of 8
@@ -402,13 +407,6 @@ int mfma_lds_wave_bytes(int d_k, int d_v) {
   const int fold = (32 + kMaxGroup * 16 * nt) * 4;
   const int need = tiles > fold ? tiles : fold;
   return (need + 127) / 128 * 128;
-}
-
-// Rows, counted from a tile's first row, that the whole-KB loads of a tile reach into.
-int mfma_fast_rows(int d_k, int d_v) {
-  const int kb = 1024 * 2 * ((d_k + 31) / 32), vb = 1024 * ((d_v + 15) / 16);
-  const int kr = (kb + 2 * d_k - 1) / (2 * d_k), vr = (vb + 2 * d_v - 1) / (2 * d_v);
-  return kr > vr ? kr : vr;
 }
 
 hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t stream) {

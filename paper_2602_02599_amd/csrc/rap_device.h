@@ -54,7 +54,6 @@ struct DecodeArgs {
   int32_t batch, n_q, n_kv, group, n_pairs, d_k, d_v;
   int32_t max_len, rows_per_split, n_split;
   int32_t lds_wave_bytes;   // matrix-core kernel: LDS slice of one wavefront
-  int32_t fast_rows;        // matrix-core kernel: rows from a tile's base that its 1 KB-granular loads touch
   int64_t cap;
   float scale_log2e;   // softmax scale * log2(e): exponentials are taken as exp2
 };
