@@ -104,7 +104,7 @@ rap_status_t rap_rope_append(const rap_shape_t* shape, int32_t n_new, const void
   a.n_pairs = shape->n_pairs;
   a.d_v = shape->d_v;
   a.cap = shape->cache_cap;
-  a.theta = shape->rope_theta;
+  a.neg2_log2_theta_over_d = -2.0 * log2(shape->rope_theta) / static_cast<double>(shape->d_head);
   return rap::launch_append(a, static_cast<hipStream_t>(stream)) == hipSuccess ? RAP_OK : RAP_ERR_HIP;
 }
 

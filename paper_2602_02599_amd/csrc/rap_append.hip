@@ -6,9 +6,10 @@
 // taken in fp64 so that positions up to 2^17 and beyond stay far inside one bf16 ulp; the result is
 // rounded to bf16 once.
 //
-// Work layout: one wavefront per (token, kv head); lane c handles pairs c and c + 64, then the
-// same lanes copy the V row.  A K row is 4P bytes and a V row 2 d_v bytes, so the traffic of this
-// call is a few KB per token: it is latency bound and never near a roofline.
+// Work layout: one wavefront per (token, kv head); lane c handles pair c and V elements c and
+// c + 64.  A K row is 4P bytes and a V row 2 d_v bytes, so the traffic of this call is a few KB per
+// token: it is latency bound (one round trip for all loads, then the fp64 math, then the stores)
+// and never near a roofline.
 #include "rap_device.h"
 
 namespace rap {
@@ -21,27 +22,36 @@ __global__ __launch_bounds__(256) void append_kernel(AppendArgs a) {
   const long long n_tok = static_cast<long long>(a.batch) * a.n_new;
   if (tok >= n_tok) return;
   const int b = static_cast<int>(tok / a.n_new);
+  const int P = a.n_pairs;
+
+  // Everything this lane will need is requested at once (one memory round trip): the position,
+  // its pair's original index and two elements, and its two V elements.  P <= 64 and d_v <= 128,
+  // so one pair and two V elements per lane cover the row.
+  const bool has_pair = lane < P;
+  const bool has_v0 = lane < a.d_v, has_v1 = lane + kWave < a.d_v;
+  const uint16_t* ksrc = a.k_new + (tok * a.n_kv + h) * (2 * P);
+  const uint16_t* vsrc = a.v_new + (tok * a.n_kv + h) * a.d_v;
   const int t = a.pos[tok];
+  const int j = has_pair ? a.keep[h * P + lane] : 0;
+  const uint16_t kx = has_pair ? ksrc[lane] : 0, ky = has_pair ? ksrc[lane + P] : 0;
+  const uint16_t v0 = has_v0 ? vsrc[lane] : 0, v1 = has_v1 ? vsrc[lane + kWave] : 0;
   if (t < 0 || t >= a.cap) return;                                        // documented: skipped
 
-  const int P = a.n_pairs;
-  const uint16_t* ksrc = a.k_new + (tok * a.n_kv + h) * (2 * P);
-  uint16_t* kdst = a.k_cache + ((static_cast<long long>(b) * a.n_kv + h) * a.cap + t) * (2 * P);
-  for (int c = lane; c < P; c += kWave) {
-    const int j = a.keep[h * P + c];
-    if (j < 0 || j >= a.d_head / 2) continue;                             // documented: skipped
-    const double inv_freq = pow(a.theta, -2.0 * static_cast<double>(j) / static_cast<double>(a.d_head));
-    const double phi = static_cast<double>(t) * inv_freq;
+  const long long row = (static_cast<long long>(b) * a.n_kv + h) * a.cap + t;
+  if (has_pair && j >= 0 && j < a.d_head / 2) {                           // bad index: documented skip
+    // theta^(-2j/D) = 2^(j * (-2 log2(theta) / D)); the factor is taken in fp64 on the host
+    const double phi = static_cast<double>(t) * exp2(static_cast<double>(j) * a.neg2_log2_theta_over_d);
     double sn, cs;
     sincos(phi, &sn, &cs);
-    const double x = static_cast<double>(bf16_to_f32(ksrc[c]));
-    const double y = static_cast<double>(bf16_to_f32(ksrc[c + P]));
-    kdst[c] = f64_to_bf16_rne(x * cs - y * sn);
-    kdst[c + P] = f64_to_bf16_rne(x * sn + y * cs);
+    const double x = static_cast<double>(bf16_to_f32(kx));
+    const double y = static_cast<double>(bf16_to_f32(ky));
+    uint16_t* kdst = a.k_cache + row * (2 * P);
+    kdst[lane] = f64_to_bf16_rne(x * cs - y * sn);
+    kdst[lane + P] = f64_to_bf16_rne(x * sn + y * cs);
   }
-  const uint16_t* vsrc = a.v_new + (tok * a.n_kv + h) * a.d_v;
-  uint16_t* vdst = a.v_cache + ((static_cast<long long>(b) * a.n_kv + h) * a.cap + t) * a.d_v;
-  for (int c = lane; c < a.d_v; c += kWave) vdst[c] = vsrc[c];
+  uint16_t* vdst = a.v_cache + row * a.d_v;
+  if (has_v0) vdst[lane] = v0;
+  if (has_v1) vdst[lane + kWave] = v1;
 }
 
 hipError_t launch_append(const AppendArgs& a, hipStream_t stream) {

@@ -40,7 +40,7 @@ struct AppendArgs {
   uint16_t* v_cache;
   int32_t batch, n_new, n_kv, d_head, n_pairs, d_v;
   int64_t cap;
-  double theta;
+  double neg2_log2_theta_over_d;    // -2 log2(theta_base) / D, so that theta_j = 2^(j * this)
 };
 
 struct DecodeArgs {

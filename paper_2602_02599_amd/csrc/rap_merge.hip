@@ -14,36 +14,57 @@ __global__ __launch_bounds__(128) void merge_kernel(DecodeArgs a) {
   const long long hq = blockIdx.x;                 // b * n_q + query head
   const int b = static_cast<int>(hq / a.n_q);
   const int c = threadIdx.x;
+  const bool live = c < a.d_v;
+  const float* ml = a.part_ml + hq * a.n_split * 2;
+  const float* accc = a.part_acc + hq * a.n_split * a.d_v + (live ? c : 0);
+  // The first four slots are requested before the sequence length is known (they are allocated,
+  // whatever they hold), so the common case of a few ranges costs one memory round trip.
+  float m[4], l[4], v[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const bool have = u < a.n_split;
+    m[u] = have ? ml[2 * u] : 0.f;
+    l[u] = have ? ml[2 * u + 1] : 0.f;
+    v[u] = have ? accc[static_cast<long long>(u) * a.d_v] : 0.f;
+  }
   int len = a.seq_lens[b];
   len = len < 0 ? 0 : (len > a.max_len ? a.max_len : len);
-  const int n = (len + a.rows_per_split - 1) / a.rows_per_split;
-  const float* ml = a.part_ml + hq * a.n_split * 2;
-  const float* acc = a.part_acc + hq * a.n_split * a.d_v;
-  // two passes over the n partials, four independent loads in flight per step
+  const int n = (len + a.rows_per_split - 1) / a.rows_per_split;   // ranges that hold rows
   float mstar = -INFINITY;
-  int s = 0;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    if (u >= n) { m[u] = -INFINITY; l[u] = 0.f; v[u] = 0.f; }      // unwritten slot: drop, do not multiply
+    mstar = fmaxf(mstar, m[u]);
+  }
+  int s = 4;
   for (; s + 4 <= n; s += 4) {
     const float m0 = ml[2 * s], m1 = ml[2 * s + 2], m2 = ml[2 * s + 4], m3 = ml[2 * s + 6];
     mstar = fmaxf(fmaxf(mstar, fmaxf(m0, m1)), fmaxf(m2, m3));
   }
   for (; s < n; ++s) mstar = fmaxf(mstar, ml[2 * s]);
   float den = 0.f, num = 0.f;
-  const bool live = c < a.d_v;
-  const float* accc = acc + (live ? c : 0);
-  s = 0;
-  for (; s + 4 <= n; s += 4) {
-    float m[4], l[4], v[4];
+  if (n > 0) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      m[u] = ml[2 * (s + u)];
-      l[u] = ml[2 * (s + u) + 1];
-      v[u] = accc[static_cast<long long>(s + u) * a.d_v];
+      const float w = exp2f(m[u] - mstar);                          // 2^-inf = 0 for dropped slots
+      den = fmaf(w, l[u], den);
+      num = fmaf(w, v[u], num);
+    }
+  }
+  s = 4;
+  for (; s + 4 <= n; s += 4) {
+    float mm[4], ll[4], vv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      mm[u] = ml[2 * (s + u)];
+      ll[u] = ml[2 * (s + u) + 1];
+      vv[u] = accc[static_cast<long long>(s + u) * a.d_v];
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const float w = exp2f(m[u] - mstar);
-      den = fmaf(w, l[u], den);
-      num = fmaf(w, v[u], num);
+      const float w = exp2f(mm[u] - mstar);
+      den = fmaf(w, ll[u], den);
+      num = fmaf(w, vv[u], num);
     }
   }
   for (; s < n; ++s) {
