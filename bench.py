@@ -84,22 +84,30 @@ class Job:
         self.bytes_per_step = float(np.mean([kv_bytes(w, c.seq_lens.cpu().numpy()) for c in self.cases]))
         self.i = 0
 
-    def step(self, tuning=None):
+    def step(self, tuning=None, fused_q_rope=False):
         c = self.cases[self.i % len(self.cases)]
         self.i += 1
         w = self.w
         self.rap.rap_rope_append(self.shape, w.n_new, c.k_new, c.v_new, c.pos, c.keep, c.k_cache, c.v_cache)
-        self.rap.rap_decode_attn(self.shape, c.q, c.k_cache, c.v_cache, c.seq_lens, self.max_len, self.out,
-                                 float(w.scale), self.ws, tuning)
+        if fused_q_rope:
+            # q taken as un-rotated, rotated at the last position inside the decode kernel
+            self.rap.rap_decode_attn_rope(self.shape, c.q, c.qpos_last, c.keep, c.k_cache, c.v_cache,
+                                          c.seq_lens, self.max_len, self.out, float(w.scale), self.ws, tuning)
+        else:
+            self.rap.rap_decode_attn(self.shape, c.q, c.k_cache, c.v_cache, c.seq_lens, self.max_len, self.out,
+                                     float(w.scale), self.ws, tuning)
 
-    def timed(self, steps, warmup):
+    def timed(self, steps, warmup, fused_q_rope=False):
         torch = self.torch
+        if fused_q_rope:
+            for c in self.cases:
+                c.qpos_last = c.pos[:, -1].contiguous()
         for _ in range(warmup):
-            self.step()
+            self.step(fused_q_rope=fused_q_rope)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
-            self.step()
+            self.step(fused_q_rope=fused_q_rope)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
@@ -191,6 +199,7 @@ def main():
     w = job.w
     sec = job.timed(args.steps, args.warmup)
     gbps = job.bytes_per_step / sec / 1e9
+    sec_fused = job.timed(args.steps, args.warmup, fused_q_rope=True)
     k_mean_ms, k_min_ms = job.kernel_ms(args.steps, ev)
     achieved = job.bytes_per_step / (k_mean_ms * 1e-3) / 1e9
 
@@ -228,6 +237,7 @@ def main():
         "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
         "tokens_per_s": round(w.batch / sec, 1),
         "stream_read_GBps": round(stream_gbps, 1),
+        "step_with_fused_query_rope_ms": round(sec_fused * 1e3, 5),
         "roofline": {"bound": "hbm", "kernel": "decode_mfma_kernel", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": read_traffic(os.path.join(ROOT, "profiles", "traffic_decode_mfma_%s.txt" % w.name)),

@@ -134,6 +134,28 @@ rap_status_t rap_decode_attn(const rap_shape_t* shape, const void* q,
                              void* workspace, size_t workspace_bytes,
                              const rap_tuning_t* tuning, void* stream);
 
+/* The same attention with the query-side rotation fused in: q arrives pruned but UN-rotated and
+ * is rotated at q_pos[b] by the index-aware RoPE of its KV head's kept pairs before the scores
+ * are taken (Eq. (latent-score): RoPE(X W~_q) . RoPE(X W~_k)^T; Sec. "RAP", index-aware rotation).
+ * The rotation uses the arithmetic of rap_rope_append (fp64 angle from the original pair index,
+ * one rounding to bf16), so the result is bit-identical to rotating q into a bf16 buffer first
+ * and calling rap_decode_attn; it saves that kernel and its launch.
+ *
+ *   q              dev  bf16  [batch, n_q_heads, 2P]  pruned, un-rotated, compact order
+ *   q_pos          dev  int32 [batch]  position of the query token (normally seq_lens[b] - 1)
+ *   keep_pair_idx  dev  int32 [n_kv_heads, P]  as for rap_rope_append; query head a uses the row
+ *                                              of KV head a / G; a pair whose index lies outside
+ *                                              [0, D/2) is taken as zero
+ * Everything else as rap_decode_attn.
+ */
+rap_status_t rap_decode_attn_rope(const rap_shape_t* shape, const void* q, const int32_t* q_pos,
+                                  const int32_t* keep_pair_idx,
+                                  const void* k_cache, const void* v_cache,
+                                  const int32_t* seq_lens, int64_t max_seq_len,
+                                  void* out, float scale,
+                                  void* workspace, size_t workspace_bytes,
+                                  const rap_tuning_t* tuning, void* stream);
+
 /* Measurement aids (not part of the method): a read-only streaming pass over `bytes` bytes of
  * `src` (16-byte aligned, bytes % 16 == 0) that folds everything into 16 bytes at `sink`, and a
  * plain copy of `bytes` bytes.  They give the bandwidth a trivial kernel reaches on the same

@@ -24,6 +24,8 @@ Passages of the paper each function follows:
                            (the cache holds K_latent = RoPE(X W~_k), width 2m).
   attn_ref                 Eq. (attn) with the GQA remark under it;
                            Eq. (latent-score).
+  rope_queries_ref         Eq. (latent-score), query side: RoPE(X W~_q) with the kept pairs of
+                           the query head's KV head.
   attn_full_masked_ref     App. "Method", Eq. (masked-logit-equivalence): the
                            full-width right-hand side with removed pairs zeroed.
   merge_partials_ref       log-sum-exp combination of row-partitioned softmax
@@ -233,6 +235,26 @@ def attn_ref(q, k_cache, v_cache, seq_lens, scale) -> np.ndarray:
             kf = bf16_bits_to_f64(k_cache[b, h, :n])
             vf = bf16_bits_to_f64(v_cache[b, h, :n])
             out[b, h * g:(h + 1) * g] = attn_rows_ref(qf[b, h * g:(h + 1) * g], kf, vf, scale)
+    return out
+
+
+def rope_queries_ref(q, q_pos, keep, theta_base, d_head, n_kv_heads) -> np.ndarray:
+    """Query side of Eq. (latent-score): index-aware rotation of pruned, un-rotated query rows.
+
+    q      uint16 [B, H_q, 2P] bf16 bits; q_pos int [B]; keep int [H_kv, P].
+    Query head a uses the kept pairs of KV head a // G.  Returns bf16 bits (one nearest-even
+    rounding from float64), i.e. what a rotation stage storing bf16 hands to the attention.
+    """
+    q = np.asarray(q)
+    keep = np.asarray(keep)
+    bsz, n_q, _ = q.shape
+    g = n_q // n_kv_heads
+    qf = bf16_bits_to_f64(q)
+    out = np.empty_like(q)
+    for b in range(bsz):
+        for a_h in range(n_q):
+            rot = rope_compact(qf[b, a_h], np.float64(int(q_pos[b])), keep[a_h // g], theta_base, d_head)
+            out[b, a_h] = f64_to_bf16_bits_rne(rot)
     return out
 
 

@@ -80,6 +80,10 @@ class Rap:
         L.rap_decode_attn.restype = C.c_int
         L.rap_decode_attn.argtypes = [C.POINTER(RapShape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                       C.c_void_p, C.c_float, C.c_void_p, C.c_size_t, C.POINTER(RapTuning), C.c_void_p]
+        L.rap_decode_attn_rope.restype = C.c_int
+        L.rap_decode_attn_rope.argtypes = [C.POINTER(RapShape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_void_p, C.c_int64, C.c_void_p, C.c_float, C.c_void_p, C.c_size_t,
+                                           C.POINTER(RapTuning), C.c_void_p]
         L.rap_stream_read.restype = C.c_int
         L.rap_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.rap_stream_copy.restype = C.c_int
@@ -132,6 +136,20 @@ class Rap:
                                       _ptr(workspace, None, "workspace"),
                                       0 if workspace is None else workspace.numel() * workspace.element_size(),
                                       C.byref(tuning) if tuning is not None else None, _stream(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def rap_decode_attn_rope(self, shape: RapShape, q, q_pos, keep_pair_idx, k_cache, v_cache, seq_lens, max_seq_len: int,
+                             out, scale: float, workspace=None, tuning: Optional[RapTuning] = None, stream=None,
+                             check=True) -> int:
+        st = self.lib.rap_decode_attn_rope(C.byref(shape), _ptr(q, torch.bfloat16, "q"), _ptr(q_pos, torch.int32, "q_pos"),
+                                           _ptr(keep_pair_idx, torch.int32, "keep_pair_idx"),
+                                           _ptr(k_cache, torch.bfloat16, "k_cache"), _ptr(v_cache, torch.bfloat16, "v_cache"),
+                                           _ptr(seq_lens, torch.int32, "seq_lens"), max_seq_len,
+                                           _ptr(out, torch.float32, "out"), scale, _ptr(workspace, None, "workspace"),
+                                           0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                           C.byref(tuning) if tuning is not None else None, _stream(stream))
         if check:
             self._check(st)
         return st

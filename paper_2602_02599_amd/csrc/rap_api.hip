@@ -115,9 +115,15 @@ size_t rap_decode_attn_workspace_bytes(const rap_shape_t* shape, int64_t max_seq
   return part_acc_bytes(shape, p) + part_ml_bytes(shape, p) + 256;
 }
 
-rap_status_t rap_decode_attn(const rap_shape_t* shape, const void* q, const void* k_cache, const void* v_cache,
-                             const int32_t* seq_lens, int64_t max_seq_len, void* out, float scale, void* workspace,
-                             size_t workspace_bytes, const rap_tuning_t* tuning, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// Shared body of rap_decode_attn (q_pos == keep == null) and rap_decode_attn_rope.
+rap_status_t decode_impl(const rap_shape_t* shape, const void* q, const int32_t* q_pos, const int32_t* keep,
+                         const void* k_cache, const void* v_cache, const int32_t* seq_lens, int64_t max_seq_len,
+                         void* out, float scale, void* workspace, size_t workspace_bytes, const rap_tuning_t* tuning,
+                         void* stream) {
   rap_status_t st = check_shape(shape);
   if (st != RAP_OK) return st;
   if (max_seq_len < 1) return RAP_ERR_SHAPE;
@@ -140,6 +146,10 @@ rap_status_t rap_decode_attn(const rap_shape_t* shape, const void* q, const void
   rap::DecodeArgs a;
   memset(&a, 0, sizeof(a));
   a.q = static_cast<const uint16_t*>(q);
+  a.q_pos = q_pos;
+  a.keep = keep;
+  a.neg2_log2_theta_over_d = -2.0 * log2(shape->rope_theta) / static_cast<double>(shape->d_head);
+  a.d_head = shape->d_head;
   a.k_cache = static_cast<const uint16_t*>(k_cache);
   a.v_cache = static_cast<const uint16_t*>(v_cache);
   a.seq_lens = seq_lens;
@@ -169,6 +179,29 @@ rap_status_t rap_decode_attn(const rap_shape_t* shape, const void* q, const void
     return RAP_ERR_HIP;
   if (p.n_split > 1 && rap::launch_merge(a, s) != hipSuccess) return RAP_ERR_HIP;
   return RAP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+rap_status_t rap_decode_attn(const rap_shape_t* shape, const void* q, const void* k_cache, const void* v_cache,
+                             const int32_t* seq_lens, int64_t max_seq_len, void* out, float scale, void* workspace,
+                             size_t workspace_bytes, const rap_tuning_t* tuning, void* stream) {
+  return decode_impl(shape, q, nullptr, nullptr, k_cache, v_cache, seq_lens, max_seq_len, out, scale, workspace,
+                     workspace_bytes, tuning, stream);
+}
+
+rap_status_t rap_decode_attn_rope(const rap_shape_t* shape, const void* q, const int32_t* q_pos,
+                                  const int32_t* keep_pair_idx, const void* k_cache, const void* v_cache,
+                                  const int32_t* seq_lens, int64_t max_seq_len, void* out, float scale,
+                                  void* workspace, size_t workspace_bytes, const rap_tuning_t* tuning, void* stream) {
+  if (shape && shape->batch > 0 && max_seq_len >= 1 && (!q_pos || !keep_pair_idx)) {
+    const rap_status_t st = check_shape(shape);
+    return st != RAP_OK ? st : RAP_ERR_NULL;
+  }
+  return decode_impl(shape, q, q_pos, keep_pair_idx, k_cache, v_cache, seq_lens, max_seq_len, out, scale, workspace,
+                     workspace_bytes, tuning, stream);
 }
 
 rap_status_t rap_stream_read(const void* src, size_t bytes, void* sink, void* stream) {

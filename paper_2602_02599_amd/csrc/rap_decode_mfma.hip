@@ -147,11 +147,19 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
   const int first = r0 + kTileRows * wave;
   if (first < r1) issue_loads(first);
 
-  // ---- query rows as the B operand: lane (l16 = head slot, lg = k sub-chunk)
+  // ---- query rows as the B operand: lane (l16 = head slot, lg = k sub-chunk).  With q_pos the
+  // rows arrive un-rotated: the workgroup rotates them into LDS first, while its first tile flies.
+  __shared__ uint16_t s_q[kMaxGroup * 2 * kMaxPairs];
+  const bool rope_q = a.q_pos != nullptr;
+  if (rope_q) {
+    rotate_queries_to_lds(a, b, h, tid, 256, s_q);
+    __syncthreads();
+  }
   bf16x8 qf[KCH];
   {
-    const uint32_t* qrow = reinterpret_cast<const uint32_t*>(a.q) +
-                           (static_cast<long long>(b) * a.n_q + h * G + (l16 < G ? l16 : 0)) * a.n_pairs;
+    const uint32_t* qrow = rope_q ? reinterpret_cast<const uint32_t*>(s_q) + (l16 < G ? l16 : 0) * a.n_pairs
+                                  : reinterpret_cast<const uint32_t*>(a.q) +
+                                        (static_cast<long long>(b) * a.n_q + h * G + (l16 < G ? l16 : 0)) * a.n_pairs;
 #pragma unroll
     for (int kk = 0; kk < KCH; ++kk) {
       uint32_t w[4];

@@ -62,11 +62,18 @@ __global__ __launch_bounds__(256) void decode_valu_kernel(DecodeArgs a) {
   // query fragment: dwords sub + 16 n of each of the G query rows
   const int sub = lane & 15;
   const int rr = lane >> 4;
+  __shared__ uint16_t s_q[kMaxGroup * 2 * kMaxPairs];
+  const bool rope_q = a.q_pos != nullptr;     // un-rotated queries: rotate them into LDS first
+  if (rope_q) {
+    rotate_queries_to_lds(a, b, h, tid, 256, s_q);
+    __syncthreads();
+  }
   float qlo[G][NPL], qhi[G][NPL];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    const uint32_t* qrow = reinterpret_cast<const uint32_t*>(a.q) +
-                           (static_cast<long long>(b) * a.n_q + h * G + g) * P;
+    const uint32_t* qrow = rope_q ? reinterpret_cast<const uint32_t*>(s_q) + g * P
+                                  : reinterpret_cast<const uint32_t*>(a.q) +
+                                        (static_cast<long long>(b) * a.n_q + h * G + g) * P;
 #pragma unroll
     for (int n = 0; n < NPL; ++n) {
       const int j = sub + 16 * n;

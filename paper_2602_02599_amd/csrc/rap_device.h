@@ -45,6 +45,10 @@ struct AppendArgs {
 
 struct DecodeArgs {
   const uint16_t* q;
+  const int32_t* q_pos;     // [B] or null: when given, q is un-rotated and is rotated at q_pos[b] first
+  const int32_t* keep;      // [H_kv, P] original pair indices (only with q_pos)
+  double neg2_log2_theta_over_d;
+  int32_t d_head;
   const uint16_t* k_cache;
   const uint16_t* v_cache;
   const int32_t* seq_lens;
@@ -57,6 +61,35 @@ struct DecodeArgs {
   int64_t cap;
   float scale_log2e;   // softmax scale * log2(e): exponentials are taken as exp2
 };
+
+// Index-aware RoPE of the G query rows of KV head h of sequence b, into LDS as bf16 in the
+// compact order (Eq. (latent-score): the query side of RoPE(X W~_q) . RoPE(X W~_k)^T).  Same
+// arithmetic as the cache append: angle pos * theta^(-2 j / D) with j the ORIGINAL index of the
+// kept pair, fp64 throughout, one rounding to bf16, so the rows are bit-identical to what a
+// separate rotation kernel storing bf16 would have produced.  A pair whose index lies outside
+// [0, D/2) is taken as zero.  Called by every thread of the workgroup; the caller synchronises.
+__device__ __forceinline__ void rotate_queries_to_lds(const DecodeArgs& a, int b, int h, int tid, int nthreads,
+                                                      uint16_t* s_q) {
+  const int P = a.n_pairs, G = a.group;
+  const int t = a.q_pos[b];
+  for (int e = tid; e < G * P; e += nthreads) {
+    const int g = e / P, c = e - g * P;
+    const uint16_t* qrow = a.q + (static_cast<long long>(b) * a.n_q + h * G + g) * (2 * P);
+    const int j = a.keep[h * P + c];
+    uint16_t r0 = 0, r1 = 0;
+    if (j >= 0 && j < a.d_head / 2) {
+      const double phi = static_cast<double>(t) * exp2(static_cast<double>(j) * a.neg2_log2_theta_over_d);
+      double sn, cs;
+      sincos(phi, &sn, &cs);
+      const double x = static_cast<double>(bf16_to_f32(qrow[c]));
+      const double y = static_cast<double>(bf16_to_f32(qrow[c + P]));
+      r0 = f64_to_bf16_rne(x * cs - y * sn);
+      r1 = f64_to_bf16_rne(x * sn + y * cs);
+    }
+    s_q[g * 2 * P + c] = r0;
+    s_q[g * 2 * P + c + P] = r1;
+  }
+}
 
 }  // namespace rap
 #endif  // RAP_DEVICE_H_

@@ -159,6 +159,39 @@ def test_decode_zero_length_and_clamp(rap, kernel):
     H.assert_attn_close(got, _oracle_out(case), "clamped")
 
 
+@pytest.mark.parametrize("kernel", [VALU, MFMA])
+@pytest.mark.parametrize("P,dv,Hq,Hkv,ctx,theta", [(45, 90, 8, 2, 700, 5.0e5), (58, 115, 8, 2, 300, 1.0e6),
+                                                  (32, 64, 10, 2, 1100, 1.0e6), (64, 128, 8, 1, 260, 5.0e5),
+                                                  (3, 5, 3, 1, 40, 1.0e4)])
+def test_decode_with_query_rope(rap, kernel, P, dv, Hq, Hkv, ctx, theta):
+    """rap_decode_attn_rope: un-rotated q + position + kept pairs; the oracle rotates q (float64,
+    one rounding to bf16) and attends.  Also bit-identical to feeding rap_decode_attn the
+    oracle-rotated q, and far positions."""
+    w = I.scaled(I.WORKLOADS["cfg2"], batch=3, n_q_heads=Hq, n_kv_heads=Hkv, n_pairs=P, d_v=dv, ctx=ctx, n_new=1,
+                 rope_theta=theta, ragged_min=max(1, ctx // 3), peaky_frac=0.0, seed=500 + P + ctx)
+    _say("decode+qrope kernel=%d P=%d dv=%d" % (kernel, P, dv))
+    case = I.make_case(w, device=DEV)
+    lens = case.seq_lens.cpu().numpy()
+    for q_pos_np in (lens - 1, np.array([131071, 0, 65537])):
+        q_pos = torch.from_numpy(q_pos_np.astype(np.int32)).to(DEV)
+        q_rot = O.rope_queries_ref(I.bits(case.q), q_pos_np, case.keep.cpu().numpy(), w.rope_theta, w.d_head, w.n_kv_heads)
+        ref = O.attn_ref(q_rot, I.bits(case.k_cache), I.bits(case.v_cache), lens, w.scale)
+        shp = H.shape_of(rap, case)
+        msl = int(lens.max())
+        for rps in (0, 128):
+            tun = rap.tuning(kernel=kernel, rows_per_split=rps)
+            ws = rap.new_workspace(shp, msl, tun)
+            out = torch.full((w.batch, w.n_q_heads, w.d_v), float("nan"), dtype=torch.float32, device=DEV)
+            rap.rap_decode_attn_rope(shp, case.q, q_pos, case.keep, case.k_cache, case.v_cache, case.seq_lens, msl, out,
+                                     float(w.scale), ws, tun)
+            out2 = torch.full_like(out, float("nan"))
+            rap.rap_decode_attn(shp, I.from_bits(q_rot, DEV), case.k_cache, case.v_cache, case.seq_lens, msl, out2,
+                                float(w.scale), ws, tun)
+            torch.cuda.synchronize()
+            H.assert_attn_close(out.cpu().numpy(), ref, "fused q rope rps=%d" % rps)
+            assert torch.equal(out, out2), "fused rotation differs from rotating first"
+
+
 def test_split_invariance(rap):
     """1 range vs many: same result up to fp32 rounding (merge identity on the GPU side)."""
     w = I.scaled(I.WORKLOADS["cfg2"], batch=2, ctx=4000, seed=13)

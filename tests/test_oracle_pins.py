@@ -361,6 +361,37 @@ def test_rho1_attention_is_standard_rope_attention():
     assert np.max(np.abs(got - want)) < 1e-13
 
 
+def test_query_rotation_pins():
+    """rope_queries_ref: position 0 is the identity bit for bit; head a takes the pairs of KV head
+    a // G (checked against a per-head scalar rotation with cmath); and rotating q and every key
+    by the same extra offset leaves the float64 scores unchanged (relative-position property
+    through the whole q-side + k-side chain, before any rounding)."""
+    rng = _rng(21)
+    B, Hq, Hkv, P, D, theta = 2, 6, 2, 5, 32, 1.0e4
+    keep = np.stack([np.sort(rng.choice(D // 2, P, replace=False)) for _ in range(Hkv)])
+    q = _bf16_of(rng.standard_normal((B, Hq, 2 * P)))
+    assert np.array_equal(O.rope_queries_ref(q, np.zeros(B, dtype=int), keep, theta, D, Hkv), q)
+    pos = np.array([7, 1234])
+    got = O.rope_queries_ref(q, pos, keep, theta, D, Hkv)
+    qf = O.bf16_bits_to_f64(q)
+    for b in range(B):
+        for a_h in range(Hq):
+            kp = keep[a_h // 3]
+            want = np.empty(2 * P)
+            for c in range(P):
+                z = complex(qf[b, a_h, c], qf[b, a_h, c + P]) * cmath.exp(1j * int(pos[b]) * theta ** (-2.0 * kp[c] / D))
+                want[c], want[c + P] = z.real, z.imag
+            assert np.array_equal(got[b, a_h], _bf16_of(want))
+    # offset invariance of scores in float64
+    k = rng.standard_normal((9, 2 * P))
+    kpos = np.arange(9, dtype=np.float64) + 100
+    def scores(delta):
+        qr = O.rope_compact(qf[0, 0], np.float64(108 + delta), keep[0], theta, D)
+        kr = O.rope_compact(k, kpos + delta, keep[0], theta, D)
+        return kr @ qr
+    assert np.max(np.abs(scores(0) - scores(54321))) < 1e-9
+
+
 def _brute_force(k_new_vals, v_vals, q_vals, keep, theta, D, scale, G):
     """Whole path with scalar math only: rotate, round to bf16 by nearest search, attend."""
     bits_all = np.arange(0x7F80, dtype=np.uint32).astype(np.uint16)
