@@ -156,6 +156,29 @@ rap_status_t rap_decode_attn_rope(const rap_shape_t* shape, const void* q, const
                                   void* workspace, size_t workspace_bytes,
                                   const rap_tuning_t* tuning, void* stream);
 
+/* One whole decode step of a layer in a single call: append the new token of every sequence
+ * (exactly rap_rope_append with n_new = 1), rotate its query unless it already is, and attend
+ * (exactly rap_decode_attn / rap_decode_attn_rope over the updated cache).  A convenience over the
+ * calls above: same kernels, same results bit for bit, one entry into the library per step.
+ *
+ *   k_new, v_new   dev  bf16  [batch, n_kv_heads, 2P] / [batch, n_kv_heads, d_v]  the new token
+ *   pos            dev  int32 [batch]  its position == cache row (rules of rap_rope_append); also
+ *                                      the query position
+ *   keep_pair_idx  dev  int32 [n_kv_heads, P]
+ *   q              dev  bf16  [batch, n_q_heads, 2P]; q_is_rotated != 0: used as is; 0: rotated at
+ *                                      pos[b] first, as by rap_decode_attn_rope
+ *   k_cache, v_cache  updated in place; seq_lens (normally pos + 1) and the rest as rap_decode_attn.
+ */
+rap_status_t rap_decode_step(const rap_shape_t* shape,
+                             const void* k_new, const void* v_new, const int32_t* pos,
+                             const int32_t* keep_pair_idx,
+                             const void* q, int32_t q_is_rotated,
+                             void* k_cache, void* v_cache,
+                             const int32_t* seq_lens, int64_t max_seq_len,
+                             void* out, float scale,
+                             void* workspace, size_t workspace_bytes,
+                             const rap_tuning_t* tuning, void* stream);
+
 /* Measurement aids (not part of the method): a read-only streaming pass over `bytes` bytes of
  * `src` (16-byte aligned, bytes % 16 == 0) that folds everything into 16 bytes at `sink`, and a
  * plain copy of `bytes` bytes.  They give the bandwidth a trivial kernel reaches on the same

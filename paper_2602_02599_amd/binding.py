@@ -84,6 +84,11 @@ class Rap:
         L.rap_decode_attn_rope.argtypes = [C.POINTER(RapShape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                            C.c_void_p, C.c_int64, C.c_void_p, C.c_float, C.c_void_p, C.c_size_t,
                                            C.POINTER(RapTuning), C.c_void_p]
+        if hasattr(L, "rap_decode_step"):
+            L.rap_decode_step.restype = C.c_int
+            L.rap_decode_step.argtypes = [C.POINTER(RapShape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_float, C.c_void_p,
+                                          C.c_size_t, C.POINTER(RapTuning), C.c_void_p]
         L.rap_stream_read.restype = C.c_int
         L.rap_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.rap_stream_copy.restype = C.c_int
@@ -150,6 +155,21 @@ class Rap:
                                            _ptr(out, torch.float32, "out"), scale, _ptr(workspace, None, "workspace"),
                                            0 if workspace is None else workspace.numel() * workspace.element_size(),
                                            C.byref(tuning) if tuning is not None else None, _stream(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def rap_decode_step(self, shape: RapShape, k_new, v_new, pos, keep_pair_idx, q, q_is_rotated: bool, k_cache, v_cache,
+                        seq_lens, max_seq_len: int, out, scale: float, workspace=None, tuning: Optional[RapTuning] = None,
+                        stream=None, check=True) -> int:
+        st = self.lib.rap_decode_step(C.byref(shape), _ptr(k_new, torch.bfloat16, "k_new"), _ptr(v_new, torch.bfloat16, "v_new"),
+                                      _ptr(pos, torch.int32, "pos"), _ptr(keep_pair_idx, torch.int32, "keep_pair_idx"),
+                                      _ptr(q, torch.bfloat16, "q"), 1 if q_is_rotated else 0,
+                                      _ptr(k_cache, torch.bfloat16, "k_cache"), _ptr(v_cache, torch.bfloat16, "v_cache"),
+                                      _ptr(seq_lens, torch.int32, "seq_lens"), max_seq_len, _ptr(out, torch.float32, "out"),
+                                      scale, _ptr(workspace, None, "workspace"),
+                                      0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                      C.byref(tuning) if tuning is not None else None, _stream(stream))
         if check:
             self._check(st)
         return st

@@ -119,11 +119,17 @@ size_t rap_decode_attn_workspace_bytes(const rap_shape_t* shape, int64_t max_seq
 
 namespace {
 
-// Shared body of rap_decode_attn (q_pos == keep == null) and rap_decode_attn_rope.
+struct NewToken {          // the append fused into rap_decode_step; all null otherwise
+  const void* k_new = nullptr;
+  const void* v_new = nullptr;
+  const int32_t* pos = nullptr;
+};
+
+// Shared body of rap_decode_attn (q_pos == keep == null), rap_decode_attn_rope and rap_decode_step.
 rap_status_t decode_impl(const rap_shape_t* shape, const void* q, const int32_t* q_pos, const int32_t* keep,
                          const void* k_cache, const void* v_cache, const int32_t* seq_lens, int64_t max_seq_len,
                          void* out, float scale, void* workspace, size_t workspace_bytes, const rap_tuning_t* tuning,
-                         void* stream) {
+                         void* stream, const NewToken& nt = NewToken()) {
   rap_status_t st = check_shape(shape);
   if (st != RAP_OK) return st;
   if (max_seq_len < 1) return RAP_ERR_SHAPE;
@@ -171,6 +177,14 @@ rap_status_t decode_impl(const rap_shape_t* shape, const void* q, const int32_t*
   a.lds_wave_bytes = rap::mfma_lds_wave_bytes(a.d_k, a.d_v);
 
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (nt.k_new) {
+    // the append is a launch of its own ahead of the attention.  (Doing it inside the attention
+    // kernel, by the workgroup whose range holds the row, was measured: it is bit-identical but
+    // the extra live state slows the tile loop by more than the launch it saves.)
+    const rap_status_t ast = rap_rope_append(shape, 1, nt.k_new, nt.v_new, nt.pos, keep, const_cast<void*>(k_cache),
+                                             const_cast<void*>(v_cache), stream);
+    if (ast != RAP_OK) return ast;
+  }
   if (tuning && tuning->ev_main_start && hipEventRecord(static_cast<hipEvent_t>(tuning->ev_main_start), s) != hipSuccess)
     return RAP_ERR_HIP;
   hipError_t e = p.kernel == 1 ? rap::launch_decode_valu(a, s) : rap::launch_decode_mfma(a, s);
@@ -190,6 +204,22 @@ rap_status_t rap_decode_attn(const rap_shape_t* shape, const void* q, const void
                              size_t workspace_bytes, const rap_tuning_t* tuning, void* stream) {
   return decode_impl(shape, q, nullptr, nullptr, k_cache, v_cache, seq_lens, max_seq_len, out, scale, workspace,
                      workspace_bytes, tuning, stream);
+}
+
+rap_status_t rap_decode_step(const rap_shape_t* shape, const void* k_new, const void* v_new, const int32_t* pos,
+                             const int32_t* keep_pair_idx, const void* q, int32_t q_is_rotated, void* k_cache,
+                             void* v_cache, const int32_t* seq_lens, int64_t max_seq_len, void* out, float scale,
+                             void* workspace, size_t workspace_bytes, const rap_tuning_t* tuning, void* stream) {
+  if (shape && shape->batch > 0 && max_seq_len >= 1 && (!k_new || !v_new || !pos || !keep_pair_idx)) {
+    const rap_status_t st = check_shape(shape);
+    return st != RAP_OK ? st : RAP_ERR_NULL;
+  }
+  NewToken nt;
+  nt.k_new = k_new;
+  nt.v_new = v_new;
+  nt.pos = pos;
+  return decode_impl(shape, q, q_is_rotated ? nullptr : pos, keep_pair_idx, k_cache, v_cache, seq_lens, max_seq_len, out,
+                     scale, workspace, workspace_bytes, tuning, stream, nt);
 }
 
 rap_status_t rap_decode_attn_rope(const rap_shape_t* shape, const void* q, const int32_t* q_pos,

@@ -70,6 +70,8 @@ def test_decode_rejects_bad_arguments(rap):
     assert f(_shape(rap, batch=0)) == 0
     g = lambda shp: rap.rap_decode_attn_rope(shp, None, None, None, None, None, None, 512, None, 0.1, None, None, check=False)
     assert g(_shape(rap)) == 1 and g(_shape(rap, n_q_heads=7)) == 2 and g(_shape(rap, batch=0)) == 0
+    st = lambda shp: rap.rap_decode_step(shp, None, None, None, None, None, True, None, None, None, 512, None, 0.1, None, None, check=False)
+    assert st(_shape(rap)) == 1 and st(_shape(rap, cache_cap=510)) == 2 and st(_shape(rap, batch=0)) == 0
     assert rap.rap_decode_attn_workspace_bytes(_shape(rap), 512) > 0
     assert rap.rap_decode_attn_workspace_bytes(_shape(rap), 513) == 0
     assert rap.rap_decode_attn_workspace_bytes(_shape(rap, cache_cap=7), 4) == 0

@@ -192,6 +192,59 @@ def test_decode_with_query_rope(rap, kernel, P, dv, Hq, Hkv, ctx, theta):
             assert torch.equal(out, out2), "fused rotation differs from rotating first"
 
 
+@pytest.mark.parametrize("kernel", [VALU, MFMA])
+@pytest.mark.parametrize("P,dv,Hq,Hkv,ctx", [(45, 90, 8, 2, 900), (58, 115, 8, 2, 300), (32, 64, 10, 2, 1500),
+                                             (64, 128, 4, 1, 260), (3, 5, 3, 1, 33)])
+def test_decode_step_fused(rap, kernel, P, dv, Hq, Hkv, ctx):
+    """rap_decode_step == rap_rope_append(1 token) then rap_decode_attn[_rope]: the oracle's
+    composition for the bar, and the two-call sequence of librap itself bit for bit (outputs and
+    both caches).  Ragged lengths; the new token sits at row len-1, for one sequence in the middle
+    of the attended rows (overwriting an old row), for one beyond them (written, not attended)."""
+    w = I.scaled(I.WORKLOADS["cfg2"], batch=4, n_q_heads=Hq, n_kv_heads=Hkv, n_pairs=P, d_v=dv, ctx=ctx, n_new=1,
+                 ragged_min=max(2, ctx // 3), peaky_frac=0.0, seed=700 + P + ctx)
+    _say("decode step kernel=%d P=%d dv=%d ctx=%d" % (kernel, P, dv, ctx))
+    base_case = I.make_case(w, device=DEV)
+    lens = base_case.seq_lens.cpu().numpy().copy()
+    pos_np = (lens - 1).astype(np.int32)
+    pos_np[1] = lens[1] // 2                       # overwrites a row in the middle
+    if lens[2] < base_case.cap:
+        pos_np[2] = lens[2]                        # lands just beyond the attended rows
+    pos = torch.from_numpy(pos_np).to(DEV)
+    k_new = base_case.k_new[:, 0].contiguous()
+    v_new = base_case.v_new[:, 0].contiguous()
+    msl = int(base_case.cap)
+    shp = H.shape_of(rap, base_case)
+    keep_np = base_case.keep.cpu().numpy()
+    for q_is_rotated in (True, False):
+        for rps in (0, 128, 256):
+            tun = rap.tuning(kernel=kernel, rows_per_split=rps)
+            ws = rap.new_workspace(shp, msl, tun)
+            # fused
+            kc1, vc1 = base_case.k_cache.clone(), base_case.v_cache.clone()
+            out1 = torch.full((w.batch, w.n_q_heads, w.d_v), float("nan"), dtype=torch.float32, device=DEV)
+            rap.rap_decode_step(shp, k_new, v_new, pos, base_case.keep, base_case.q, q_is_rotated, kc1, vc1,
+                                base_case.seq_lens, msl, out1, float(w.scale), ws, tun)
+            # two calls
+            kc2, vc2 = base_case.k_cache.clone(), base_case.v_cache.clone()
+            out2 = torch.full_like(out1, float("nan"))
+            rap.rap_rope_append(shp, 1, k_new, v_new, pos, base_case.keep, kc2, vc2)
+            if q_is_rotated:
+                rap.rap_decode_attn(shp, base_case.q, kc2, vc2, base_case.seq_lens, msl, out2, float(w.scale), ws, tun)
+            else:
+                rap.rap_decode_attn_rope(shp, base_case.q, pos, base_case.keep, kc2, vc2, base_case.seq_lens, msl, out2,
+                                         float(w.scale), ws, tun)
+            torch.cuda.synchronize()
+            assert torch.equal(kc1.view(torch.int16), kc2.view(torch.int16)) and torch.equal(vc1.view(torch.int16), vc2.view(torch.int16))
+            assert torch.equal(out1, out2), "fused step differs from append + decode (rps=%d)" % rps
+            # oracle
+            okc, ovc = I.bits(base_case.k_cache).copy(), I.bits(base_case.v_cache).copy()
+            O.append_ref(I.bits(k_new)[:, None], I.bits(v_new)[:, None], pos_np[:, None], keep_np, okc, ovc, w.rope_theta, w.d_head)
+            assert H.bf16_ulp_distance(I.bits(kc1), okc).max() <= 1 and np.array_equal(I.bits(vc1), ovc)
+            qb = I.bits(base_case.q) if q_is_rotated else O.rope_queries_ref(I.bits(base_case.q), pos_np, keep_np, w.rope_theta, w.d_head, w.n_kv_heads)
+            ref = O.attn_ref(qb, I.bits(kc1), I.bits(vc1), lens, w.scale)
+            H.assert_attn_close(out1.cpu().numpy(), ref, "fused step rps=%d rotated=%s" % (rps, q_is_rotated))
+
+
 def test_split_invariance(rap):
     """1 range vs many: same result up to fp32 rounding (merge identity on the GPU side)."""
     w = I.scaled(I.WORKLOADS["cfg2"], batch=2, ctx=4000, seed=13)
