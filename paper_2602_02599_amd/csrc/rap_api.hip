@@ -90,6 +90,9 @@ rap_status_t rap_rope_append(const rap_shape_t* shape, int32_t n_new, const void
   if (n_new == 0 || shape->batch == 0) return RAP_OK;
   if (!k_new || !v_new || !pos || !keep_pair_idx || !k_cache || !v_cache) return RAP_ERR_NULL;
   if (static_cast<int64_t>(shape->batch) * n_new > 0x7fffffffLL) return RAP_ERR_UNSUPPORTED;
+  if ((reinterpret_cast<uintptr_t>(k_new) & 3) || (reinterpret_cast<uintptr_t>(v_new) & 3) ||
+      (reinterpret_cast<uintptr_t>(k_cache) & 3) || (reinterpret_cast<uintptr_t>(v_cache) & 3))
+    return RAP_ERR_SHAPE;
   rap::AppendArgs a;
   a.k_new = static_cast<const uint16_t*>(k_new);
   a.v_new = static_cast<const uint16_t*>(v_new);

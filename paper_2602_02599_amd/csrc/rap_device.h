@@ -18,17 +18,20 @@ __device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_flo
 __device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
 
-// fp64 -> bf16 with a single round-to-nearest-even: truncate to fp32 keeping a sticky bit
-// (round-to-odd), then round the fp32 to its upper 16 bits.
+// fp64 -> bf16 with a single round-to-nearest-even.  The hardware conversion to fp32 (nearest
+// even) cannot carry a value across a bf16 rounding boundary, because every such boundary is an
+// fp32 number; it can only land ON one (low half exactly 0x8000) from either side.  In that case
+// the fp32 is moved one step back towards the side x came from, after which rounding the fp32 to
+// its upper 16 bits gives the correctly rounded result.
 __device__ __forceinline__ uint16_t f64_to_bf16_rne(double x) {
-  float f = __double2float_rz(x);
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7f800000u) == 0x7f800000u) {                 // inf / nan pass through
-    return static_cast<uint16_t>((u >> 16) | ((u & 0xffffu) ? 0x40u : 0u));
-  }
-  if (static_cast<double>(f) != x) u |= 1u;                // sticky
+  const float f = static_cast<float>(x);
+  const uint32_t u0 = __float_as_uint(f);
+  const double fd = static_cast<double>(f);
+  uint32_t u = u0 + ((fabs(x) > fabs(fd)) ? 1u : 0u);               // sign-magnitude: +1 is away from zero
+  u -= (fabs(x) < fabs(fd)) ? 1u : 0u;
+  u = (u0 & 0xffffu) == 0x8000u ? u : u0;
   u += 0x7fffu + ((u >> 16) & 1u);
-  return static_cast<uint16_t>(u >> 16);
+  return static_cast<uint16_t>(x != x ? (u0 >> 16) | 0x40u : u >> 16);   // NaN stays NaN
 }
 
 struct AppendArgs {

@@ -67,6 +67,95 @@ def test_append_far_positions(rap, theta):
     assert off <= n // 1000 + 1
 
 
+@pytest.mark.parametrize("P,dv,H_kv,n_new,B,theta", [(45, 90, 8, 100, 2, 5.0e5), (58, 115, 2, 37, 3, 1.0e6), (32, 64, 4, 16, 1, 1.0e6),
+                                                    (64, 128, 2, 300, 2, 5.0e5), (3, 5, 2, 65, 2, 1.0e4)])
+def test_append_bulk(rap, P, dv, H_kv, n_new, B, theta):
+    """Prefill-sized appends take the run-based kernel (angle advanced by one rotation per
+    consecutive position): consecutive runs, runs with jumps and repeats of far positions,
+    out-of-range positions in the middle of a run."""
+    w = I.scaled(I.WORKLOADS["cfg4"], batch=B, n_q_heads=H_kv, n_kv_heads=H_kv, n_pairs=P, d_v=dv, ctx=131072, n_new=n_new,
+                 rope_theta=theta, seed=60 + P)
+    _say("append bulk P=%d dv=%d n_new=%d" % (P, dv, n_new))
+    case = I.make_case(I.scaled(w, ctx=4096 + n_new), device=DEV)
+    rng = np.random.Generator(np.random.PCG64(5))
+    for mode in ("consecutive", "jumps"):
+        if mode == "consecutive":
+            start = rng.integers(0, case.cap - n_new, size=B)
+            pos = start[:, None] + np.arange(n_new)[None, :]
+        else:
+            pos = np.empty((B, n_new), dtype=np.int64)
+            for b in range(B):
+                perm = rng.permutation(case.cap)[:n_new]          # distinct rows, arbitrary order
+                seg = np.sort(perm[: n_new // 2])                  # first half ascending with gaps
+                pos[b] = np.concatenate([seg, perm[n_new // 2:]])
+            pos[0, 3] = -5                                         # skipped
+            pos[B - 1, n_new - 2] = case.cap + 7                   # skipped
+        case.pos = torch.from_numpy(pos.astype(np.int32)).to(DEV)
+        kc, vc = I.bits(case.k_cache), I.bits(case.v_cache)
+        H.run_append(rap, case)
+        torch.cuda.synchronize()
+        ok = (pos >= 0) & (pos < case.cap)
+        okc, ovc = kc.copy(), vc.copy()
+        keep = case.keep.cpu().numpy()
+        k_new, v_new = I.bits(case.k_new), I.bits(case.v_new)
+        for b in range(B):
+            for n in range(n_new):
+                if ok[b, n]:
+                    t = int(pos[b, n])
+                    for h in range(H_kv):
+                        rot = O.rope_compact(O.bf16_bits_to_f64(k_new[b, n, h]), np.float64(t), keep[h], theta, w.d_head)
+                        okc[b, h, t] = O.f64_to_bf16_bits_rne(rot)
+                        ovc[b, h, t] = v_new[b, n, h]
+        gk, gv = I.bits(case.k_cache), I.bits(case.v_cache)
+        assert np.array_equal(gv, ovc), mode + ": V cache differs"
+        dist = H.bf16_ulp_distance(gk, okc)
+        assert dist.max() <= 1, "%s: K off by %d ulp" % (mode, dist.max())
+        assert (dist != 0).sum() <= dist.size // 1000 + 1
+
+
+@pytest.mark.parametrize("P,dv", [(45, 90), (58, 115)])
+def test_append_bulk_long(rap, P, dv):
+    """A prefill-sized append (each wavefront walks several runs and carries the angle from one
+    run into the next): V against the input bits everywhere, K against the oracle on sampled rows
+    that include run and wavefront boundaries, a jump in the positions and a shuffled stretch."""
+    B, H_kv, n_new = 4, 8, 16400
+    w = I.scaled(I.WORKLOADS["cfg4"], batch=B, n_q_heads=H_kv, n_kv_heads=H_kv, n_pairs=P, d_v=dv, ctx=n_new + 40, n_new=n_new,
+                 rope_theta=5.0e5, seed=77)
+    _say("append bulk long P=%d dv=%d" % (P, dv))
+    case = I.make_case(w, device=DEV, fill_unused=False)
+    assert case.cap >= n_new + 40
+    pos = np.tile(np.arange(n_new, dtype=np.int64), (B, 1)) + np.array([0, 3, 17, 1])[:, None]
+    pos[3, 8000:] += 5                                             # a jump inside a wavefront's walk
+    rng = np.random.Generator(np.random.PCG64(9))
+    pos[2, 4100:4200] = pos[2, 4100:4200][rng.permutation(100)]    # runs that are not in order
+    pos[1, 12345] = -1                                             # skipped
+    case.pos = torch.from_numpy(pos.astype(np.int32)).to(DEV)
+    before_k = I.bits(case.k_cache)[1, :, 12345 + 3].copy()
+    H.run_append(rap, case)
+    torch.cuda.synchronize()
+    gk, gv = I.bits(case.k_cache), I.bits(case.v_cache)
+    k_new, v_new = I.bits(case.k_new), I.bits(case.v_new)
+    keep = case.keep.cpu().numpy()
+    for b in range(B):
+        ok = pos[b] >= 0
+        assert np.array_equal(gv[b][:, pos[b][ok]], np.transpose(v_new[b][ok], (1, 0, 2))), "V rows differ, b=%d" % b
+    assert np.array_equal(gk[1, :, 12345 + 3], before_k), "skipped row was written"
+    ns = np.unique(np.concatenate([rng.integers(0, n_new, 400), [0, 15, 16, 63, 64, 65, 255, 256, 257, 4099, 4100, 4150, 4199, 4200,
+                                                                   7999, 8000, 8001, 12344, 12346, n_new - 17, n_new - 16, n_new - 1]]))
+    worst, n_off, n_all = 0, 0, 0
+    for b in range(B):
+        for n in ns:
+            t = int(pos[b, n])
+            if t < 0:
+                continue
+            for h in range(H_kv):
+                ref = O.f64_to_bf16_bits_rne(O.rope_compact(O.bf16_bits_to_f64(k_new[b, n, h]), np.float64(t), keep[h], w.rope_theta, w.d_head))
+                dist = H.bf16_ulp_distance(gk[b, h, t], ref)
+                worst = max(worst, int(dist.max())); n_off += int((dist != 0).sum()); n_all += dist.size
+    assert worst <= 1, "K off by %d ulp" % worst
+    assert n_off <= n_all // 1000 + 1, "%d of %d elements differ" % (n_off, n_all)
+
+
 def test_append_skips_out_of_range(rap):
     w = I.scaled(I.WORKLOADS["cfg2"], batch=1, ctx=64, n_new=3, peaky_frac=0.0, seed=5)
     case = I.make_case(w, device=DEV)
