@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void append_kernel(AppendArgs a) {
     // theta^(-2j/D) = 2^(j * (-2 log2(theta) / D)); the factor is taken in fp64 on the host
     const double phi = static_cast<double>(t) * exp2(static_cast<double>(j) * a.neg2_log2_theta_over_d);
     double sn, cs;
-    sincos(phi, &sn, &cs);
+    sincos_f64(phi, &sn, &cs);
     const double x = static_cast<double>(bf16_to_f32(kx));
     const double y = static_cast<double>(bf16_to_f32(ky));
     uint16_t* kdst = a.k_cache + row * (2 * P);
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs
   const bool rot = j >= 0 && j < a.d_head / 2;                  // bad index: pair is skipped
   const double f = rot ? exp2(static_cast<double>(j) * a.neg2_log2_theta_over_d) : 0.0;
   double sf, cf;
-  sincos(f, &sf, &cf);                                           // one step of the position
+  sincos_f64(f, &sf, &cf);                                           // one step of the position
   const int x_lane = has_pair ? (lane >> 1) << 2 : 0, x_half = lane & 1;
   const int y_lane = has_pair ? ((lane + P) >> 1) << 2 : 0, y_half = (lane + P) & 1;
   // memory role: lane i < P moves word i = elements 2i (pair c0) and 2i+1 (pair c1)
@@ -136,7 +136,7 @@ __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs
                   static_cast<uint32_t>((vsrc0 + i * vstride)[vl1]) << 16;
         }
       }
-      if (!(anchored && t0 == t_next)) sincos(static_cast<double>(t0) * f, &sn, &cs);   // exact
+      if (!(anchored && t0 == t_next)) sincos_f64(static_cast<double>(t0) * f, &sn, &cs);   // exact
       const long long row0 = (static_cast<long long>(b) * a.n_kv + h) * a.cap + t0;
       uint16_t* kdst0 = a.k_cache + row0 * (2 * P);
       uint16_t* vdst0 = a.v_cache + row0 * a.d_v;
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs
       const long long row = (static_cast<long long>(b) * a.n_kv + h) * a.cap + t;
       if (rot) {
         double s1, c1d;
-        sincos(static_cast<double>(t) * f, &s1, &c1d);
+        sincos_f64(static_cast<double>(t) * f, &s1, &c1d);
         const double x = static_cast<double>(bf16_to_f32(ksrc[lane]));
         const double y = static_cast<double>(bf16_to_f32(ksrc[lane + P]));
         uint16_t* kdst = a.k_cache + row * (2 * P);
