@@ -84,30 +84,32 @@ class Job:
         self.bytes_per_step = float(np.mean([kv_bytes(w, c.seq_lens.cpu().numpy()) for c in self.cases]))
         self.i = 0
 
-    def step(self, tuning=None, fused_q_rope=False):
+    def step(self, tuning=None, mode="two"):
+        """One decode step.  mode "step": one rap_decode_step call (query already rotated);
+        "step_rope": the same with the query rotation fused in; "two": rap_rope_append then
+        rap_decode_attn.  Workloads that append several tokens per step always take "two"."""
         c = self.cases[self.i % len(self.cases)]
         self.i += 1
         w = self.w
-        self.rap.rap_rope_append(self.shape, w.n_new, c.k_new, c.v_new, c.pos, c.keep, c.k_cache, c.v_cache)
-        if fused_q_rope:
-            # q taken as un-rotated, rotated at the last position inside the decode kernel
-            self.rap.rap_decode_attn_rope(self.shape, c.q, c.qpos_last, c.keep, c.k_cache, c.v_cache,
-                                          c.seq_lens, self.max_len, self.out, float(w.scale), self.ws, tuning)
-        else:
+        if w.n_new != 1 or mode == "two":
+            self.rap.rap_rope_append(self.shape, w.n_new, c.k_new, c.v_new, c.pos, c.keep, c.k_cache, c.v_cache)
             self.rap.rap_decode_attn(self.shape, c.q, c.k_cache, c.v_cache, c.seq_lens, self.max_len, self.out,
                                      float(w.scale), self.ws, tuning)
+        else:
+            self.rap.rap_decode_step(self.shape, c.k_new1, c.v_new1, c.pos1, c.keep, c.q, mode == "step", c.k_cache,
+                                     c.v_cache, c.seq_lens, self.max_len, self.out, float(w.scale), self.ws, tuning)
 
-    def timed(self, steps, warmup, fused_q_rope=False):
+    def timed(self, steps, warmup, mode="two"):
         torch = self.torch
-        if fused_q_rope:
-            for c in self.cases:
-                c.qpos_last = c.pos[:, -1].contiguous()
+        for c in self.cases:
+            c.k_new1, c.v_new1 = c.k_new[:, -1].contiguous(), c.v_new[:, -1].contiguous()
+            c.pos1 = c.pos[:, -1].contiguous()
         for _ in range(warmup):
-            self.step(fused_q_rope=fused_q_rope)
+            self.step(mode=mode)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
-            self.step(fused_q_rope=fused_q_rope)
+            self.step(mode=mode)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
@@ -199,7 +201,8 @@ def main():
     w = job.w
     sec = job.timed(args.steps, args.warmup)
     gbps = job.bytes_per_step / sec / 1e9
-    sec_fused = job.timed(args.steps, args.warmup, fused_q_rope=True)
+    sec_one = job.timed(args.steps, args.warmup, mode="step")
+    sec_rope = job.timed(args.steps, args.warmup, mode="step_rope")
     k_mean_ms, k_min_ms = job.kernel_ms(args.steps, ev)
     achieved = job.bytes_per_step / (k_mean_ms * 1e-3) / 1e9
 
@@ -231,13 +234,17 @@ def main():
         "value": round(gbps, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(sec * 1e3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 storage, f32 accumulate", "data": "synthetic",
-        "config": {"workload": "%s: B=%d, %d/%d heads, ctx=%d, d_k=%d, d_v=%d, rho=%.1f, one layer; step = rope_append(1 token/seq) + decode_attn"
-                               % (w.name, w.batch, w.n_q_heads, w.n_kv_heads, w.ctx, w.d_k, w.d_v, w.n_pairs / (w.d_head / 2)),
+        "config": {"workload": "%s: B=%d, %d/%d heads, ctx=%d, d_k=%d, d_v=%d, rho=%.1f, one layer; step = rap_rope_append(%d token/seq) + rap_decode_attn"
+                               % (w.name, w.batch, w.n_q_heads, w.n_kv_heads, w.ctx, w.d_k, w.d_v, w.n_pairs / (w.d_head / 2), w.n_new),
                    "cache_copies_rotated": args.buffers, "kv_bytes_per_step": int(job.bytes_per_step)},
         "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
         "tokens_per_s": round(w.batch / sec, 1),
         "stream_read_GBps": round(stream_gbps, 1),
-        "step_with_fused_query_rope_ms": round(sec_fused * 1e3, 5),
+        # the same step as ONE rap_decode_step call (new token handled inside the attention launch),
+        # with the query already rotated and with the query rotation fused in as well
+        "one_call_step": {"calls": "rap_decode_step", "ms_per_step": round(sec_one * 1e3, 5),
+                          "value": round(job.bytes_per_step / sec_one / 1e9, 2), "unit": "GB/s",
+                          "ms_per_step_with_query_rope": round(sec_rope * 1e3, 5)},
         "roofline": {"bound": "hbm", "kernel": "decode_mfma_kernel", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": read_traffic(os.path.join(ROOT, "profiles", "traffic_decode_mfma_%s.txt" % w.name)),

@@ -157,9 +157,15 @@ rap_status_t rap_decode_attn_rope(const rap_shape_t* shape, const void* q, const
                                   const rap_tuning_t* tuning, void* stream);
 
 /* One whole decode step of a layer in a single call: append the new token of every sequence
- * (exactly rap_rope_append with n_new = 1), rotate its query unless it already is, and attend
- * (exactly rap_decode_attn / rap_decode_attn_rope over the updated cache).  A convenience over the
- * calls above: same kernels, same results bit for bit, one entry into the library per step.
+ * (the result of rap_rope_append with n_new = 1), rotate its query unless it already is, and
+ * attend (the result of rap_decode_attn / rap_decode_attn_rope over the updated cache).
+ * On the matrix-core kernel the append is not a launch of its own: the attention kernel scans
+ * the cache without row pos[b], one extra workgroup per (sequence, KV head) rotates the new K
+ * row, writes it and the V row into the caches and scores the token straight from registers, and
+ * the combining kernel folds that score in.  The caches end up bit-identical to the two-call
+ * sequence and every value entering the sums is the same; only the order of fp32 additions
+ * differs (outputs agree to fp32 rounding).  The workspace is required whatever the number of
+ * row ranges.  With tuning->kernel = 1 (vector-ALU kernel) the call is the two launches.
  *
  *   k_new, v_new   dev  bf16  [batch, n_kv_heads, 2P] / [batch, n_kv_heads, d_v]  the new token
  *   pos            dev  int32 [batch]  its position == cache row (rules of rap_rope_append); also

@@ -71,10 +71,10 @@ rap_status_t make_plan(const rap_shape_t* s, int64_t max_seq_len, const rap_tuni
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 size_t part_acc_bytes(const rap_shape_t* s, const Plan& p) {
-  return align_up(static_cast<size_t>(s->batch) * s->n_q_heads * p.n_split * s->d_v * sizeof(float), 256);
+  return align_up(static_cast<size_t>(s->batch) * s->n_q_heads * (p.n_split + 1) * s->d_v * sizeof(float), 256);
 }
 size_t part_ml_bytes(const rap_shape_t* s, const Plan& p) {
-  return align_up(static_cast<size_t>(s->batch) * s->n_q_heads * p.n_split * 2 * sizeof(float), 256);
+  return align_up(static_cast<size_t>(s->batch) * s->n_q_heads * (p.n_split + 1) * 2 * sizeof(float), 256);
 }
 
 }  // namespace
@@ -146,11 +146,15 @@ rap_status_t decode_impl(const rap_shape_t* shape, const void* q, const int32_t*
   st = make_plan(shape, max_seq_len, tuning, &p);
   if (st != RAP_OK) return st;
   const size_t need = part_acc_bytes(shape, p) + part_ml_bytes(shape, p) + 256;
-  if (p.n_split > 1) {
+  // the one-call step on the matrix-core kernel hands the new token to the combining kernel, which
+  // therefore always runs
+  const bool fused_step = nt.k_new != nullptr && p.kernel == 2;
+  if (p.n_split > 1 || fused_step) {
     if (!workspace || workspace_bytes < need) return RAP_ERR_WORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) & 255) return RAP_ERR_WORKSPACE;
   }
-  if (p.n_split > 65535) return RAP_ERR_UNSUPPORTED;
+  if (p.n_split > 65535 ||
+      (static_cast<int64_t>(p.n_split) + 1) * shape->n_kv_heads * shape->batch > 0x7fffffffLL) return RAP_ERR_UNSUPPORTED;
 
   rap::DecodeArgs a;
   memset(&a, 0, sizeof(a));
@@ -175,15 +179,23 @@ rap_status_t decode_impl(const rap_shape_t* shape, const void* q, const int32_t*
   a.max_len = static_cast<int32_t>(max_seq_len);
   a.rows_per_split = p.rows_per_split;
   a.n_split = p.n_split;
+  a.n_slots = p.n_split;
   a.cap = shape->cache_cap;
   a.scale_log2e = scale * 1.4426950408889634f;
   a.lds_wave_bytes = rap::mfma_lds_wave_bytes(a.d_k, a.d_v);
+  a.direct_out = (p.n_split == 1 && !fused_step) ? 1 : 0;
+  if (fused_step) {
+    a.k_new = static_cast<const uint16_t*>(nt.k_new);
+    a.v_new = static_cast<const uint16_t*>(nt.v_new);
+    a.new_pos = nt.pos;
+    a.n_slots = p.n_split + 1;
+    a.k_cache_w = static_cast<uint16_t*>(const_cast<void*>(k_cache));
+    a.v_cache_w = static_cast<uint16_t*>(const_cast<void*>(v_cache));
+  }
 
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (nt.k_new) {
-    // the append is a launch of its own ahead of the attention.  (Doing it inside the attention
-    // kernel, by the workgroup whose range holds the row, was measured: it is bit-identical but
-    // the extra live state slows the tile loop by more than the launch it saves.)
+  if (nt.k_new && !fused_step) {
+    // vector-ALU kernel: the append is a launch of its own ahead of the attention
     const rap_status_t ast = rap_rope_append(shape, 1, nt.k_new, nt.v_new, nt.pos, keep, const_cast<void*>(k_cache),
                                              const_cast<void*>(v_cache), stream);
     if (ast != RAP_OK) return ast;
@@ -194,7 +206,7 @@ rap_status_t decode_impl(const rap_shape_t* shape, const void* q, const int32_t*
   if (e != hipSuccess) return RAP_ERR_HIP;
   if (tuning && tuning->ev_main_stop && hipEventRecord(static_cast<hipEvent_t>(tuning->ev_main_stop), s) != hipSuccess)
     return RAP_ERR_HIP;
-  if (p.n_split > 1 && rap::launch_merge(a, s) != hipSuccess) return RAP_ERR_HIP;
+  if ((p.n_split > 1 || fused_step) && rap::launch_merge(a, s) != hipSuccess) return RAP_ERR_HIP;
   return RAP_OK;
 }
 

@@ -60,6 +60,89 @@ __device__ __forceinline__ void wave_lds_sync() {
 // before the accumulators are rescaled: 2^64 * (rows of a range) * |v| stays far below fp32 max.
 constexpr float kHeadroom = 64.f;
 
+// One-call decode step: the new token, handled by one wavefront of a workgroup of its own per
+// (b, h) (grid index n_split, next to the workgroups that scan the ranges), so that nobody who
+// streams rows waits for it.  Lane c < P rotates pair c of the
+// new K row exactly as the append kernel does (Eq. (rope) at the pair's original index, fp64, one
+// rounding to bf16) and writes it into the cache, the lanes copy the V row, and the rotated row,
+// still in registers, is scored against the G query rows (s_q: rotated query rows in LDS, or null
+// when the query arrived rotated).  The token is left as (m = score, l = 1, acc = V row) in the
+// slot behind the ranges, with m = -inf when row t is not among the attended ones.  All values
+// are those a separate append followed by reading the cache would have produced.  The loads are
+// a step of their own so that they can be requested together with the workgroup's other first loads.
+struct TokenRegs {
+  int j;
+  uint16_t kx, ky, v0, v1;
+  uint16_t qx[kMaxGroup], qy[kMaxGroup];
+};
+
+__device__ __forceinline__ void token_load(const DecodeArgs& a, int b, int h, int lane, bool rope_q, TokenRegs& r) {
+  const int P = a.n_pairs;
+  const long long nrow = static_cast<long long>(b) * a.n_kv + h;
+  const bool hp = lane < P;
+  r.j = hp ? a.keep[h * P + lane] : -1;
+  r.kx = hp ? a.k_new[nrow * 2 * P + lane] : 0;
+  r.ky = hp ? a.k_new[nrow * 2 * P + lane + P] : 0;
+  r.v0 = lane < a.d_v ? a.v_new[nrow * a.d_v + lane] : 0;
+  r.v1 = lane + kWave < a.d_v ? a.v_new[nrow * a.d_v + lane + kWave] : 0;
+#pragma unroll
+  for (int g = 0; g < kMaxGroup; ++g) {
+    const bool have = !rope_q && hp && g < a.group;
+    const uint16_t* qrow = a.q + (static_cast<long long>(b) * a.n_q + h * a.group + (g < a.group ? g : 0)) * 2 * P;
+    r.qx[g] = have ? qrow[lane] : 0;
+    r.qy[g] = have ? qrow[lane + P] : 0;
+  }
+}
+
+__device__ __forceinline__ void token_finish(const DecodeArgs& a, int b, int h, int lane, int t, bool attended,
+                                             const uint16_t* s_q, const TokenRegs& r) {
+  const int P = a.n_pairs;
+  const bool stored = t >= 0 && t < a.cap;
+  const long long nrow = static_cast<long long>(b) * a.n_kv + h;
+  const long long row = nrow * a.cap + t;
+  uint16_t kxr = 0, kyr = 0;
+  if (lane < P && stored) {
+    if (r.j >= 0 && r.j < a.d_head / 2) {
+      const double phi = static_cast<double>(t) * exp2(static_cast<double>(r.j) * a.neg2_log2_theta_over_d);
+      double sn, cs;
+      sincos_f64(phi, &sn, &cs);
+      const double x = static_cast<double>(bf16_to_f32(r.kx)), y = static_cast<double>(bf16_to_f32(r.ky));
+      kxr = f64_to_bf16_rne(x * cs - y * sn);
+      kyr = f64_to_bf16_rne(x * sn + y * cs);
+      a.k_cache_w[row * 2 * P + lane] = kxr;
+      a.k_cache_w[row * 2 * P + lane + P] = kyr;
+    } else {   // bad pair index: the append leaves these two elements as they are
+      kxr = a.k_cache_w[row * 2 * P + lane];
+      kyr = a.k_cache_w[row * 2 * P + lane + P];
+    }
+  }
+  if (stored) {
+    if (lane < a.d_v) a.v_cache_w[row * a.d_v + lane] = r.v0;
+    if (lane + kWave < a.d_v) a.v_cache_w[row * a.d_v + lane + kWave] = r.v1;
+  }
+  const float kxf = bf16_to_f32(kxr), kyf = bf16_to_f32(kyr);
+#pragma unroll
+  for (int g = 0; g < kMaxGroup; ++g) {
+    if (g < a.group) {
+      uint16_t qx = r.qx[g], qy = r.qy[g];
+      if (s_q != nullptr && lane < P) {
+        qx = s_q[g * 2 * P + lane];
+        qy = s_q[g * 2 * P + lane + P];
+      }
+      float part = lane < P ? fmaf(bf16_to_f32(qx), kxf, bf16_to_f32(qy) * kyf) : 0.f;
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) part += __shfl_xor(part, o);
+      const long long slot = (static_cast<long long>(b) * a.n_q + h * a.group + g) * a.n_slots + a.n_split;
+      if (lane == 0) {
+        a.part_ml[slot * 2 + 0] = attended ? part * a.scale_log2e : -INFINITY;
+        a.part_ml[slot * 2 + 1] = attended ? 1.f : 0.f;
+      }
+      if (lane < a.d_v) a.part_acc[slot * a.d_v + lane] = attended ? bf16_to_f32(r.v0) : 0.f;
+      if (lane + kWave < a.d_v) a.part_acc[slot * a.d_v + lane + kWave] = attended ? bf16_to_f32(r.v1) : 0.f;
+    }
+  }
+}
+
 // KCH = ceil(d_k / 32) score k-steps, NT = 16-channel output tiles.  VPAIR (even d_v): a lane
 // reads two adjacent V channels with one 4-byte LDS read and tile nt holds channels
 // 32 (nt / 2) + 2 l16 + (nt & 1); otherwise 2-byte reads and tile nt holds channels 16 nt + l16.
@@ -74,17 +157,47 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction
   const int l16 = lane & 15;
   const int lg = lane >> 4;
-  const int split = blockIdx.x;
-  const int h = blockIdx.y;
-  const int b = blockIdx.z;
+  // One-dimensional grid.  Workgroup L < n_split * H_kv * B scans a row range: consecutive L share
+  // a (b, h), and the range index is rotated by the (b, h) index so that range 0 of different
+  // sequences falls on different XCDs (hardware places workgroup L on XCD L mod 8; with a ragged
+  // batch the low ranges are the ones that hold rows, and n_split is often a multiple of 8).
+  // The workgroups after those, one per (b, h), exist in the decode step only and take the new
+  // token; coming last they do not disturb the placement of the scanning workgroups.
+  const int n_scan = a.n_split * a.n_kv * a.batch;
+  const int wg = blockIdx.x;
+  const int slab_id = wg < n_scan ? wg / a.n_split : wg - n_scan;
+  const int split = wg < n_scan ? (wg - slab_id * a.n_split + slab_id) % a.n_split : a.n_split;
+  const int h = slab_id % a.n_kv;
+  const int b = slab_id / a.n_kv;
 
   int len = a.seq_lens[b];
   len = len < 0 ? 0 : (len > a.max_len ? a.max_len : len);
+  // One-call decode step: the new token's row is not in the cache yet.  As the last row it simply
+  // shortens the sequence; anywhere else inside it, the row is masked like the rows beyond the end.
+  int t_skip = -1;
+  __shared__ uint16_t s_q[kMaxGroup * 2 * kMaxPairs];
+  const bool rope_q = a.q_pos != nullptr;
+  bool tok_attended = false;
+  if (a.new_pos != nullptr) {
+    t_skip = a.new_pos[b];
+    tok_attended = t_skip >= 0 && t_skip < len;
+    if (len > 0 && t_skip == len - 1) len -= 1;
+  }
+  if (split == a.n_split) {                            // the workgroup of the new token (decode step only)
+    TokenRegs tk;
+    if (wave == 0) token_load(a, b, h, lane, rope_q, tk);
+    if (rope_q) {
+      rotate_queries_to_lds(a, b, h, tid, 256, s_q);
+      __syncthreads();
+    }
+    if (wave == 0) token_finish(a, b, h, lane, t_skip, tok_attended, rope_q ? s_q : nullptr, tk);
+    return;
+  }
   const int r0 = split * a.rows_per_split;
   if (r0 >= len) {
     // no rows for this workgroup.  With a single range nobody else writes the output row of an
     // empty sequence; with several ranges the combining kernel does.
-    if (a.n_split == 1)
+    if (a.direct_out)
       for (int e = tid; e < a.group * a.d_v; e += 256)
         a.out[(static_cast<long long>(b) * a.n_q + h * a.group) * a.d_v + e] = 0.f;
     return;
@@ -149,8 +262,6 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
 
   // ---- query rows as the B operand: lane (l16 = head slot, lg = k sub-chunk).  With q_pos the
   // rows arrive un-rotated: the workgroup rotates them into LDS first, while its first tile flies.
-  __shared__ uint16_t s_q[kMaxGroup * 2 * kMaxPairs];
-  const bool rope_q = a.q_pos != nullptr;
   if (rope_q) {
     rotate_queries_to_lds(a, b, h, tid, 256, s_q);
     __syncthreads();
@@ -218,6 +329,7 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
 
     // ---- softmax numerators against a reference that rarely moves (log2 units)
     const int nv = min(kTileRows, r1 - base);       // valid rows in this tile, >= 1
+    const int skip_rel = t_skip - base;             // the one row to leave out, if it is in this tile
     float x[2][4];
     float tmax = -INFINITY;
 #pragma unroll
@@ -225,7 +337,7 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const float s = sc[rt][r] * a.scale_log2e;
-        x[rt][r] = (16 * rt + 4 * lg + r) < nv ? s : -INFINITY;
+        x[rt][r] = ((16 * rt + 4 * lg + r) < nv && (16 * rt + 4 * lg + r) != skip_rel) ? s : -INFINITY;
         tmax = fmaxf(tmax, x[rt][r]);
       }
     if (__any(tmax > m_run + kHeadroom)) {
@@ -350,13 +462,13 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
       }
     }
     const long long hq = static_cast<long long>(b) * a.n_q + h * G + g;
-    if (a.n_split == 1) {
+    if (a.direct_out) {
       a.out[hq * dv + c] = den > 0.f ? num / den : 0.f;
     } else {
-      a.part_acc[(hq * a.n_split + split) * dv + c] = num;
+      a.part_acc[(hq * a.n_slots + split) * dv + c] = num;
       if (c == 0) {
-        a.part_ml[(hq * a.n_split + split) * 2 + 0] = mstar;
-        a.part_ml[(hq * a.n_split + split) * 2 + 1] = den;
+        a.part_ml[(hq * a.n_slots + split) * 2 + 0] = mstar;
+        a.part_ml[(hq * a.n_slots + split) * 2 + 1] = den;
       }
     }
   }
@@ -364,7 +476,8 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
 
 template <int KCH, int NT, bool VPAIR>
 hipError_t launch_inst(const DecodeArgs& a, hipStream_t stream) {
-  dim3 grid(a.n_split, a.n_kv, a.batch), block(256);
+  // scanning workgroups, then (decode step: n_slots = n_split + 1) one per (b, h) for the new token
+  dim3 grid(static_cast<unsigned>(a.n_slots) * a.n_kv * a.batch), block(256);
   const size_t lds = 4 * static_cast<size_t>(a.lds_wave_bytes);
   if (lds > 64 * 1024) {
     // more than the default dynamic-LDS limit: raise it once per kernel (gfx950 has 160 KB per CU)

@@ -39,7 +39,7 @@ __global__ __launch_bounds__(256) void decode_valu_kernel(DecodeArgs a) {
   if (r0 >= len) {
     // no rows for this workgroup.  With a single range nobody else writes the output row of an
     // empty sequence; with several ranges the combining kernel does.
-    if (a.n_split == 1)
+    if (a.direct_out)
       for (int e = tid; e < G * a.d_v; e += 256)
         a.out[(static_cast<long long>(b) * a.n_q + h * G) * a.d_v + e] = 0.f;
     return;
@@ -189,17 +189,17 @@ __global__ __launch_bounds__(256) void decode_valu_kernel(DecodeArgs a) {
     const int g = e / dv, c = e - g * dv;
     const float s = s_red[0][g][c] + s_red[1][g][c] + s_red[2][g][c] + s_red[3][g][c];
     const long long hq = static_cast<long long>(b) * a.n_q + h * G + g;
-    if (a.n_split == 1) {
+    if (a.direct_out) {
       const float l = s_l[g];
       a.out[hq * dv + c] = l > 0.f ? s / l : 0.f;
     } else {
-      a.part_acc[(hq * a.n_split + split) * dv + c] = s;
+      a.part_acc[(hq * a.n_slots + split) * dv + c] = s;
     }
   }
   if (a.n_split > 1 && tid < G) {
     const long long hq = static_cast<long long>(b) * a.n_q + h * G + tid;
-    a.part_ml[(hq * a.n_split + split) * 2 + 0] = s_m[tid];
-    a.part_ml[(hq * a.n_split + split) * 2 + 1] = s_l[tid];
+    a.part_ml[(hq * a.n_slots + split) * 2 + 0] = s_m[tid];
+    a.part_ml[(hq * a.n_slots + split) * 2 + 1] = s_l[tid];
   }
 }
 

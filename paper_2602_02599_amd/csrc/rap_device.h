@@ -89,11 +89,22 @@ struct DecodeArgs {
   const uint16_t* k_cache;
   const uint16_t* v_cache;
   const int32_t* seq_lens;
+  // one-call decode step (all null otherwise): the new token of every sequence.  The attention
+  // kernel leaves cache row new_pos[b] out of its scan; its first workgroup of each (b, h) rotates
+  // the new K row, writes it and the V row into the caches and leaves the token's score and V row
+  // as one more partial (slot n_split) for the combining kernel.
+  const uint16_t* k_new;    // [B, H_kv, 2P] before rotation
+  const uint16_t* v_new;    // [B, H_kv, d_v]
+  const int32_t* new_pos;   // [B]
+  uint16_t* k_cache_w;
+  uint16_t* v_cache_w;
+  int32_t direct_out;       // one range and no combining kernel: the attention kernel writes out itself
   float* out;          // [B, H_q, d_v]
   float* part_acc;     // [B, H_q, n_split, d_v]   un-normalised accumulators
   float* part_ml;      // [B, H_q, n_split, 2]     (running max in log2 units, running sum)
   int32_t batch, n_q, n_kv, group, n_pairs, d_k, d_v;
   int32_t max_len, rows_per_split, n_split;
+  int32_t n_slots;          // partial slots per query head: n_split, plus one in the decode step
   int32_t lds_wave_bytes;   // matrix-core kernel: LDS slice of one wavefront
   int64_t cap;
   float scale_log2e;   // softmax scale * log2(e): exponentials are taken as exp2

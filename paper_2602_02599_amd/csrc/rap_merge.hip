@@ -6,6 +6,8 @@
 //   out = sum_s 2^(m_s - m*) acc_s / sum_s 2^(m_s - m*) l_s,   m* = max_s m_s,
 // which is Eq. (attn) regrouped by row ranges.  Only the ranges that hold rows of this sequence
 // (ceil(len / rows_per_split) of them) were written by the first stage and only those are read.
+// In the one-call decode step there is one more slot behind the ranges, always written: the new
+// token on its own (m = its score, l = 1, acc = its V row, or m = -inf when it is not attended).
 #include "rap_device.h"
 
 namespace rap {
@@ -15,8 +17,13 @@ __global__ __launch_bounds__(128) void merge_kernel(DecodeArgs a) {
   const int b = static_cast<int>(hq / a.n_q);
   const int c = threadIdx.x;
   const bool live = c < a.d_v;
-  const float* ml = a.part_ml + hq * a.n_split * 2;
-  const float* accc = a.part_acc + hq * a.n_split * a.d_v + (live ? c : 0);
+  const float* ml = a.part_ml + hq * a.n_slots * 2;
+  const float* accc = a.part_acc + hq * a.n_slots * a.d_v + (live ? c : 0);
+  const bool tok = a.new_pos != nullptr;
+  const float m_tok = tok ? ml[2 * a.n_split] : -INFINITY;
+  const float l_tok = tok ? ml[2 * a.n_split + 1] : 0.f;
+  const float v_tok = tok ? accc[static_cast<long long>(a.n_split) * a.d_v] : 0.f;
+  const int t_new = tok ? a.new_pos[b] : -1;
   // The first four slots are requested before the sequence length is known (they are allocated,
   // whatever they hold), so the common case of a few ranges costs one memory round trip.
   float m[4], l[4], v[4];
@@ -29,8 +36,9 @@ __global__ __launch_bounds__(128) void merge_kernel(DecodeArgs a) {
   }
   int len = a.seq_lens[b];
   len = len < 0 ? 0 : (len > a.max_len ? a.max_len : len);
+  if (len > 0 && t_new == len - 1) len -= 1;       // the first stage stopped before the new token's row
   const int n = (len + a.rows_per_split - 1) / a.rows_per_split;   // ranges that hold rows
-  float mstar = -INFINITY;
+  float mstar = m_tok;
 #pragma unroll
   for (int u = 0; u < 4; ++u) {
     if (u >= n) { m[u] = -INFINITY; l[u] = 0.f; v[u] = 0.f; }      // unwritten slot: drop, do not multiply
@@ -43,6 +51,10 @@ __global__ __launch_bounds__(128) void merge_kernel(DecodeArgs a) {
   }
   for (; s < n; ++s) mstar = fmaxf(mstar, ml[2 * s]);
   float den = 0.f, num = 0.f;
+  if (m_tok > -INFINITY) {
+    den = exp2f(m_tok - mstar) * l_tok;
+    num = exp2f(m_tok - mstar) * v_tok;
+  }
   if (n > 0) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
