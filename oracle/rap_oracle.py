@@ -238,6 +238,39 @@ def attn_ref(q, k_cache, v_cache, seq_lens, scale) -> np.ndarray:
     return out
 
 
+def prefill_attn_ref(q, k_cache, v_cache, seq_lens, scale) -> np.ndarray:
+    """Causal GQA attention of the last n_new tokens of every sequence over the compact cache
+    (Eq. (attn) per query token with the decoder-only visibility rule: a token sees itself and
+    everything before it; the rule itself is the standard one, the paper does not restate it).
+
+    q        uint16 [B, n_new, H_q, d_k]  bf16 bits, pruned and already rotated; query i of
+                                          sequence b sits at position p = seq_lens[b] - n_new + i
+    k_cache  uint16 [B, H_kv, cap, d_k]   rows [0, seq_lens[b]) valid (the new tokens' own rows
+    v_cache  uint16 [B, H_kv, cap, d_v]   are already in the cache)
+    returns  float64 [B, n_new, H_q, d_v]; query i attends rows [0, p]; p < 0 gives zeros.
+    """
+    q = np.asarray(q)
+    bsz, n_new, n_q, _ = q.shape
+    n_kv = k_cache.shape[1]
+    g = n_q // n_kv
+    if g * n_kv != n_q:
+        raise ValueError("n_q_heads must be a multiple of n_kv_heads")
+    d_v = v_cache.shape[3]
+    out = np.zeros((bsz, n_new, n_q, d_v), dtype=np.float64)
+    qf = bf16_bits_to_f64(q)
+    for b in range(bsz):
+        n = int(seq_lens[b])
+        for h in range(n_kv):
+            kf = bf16_bits_to_f64(k_cache[b, h, :max(n, 0)])
+            vf = bf16_bits_to_f64(v_cache[b, h, :max(n, 0)])
+            for i in range(n_new):
+                p = n - n_new + i
+                if p < 0:
+                    continue
+                out[b, i, h * g:(h + 1) * g] = attn_rows_ref(qf[b, i, h * g:(h + 1) * g], kf[:p + 1], vf[:p + 1], scale)
+    return out
+
+
 def rope_queries_ref(q, q_pos, keep, theta_base, d_head, n_kv_heads) -> np.ndarray:
     """Query side of Eq. (latent-score): index-aware rotation of pruned, un-rotated query rows.
 

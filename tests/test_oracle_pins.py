@@ -446,6 +446,97 @@ def test_brute_force_tiny(P, dv, G, S):
     assert np.max(np.abs(got - np.array(bo))) < 1e-14
 
 
+# ---------------------------------------------------------------- causal prefill attention
+
+
+def test_prefill_equals_torch_sdpa_causal_float64():
+    """Full prefill (len == n_new): a library routine (torch SDPA, float64, CPU, is_causal) on
+    explicitly repeat-interleaved KV heads.  Catches an off-by-one in the visible range, a
+    transposed operand, a wrong head mapping."""
+    rng = _rng(41)
+    B, Hq, Hkv, dk, dv, S = 2, 6, 2, 10, 7, 29
+    q = _bf16_of(rng.standard_normal((B, S, Hq, dk)))
+    kc = _bf16_of(rng.standard_normal((B, Hkv, S + 3, dk)))
+    vc = _bf16_of(rng.standard_normal((B, Hkv, S + 3, dv)))
+    scale = 0.41
+    got = O.prefill_attn_ref(q, kc, vc, np.array([S, S]), scale)
+    tq = torch.from_numpy(O.bf16_bits_to_f64(q)).permute(0, 2, 1, 3)
+    tk = torch.from_numpy(O.bf16_bits_to_f64(kc[:, :, :S])).repeat_interleave(Hq // Hkv, dim=1)
+    tv = torch.from_numpy(O.bf16_bits_to_f64(vc[:, :, :S])).repeat_interleave(Hq // Hkv, dim=1)
+    want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, scale=scale, is_causal=True).permute(0, 2, 1, 3).numpy()
+    assert np.max(np.abs(got - want)) < 1e-13
+
+
+def test_prefill_closed_forms():
+    """Identical keys make every visible row equally likely, so query i returns the plain mean of
+    V rows [0, p_i] with p_i = len - n_new + i (chunked prefill: len > n_new); position 0 returns
+    V[0]; a sequence shorter than n_new gives zero rows for the queries before its start; heads
+    read their own KV head."""
+    rng = _rng(42)
+    B, Hq, Hkv, dk, dv, n_new, cap = 3, 4, 2, 6, 5, 7, 24
+    lens = np.array([7, 19, 4])
+    krow = rng.standard_normal((Hkv, dk))
+    kc = _bf16_of(np.broadcast_to(krow[None, :, None, :], (B, Hkv, cap, dk)).copy())
+    vc = _bf16_of(rng.standard_normal((B, Hkv, cap, dv)))
+    q = _bf16_of(rng.standard_normal((B, n_new, Hq, dk)))
+    got = O.prefill_attn_ref(q, kc, vc, lens, 0.8)
+    vf = O.bf16_bits_to_f64(vc)
+    for b in range(B):
+        for i in range(n_new):
+            p = lens[b] - n_new + i
+            for a_h in range(Hq):
+                want = vf[b, a_h // (Hq // Hkv), :p + 1].mean(axis=0) if p >= 0 else np.zeros(dv)
+                assert np.max(np.abs(got[b, i, a_h] - want)) < 1e-14, (b, i, a_h)
+    assert np.array_equal(got[0, 0, 0], vf[0, 0, 0])                       # position 0 sees only itself
+    assert np.all(got[2, :3] == 0.0) and np.any(got[2, 3] != 0.0)            # len 4 < n_new 7
+
+
+def test_prefill_causality_and_last_row_is_decode():
+    """What lies after a query's position cannot change its output, and the last query of a
+    sequence is the decode case (same rows, one query token)."""
+    rng = _rng(43)
+    B, Hq, Hkv, dk, dv, n_new, cap = 2, 6, 3, 8, 4, 5, 16
+    lens = np.array([12, 9])
+    q = _bf16_of(rng.standard_normal((B, n_new, Hq, dk)))
+    kc = _bf16_of(rng.standard_normal((B, Hkv, cap, dk)))
+    vc = _bf16_of(rng.standard_normal((B, Hkv, cap, dv)))
+    base = O.prefill_attn_ref(q, kc, vc, lens, 0.5)
+    kc2, vc2 = kc.copy(), vc.copy()
+    for b in range(B):
+        cut = lens[b] - 2                       # rows cut.. are later than query n_new - 3
+        kc2[b, :, cut:] = _bf16_of(rng.standard_normal((Hkv, cap - cut, dk)) * 5)
+        vc2[b, :, cut:] = _bf16_of(rng.standard_normal((Hkv, cap - cut, dv)) * 5)
+    pert = O.prefill_attn_ref(q, kc2, vc2, lens, 0.5)
+    assert np.array_equal(base[:, :n_new - 2], pert[:, :n_new - 2])
+    assert not np.array_equal(base[:, n_new - 2:], pert[:, n_new - 2:])
+    dec = O.attn_ref(q[:, -1], kc, vc, lens, 0.5)
+    assert np.array_equal(base[:, -1], dec)
+
+
+def test_prefill_brute_force_tiny():
+    """Explicit Python loops with math.exp over every (query, visible row)."""
+    rng = _rng(44)
+    B, Hq, Hkv, dk, dv, n_new, cap, scale = 1, 4, 2, 3, 2, 4, 8, 0.7
+    lens = np.array([6])
+    q = _bf16_of(rng.standard_normal((B, n_new, Hq, dk)))
+    kc = _bf16_of(rng.standard_normal((B, Hkv, cap, dk)))
+    vc = _bf16_of(rng.standard_normal((B, Hkv, cap, dv)))
+    got = O.prefill_attn_ref(q, kc, vc, lens, scale)
+    qf, kf, vf = O.bf16_bits_to_f64(q).tolist(), O.bf16_bits_to_f64(kc).tolist(), O.bf16_bits_to_f64(vc).tolist()
+    G = Hq // Hkv
+    for i in range(n_new):
+        p = int(lens[0]) - n_new + i
+        for a_h in range(Hq):
+            h = a_h // G
+            sc = [scale * sum(qf[0][i][a_h][e] * kf[0][h][t][e] for e in range(dk)) for t in range(p + 1)]
+            mx = max(sc)
+            ex = [math.exp(x - mx) for x in sc]
+            z = sum(ex)
+            for c in range(dv):
+                want = sum(ex[t] * vf[0][h][t][c] for t in range(p + 1)) / z
+                assert abs(got[0, i, a_h, c] - want) < 1e-14
+
+
 def test_split_merge_identity():
     """Merging (m, l, acc) partials over any partition of the rows gives the unsplit result."""
     rng = _rng(17)
