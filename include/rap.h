@@ -156,6 +156,24 @@ rap_status_t rap_decode_attn_rope(const rap_shape_t* shape, const void* q, const
                                   void* workspace, size_t workspace_bytes,
                                   const rap_tuning_t* tuning, void* stream);
 
+/* Causal attention of the last n_new tokens of every sequence over the compact cache: the prefill
+ * (or chunked-prefill) counterpart of rap_decode_attn, Eq. (attn) with the GQA remark per query
+ * token at the pruned widths of Eq. (latent-score).  Query i of sequence b sits at position
+ * p = seq_lens[b] - n_new + i and attends cache rows [0, p] (itself included; the decoder-only
+ * visibility rule).  The rows of the new tokens must already be in the cache (rap_rope_append).
+ *
+ *   q         dev  bf16  [batch, n_new, n_q_heads, 2P]  pruned, already rotated, compact order
+ *   k_cache, v_cache, seq_lens, max_seq_len, scale      as for rap_decode_attn
+ *   out       dev  fp32  [batch, n_new, n_q_heads, d_v] every row written; p < 0 (a sequence
+ *                                                        shorter than n_new) gives a zero row
+ * No workspace: a workgroup owns a block of query tokens and walks the rows they see.
+ * Errors as rap_decode_attn; n_new < 0 is RAP_ERR_SHAPE, n_new == 0 returns RAP_OK at once.
+ */
+rap_status_t rap_prefill_attn(const rap_shape_t* shape, int32_t n_new, const void* q,
+                              const void* k_cache, const void* v_cache,
+                              const int32_t* seq_lens, int64_t max_seq_len,
+                              void* out, float scale, void* stream);
+
 /* One whole decode step of a layer in a single call: append the new token of every sequence
  * (the result of rap_rope_append with n_new = 1), rotate its query unless it already is, and
  * attend (the result of rap_decode_attn / rap_decode_attn_rope over the updated cache).

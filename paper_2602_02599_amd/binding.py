@@ -89,6 +89,9 @@ class Rap:
             L.rap_decode_step.argtypes = [C.POINTER(RapShape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_float, C.c_void_p,
                                           C.c_size_t, C.POINTER(RapTuning), C.c_void_p]
+        L.rap_prefill_attn.restype = C.c_int
+        L.rap_prefill_attn.argtypes = [C.POINTER(RapShape), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                       C.c_int64, C.c_void_p, C.c_float, C.c_void_p]
         L.rap_stream_read.restype = C.c_int
         L.rap_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.rap_stream_copy.restype = C.c_int
@@ -170,6 +173,16 @@ class Rap:
                                       scale, _ptr(workspace, None, "workspace"),
                                       0 if workspace is None else workspace.numel() * workspace.element_size(),
                                       C.byref(tuning) if tuning is not None else None, _stream(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def rap_prefill_attn(self, shape: RapShape, n_new: int, q, k_cache, v_cache, seq_lens, max_seq_len: int, out,
+                         scale: float, stream=None, check=True) -> int:
+        st = self.lib.rap_prefill_attn(C.byref(shape), n_new, _ptr(q, torch.bfloat16, "q"),
+                                       _ptr(k_cache, torch.bfloat16, "k_cache"), _ptr(v_cache, torch.bfloat16, "v_cache"),
+                                       _ptr(seq_lens, torch.int32, "seq_lens"), max_seq_len, _ptr(out, torch.float32, "out"),
+                                       scale, _stream(stream))
         if check:
             self._check(st)
         return st

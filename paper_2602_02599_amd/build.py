@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librap.so")
-SOURCES = ["rap_api.hip", "rap_append.hip", "rap_decode_valu.hip", "rap_decode_mfma.hip", "rap_merge.hip", "rap_stream.hip"]
+SOURCES = ["rap_api.hip", "rap_append.hip", "rap_decode_valu.hip", "rap_decode_mfma.hip", "rap_merge.hip", "rap_stream.hip", "rap_prefill.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -11,6 +11,7 @@ hipError_t launch_append(const AppendArgs& a, hipStream_t stream);
 hipError_t launch_decode_valu(const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_merge(const DecodeArgs& a, hipStream_t stream);
+hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream);
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t stream);
 hipError_t launch_stream_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 int mfma_lds_wave_bytes(int d_k, int d_v);
@@ -247,6 +248,39 @@ rap_status_t rap_decode_attn_rope(const rap_shape_t* shape, const void* q, const
   }
   return decode_impl(shape, q, q_pos, keep_pair_idx, k_cache, v_cache, seq_lens, max_seq_len, out, scale, workspace,
                      workspace_bytes, tuning, stream);
+}
+
+rap_status_t rap_prefill_attn(const rap_shape_t* shape, int32_t n_new, const void* q, const void* k_cache,
+                              const void* v_cache, const int32_t* seq_lens, int64_t max_seq_len, void* out, float scale,
+                              void* stream) {
+  rap_status_t st = check_shape(shape);
+  if (st != RAP_OK) return st;
+  if (n_new < 0 || max_seq_len < 1) return RAP_ERR_SHAPE;
+  if (max_seq_len > shape->cache_cap) return RAP_ERR_CAPACITY;
+  if (n_new == 0 || shape->batch == 0) return RAP_OK;
+  if (!q || !k_cache || !v_cache || !seq_lens || !out) return RAP_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(k_cache) & 15) || (reinterpret_cast<uintptr_t>(v_cache) & 15) ||
+      (reinterpret_cast<uintptr_t>(q) & 3) || (reinterpret_cast<uintptr_t>(out) & 3))
+    return RAP_ERR_SHAPE;
+  if (static_cast<int64_t>(shape->batch) * n_new > 0x7fffffffLL) return RAP_ERR_UNSUPPORTED;
+  rap::PrefillArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = static_cast<const uint16_t*>(q);
+  a.k_cache = static_cast<const uint16_t*>(k_cache);
+  a.v_cache = static_cast<const uint16_t*>(v_cache);
+  a.seq_lens = seq_lens;
+  a.out = static_cast<float*>(out);
+  a.batch = shape->batch;
+  a.n_new = n_new;
+  a.n_q = shape->n_q_heads;
+  a.n_kv = shape->n_kv_heads;
+  a.group = shape->n_q_heads / shape->n_kv_heads;
+  a.d_k = 2 * shape->n_pairs;
+  a.d_v = shape->d_v;
+  a.max_len = static_cast<int32_t>(max_seq_len);
+  a.cap = shape->cache_cap;
+  a.scale_log2e = scale * 1.4426950408889634f;
+  return rap::launch_prefill(a, static_cast<hipStream_t>(stream)) == hipSuccess ? RAP_OK : RAP_ERR_HIP;
 }
 
 rap_status_t rap_stream_read(const void* src, size_t bytes, void* sink, void* stream) {

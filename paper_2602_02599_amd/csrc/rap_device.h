@@ -110,6 +110,20 @@ struct DecodeArgs {
   float scale_log2e;   // softmax scale * log2(e): exponentials are taken as exp2
 };
 
+struct PrefillArgs {
+  const uint16_t* q;        // [B, n_new, H_q, d_k] rotated
+  const uint16_t* k_cache;
+  const uint16_t* v_cache;
+  const int32_t* seq_lens;
+  float* out;               // [B, n_new, H_q, d_v]
+  int32_t batch, n_new, n_q, n_kv, group, d_k, d_v, max_len;
+  int32_t tok_per_wg;       // query tokens per workgroup: (64 NQ) / G
+  int32_t n_qblk;           // ceil(n_new / tok_per_wg)
+  int32_t lds_buf_bytes;    // one K + V tile buffer
+  int64_t cap;
+  float scale_log2e;
+};
+
 // Index-aware RoPE of the G query rows of KV head h of sequence b, into LDS as bf16 in the
 // compact order (Eq. (latent-score): the query side of RoPE(X W~_q) . RoPE(X W~_k)^T).  Same
 // arithmetic as the cache append: angle pos * theta^(-2 j / D) with j the ORIGINAL index of the

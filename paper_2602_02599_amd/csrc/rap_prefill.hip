@@ -1,0 +1,427 @@
+// Causal prefill attention over the compact cache: rap_prefill_attn.
+//
+// Eq. (attn) for the last n_new tokens of every sequence at once, each token seeing the cache rows
+// up to and including its own (the decoder-only rule), at the pruned widths d_k = 2P and d_v.
+// Unlike the decode step this is a dense contraction (n_new x len scores per head), so it is
+// bound by the matrix cores, and the design is about feeding them:
+//
+//  * A workgroup takes a block of consecutive query tokens of one (sequence, KV head) together
+//    with all G query heads of that KV head: its 64 NQ "columns" are (token, head) pairs, so a K
+//    or V tile staged in LDS once serves G times as many scores as it would per head.
+//  * Everything is computed transposed, as in the decode kernel: S^T[key][column] = K_tile . q on
+//    v_mfma_f32_16x16x32_bf16 with the K tile as the A operand from LDS and the query columns,
+//    resident in registers, as the B operand; in the result layout a lane holds eight keys of one
+//    column, which are exactly the contraction slots of the P.V instruction when those are
+//    numbered accordingly, so probabilities never leave the lane.  A K fragment read from LDS is
+//    used for NQ column blocks, and so is the gathered V operand.
+//  * Tiles of 64 keys are staged by the whole workgroup (flat 16-byte loads into registers one
+//    tile ahead, parked into the other LDS buffer, one barrier per tile).
+//  * Online softmax in the log2 domain against a per-column reference that moves only when a
+//    score outgrows it by 2^64; the causal mask is applied only on the tiles that straddle the
+//    diagonal of the wavefront's columns, later tiles are skipped by the wavefront, earlier ones
+//    need no mask.
+//
+// Garbage safety as in the decode kernel: rows at or beyond the sequence length may hold any bits;
+// they are never visible (a select to -inf), their V reads are redirected to the last valid row,
+// K fragments are masked beyond d_k, and loads never touch rows >= round-up-8(len) <= cap.
+#include "rap_device.h"
+
+namespace rap {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+constexpr int kKeysPerTile = 64;     // staged per barrier
+constexpr int kSub = 32;             // keys per matrix-instruction group (two 16-row fragments)
+constexpr float kHeadroomP = 64.f;   // log2 units a score may exceed the reference before a rescale
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+template <int KCH, int NT, bool VPAIR, int NQ>
+__global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
+  constexpr int NCK = (kKeysPerTile * 64 * KCH + 4095) / 4096;   // 16-byte chunks per thread, K tile
+  constexpr int NCV = (kKeysPerTile * 32 * NT + 4095) / 4096;    // same, V tile
+  extern __shared__ __align__(16) unsigned char smem[];
+
+  int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l16 = lane & 15;
+  const int lg = lane >> 4;
+
+  // heaviest query blocks (the last tokens, which see the most rows) first
+  const int slabs = a.n_kv * a.batch;
+  const int wg = blockIdx.x;
+  const int qb = a.n_qblk - 1 - wg / slabs;
+  const int slab_id = wg - (wg / slabs) * slabs;
+  const int h = slab_id % a.n_kv;
+  const int b = slab_id / a.n_kv;
+
+  int len = a.seq_lens[b];
+  len = len < 0 ? 0 : (len > a.max_len ? a.max_len : len);
+  const int G = a.group;
+  const int dk = a.d_k, dv = a.d_v;
+  const int BT = a.tok_per_wg;
+  const int i0 = qb * BT;
+  const int i_end = min(a.n_new, i0 + BT);
+  const int shift = len - a.n_new;                 // position of token i is shift + i
+  const int n_keys = min(len, shift + i_end);      // rows the block's last token sees
+  const long long out_row0 = (static_cast<long long>(b) * a.n_new) * a.n_q + h * G;   // + i * n_q + g
+
+  if (n_keys <= 0) {
+    // every token of this block lies before the start of its sequence: zero rows
+    for (int e = tid; e < (i_end - i0) * G * dv; e += 256) {
+      const int c = e % dv, r = e / dv;
+      const int g = r % G, i = i0 + r / G;
+      a.out[(out_row0 + static_cast<long long>(i) * a.n_q + g) * dv + c] = 0.f;
+    }
+    return;
+  }
+
+  // ---- this lane's columns: (token, head) pairs, and their positions
+  int pos_col[NQ];
+  bool col_valid[NQ];
+  int wmin = 0x7fffffff, wmax = -1;
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq) {
+    const int cw = (wave * NQ + nq) * 16 + l16;
+    const int tl = cw / G;
+    const int i = i0 + tl;
+    col_valid[nq] = tl < BT && i < a.n_new && shift + i >= 0;
+    pos_col[nq] = col_valid[nq] ? shift + i : 0;
+    wmin = min(wmin, col_valid[nq] ? pos_col[nq] : 0x7fffffff);
+    wmax = max(wmax, col_valid[nq] ? pos_col[nq] : -1);
+  }
+#pragma unroll
+  for (int o = 1; o < 16; o <<= 1) {
+    wmin = min(wmin, __shfl_xor(wmin, o));
+    wmax = max(wmax, __shfl_xor(wmax, o));
+  }
+  wmin = __builtin_amdgcn_readfirstlane(wmin);
+  wmax = __builtin_amdgcn_readfirstlane(wmax);
+
+  // ---- query columns as the B operand: lane (l16 = column, lg = k sub-chunk)
+  bf16x8 qf[NQ][KCH];
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq) {
+    const int cw = (wave * NQ + nq) * 16 + l16;
+    const int tl = cw / G, g = cw - (cw / G) * G;
+    const uint32_t* qrow = reinterpret_cast<const uint32_t*>(a.q) +
+                           ((static_cast<long long>(b) * a.n_new + (col_valid[nq] ? i0 + tl : 0)) * a.n_q + h * G +
+                            (col_valid[nq] ? g : 0)) * (dk / 2);
+#pragma unroll
+    for (int kk = 0; kk < KCH; ++kk) {
+      uint32_t w[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int e = 32 * kk + 8 * lg + 2 * i;
+        w[i] = (col_valid[nq] && e < dk) ? qrow[e >> 1] : 0u;
+      }
+      qf[nq][kk] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+    }
+  }
+
+  const int pitch_k = 2 * dk, pitch_v = 2 * dv;    // bytes
+  const long long slab = static_cast<long long>(b) * a.n_kv + h;
+  const unsigned char* kslab = reinterpret_cast<const unsigned char*>(a.k_cache) + slab * a.cap * pitch_k;
+  const unsigned char* vslab = reinterpret_cast<const unsigned char*>(a.v_cache) + slab * a.cap * pitch_v;
+  const int len8 = (len + 7) & ~7;                 // <= cache_cap: rows below it are readable
+  const int kbytes = kKeysPerTile * pitch_k, vbytes = kKeysPerTile * pitch_v;
+  unsigned char* kbuf[2] = {smem, smem + a.lds_buf_bytes};
+  const int v_off = (kbytes + 64 + 127) & ~127;    // slack: the last K fragment read runs past the tile
+
+  uint4 kst[NCK], vst[NCV];
+  auto issue = [&](int t) {
+    const int base = t * kKeysPerTile;
+    const int rows = min(kKeysPerTile, len8 - base);           // multiple of 8, >= 8
+    const int kval = rows * pitch_k, vval = rows * pitch_v;    // multiples of 16
+    const unsigned char* kg = kslab + static_cast<long long>(base) * pitch_k;
+    const unsigned char* vg = vslab + static_cast<long long>(base) * pitch_v;
+#pragma unroll
+    for (int j = 0; j < NCK; ++j) {
+      const int off = (j * 256 + tid) * 16;
+      kst[j] = off < kval ? *reinterpret_cast<const uint4*>(kg + off) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < NCV; ++j) {
+      const int off = (j * 256 + tid) * 16;
+      vst[j] = off < vval ? *reinterpret_cast<const uint4*>(vg + off) : make_uint4(0, 0, 0, 0);
+    }
+  };
+  auto park = [&](int which) {
+    unsigned char* kt = kbuf[which];
+    unsigned char* vt = kt + v_off;
+#pragma unroll
+    for (int j = 0; j < NCK; ++j) {
+      const int off = (j * 256 + tid) * 16;
+      if (off < kbytes) *reinterpret_cast<uint4*>(kt + off) = kst[j];
+    }
+#pragma unroll
+    for (int j = 0; j < NCV; ++j) {
+      const int off = (j * 256 + tid) * 16;
+      if (off < vbytes) *reinterpret_cast<uint4*>(vt + off) = vst[j];
+    }
+  };
+
+  f32x4 acc[NQ][NT];
+  float m_run[NQ], l_run[NQ];
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq) {
+    m_run[nq] = -INFINITY;
+    l_run[nq] = 0.f;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[nq][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  uint32_t kmask[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) kmask[i] = (32 * (KCH - 1) + 8 * lg + 2 * i) < dk ? 0xffffffffu : 0u;
+  int koff[2];
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt) koff[rt] = (16 * rt + l16) * pitch_k + 16 * lg;
+  int voff[2][4];
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) voff[rt][r] = (16 * rt + 4 * lg + r) * pitch_v + (VPAIR ? 4 : 2) * l16;
+
+  const int n_tiles = (n_keys + kKeysPerTile - 1) / kKeysPerTile;
+  issue(0);
+  park(0);
+  __syncthreads();
+  if (n_tiles > 1) issue(1);
+
+  for (int t = 0; t < n_tiles; ++t) {
+    const unsigned char* kt0 = kbuf[t & 1];
+    const unsigned char* vt0 = kt0 + v_off;
+#pragma unroll 1
+    for (int sub = 0; sub < kKeysPerTile / kSub; ++sub) {
+      const int sbase = t * kKeysPerTile + kSub * sub;
+      if (sbase > wmax || sbase >= n_keys) break;   // nothing of this or any later key group is visible here
+      const unsigned char* kt = kt0 + sub * kSub * pitch_k;
+      const unsigned char* vt = vt0 + sub * kSub * pitch_v;
+      const int nv = min(kSub, len - sbase);         // rows of the group that exist, >= 1
+      const bool no_mask = sbase + kSub - 1 <= wmin;
+
+      // ---- scores: sc[nq][rt][r] = column (nq, l16) . K[sbase + 16 rt + 4 lg + r]
+      f32x4 sc[NQ][2];
+#pragma unroll
+      for (int nq = 0; nq < NQ; ++nq) sc[nq][0] = sc[nq][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt) {
+#pragma unroll
+        for (int kk = 0; kk < KCH; ++kk) {
+          const uint32_t* p = reinterpret_cast<const uint32_t*>(kt + koff[rt] + 64 * kk);
+          uint4 w = make_uint4(p[0], p[1], p[2], p[3]);
+          if (kk == KCH - 1) {
+            w.x &= kmask[0];
+            w.y &= kmask[1];
+            w.z &= kmask[2];
+            w.w &= kmask[3];
+          }
+          const bf16x8 kf = __builtin_bit_cast(bf16x8, w);
+#pragma unroll
+          for (int nq = 0; nq < NQ; ++nq)
+            sc[nq][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[nq][kk], sc[nq][rt], 0, 0, 0);
+        }
+      }
+
+      // ---- softmax numerators per column block, packed straight into the P.V operand
+      uint4 p_hi[NQ], p_lo[NQ];
+#pragma unroll
+      for (int nq = 0; nq < NQ; ++nq) {
+        float x[2][4];
+        float tmax = -INFINITY;
+        const int rel = pos_col[nq] - sbase;         // keys 0..rel of the group are visible to this column
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float s = sc[nq][rt][r] * a.scale_log2e;
+            x[rt][r] = (no_mask || (16 * rt + 4 * lg + r) <= rel) ? s : -INFINITY;
+            tmax = fmaxf(tmax, x[rt][r]);
+          }
+        if (__any(tmax > m_run[nq] + kHeadroomP)) {
+          tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+          tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+          const float m_new = fmaxf(m_run[nq], tmax);
+          // a column that has seen nothing yet and sees nothing here keeps its -inf reference
+          const float alpha = m_new > -INFINITY ? __builtin_amdgcn_exp2f(m_run[nq] - m_new) : 0.f;
+          l_run[nq] *= alpha;
+#pragma unroll
+          for (int reg = 0; reg < 4; ++reg) {
+            const float at = __shfl(alpha, 4 * lg + reg);   // the column this accumulator register holds
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) acc[nq][nt][reg] *= at;
+          }
+          m_run[nq] = m_new;
+        }
+        const float mref = m_run[nq] > -INFINITY ? m_run[nq] : 0.f;   // -inf - -inf would be NaN
+        float pr[2][4];
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            pr[rt][r] = __builtin_amdgcn_exp2f(x[rt][r] - mref);
+            l_run[nq] += pr[rt][r];
+          }
+        uint32_t* ph = reinterpret_cast<uint32_t*>(&p_hi[nq]);
+        uint32_t* pl = reinterpret_cast<uint32_t*>(&p_lo[nq]);
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          const float a0 = pr[d >> 1][2 * (d & 1)], a1 = pr[d >> 1][2 * (d & 1) + 1];
+          const uint32_t hh = pack2(a0, a1);
+          ph[d] = hh;
+          pl[d] = pack2(a0 - bf16_lo(hh), a1 - bf16_hi(hh));
+        }
+      }
+
+      // ---- P.V: acc[nq][nt][reg] (column 4 lg + reg of block nq, channel slot l16 of tile nt)
+      int vo[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int row = min(16 * (j >> 2) + 4 * lg + (j & 3), nv - 1);
+        vo[j] = nv == kSub ? voff[j >> 2][j & 3] : row * pitch_v + (VPAIR ? 4 : 2) * l16;
+      }
+      if constexpr (VPAIR) {
+#pragma unroll
+        for (int np = 0; np < NT / 2; ++np) {
+          uint32_t w[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) w[j] = *reinterpret_cast<const uint32_t*>(vt + vo[j] + 64 * np);
+          uint4 be, bo;   // even / odd channel of the pair, rows packed two by two
+          be.x = __builtin_amdgcn_perm(w[1], w[0], 0x05040100u);
+          be.y = __builtin_amdgcn_perm(w[3], w[2], 0x05040100u);
+          be.z = __builtin_amdgcn_perm(w[5], w[4], 0x05040100u);
+          be.w = __builtin_amdgcn_perm(w[7], w[6], 0x05040100u);
+          bo.x = __builtin_amdgcn_perm(w[1], w[0], 0x07060302u);
+          bo.y = __builtin_amdgcn_perm(w[3], w[2], 0x07060302u);
+          bo.z = __builtin_amdgcn_perm(w[5], w[4], 0x07060302u);
+          bo.w = __builtin_amdgcn_perm(w[7], w[6], 0x07060302u);
+          const bf16x8 vbe = __builtin_bit_cast(bf16x8, be), vbo = __builtin_bit_cast(bf16x8, bo);
+#pragma unroll
+          for (int nq = 0; nq < NQ; ++nq) {
+            const bf16x8 pa_hi = __builtin_bit_cast(bf16x8, p_hi[nq]), pa_lo = __builtin_bit_cast(bf16x8, p_lo[nq]);
+            acc[nq][2 * np] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi, vbe, acc[nq][2 * np], 0, 0, 0);
+            acc[nq][2 * np + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi, vbo, acc[nq][2 * np + 1], 0, 0, 0);
+            acc[nq][2 * np] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_lo, vbe, acc[nq][2 * np], 0, 0, 0);
+            acc[nq][2 * np + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_lo, vbo, acc[nq][2 * np + 1], 0, 0, 0);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          uint32_t u[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) u[j] = *reinterpret_cast<const uint16_t*>(vt + vo[j] + 32 * nt);
+          const uint4 bv = make_uint4(u[0] | (u[1] << 16), u[2] | (u[3] << 16), u[4] | (u[5] << 16), u[6] | (u[7] << 16));
+          const bf16x8 vb = __builtin_bit_cast(bf16x8, bv);
+#pragma unroll
+          for (int nq = 0; nq < NQ; ++nq) {
+            const bf16x8 pa_hi = __builtin_bit_cast(bf16x8, p_hi[nq]), pa_lo = __builtin_bit_cast(bf16x8, p_lo[nq]);
+            acc[nq][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi, vb, acc[nq][nt], 0, 0, 0);
+            acc[nq][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_lo, vb, acc[nq][nt], 0, 0, 0);
+          }
+        }
+      }
+    }
+
+    // ---- next tile into the other buffer (its last readers passed the previous barrier)
+    if (t + 1 < n_tiles) park((t + 1) & 1);
+    __syncthreads();
+    if (t + 2 < n_tiles) issue(t + 2);
+  }
+
+  // ---- normalise and store: accumulator register reg of lane (l16, lg) is column 4 lg + reg
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq) {
+    float l = l_run[nq];
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+#pragma unroll
+    for (int reg = 0; reg < 4; ++reg) {
+      const int col = 4 * lg + reg;
+      const float lc = __shfl(l, col);
+      const int cw = (wave * NQ + nq) * 16 + col;
+      const int tl = cw / G, g = cw - (cw / G) * G;
+      const int i = i0 + tl;
+      if (tl < BT && i < a.n_new) {
+        const float inv = (shift + i >= 0 && lc > 0.f) ? 1.f / lc : 0.f;
+        float* orow = a.out + (out_row0 + static_cast<long long>(i) * a.n_q + g) * dv;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          const int c = VPAIR ? 32 * (nt >> 1) + 2 * l16 + (nt & 1) : 16 * nt + l16;
+          if (c < dv) orow[c] = acc[nq][nt][reg] * inv;
+        }
+      }
+    }
+  }
+}
+
+template <int KCH, int NT, bool VPAIR, int NQ>
+hipError_t launch_prefill_inst(PrefillArgs a, hipStream_t stream) {
+  a.tok_per_wg = (64 * NQ) / a.group;
+  a.n_qblk = (a.n_new + a.tok_per_wg - 1) / a.tok_per_wg;
+  const int kbytes = kKeysPerTile * 2 * a.d_k, vbytes = kKeysPerTile * 2 * a.d_v;
+  a.lds_buf_bytes = ((kbytes + 64 + 127) & ~127) + ((vbytes + 64 + 127) & ~127);
+  const size_t lds = 2 * static_cast<size_t>(a.lds_buf_bytes);
+  if (lds > 64 * 1024) {
+    static int raised_to = 0;
+    if (raised_to < static_cast<int>(lds)) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<KCH, NT, VPAIR, NQ>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+      if (e != hipSuccess) return e;
+      raised_to = static_cast<int>(lds);
+    }
+  }
+  const long long n_wg = static_cast<long long>(a.n_qblk) * a.n_kv * a.batch;
+  if (n_wg > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((prefill_kernel<KCH, NT, VPAIR, NQ>), dim3(static_cast<unsigned>(n_wg)), dim3(256), lds, stream, a);
+  return hipGetLastError();
+}
+
+template <int KCH, int NQ>
+hipError_t launch_prefill_k(const PrefillArgs& a, hipStream_t stream) {
+  const int nt = (a.d_v + 15) / 16;
+  if ((a.d_v & 1) == 0 && (nt & 1) == 0) {
+    switch (nt) {
+      case 2: return launch_prefill_inst<KCH, 2, true, NQ>(a, stream);
+      case 4: return launch_prefill_inst<KCH, 4, true, NQ>(a, stream);
+      case 6: return launch_prefill_inst<KCH, 6, true, NQ>(a, stream);
+      case 8: return launch_prefill_inst<KCH, 8, true, NQ>(a, stream);
+      default: return hipErrorInvalidValue;
+    }
+  }
+  switch (nt) {
+    case 1: return launch_prefill_inst<KCH, 1, false, NQ>(a, stream);
+    case 2: return launch_prefill_inst<KCH, 2, false, NQ>(a, stream);
+    case 3: return launch_prefill_inst<KCH, 3, false, NQ>(a, stream);
+    case 4: return launch_prefill_inst<KCH, 4, false, NQ>(a, stream);
+    case 5: return launch_prefill_inst<KCH, 5, false, NQ>(a, stream);
+    case 6: return launch_prefill_inst<KCH, 6, false, NQ>(a, stream);
+    case 7: return launch_prefill_inst<KCH, 7, false, NQ>(a, stream);
+    case 8: return launch_prefill_inst<KCH, 8, false, NQ>(a, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream) {
+  switch ((a.d_k + 31) / 32) {
+    case 1: return launch_prefill_k<1, 4>(a, stream);
+    case 2: return launch_prefill_k<2, 4>(a, stream);
+    case 3: return launch_prefill_k<3, 4>(a, stream);
+    case 4: return launch_prefill_k<4, 2>(a, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace rap

@@ -3,6 +3,8 @@
 Bars: appended K rows within 1 bf16 ulp of the oracle's single-rounded row (V rows bit-exact);
 attention outputs max-abs <= 1e-2 and mean-relative (mean |diff| / mean |ref|) <= 1e-3.
 """
+import math
+
 import numpy as np
 import pytest
 import torch
@@ -380,6 +382,93 @@ def test_decode_step_edges(rap, kernel):
         v_row = O.bf16_bits_to_f64(I.bits(v_new)[0])              # [H_kv, d_v]
         G = w.n_q_heads // w.n_kv_heads
         assert np.abs(got[0] - np.repeat(v_row, G, axis=0)).max() <= 1e-6
+
+
+# ---------------------------------------------------------------- causal prefill attention
+
+
+def _prefill_case(P, dv, Hq, Hkv, n_new, lens, seed, scale=None, nan_beyond=False):
+    """Cache rows N(0,1) as bf16 (taken as already rotated), q likewise; lens are the lengths after
+    the n_new tokens were appended."""
+    lens = np.asarray(lens, dtype=np.int64)
+    B = len(lens)
+    cap = int((max(int(lens.max()), 1) + 7) // 8 * 8) + 8
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(seed)
+    kc = torch.randn((B, Hkv, cap, 2 * P), generator=gen, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    vc = torch.randn((B, Hkv, cap, dv), generator=gen, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    q = torch.randn((B, n_new, Hq, 2 * P), generator=gen, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    if nan_beyond:
+        for b in range(B):
+            kc[b, :, int(lens[b]):] = float("nan")
+            vc[b, :, int(lens[b]):] = float("nan")
+    return q, kc, vc, torch.from_numpy(lens.astype(np.int32)).to(DEV), cap, (scale if scale is not None else 1.0 / math.sqrt(2 * P))
+
+
+@pytest.mark.parametrize("P,dv,Hq,Hkv,n_new,lens", [
+    (45, 90, 8, 2, 200, [200, 333, 150]),          # full, chunked, shorter than n_new
+    (58, 115, 8, 2, 130, [130, 517]),              # odd d_v
+    (32, 64, 10, 2, 97, [97, 400, 1]),             # group of 5
+    (64, 128, 4, 1, 150, [150, 260]),              # rho = 1 widths
+    (45, 90, 24, 8, 70, [70, 71]),                 # group of 3
+    (3, 5, 3, 1, 33, [33, 40, 5]),
+    (45, 90, 8, 8, 300, [300]),                    # no grouping: 256 tokens per workgroup
+    (45, 90, 8, 1, 40, [40, 1000]),                # group of 8
+])
+def test_prefill_small(rap, P, dv, Hq, Hkv, n_new, lens):
+    """rap_prefill_attn against the oracle, element by element: several key tiles, ragged tails,
+    chunked prefill (len > n_new), sequences shorter than n_new (zero rows), garbage beyond len."""
+    _say("prefill P=%d dv=%d heads %d/%d n_new=%d lens=%s" % (P, dv, Hq, Hkv, n_new, lens))
+    q, kc, vc, sl, cap, scale = _prefill_case(P, dv, Hq, Hkv, n_new, lens, seed=900 + P + n_new, nan_beyond=True)
+    shp = rap.shape(len(lens), Hq, Hkv, 128, P, dv, cap, 5.0e5)
+    out = torch.full((len(lens), n_new, Hq, dv), float("nan"), dtype=torch.float32, device=DEV)
+    rap.rap_prefill_attn(shp, n_new, q, kc, vc, sl, cap, out, scale)
+    torch.cuda.synchronize()
+    ref = O.prefill_attn_ref(I.bits(q), I.bits(kc), I.bits(vc), np.asarray(lens), scale)
+    H.assert_attn_close(out.cpu().numpy(), ref, "prefill")
+
+
+def test_prefill_last_row_is_decode(rap):
+    """The last query of a prefill is the decode case: same numbers as rap_decode_attn (to fp32
+    rounding: other tiling of the same sums)."""
+    P, dv, Hq, Hkv, n_new, lens = 45, 90, 8, 2, 64, [777, 1500]
+    q, kc, vc, sl, cap, scale = _prefill_case(P, dv, Hq, Hkv, n_new, lens, seed=77)
+    shp = rap.shape(len(lens), Hq, Hkv, 128, P, dv, cap, 5.0e5)
+    out = torch.empty((len(lens), n_new, Hq, dv), dtype=torch.float32, device=DEV)
+    rap.rap_prefill_attn(shp, n_new, q, kc, vc, sl, cap, out, scale)
+    dec = torch.empty((len(lens), Hq, dv), dtype=torch.float32, device=DEV)
+    ws = rap.new_workspace(shp, cap, None)
+    rap.rap_decode_attn(shp, q[:, -1].contiguous(), kc, vc, sl, cap, dec, scale, ws, None)
+    torch.cuda.synchronize()
+    rel = (out[:, -1] - dec).abs().max().item() / dec.abs().max().item()
+    assert rel <= 2e-5, rel
+
+
+def test_prefill_cfg2_sampled(rap):
+    """Full prefill at the cfg2 shape (16 x 8192 tokens, 32/8 heads, d = 90), sampled (b, token,
+    head) rows against the oracle computed one by one."""
+    w = I.WORKLOADS["cfg2"]
+    B, S, Hq, Hkv, P, dv = w.batch, w.ctx, w.n_q_heads, w.n_kv_heads, w.n_pairs, w.d_v
+    _say("prefill cfg2 full size")
+    q, kc, vc, sl, cap, scale = _prefill_case(P, dv, Hq, Hkv, S, [S] * B, seed=5)
+    shp = rap.shape(B, Hq, Hkv, w.d_head, P, dv, cap, w.rope_theta)
+    out = torch.full((B, S, Hq, dv), float("nan"), dtype=torch.float32, device=DEV)
+    rap.rap_prefill_attn(shp, S, q, kc, vc, sl, cap, out, scale)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    rng = np.random.Generator(np.random.PCG64(3))
+    G = Hq // Hkv
+    picks = [(int(rng.integers(B)), int(rng.integers(S)), int(rng.integers(Hq))) for _ in range(60)]
+    picks += [(0, 0, 0), (B - 1, S - 1, Hq - 1), (3, 63, 5), (3, 64, 5), (7, 4095, 17), (7, 4096, 17)]
+    got, ref = [], []
+    for b, i, a_h in picks:
+        h = a_h // G
+        kf = O.bf16_bits_to_f64(I.bits(kc[b, h, :i + 1]))
+        vf = O.bf16_bits_to_f64(I.bits(vc[b, h, :i + 1]))
+        qf = O.bf16_bits_to_f64(I.bits(q[b, i, a_h]))[None, :]
+        ref.append(O.attn_rows_ref(qf, kf, vf, scale)[0])
+        got.append(out[b, i, a_h].cpu().numpy())
+    H.assert_attn_close(np.array(got), np.array(ref), "prefill cfg2 sampled")
 
 
 def test_split_invariance(rap):
