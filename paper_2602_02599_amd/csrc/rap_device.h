@@ -120,6 +120,8 @@ struct PrefillArgs {
   int32_t tok_per_wg;       // query tokens per workgroup: (64 NQ) / G
   int32_t n_qblk;           // ceil(n_new / tok_per_wg)
   int32_t lds_buf_bytes;    // one K + V tile buffer
+  int32_t pad_k, pad_v;     // LDS row padding in bytes (0 or 16)
+  int32_t shift_k, shift_v; // log2 of the cache row pitch when padded, else 31
   int64_t cap;
   float scale_log2e;
 };

@@ -21,9 +21,9 @@
 //    diagonal of the wavefront's columns, later tiles are skipped by the wavefront, earlier ones
 //    need no mask.
 //
-// Garbage safety as in the decode kernel: rows at or beyond the sequence length may hold any bits;
-// they are never visible (a select to -inf), their V reads are redirected to the last valid row,
-// K fragments are masked beyond d_k, and loads never touch rows >= round-up-8(len) <= cap.
+// Garbage safety: rows at or beyond the sequence length may hold any bits; their scores are never
+// visible (a select to -inf), their V rows are cleared on the way into LDS, K fragments are masked
+// beyond d_k, and loads never touch rows >= round-up-8(len) <= cap.
 #include "rap_device.h"
 
 namespace rap {
@@ -34,6 +34,8 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((address_space(1))) const void* global_ptr_t;
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
 constexpr int kKeysPerTile = 64;     // staged per barrier
 constexpr int kSub = 32;             // keys per matrix-instruction group (two 16-row fragments)
@@ -44,7 +46,7 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-template <int KCH, int NT, bool VPAIR, int NQ>
+template <int KCH, int NT, bool VPAIR, int NQ, bool DIRECT>
 __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   constexpr int NCK = (kKeysPerTile * 64 * KCH + 4095) / 4096;   // 16-byte chunks per thread, K tile
   constexpr int NCV = (kKeysPerTile * 32 * NT + 4095) / 4096;    // same, V tile
@@ -128,16 +130,18 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     }
   }
 
-  const int pitch_k = 2 * dk, pitch_v = 2 * dv;    // bytes
+  const int pitch_k = 2 * dk, pitch_v = 2 * dv;    // bytes, in the cache
+  // In LDS a row pitch that is a multiple of 128 bytes gets 16 bytes of padding: otherwise the 16
+  // rows a fragment read touches would all start in the same bank.
+  const int lpk = pitch_k + a.pad_k, lpv = pitch_v + a.pad_v;
   const long long slab = static_cast<long long>(b) * a.n_kv + h;
   const unsigned char* kslab = reinterpret_cast<const unsigned char*>(a.k_cache) + slab * a.cap * pitch_k;
   const unsigned char* vslab = reinterpret_cast<const unsigned char*>(a.v_cache) + slab * a.cap * pitch_v;
   const int len8 = (len + 7) & ~7;                 // <= cache_cap: rows below it are readable
-  const int kbytes = kKeysPerTile * pitch_k, vbytes = kKeysPerTile * pitch_v;
-  unsigned char* kbuf[2] = {smem, smem + a.lds_buf_bytes};
-  const int v_off = (kbytes + 64 + 127) & ~127;    // slack: the last K fragment read runs past the tile
+  const int kbytes = kKeysPerTile * pitch_k, vbytes = kKeysPerTile * pitch_v;   // bytes fetched per tile
+  const int v_off = (kKeysPerTile * lpk + 64 + 127) & ~127;   // slack: the last K fragment read runs past the tile
 
-  uint4 kst[NCK], vst[NCV];
+  uint4 kst[DIRECT ? 1 : NCK], vst[DIRECT ? 1 : NCV];
   auto issue = [&](int t) {
     const int base = t * kKeysPerTile;
     const int rows = min(kKeysPerTile, len8 - base);           // multiple of 8, >= 8
@@ -156,17 +160,41 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     }
   };
   auto park = [&](int which) {
-    unsigned char* kt = kbuf[which];
+    unsigned char* kt = smem + which * a.lds_buf_bytes;
     unsigned char* vt = kt + v_off;
 #pragma unroll
     for (int j = 0; j < NCK; ++j) {
       const int off = (j * 256 + tid) * 16;
-      if (off < kbytes) *reinterpret_cast<uint4*>(kt + off) = kst[j];
+      if (off < kbytes) *reinterpret_cast<uint4*>(kt + off + ((off >> a.shift_k) << 4)) = kst[j];
     }
 #pragma unroll
     for (int j = 0; j < NCV; ++j) {
       const int off = (j * 256 + tid) * 16;
-      if (off < vbytes) *reinterpret_cast<uint4*>(vt + off) = vst[j];
+      if (off < vbytes) *reinterpret_cast<uint4*>(vt + off + ((off >> a.shift_v) << 4)) = vst[j];
+    }
+  };
+
+  // Without LDS padding the tile is a flat copy, and the 16-byte loads can write LDS themselves
+  // (lane i of a wavefront lands at the wavefront's LDS base + 16 i): no staging registers.
+  auto issue_direct = [&](int t) {
+    const int base = t * kKeysPerTile;
+    const int rows = min(kKeysPerTile, len8 - base);
+    const int kval = rows * pitch_k, vval = rows * pitch_v;
+    const unsigned char* kg = kslab + static_cast<long long>(base) * pitch_k;
+    const unsigned char* vg = vslab + static_cast<long long>(base) * pitch_v;
+    unsigned char* kt = smem + (t & 1) * a.lds_buf_bytes;
+    unsigned char* vt = kt + v_off;
+#pragma unroll
+    for (int j = 0; j < NCK; ++j) {
+      const int off = (j * 256 + tid) * 16;
+      if (off < kval)
+        __builtin_amdgcn_global_load_lds((global_ptr_t)(kg + off), (lds_ptr_t)(kt + (j * 256 + wave * 64) * 16), 16, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < NCV; ++j) {
+      const int off = (j * 256 + tid) * 16;
+      if (off < vval)
+        __builtin_amdgcn_global_load_lds((global_ptr_t)(vg + off), (lds_ptr_t)(vt + (j * 256 + wave * 64) * 16), 16, 0, 0);
     }
   };
 
@@ -180,34 +208,48 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     for (int nt = 0; nt < NT; ++nt) acc[nq][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  uint32_t kmask[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) kmask[i] = (32 * (KCH - 1) + 8 * lg + 2 * i) < dk ? 0xffffffffu : 0u;
+  const int klim = dk - 32 * (KCH - 1) - 8 * lg;   // elements of this lane's last K fragment that exist
   int koff[2];
 #pragma unroll
-  for (int rt = 0; rt < 2; ++rt) koff[rt] = (16 * rt + l16) * pitch_k + 16 * lg;
+  for (int rt = 0; rt < 2; ++rt) koff[rt] = (16 * rt + l16) * lpk + 16 * lg;
   int voff[2][4];
 #pragma unroll
   for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) voff[rt][r] = (16 * rt + 4 * lg + r) * pitch_v + (VPAIR ? 4 : 2) * l16;
+    for (int r = 0; r < 4; ++r) voff[rt][r] = (16 * rt + 4 * lg + r) * lpv + (VPAIR ? 4 : 2) * l16;
 
   const int n_tiles = (n_keys + kKeysPerTile - 1) / kKeysPerTile;
-  issue(0);
-  park(0);
-  __syncthreads();
-  if (n_tiles > 1) issue(1);
+  if constexpr (DIRECT) {
+    issue_direct(0);
+  } else {
+    issue(0);
+    park(0);
+    __syncthreads();
+    if (n_tiles > 1) issue(1);
+  }
 
   for (int t = 0; t < n_tiles; ++t) {
-    const unsigned char* kt0 = kbuf[t & 1];
-    const unsigned char* vt0 = kt0 + v_off;
+    unsigned char* kt0 = smem + (t & 1) * a.lds_buf_bytes;
+    unsigned char* vt0 = kt0 + v_off;
+    if constexpr (DIRECT) {
+      __builtin_amdgcn_s_waitcnt(0);       // this wavefront's share of tile t has landed
+      __syncthreads();                     // everybody's has, and nobody still reads the other buffer
+      if (t + 1 < n_tiles) issue_direct(t + 1);
+    }
+    if ((t + 1) * kKeysPerTile > len) {
+      // The V rows at or beyond the sequence length may hold anything (NaN included) and a zero
+      // probability does not silence a NaN: in the one tile that holds the end of the sequence
+      // they are cleared in LDS before use.
+      for (int o = (len - t * kKeysPerTile) * lpv + 2 * tid; o < kKeysPerTile * lpv; o += 512)
+        *reinterpret_cast<uint16_t*>(vt0 + o) = 0;
+      __syncthreads();
+    }
 #pragma unroll 1
     for (int sub = 0; sub < kKeysPerTile / kSub; ++sub) {
       const int sbase = t * kKeysPerTile + kSub * sub;
       if (sbase > wmax || sbase >= n_keys) break;   // nothing of this or any later key group is visible here
-      const unsigned char* kt = kt0 + sub * kSub * pitch_k;
-      const unsigned char* vt = vt0 + sub * kSub * pitch_v;
-      const int nv = min(kSub, len - sbase);         // rows of the group that exist, >= 1
+      const unsigned char* kt = kt0 + sub * kSub * lpk;
+      const unsigned char* vt = vt0 + sub * kSub * lpv;
       const bool no_mask = sbase + kSub - 1 <= wmin;
 
       // ---- scores: sc[nq][rt][r] = column (nq, l16) . K[sbase + 16 rt + 4 lg + r]
@@ -220,11 +262,11 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
         for (int kk = 0; kk < KCH; ++kk) {
           const uint32_t* p = reinterpret_cast<const uint32_t*>(kt + koff[rt] + 64 * kk);
           uint4 w = make_uint4(p[0], p[1], p[2], p[3]);
-          if (kk == KCH - 1) {
-            w.x &= kmask[0];
-            w.y &= kmask[1];
-            w.z &= kmask[2];
-            w.w &= kmask[3];
+          if (kk == KCH - 1) {                      // beyond d_k lies the next row (or stale LDS)
+            w.x = klim > 0 ? w.x : 0u;
+            w.y = klim > 2 ? w.y : 0u;
+            w.z = klim > 4 ? w.z : 0u;
+            w.w = klim > 6 ? w.w : 0u;
           }
           const bf16x8 kf = __builtin_bit_cast(bf16x8, w);
 #pragma unroll
@@ -284,18 +326,12 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
       }
 
       // ---- P.V: acc[nq][nt][reg] (column 4 lg + reg of block nq, channel slot l16 of tile nt)
-      int vo[8];
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int row = min(16 * (j >> 2) + 4 * lg + (j & 3), nv - 1);
-        vo[j] = nv == kSub ? voff[j >> 2][j & 3] : row * pitch_v + (VPAIR ? 4 : 2) * l16;
-      }
       if constexpr (VPAIR) {
 #pragma unroll
         for (int np = 0; np < NT / 2; ++np) {
           uint32_t w[8];
 #pragma unroll
-          for (int j = 0; j < 8; ++j) w[j] = *reinterpret_cast<const uint32_t*>(vt + vo[j] + 64 * np);
+          for (int j = 0; j < 8; ++j) w[j] = *reinterpret_cast<const uint32_t*>(vt + voff[j >> 2][j & 3] + 64 * np);
           uint4 be, bo;   // even / odd channel of the pair, rows packed two by two
           be.x = __builtin_amdgcn_perm(w[1], w[0], 0x05040100u);
           be.y = __builtin_amdgcn_perm(w[3], w[2], 0x05040100u);
@@ -320,7 +356,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
         for (int nt = 0; nt < NT; ++nt) {
           uint32_t u[8];
 #pragma unroll
-          for (int j = 0; j < 8; ++j) u[j] = *reinterpret_cast<const uint16_t*>(vt + vo[j] + 32 * nt);
+          for (int j = 0; j < 8; ++j) u[j] = *reinterpret_cast<const uint16_t*>(vt + voff[j >> 2][j & 3] + 32 * nt);
           const uint4 bv = make_uint4(u[0] | (u[1] << 16), u[2] | (u[3] << 16), u[4] | (u[5] << 16), u[6] | (u[7] << 16));
           const bf16x8 vb = __builtin_bit_cast(bf16x8, bv);
 #pragma unroll
@@ -333,10 +369,12 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
       }
     }
 
-    // ---- next tile into the other buffer (its last readers passed the previous barrier)
-    if (t + 1 < n_tiles) park((t + 1) & 1);
-    __syncthreads();
-    if (t + 2 < n_tiles) issue(t + 2);
+    if constexpr (!DIRECT) {
+      // ---- next tile into the other buffer (its last readers passed the previous barrier)
+      if (t + 1 < n_tiles) park((t + 1) & 1);
+      __syncthreads();
+      if (t + 2 < n_tiles) issue(t + 2);
+    }
   }
 
   // ---- normalise and store: accumulator register reg of lane (l16, lg) is column 4 lg + reg
@@ -365,26 +403,42 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   }
 }
 
-template <int KCH, int NT, bool VPAIR, int NQ>
-hipError_t launch_prefill_inst(PrefillArgs a, hipStream_t stream) {
-  a.tok_per_wg = (64 * NQ) / a.group;
-  a.n_qblk = (a.n_new + a.tok_per_wg - 1) / a.tok_per_wg;
-  const int kbytes = kKeysPerTile * 2 * a.d_k, vbytes = kKeysPerTile * 2 * a.d_v;
-  a.lds_buf_bytes = ((kbytes + 64 + 127) & ~127) + ((vbytes + 64 + 127) & ~127);
-  const size_t lds = 2 * static_cast<size_t>(a.lds_buf_bytes);
+template <int KCH, int NT, bool VPAIR, int NQ, bool DIRECT>
+hipError_t launch_prefill_go(const PrefillArgs& a, size_t lds, long long n_wg, hipStream_t stream) {
   if (lds > 64 * 1024) {
     static int raised_to = 0;
     if (raised_to < static_cast<int>(lds)) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<KCH, NT, VPAIR, NQ>),
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<KCH, NT, VPAIR, NQ, DIRECT>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
       if (e != hipSuccess) return e;
       raised_to = static_cast<int>(lds);
     }
   }
+  hipLaunchKernelGGL((prefill_kernel<KCH, NT, VPAIR, NQ, DIRECT>), dim3(static_cast<unsigned>(n_wg)), dim3(256), lds, stream, a);
+  return hipGetLastError();
+}
+
+template <int KCH, int NT, bool VPAIR, int NQ>
+hipError_t launch_prefill_inst(PrefillArgs a, hipStream_t stream) {
+  a.tok_per_wg = (64 * NQ) / a.group;
+  a.n_qblk = (a.n_new + a.tok_per_wg - 1) / a.tok_per_wg;
+  // padded LDS rows for pitches of 128 or 256 bytes (the shift turns a byte offset into its row)
+  const int pk = 2 * a.d_k, pv = 2 * a.d_v;
+  a.pad_k = (pk % 128 == 0) ? 16 : 0;
+  a.pad_v = (pv % 128 == 0) ? 16 : 0;
+  a.shift_k = a.pad_k ? (pk == 128 ? 7 : 8) : 31;
+  a.shift_v = a.pad_v ? (pv == 128 ? 7 : 8) : 31;
+  const int kbytes = kKeysPerTile * (pk + a.pad_k), vbytes = kKeysPerTile * (pv + a.pad_v);
+  a.lds_buf_bytes = ((kbytes + 64 + 127) & ~127) + ((vbytes + 64 + 127) & ~127);
+  const size_t lds = 2 * static_cast<size_t>(a.lds_buf_bytes);
   const long long n_wg = static_cast<long long>(a.n_qblk) * a.n_kv * a.batch;
   if (n_wg > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((prefill_kernel<KCH, NT, VPAIR, NQ>), dim3(static_cast<unsigned>(n_wg)), dim3(256), lds, stream, a);
-  return hipGetLastError();
+  // padded rows only occur at 128- and 256-byte pitches (d = 64, 128), where the kernel also has
+  // registers to spare for staging
+  if constexpr ((KCH == 2 || KCH == 4) || (NT == 4 || NT == 8)) {
+    if (a.pad_k || a.pad_v) return launch_prefill_go<KCH, NT, VPAIR, NQ, false>(a, lds, n_wg, stream);
+  }
+  return launch_prefill_go<KCH, NT, VPAIR, NQ, true>(a, lds, n_wg, stream);
 }
 
 template <int KCH, int NQ>
