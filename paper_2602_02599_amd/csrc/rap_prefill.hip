@@ -24,6 +24,8 @@
 // Garbage safety: rows at or beyond the sequence length may hold any bits; their scores are never
 // visible (a select to -inf), their V rows are cleared on the way into LDS, K fragments are masked
 // beyond d_k, and loads never touch rows >= round-up-8(len) <= cap.
+#include <utility>
+
 #include "rap_device.h"
 
 namespace rap {
@@ -39,6 +41,16 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
 constexpr int kKeysPerTile = 64;     // staged per barrier
 constexpr int kSub = 32;             // keys per matrix-instruction group (two 16-row fragments)
+struct Yes { static constexpr bool value = true; };
+struct No { static constexpr bool value = false; };
+
+// f(integral_constant<int, 0>), ..., f(integral_constant<int, N - 1>): a loop whose index is a
+// constant inside the body (register arrays must never be indexed by a run-time value)
+template <int... Is, class F>
+__device__ __forceinline__ void static_for(std::integer_sequence<int, Is...>, F&& f) {
+  (f(std::integral_constant<int, Is>()), ...);
+}
+
 constexpr float kHeadroomP = 64.f;   // log2 units a score may exceed the reference before a rescale
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
@@ -208,6 +220,10 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     for (int nt = 0; nt < NT; ++nt) acc[nq][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
+  // A spare channel slot (d_v not a multiple of 16) carries the constant 1, so that the row sums
+  // of the probabilities come out of the P.V product: slot l16 = 15 of the last channel tile.
+  const bool ones = (dv & 15) != 0;
+  const bool ones_lane = ones && l16 == 15;
   const int klim = dk - 32 * (KCH - 1) - 8 * lg;   // elements of this lane's last K fragment that exist
   int koff[2];
 #pragma unroll
@@ -250,7 +266,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
       if (sbase > wmax || sbase >= n_keys) break;   // nothing of this or any later key group is visible here
       const unsigned char* kt = kt0 + sub * kSub * lpk;
       const unsigned char* vt = vt0 + sub * kSub * lpv;
-      const bool no_mask = sbase + kSub - 1 <= wmin;
+      const bool no_mask = sbase + kSub - 1 <= wmin && a.scale_log2e >= 0.f;
 
       // ---- scores: sc[nq][rt][r] = column (nq, l16) . K[sbase + 16 rt + 4 lg + r]
       f32x4 sc[NQ][2];
@@ -275,21 +291,34 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
         }
       }
 
-      // ---- softmax numerators per column block, packed straight into the P.V operand
+      // ---- softmax numerators per column block, packed straight into the P.V operand.  When the
+      // group straddles the diagonal of this wavefront's columns (or the scale is negative) every
+      // score gets its visibility test; otherwise all 32 keys are visible to all columns and scale
+      // and reference fold into one multiply-add per score.
       uint4 p_hi[NQ], p_lo[NQ];
 #pragma unroll
       for (int nq = 0; nq < NQ; ++nq) {
-        float x[2][4];
+        float x[2][4];                               // exponent arguments before the reference is taken off
         float tmax = -INFINITY;
-        const int rel = pos_col[nq] - sbase;         // keys 0..rel of the group are visible to this column
+        if (no_mask) {
 #pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
+          for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const float s = sc[nq][rt][r] * a.scale_log2e;
-            x[rt][r] = (no_mask || (16 * rt + 4 * lg + r) <= rel) ? s : -INFINITY;
-            tmax = fmaxf(tmax, x[rt][r]);
-          }
+            for (int r = 0; r < 4; ++r) {
+              x[rt][r] = sc[nq][rt][r];
+              tmax = fmaxf(tmax, x[rt][r]);
+            }
+          tmax *= a.scale_log2e;                     // scale >= 0 on this path
+        } else {
+          const int rel = pos_col[nq] - sbase;       // keys 0..rel of the group are visible to this column
+#pragma unroll
+          for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              x[rt][r] = (16 * rt + 4 * lg + r) <= rel ? sc[nq][rt][r] * a.scale_log2e : -INFINITY;
+              tmax = fmaxf(tmax, x[rt][r]);
+            }
+        }
         if (__any(tmax > m_run[nq] + kHeadroomP)) {
           tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
           tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
@@ -306,14 +335,14 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
           m_run[nq] = m_new;
         }
         const float mref = m_run[nq] > -INFINITY ? m_run[nq] : 0.f;   // -inf - -inf would be NaN
+        const float mul = no_mask ? a.scale_log2e : 1.f;               // masked scores are scaled already
         float pr[2][4];
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            pr[rt][r] = __builtin_amdgcn_exp2f(x[rt][r] - mref);
-            l_run[nq] += pr[rt][r];
-          }
+          for (int r = 0; r < 4; ++r) pr[rt][r] = __builtin_amdgcn_exp2f(fmaf(x[rt][r], mul, -mref));
+        if (!ones)                                   // otherwise the sum comes out of the P.V product
+          l_run[nq] += ((pr[0][0] + pr[0][1]) + (pr[0][2] + pr[0][3])) + ((pr[1][0] + pr[1][1]) + (pr[1][2] + pr[1][3]));
         uint32_t* ph = reinterpret_cast<uint32_t*>(&p_hi[nq]);
         uint32_t* pl = reinterpret_cast<uint32_t*>(&p_lo[nq]);
 #pragma unroll
@@ -341,6 +370,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
           bo.y = __builtin_amdgcn_perm(w[3], w[2], 0x07060302u);
           bo.z = __builtin_amdgcn_perm(w[5], w[4], 0x07060302u);
           bo.w = __builtin_amdgcn_perm(w[7], w[6], 0x07060302u);
+          if (np == NT / 2 - 1 && ones_lane) bo = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
           const bf16x8 vbe = __builtin_bit_cast(bf16x8, be), vbo = __builtin_bit_cast(bf16x8, bo);
 #pragma unroll
           for (int nq = 0; nq < NQ; ++nq) {
@@ -357,7 +387,8 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
           uint32_t u[8];
 #pragma unroll
           for (int j = 0; j < 8; ++j) u[j] = *reinterpret_cast<const uint16_t*>(vt + voff[j >> 2][j & 3] + 32 * nt);
-          const uint4 bv = make_uint4(u[0] | (u[1] << 16), u[2] | (u[3] << 16), u[4] | (u[5] << 16), u[6] | (u[7] << 16));
+          uint4 bv = make_uint4(u[0] | (u[1] << 16), u[2] | (u[3] << 16), u[4] | (u[5] << 16), u[6] | (u[7] << 16));
+          if (nt == NT - 1 && ones_lane) bv = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
           const bf16x8 vb = __builtin_bit_cast(bf16x8, bv);
 #pragma unroll
           for (int nq = 0; nq < NQ; ++nq) {
@@ -386,7 +417,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
     for (int reg = 0; reg < 4; ++reg) {
       const int col = 4 * lg + reg;
-      const float lc = __shfl(l, col);
+      const float lc = ones ? __shfl(acc[nq][NT - 1][reg], 16 * lg + 15) : __shfl(l, col);
       const int cw = (wave * NQ + nq) * 16 + col;
       const int tl = cw / G, g = cw - (cw / G) * G;
       const int i = i0 + tl;
