@@ -58,7 +58,7 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-template <int KCH, int NT, bool VPAIR, int NQ, bool DIRECT>
+template <int KCH, int NT, bool VPAIR, int NQ, bool DIRECT, bool ONES>
 __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   constexpr int NCK = (kKeysPerTile * 64 * KCH + 4095) / 4096;   // 16-byte chunks per thread, K tile
   constexpr int NCV = (kKeysPerTile * 32 * NT + 4095) / 4096;    // same, V tile
@@ -222,8 +222,6 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 
   // A spare channel slot (d_v not a multiple of 16) carries the constant 1, so that the row sums
   // of the probabilities come out of the P.V product: slot l16 = 15 of the last channel tile.
-  const bool ones = (dv & 15) != 0;
-  const bool ones_lane = ones && l16 == 15;
   const int klim = dk - 32 * (KCH - 1) - 8 * lg;   // elements of this lane's last K fragment that exist
   int koff[2];
 #pragma unroll
@@ -266,9 +264,9 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
       if (sbase > wmax || sbase >= n_keys) break;   // nothing of this or any later key group is visible here
       const unsigned char* kt = kt0 + sub * kSub * lpk;
       const unsigned char* vt = vt0 + sub * kSub * lpv;
-      const bool no_mask = sbase + kSub - 1 <= wmin && a.scale_log2e >= 0.f;
+      const bool no_mask = sbase + kSub - 1 <= wmin;
 
-      // ---- scores: sc[nq][rt][r] = column (nq, l16) . K[sbase + 16 rt + 4 lg + r]
+      // ---- A. scores sc[nq][rt][r] = column (nq, l16) . K[sbase + 16 rt + 4 lg + r]
       f32x4 sc[NQ][2];
 #pragma unroll
       for (int nq = 0; nq < NQ; ++nq) sc[nq][0] = sc[nq][1] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -290,39 +288,37 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
             sc[nq][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[nq][kk], sc[nq][rt], 0, 0, 0);
         }
       }
-
-      // ---- softmax numerators per column block, packed straight into the P.V operand.  When the
-      // group straddles the diagonal of this wavefront's columns (or the scale is negative) every
-      // score gets its visibility test; otherwise all 32 keys are visible to all columns and scale
-      // and reference fold into one multiply-add per score.
-      uint4 p_hi[NQ], p_lo[NQ];
+      // ---- B. the visibility test where the group straddles the diagonal of this wavefront's
+      // columns, block maxima, and the rare move of a reference.  With all 32 keys visible and a
+      // non-negative scale the raw scores stay as they are: scale and reference then fold into
+      // one multiply-add per score (mul), and the maximum is scaled instead of the scores.
+      bool grow = false;
+      const bool raw = no_mask && a.scale_log2e >= 0.f;
+      const float mul = raw ? a.scale_log2e : 1.f;
+      if (!raw) {
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq) {
+          const int rel = no_mask ? kSub : pos_col[nq] - sbase;   // keys 0..rel of the group are visible to this column
+#pragma unroll
+          for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              sc[nq][rt][r] = (16 * rt + 4 * lg + r) <= rel ? sc[nq][rt][r] * a.scale_log2e : -INFINITY;
+        }
+      }
+      float tmax[NQ];
 #pragma unroll
       for (int nq = 0; nq < NQ; ++nq) {
-        float x[2][4];                               // exponent arguments before the reference is taken off
-        float tmax = -INFINITY;
-        if (no_mask) {
+        tmax[nq] = fmaxf(fmaxf(fmaxf(sc[nq][0][0], sc[nq][0][1]), fmaxf(sc[nq][0][2], sc[nq][0][3])),
+                         fmaxf(fmaxf(sc[nq][1][0], sc[nq][1][1]), fmaxf(sc[nq][1][2], sc[nq][1][3]))) * mul;
+        grow = grow || tmax[nq] > m_run[nq] + kHeadroomP;
+      }
+      if (__any(grow)) {
 #pragma unroll
-          for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              x[rt][r] = sc[nq][rt][r];
-              tmax = fmaxf(tmax, x[rt][r]);
-            }
-          tmax *= a.scale_log2e;                     // scale >= 0 on this path
-        } else {
-          const int rel = pos_col[nq] - sbase;       // keys 0..rel of the group are visible to this column
-#pragma unroll
-          for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              x[rt][r] = (16 * rt + 4 * lg + r) <= rel ? sc[nq][rt][r] * a.scale_log2e : -INFINITY;
-              tmax = fmaxf(tmax, x[rt][r]);
-            }
-        }
-        if (__any(tmax > m_run[nq] + kHeadroomP)) {
-          tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-          tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-          const float m_new = fmaxf(m_run[nq], tmax);
+        for (int nq = 0; nq < NQ; ++nq) {
+          float tm = fmaxf(tmax[nq], __shfl_xor(tmax[nq], 16));
+          tm = fmaxf(tm, __shfl_xor(tm, 32));
+          const float m_new = fmaxf(m_run[nq], tm);
           // a column that has seen nothing yet and sees nothing here keeps its -inf reference
           const float alpha = m_new > -INFINITY ? __builtin_amdgcn_exp2f(m_run[nq] - m_new) : 0.f;
           l_run[nq] *= alpha;
@@ -334,14 +330,28 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
           }
           m_run[nq] = m_new;
         }
+      }
+
+      // ---- C. numerators, packed straight into the P.V operand: a bf16 head and a bf16 remainder
+      // of every probability (16 significant bits); the remainder p - head comes from one
+      // two-term dot instruction per value (head . (-1, 0) + p, exact)
+      uint4 p_hi[NQ], p_lo[NQ];
+      // The two selectors are kept in scalar registers behind an empty asm: as literals the
+      // compiler encodes (-1, 0) as the inline constant -1.0, which the hardware reads as the
+      // fp32 pattern 0xbf800000 = (0, -1) for this instruction (checked with a small probe).
+      uint32_t sel_lo = 0x0000bf80u, sel_hi = 0xbf800000u;
+      asm volatile("" : "+s"(sel_lo), "+s"(sel_hi));
+      const bf16x2 minus_lo = __builtin_bit_cast(bf16x2, sel_lo);   // (-1, 0)
+      const bf16x2 minus_hi = __builtin_bit_cast(bf16x2, sel_hi);   // (0, -1)
+#pragma unroll
+      for (int nq = 0; nq < NQ; ++nq) {
         const float mref = m_run[nq] > -INFINITY ? m_run[nq] : 0.f;   // -inf - -inf would be NaN
-        const float mul = no_mask ? a.scale_log2e : 1.f;               // masked scores are scaled already
         float pr[2][4];
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-          for (int r = 0; r < 4; ++r) pr[rt][r] = __builtin_amdgcn_exp2f(fmaf(x[rt][r], mul, -mref));
-        if (!ones)                                   // otherwise the sum comes out of the P.V product
+          for (int r = 0; r < 4; ++r) pr[rt][r] = __builtin_amdgcn_exp2f(fmaf(sc[nq][rt][r], mul, -mref));
+        if constexpr (!ONES)                         // otherwise the sum comes out of the P.V product
           l_run[nq] += ((pr[0][0] + pr[0][1]) + (pr[0][2] + pr[0][3])) + ((pr[1][0] + pr[1][1]) + (pr[1][2] + pr[1][3]));
         uint32_t* ph = reinterpret_cast<uint32_t*>(&p_hi[nq]);
         uint32_t* pl = reinterpret_cast<uint32_t*>(&p_lo[nq]);
@@ -349,12 +359,15 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
         for (int d = 0; d < 4; ++d) {
           const float a0 = pr[d >> 1][2 * (d & 1)], a1 = pr[d >> 1][2 * (d & 1) + 1];
           const uint32_t hh = pack2(a0, a1);
+          const bf16x2 hv = __builtin_bit_cast(bf16x2, hh);
           ph[d] = hh;
-          pl[d] = pack2(a0 - bf16_lo(hh), a1 - bf16_hi(hh));
+          pl[d] = pack2(__builtin_amdgcn_fdot2_f32_bf16(hv, minus_lo, a0, false),
+                        __builtin_amdgcn_fdot2_f32_bf16(hv, minus_hi, a1, false));
         }
       }
 
-      // ---- P.V: acc[nq][nt][reg] (column 4 lg + reg of block nq, channel slot l16 of tile nt)
+      // ---- D. P.V: acc[nq][nt][reg] (column 4 lg + reg of block nq, channel slot l16 of tile nt);
+      // a gathered V operand serves all NQ blocks
       if constexpr (VPAIR) {
 #pragma unroll
         for (int np = 0; np < NT / 2; ++np) {
@@ -370,7 +383,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
           bo.y = __builtin_amdgcn_perm(w[3], w[2], 0x07060302u);
           bo.z = __builtin_amdgcn_perm(w[5], w[4], 0x07060302u);
           bo.w = __builtin_amdgcn_perm(w[7], w[6], 0x07060302u);
-          if (np == NT / 2 - 1 && ones_lane) bo = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
+          if (ONES && np == NT / 2 - 1 && l16 == 15) bo = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
           const bf16x8 vbe = __builtin_bit_cast(bf16x8, be), vbo = __builtin_bit_cast(bf16x8, bo);
 #pragma unroll
           for (int nq = 0; nq < NQ; ++nq) {
@@ -388,7 +401,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
           for (int j = 0; j < 8; ++j) u[j] = *reinterpret_cast<const uint16_t*>(vt + voff[j >> 2][j & 3] + 32 * nt);
           uint4 bv = make_uint4(u[0] | (u[1] << 16), u[2] | (u[3] << 16), u[4] | (u[5] << 16), u[6] | (u[7] << 16));
-          if (nt == NT - 1 && ones_lane) bv = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
+          if (ONES && nt == NT - 1 && l16 == 15) bv = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
           const bf16x8 vb = __builtin_bit_cast(bf16x8, bv);
 #pragma unroll
           for (int nq = 0; nq < NQ; ++nq) {
@@ -417,7 +430,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
     for (int reg = 0; reg < 4; ++reg) {
       const int col = 4 * lg + reg;
-      const float lc = ones ? __shfl(acc[nq][NT - 1][reg], 16 * lg + 15) : __shfl(l, col);
+      const float lc = ONES ? __shfl(acc[nq][NT - 1][reg], 16 * lg + 15) : __shfl(l, col);
       const int cw = (wave * NQ + nq) * 16 + col;
       const int tl = cw / G, g = cw - (cw / G) * G;
       const int i = i0 + tl;
@@ -434,19 +447,26 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   }
 }
 
-template <int KCH, int NT, bool VPAIR, int NQ, bool DIRECT>
-hipError_t launch_prefill_go(const PrefillArgs& a, size_t lds, long long n_wg, hipStream_t stream) {
+template <int KCH, int NT, bool VPAIR, int NQ, bool DIRECT, bool ONES>
+hipError_t launch_prefill_go2(const PrefillArgs& a, size_t lds, long long n_wg, hipStream_t stream) {
   if (lds > 64 * 1024) {
     static int raised_to = 0;
     if (raised_to < static_cast<int>(lds)) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<KCH, NT, VPAIR, NQ, DIRECT>),
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<KCH, NT, VPAIR, NQ, DIRECT, ONES>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
       if (e != hipSuccess) return e;
       raised_to = static_cast<int>(lds);
     }
   }
-  hipLaunchKernelGGL((prefill_kernel<KCH, NT, VPAIR, NQ, DIRECT>), dim3(static_cast<unsigned>(n_wg)), dim3(256), lds, stream, a);
+  hipLaunchKernelGGL((prefill_kernel<KCH, NT, VPAIR, NQ, DIRECT, ONES>), dim3(static_cast<unsigned>(n_wg)), dim3(256), lds, stream, a);
   return hipGetLastError();
+}
+
+// a spare channel slot exists exactly when d_v is not a multiple of 16
+template <int KCH, int NT, bool VPAIR, int NQ, bool DIRECT>
+hipError_t launch_prefill_go(const PrefillArgs& a, size_t lds, long long n_wg, hipStream_t stream) {
+  if ((a.d_v & 15) != 0) return launch_prefill_go2<KCH, NT, VPAIR, NQ, DIRECT, true>(a, lds, n_wg, stream);
+  return launch_prefill_go2<KCH, NT, VPAIR, NQ, DIRECT, false>(a, lds, n_wg, stream);
 }
 
 template <int KCH, int NT, bool VPAIR, int NQ>
