@@ -28,6 +28,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 
 
@@ -156,6 +157,36 @@ def cpu_baseline(I, case, min_seconds=10.0):
             "tokens_per_s": round(w.batch * n / dt, 3), "host_cpus": len(os.sched_getaffinity(0))}
 
 
+def prefill_figure(rap, torch, w, dev, reps=5):
+    """Causal prefill attention (rap_prefill_attn) at the workload's shape: every sequence prefilled
+    from scratch, HIP-event timing on torch's stream (the call is issued there).  Algorithmic
+    flops: 2 (d_k + d_v) per (query token, visible row, query head)."""
+    import math
+    B, S = w.batch, w.ctx
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed)
+    kc = torch.randn((B, w.n_kv_heads, S, w.d_k), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    vc = torch.randn((B, w.n_kv_heads, S, w.d_v), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    q = torch.randn((B, S, w.n_q_heads, w.d_k), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    sl = torch.full((B,), S, dtype=torch.int32, device=dev)
+    out = torch.empty((B, S, w.n_q_heads, w.d_v), dtype=torch.float32, device=dev)
+    shp = rap.shape(B, w.n_q_heads, w.n_kv_heads, w.d_head, w.n_pairs, w.d_v, S, w.rope_theta)
+    for _ in range(2):
+        rap.rap_prefill_attn(shp, S, q, kc, vc, sl, S, out, float(w.scale))
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in evs:
+        a.record()
+        rap.rap_prefill_attn(shp, S, q, kc, vc, sl, S, out, float(w.scale))
+        b.record()
+    torch.cuda.synchronize()
+    ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+    flops = B * w.n_q_heads * (S * (S + 1) / 2) * 2 * (w.d_k + w.d_v)
+    del kc, vc, q, out
+    torch.cuda.empty_cache()
+    return ms, flops
+
+
 def read_traffic(path):
     """HBM bytes per launch of the dominant kernel from the committed counter summary, if present."""
     try:
@@ -179,6 +210,7 @@ def main():
     ap.add_argument("--buffers", type=int, default=4, help="distinct cache copies rotated through")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-control", action="store_true", help="skip the rho = 1.0 control")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the causal prefill attention figure")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain copies of 256 MiB (known-size reference for hardware byte counters)")
     args = ap.parse_args()
@@ -265,6 +297,23 @@ def main():
         torch.cuda.empty_cache()
     else:
         case0 = job.cases[0]
+
+    if not args.no_prefill and w.ragged_min is None and w.batch * w.ctx * w.n_q_heads * w.d_v * 4 <= 8 << 30:
+        # next row of the path (not part of `value`): causal prefill attention at the same shape
+        case0 = job.cases[0]
+        del job.cases[1:]
+        torch.cuda.empty_cache()
+        pms, pflops = prefill_figure(rap, torch, w, dev)
+        pf = {"call": "rap_prefill_attn", "tokens_per_sequence": w.ctx, "ms": round(pms, 4),
+              "roofline": {"bound": "mfma", "kernel": "prefill_kernel", "achieved": round(pflops / pms / 1e9, 1),
+                           "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                           "frac": round(pflops / pms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                           "algorithmic_flops_per_launch": int(pflops)}}
+        if not args.no_control and (args.workload + "_rho1") in I.WORKLOADS:
+            cms, cflops = prefill_figure(rap, torch, I.WORKLOADS[args.workload + "_rho1"], dev)
+            pf["rho1_control"] = {"ms": round(cms, 4), "achieved": round(cflops / cms / 1e9, 1), "unit": "TFLOP/s",
+                                  "speedup_of_pruned": round(cms / pms, 4), "flop_ratio": round(cflops / pflops, 4)}
+        result["prefill"] = pf
 
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(I, case0)
