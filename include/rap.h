@@ -58,6 +58,14 @@ typedef struct rap_shape {
   int32_t d_v;        /* kept V channels                                         */
   int64_t cache_cap;  /* rows per (batch, kv head) in both caches                */
   double rope_theta;  /* theta_base                                              */
+  /* Optional frequency table, dev fp64 [n_kv_heads, P], or NULL.  When given it replaces both
+   * rope_theta and keep_pair_idx (which may then be NULL) in every call that rotates: compact
+   * pair c of KV head h turns by pair_inv_freq[h][c] radians per position.  This is how the RoPE
+   * variants of Sec. "Practical Considerations" enter: a scaled table (YaRN and the like) is
+   * gathered at the kept pairs by the caller, and an entry of 0 leaves a pair un-rotated, which
+   * is the hybrid rule for partial-rotary heads and NoPE layers (App. "RoPE in Recent Open
+   * LLMs"): channels kept by plain channel pruning ride along as frequency-0 pairs.           */
+  const double* pair_inv_freq;
 } rap_shape_t;
 
 /* Optional knobs for rap_decode_attn; NULL or all-zero means "choose for me". */
@@ -155,6 +163,19 @@ rap_status_t rap_decode_attn_rope(const rap_shape_t* shape, const void* q, const
                                   void* out, float scale,
                                   void* workspace, size_t workspace_bytes,
                                   const rap_tuning_t* tuning, void* stream);
+
+/* Query-side index-aware RoPE for many tokens (the prefill counterpart of the rotation fused into
+ * rap_decode_attn_rope): Eq. (latent-score), RoPE(X W~_q), with the arithmetic of rap_rope_append
+ * (fp64 angle from the pair's original index or from pair_inv_freq, one rounding to bf16).
+ *
+ *   q              dev  bf16  [batch, n_new, n_q_heads, 2P]  pruned, un-rotated, compact order
+ *   pos            dev  int32 [batch, n_new]  position of each token (any int32; no range rule)
+ *   keep_pair_idx  dev  int32 [n_kv_heads, P]; query head a uses the row of KV head a / G; a pair
+ *                                              whose index lies outside [0, D/2) is stored as zero
+ *   q_out          dev  bf16  [batch, n_new, n_q_heads, 2P]  may be the same buffer as q
+ */
+rap_status_t rap_rope_queries(const rap_shape_t* shape, int32_t n_new, const void* q, const int32_t* pos,
+                              const int32_t* keep_pair_idx, void* q_out, void* stream);
 
 /* Causal attention of the last n_new tokens of every sequence over the compact cache: the prefill
  * (or chunked-prefill) counterpart of rap_decode_attn, Eq. (attn) with the GQA remark per query

@@ -148,6 +148,22 @@ def rope_compact(x: np.ndarray, t, keep: np.ndarray, theta_base: float, d_head: 
     return np.concatenate([a * c - b * s, a * s + b * c], axis=-1)
 
 
+def rope_compact_freq(x: np.ndarray, t, pair_freq: np.ndarray) -> np.ndarray:
+    """Rotation of a compact row [..., 2P] whose pair c turns by pair_freq[c] radians per position:
+    the form Eq. (rope) takes under the RoPE variants of Sec. "Practical Considerations" (a scaled
+    frequency table gathered at the kept pairs) and under the hybrid rule (frequency 0 = a kept
+    channel pair that is not rotated).  Same block [[cos, -sin], [sin, cos]] on (c, c + P)."""
+    x = np.asarray(x, dtype=np.float64)
+    pair_freq = np.asarray(pair_freq, dtype=np.float64)
+    p = pair_freq.shape[-1]
+    if x.shape[-1] != 2 * p:
+        raise ValueError("compact row must have 2P elements")
+    phi = np.asarray(t, dtype=np.float64)[..., None] * pair_freq
+    c, s_ = np.cos(phi), np.sin(phi)
+    a, b = x[..., :p], x[..., p:]
+    return np.concatenate([a * c - b * s_, a * s_ + b * c], axis=-1)
+
+
 def select_pairs(x_full: np.ndarray, keep: np.ndarray) -> np.ndarray:
     """E_k applied to a full-width row: gather dims keep and keep + D/2."""
     d = x_full.shape[-1]
@@ -161,7 +177,7 @@ def select_pairs(x_full: np.ndarray, keep: np.ndarray) -> np.ndarray:
 # --------------------------------------------------------------------------
 
 
-def append_ref(k_new, v_new, pos, keep, k_cache, v_cache, theta_base, d_head):
+def append_ref(k_new, v_new, pos, keep, k_cache, v_cache, theta_base, d_head, pair_freq=None):
     """Rotate each new compact K row at its position and store K, V rows.
 
     k_new   uint16 [B, n_new, H_kv, 2P]  bf16 bits, before rotation
@@ -184,7 +200,10 @@ def append_ref(k_new, v_new, pos, keep, k_cache, v_cache, theta_base, d_head):
         for n in range(n_new):
             t = int(pos[b, n])
             for h in range(n_kv):
-                rot = rope_compact(kf[b, n, h], np.float64(t), keep[h], theta_base, d_head)
+                if pair_freq is None:
+                    rot = rope_compact(kf[b, n, h], np.float64(t), keep[h], theta_base, d_head)
+                else:       # caller's frequency table [H_kv, P] instead of theta_base and keep
+                    rot = rope_compact_freq(kf[b, n, h], np.float64(t), pair_freq[h])
                 k_cache[b, h, t, :] = f64_to_bf16_bits_rne(rot)
                 v_cache[b, h, t, :] = v_new[b, n, h, :]
 
@@ -271,7 +290,7 @@ def prefill_attn_ref(q, k_cache, v_cache, seq_lens, scale) -> np.ndarray:
     return out
 
 
-def rope_queries_ref(q, q_pos, keep, theta_base, d_head, n_kv_heads) -> np.ndarray:
+def rope_queries_ref(q, q_pos, keep, theta_base, d_head, n_kv_heads, pair_freq=None) -> np.ndarray:
     """Query side of Eq. (latent-score): index-aware rotation of pruned, un-rotated query rows.
 
     q      uint16 [B, H_q, 2P] bf16 bits; q_pos int [B]; keep int [H_kv, P].
@@ -286,7 +305,10 @@ def rope_queries_ref(q, q_pos, keep, theta_base, d_head, n_kv_heads) -> np.ndarr
     out = np.empty_like(q)
     for b in range(bsz):
         for a_h in range(n_q):
-            rot = rope_compact(qf[b, a_h], np.float64(int(q_pos[b])), keep[a_h // g], theta_base, d_head)
+            if pair_freq is None:
+                rot = rope_compact(qf[b, a_h], np.float64(int(q_pos[b])), keep[a_h // g], theta_base, d_head)
+            else:
+                rot = rope_compact_freq(qf[b, a_h], np.float64(int(q_pos[b])), pair_freq[a_h // g])
             out[b, a_h] = f64_to_bf16_bits_rne(rot)
     return out
 

@@ -25,6 +25,7 @@ class RapShape(C.Structure):
     _fields_ = [
         ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("d_head", C.c_int32),
         ("n_pairs", C.c_int32), ("d_v", C.c_int32), ("cache_cap", C.c_int64), ("rope_theta", C.c_double),
+        ("pair_inv_freq", C.c_void_p),
     ]
 
 
@@ -89,6 +90,8 @@ class Rap:
             L.rap_decode_step.argtypes = [C.POINTER(RapShape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_float, C.c_void_p,
                                           C.c_size_t, C.POINTER(RapTuning), C.c_void_p]
+        L.rap_rope_queries.restype = C.c_int
+        L.rap_rope_queries.argtypes = [C.POINTER(RapShape), C.c_int32] + [C.c_void_p] * 5
         L.rap_prefill_attn.restype = C.c_int
         L.rap_prefill_attn.argtypes = [C.POINTER(RapShape), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_int64, C.c_void_p, C.c_float, C.c_void_p]
@@ -113,8 +116,15 @@ class Rap:
         return int(self.lib.rap_version())
 
     @staticmethod
-    def shape(batch, n_q_heads, n_kv_heads, d_head, n_pairs, d_v, cache_cap, rope_theta) -> RapShape:
-        return RapShape(batch, n_q_heads, n_kv_heads, d_head, n_pairs, d_v, cache_cap, rope_theta)
+    def shape(batch, n_q_heads, n_kv_heads, d_head, n_pairs, d_v, cache_cap, rope_theta, pair_inv_freq=None) -> RapShape:
+        """pair_inv_freq: optional float64 GPU tensor [n_kv_heads, n_pairs] (see rap_shape_t); the
+        returned object keeps a reference to it."""
+        if pair_inv_freq is not None and tuple(pair_inv_freq.shape) != (n_kv_heads, n_pairs):
+            raise ValueError("pair_inv_freq must be [n_kv_heads, n_pairs]")
+        shp = RapShape(batch, n_q_heads, n_kv_heads, d_head, n_pairs, d_v, cache_cap, rope_theta,
+                       _ptr(pair_inv_freq, torch.float64, "pair_inv_freq"))
+        shp._keep_alive = pair_inv_freq
+        return shp
 
     @staticmethod
     def tuning(kernel=0, rows_per_split=0, ev_main_start=None, ev_main_stop=None) -> RapTuning:
@@ -173,6 +183,14 @@ class Rap:
                                       scale, _ptr(workspace, None, "workspace"),
                                       0 if workspace is None else workspace.numel() * workspace.element_size(),
                                       C.byref(tuning) if tuning is not None else None, _stream(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def rap_rope_queries(self, shape: RapShape, n_new: int, q, pos, keep_pair_idx, q_out, stream=None, check=True) -> int:
+        st = self.lib.rap_rope_queries(C.byref(shape), n_new, _ptr(q, torch.bfloat16, "q"), _ptr(pos, torch.int32, "pos"),
+                                       _ptr(keep_pair_idx, torch.int32, "keep_pair_idx"), _ptr(q_out, torch.bfloat16, "q_out"),
+                                       _stream(stream))
         if check:
             self._check(st)
         return st

@@ -8,6 +8,7 @@
 
 namespace rap {
 hipError_t launch_append(const AppendArgs& a, hipStream_t stream);
+hipError_t launch_rope_queries(const AppendArgs& a, hipStream_t stream);
 hipError_t launch_decode_valu(const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_merge(const DecodeArgs& a, hipStream_t stream);
@@ -89,7 +90,7 @@ rap_status_t rap_rope_append(const rap_shape_t* shape, int32_t n_new, const void
   if (st != RAP_OK) return st;
   if (n_new < 0) return RAP_ERR_SHAPE;
   if (n_new == 0 || shape->batch == 0) return RAP_OK;
-  if (!k_new || !v_new || !pos || !keep_pair_idx || !k_cache || !v_cache) return RAP_ERR_NULL;
+  if (!k_new || !v_new || !pos || (!keep_pair_idx && !shape->pair_inv_freq) || !k_cache || !v_cache) return RAP_ERR_NULL;
   if (static_cast<int64_t>(shape->batch) * n_new > 0x7fffffffLL) return RAP_ERR_UNSUPPORTED;
   if ((reinterpret_cast<uintptr_t>(k_new) & 3) || (reinterpret_cast<uintptr_t>(v_new) & 3) ||
       (reinterpret_cast<uintptr_t>(k_cache) & 3) || (reinterpret_cast<uintptr_t>(v_cache) & 3))
@@ -99,6 +100,7 @@ rap_status_t rap_rope_append(const rap_shape_t* shape, int32_t n_new, const void
   a.v_new = static_cast<const uint16_t*>(v_new);
   a.pos = pos;
   a.keep = keep_pair_idx;
+  a.pair_freq = shape->pair_inv_freq;
   a.k_cache = static_cast<uint16_t*>(k_cache);
   a.v_cache = static_cast<uint16_t*>(v_cache);
   a.batch = shape->batch;
@@ -107,9 +109,38 @@ rap_status_t rap_rope_append(const rap_shape_t* shape, int32_t n_new, const void
   a.d_head = shape->d_head;
   a.n_pairs = shape->n_pairs;
   a.d_v = shape->d_v;
+  a.group = 1;
   a.cap = shape->cache_cap;
   a.neg2_log2_theta_over_d = -2.0 * log2(shape->rope_theta) / static_cast<double>(shape->d_head);
   return rap::launch_append(a, static_cast<hipStream_t>(stream)) == hipSuccess ? RAP_OK : RAP_ERR_HIP;
+}
+
+rap_status_t rap_rope_queries(const rap_shape_t* shape, int32_t n_new, const void* q, const int32_t* pos,
+                              const int32_t* keep_pair_idx, void* q_out, void* stream) {
+  rap_status_t st = check_shape(shape);
+  if (st != RAP_OK) return st;
+  if (n_new < 0) return RAP_ERR_SHAPE;
+  if (n_new == 0 || shape->batch == 0) return RAP_OK;
+  if (!q || !pos || (!keep_pair_idx && !shape->pair_inv_freq) || !q_out) return RAP_ERR_NULL;
+  if (static_cast<int64_t>(shape->batch) * n_new > 0x7fffffffLL) return RAP_ERR_UNSUPPORTED;
+  if ((reinterpret_cast<uintptr_t>(q) & 3) || (reinterpret_cast<uintptr_t>(q_out) & 3)) return RAP_ERR_SHAPE;
+  rap::AppendArgs a;
+  memset(&a, 0, sizeof(a));
+  a.k_new = static_cast<const uint16_t*>(q);
+  a.pos = pos;
+  a.keep = keep_pair_idx;
+  a.pair_freq = shape->pair_inv_freq;
+  a.k_cache = static_cast<uint16_t*>(q_out);
+  a.batch = shape->batch;
+  a.n_new = n_new;
+  a.n_kv = shape->n_q_heads;          // heads per token row of the input
+  a.d_head = shape->d_head;
+  a.n_pairs = shape->n_pairs;
+  a.d_v = 0;
+  a.group = shape->n_q_heads / shape->n_kv_heads;
+  a.cap = shape->cache_cap;
+  a.neg2_log2_theta_over_d = -2.0 * log2(shape->rope_theta) / static_cast<double>(shape->d_head);
+  return rap::launch_rope_queries(a, static_cast<hipStream_t>(stream)) == hipSuccess ? RAP_OK : RAP_ERR_HIP;
 }
 
 size_t rap_decode_attn_workspace_bytes(const rap_shape_t* shape, int64_t max_seq_len, const rap_tuning_t* tuning) {
@@ -162,6 +193,7 @@ rap_status_t decode_impl(const rap_shape_t* shape, const void* q, const int32_t*
   a.q = static_cast<const uint16_t*>(q);
   a.q_pos = q_pos;
   a.keep = keep;
+  a.pair_freq = shape->pair_inv_freq;
   a.neg2_log2_theta_over_d = -2.0 * log2(shape->rope_theta) / static_cast<double>(shape->d_head);
   a.d_head = shape->d_head;
   a.k_cache = static_cast<const uint16_t*>(k_cache);
@@ -226,7 +258,7 @@ rap_status_t rap_decode_step(const rap_shape_t* shape, const void* k_new, const 
                              const int32_t* keep_pair_idx, const void* q, int32_t q_is_rotated, void* k_cache,
                              void* v_cache, const int32_t* seq_lens, int64_t max_seq_len, void* out, float scale,
                              void* workspace, size_t workspace_bytes, const rap_tuning_t* tuning, void* stream) {
-  if (shape && shape->batch > 0 && max_seq_len >= 1 && (!k_new || !v_new || !pos || !keep_pair_idx)) {
+  if (shape && shape->batch > 0 && max_seq_len >= 1 && (!k_new || !v_new || !pos || (!keep_pair_idx && !shape->pair_inv_freq))) {
     const rap_status_t st = check_shape(shape);
     return st != RAP_OK ? st : RAP_ERR_NULL;
   }
@@ -242,7 +274,7 @@ rap_status_t rap_decode_attn_rope(const rap_shape_t* shape, const void* q, const
                                   const int32_t* keep_pair_idx, const void* k_cache, const void* v_cache,
                                   const int32_t* seq_lens, int64_t max_seq_len, void* out, float scale,
                                   void* workspace, size_t workspace_bytes, const rap_tuning_t* tuning, void* stream) {
-  if (shape && shape->batch > 0 && max_seq_len >= 1 && (!q_pos || !keep_pair_idx)) {
+  if (shape && shape->batch > 0 && max_seq_len >= 1 && (!q_pos || (!keep_pair_idx && !shape->pair_inv_freq))) {
     const rap_status_t st = check_shape(shape);
     return st != RAP_OK ? st : RAP_ERR_NULL;
   }

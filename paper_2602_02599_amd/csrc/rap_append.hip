@@ -32,15 +32,15 @@ __global__ __launch_bounds__(256) void append_kernel(AppendArgs a) {
   const uint16_t* ksrc = a.k_new + (tok * a.n_kv + h) * (2 * P);
   const uint16_t* vsrc = a.v_new + (tok * a.n_kv + h) * a.d_v;
   const int t = a.pos[tok];
-  const int j = has_pair ? a.keep[h * P + lane] : 0;
+  double f = 0.0;
+  const bool rot = has_pair && pair_frequency(a.keep, a.pair_freq, a.neg2_log2_theta_over_d, a.d_head, h * P + lane, &f);
   const uint16_t kx = has_pair ? ksrc[lane] : 0, ky = has_pair ? ksrc[lane + P] : 0;
   const uint16_t v0 = has_v0 ? vsrc[lane] : 0, v1 = has_v1 ? vsrc[lane + kWave] : 0;
   if (t < 0 || t >= a.cap) return;                                        // documented: skipped
 
   const long long row = (static_cast<long long>(b) * a.n_kv + h) * a.cap + t;
-  if (has_pair && j >= 0 && j < a.d_head / 2) {                           // bad index: documented skip
-    // theta^(-2j/D) = 2^(j * (-2 log2(theta) / D)); the factor is taken in fp64 on the host
-    const double phi = static_cast<double>(t) * exp2(static_cast<double>(j) * a.neg2_log2_theta_over_d);
+  if (rot) {                                                              // bad index: documented skip
+    const double phi = static_cast<double>(t) * f;
     double sn, cs;
     sincos_f64(phi, &sn, &cs);
     const double x = static_cast<double>(bf16_to_f32(kx));
@@ -74,7 +74,10 @@ __device__ __forceinline__ uint32_t lane_read(int byte_addr, uint32_t v) {
   return static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(byte_addr, static_cast<int>(v)));
 }
 
-template <bool VDWORD>
+// QUERY: the same walk over query rows (rap_rope_queries): no V, no cache; row (b, n, head) of
+// the input is rotated at pos[b][n] with the kept pairs of KV head head / G and stored at the same
+// place of the output; a pair with a bad index is stored as zero.
+template <bool VDWORD, bool QUERY>
 __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs_per_wave) {
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -87,9 +90,9 @@ __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs
 
   // arithmetic role: lane c < P rotates pair c
   const bool has_pair = lane < P;
-  const int j = has_pair ? a.keep[h * P + lane] : -1;
-  const bool rot = j >= 0 && j < a.d_head / 2;                  // bad index: pair is skipped
-  const double f = rot ? exp2(static_cast<double>(j) * a.neg2_log2_theta_over_d) : 0.0;
+  double f = 0.0;                                               // bad index: pair is skipped
+  const bool rot = has_pair && pair_frequency(a.keep, a.pair_freq, a.neg2_log2_theta_over_d, a.d_head,
+                                              (QUERY ? h / a.group : h) * P + lane, &f);
   double sf, cf;
   sincos_f64(f, &sf, &cf);                                           // one step of the position
   const int x_lane = has_pair ? (lane >> 1) << 2 : 0, x_half = lane & 1;
@@ -100,8 +103,8 @@ __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs
   const bool x0 = e0 < P, x1 = e1 < P;                          // element is the x half of its pair
   const int c0 = has_k ? (x0 ? e0 : e0 - P) << 2 : 0, c1 = has_k ? (x1 ? e1 : e1 - P) << 2 : 0;
   const bool ok0 = has_k && lane_read(c0, rot) != 0, ok1 = has_k && lane_read(c1, rot) != 0;
-  const bool has_v0 = VDWORD ? 2 * lane < a.d_v : lane < a.d_v;
-  const bool has_v1 = !VDWORD && lane + kWave < a.d_v;
+  const bool has_v0 = !QUERY && (VDWORD ? 2 * lane < a.d_v : lane < a.d_v);
+  const bool has_v1 = !QUERY && !VDWORD && lane + kWave < a.d_v;
   const int kl = has_k ? lane : 0;
   const int vl0 = has_v0 ? lane : 0, vl1 = has_v1 ? lane + kWave : 0;
 
@@ -115,12 +118,12 @@ __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs
     const int cnt = min(kBulkRun, a.n_new - n0);
     const long long tok0 = static_cast<long long>(b) * a.n_new + n0;
     const uint16_t* ksrc0 = a.k_new + (tok0 * a.n_kv + h) * (2 * P);
-    const uint16_t* vsrc0 = a.v_new + (tok0 * a.n_kv + h) * a.d_v;
+    const uint16_t* vsrc0 = QUERY ? nullptr : a.v_new + (tok0 * a.n_kv + h) * a.d_v;
     const int tv = lane < cnt ? pos[n0 + lane] : 0;
     const int t0 = __builtin_amdgcn_readfirstlane(tv);
     // (a last, shorter run takes the general loop: at most kBulkRun - 1 tokens per sequence and head)
-    const bool in_order = cnt == kBulkRun && __all(lane >= kBulkRun || tv == t0 + lane) && t0 >= 0 &&
-                          static_cast<long long>(t0) + kBulkRun <= a.cap;
+    const bool in_order = cnt == kBulkRun && __all(lane >= kBulkRun || tv == t0 + lane) &&
+                          (QUERY || (t0 >= 0 && static_cast<long long>(t0) + kBulkRun <= a.cap));
 
     if (in_order) {
       // Loads are unconditional (straight-line code, all in flight together): lanes with nothing
@@ -129,7 +132,9 @@ __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs
 #pragma unroll
       for (int i = 0; i < kBulkRun; ++i) {
         kw[i] = reinterpret_cast<const uint32_t*>(ksrc0 + i * kstride)[kl];
-        if (VDWORD) {
+        if (QUERY) {
+          vw[i] = 0;
+        } else if (VDWORD) {
           vw[i] = reinterpret_cast<const uint32_t*>(vsrc0 + i * vstride)[vl0];
         } else {
           vw[i] = static_cast<uint32_t>((vsrc0 + i * vstride)[vl0]) |
@@ -138,8 +143,9 @@ __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs
       }
       if (!(anchored && t0 == t_next)) sincos_f64(static_cast<double>(t0) * f, &sn, &cs);   // exact
       const long long row0 = (static_cast<long long>(b) * a.n_kv + h) * a.cap + t0;
-      uint16_t* kdst0 = a.k_cache + row0 * (2 * P);
-      uint16_t* vdst0 = a.v_cache + row0 * a.d_v;
+      uint16_t* kdst0 = QUERY ? a.k_cache + (tok0 * a.n_kv + h) * (2 * P) : a.k_cache + row0 * (2 * P);
+      const long long kdstride = QUERY ? kstride : 2 * P;          // consecutive cache rows, or the input's layout
+      uint16_t* vdst0 = QUERY ? nullptr : a.v_cache + row0 * a.d_v;
 #pragma unroll
       for (int i = 0; i < kBulkRun; ++i) {
         {
@@ -153,15 +159,18 @@ __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs
           cs = c2;
           const uint32_t p0 = lane_read(c0, o), p1 = lane_read(c1, o);
           const uint32_t o0 = x0 ? p0 & 0xffffu : p0 >> 16, o1 = x1 ? p1 & 0xffffu : p1 >> 16;
-          uint16_t* kdst = kdst0 + static_cast<long long>(i) * (2 * P);
-          if (ok0 && ok1) {
+          uint16_t* kdst = kdst0 + i * kdstride;
+          if (QUERY) {
+            if (has_k) reinterpret_cast<uint32_t*>(kdst)[lane] = (ok0 ? o0 : 0u) | ((ok1 ? o1 : 0u) << 16);
+          } else if (ok0 && ok1) {
             reinterpret_cast<uint32_t*>(kdst)[lane] = o0 | (o1 << 16);
           } else {
             if (ok0) kdst[e0] = static_cast<uint16_t>(o0);
             if (ok1) kdst[e1] = static_cast<uint16_t>(o1);
           }
           uint16_t* vdst = vdst0 + static_cast<long long>(i) * a.d_v;
-          if (VDWORD) {
+          if (QUERY) {
+          } else if (VDWORD) {
             if (has_v0) reinterpret_cast<uint32_t*>(vdst)[lane] = vw[i];
           } else {
             if (has_v0) vdst[lane] = static_cast<uint16_t>(vw[i]);
@@ -178,8 +187,25 @@ __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs
     anchored = false;
     for (int i = 0; i < cnt; ++i) {
       const int t = pos[n0 + i];
-      if (t < 0 || t >= a.cap) continue;                         // documented: skipped
       const uint16_t* ksrc = ksrc0 + i * kstride;
+      if (QUERY) {
+        uint16_t r0 = 0, r1 = 0;
+        if (rot) {
+          double s1, c1d;
+          sincos_f64(static_cast<double>(t) * f, &s1, &c1d);
+          const double x = static_cast<double>(bf16_to_f32(ksrc[lane]));
+          const double y = static_cast<double>(bf16_to_f32(ksrc[lane + P]));
+          r0 = f64_to_bf16_rne(x * c1d - y * s1);
+          r1 = f64_to_bf16_rne(x * s1 + y * c1d);
+        }
+        if (has_pair) {
+          uint16_t* qdst = a.k_cache + ((tok0 + i) * a.n_kv + h) * (2 * P);
+          qdst[lane] = r0;
+          qdst[lane + P] = r1;
+        }
+        continue;
+      }
+      if (t < 0 || t >= a.cap) continue;                         // documented: skipped
       const uint16_t* vsrc = vsrc0 + i * vstride;
       const long long row = (static_cast<long long>(b) * a.n_kv + h) * a.cap + t;
       if (rot) {
@@ -207,13 +233,24 @@ hipError_t launch_append(const AppendArgs& a, hipStream_t stream) {
     const int per_wg = 4 * rpw * kBulkRun;
     dim3 grid(static_cast<unsigned>((a.n_new + per_wg - 1) / per_wg), static_cast<unsigned>(a.n_kv),
               static_cast<unsigned>(a.batch));
-    if ((a.d_v & 1) == 0) hipLaunchKernelGGL(append_bulk_kernel<true>, grid, dim3(256), 0, stream, a, rpw);
-    else hipLaunchKernelGGL(append_bulk_kernel<false>, grid, dim3(256), 0, stream, a, rpw);
+    if ((a.d_v & 1) == 0) hipLaunchKernelGGL((append_bulk_kernel<true, false>), grid, dim3(256), 0, stream, a, rpw);
+    else hipLaunchKernelGGL((append_bulk_kernel<false, false>), grid, dim3(256), 0, stream, a, rpw);
     return hipGetLastError();
   }
   const long long n_tok = static_cast<long long>(a.batch) * a.n_new;
   dim3 grid(static_cast<unsigned>((n_tok + 3) / 4), static_cast<unsigned>(a.n_kv), 1);
   hipLaunchKernelGGL(append_kernel, grid, dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+// Query rows: k_new = input, k_cache = output (same layout), n_kv = number of query heads, group = G.
+hipError_t launch_rope_queries(const AppendArgs& a, hipStream_t stream) {
+  const long long runs = static_cast<long long>((a.n_new + kBulkRun - 1) / kBulkRun) * a.n_kv * a.batch;
+  const int rpw = runs >= 32768 ? 4 : runs >= 16384 ? 2 : 1;
+  const int per_wg = 4 * rpw * kBulkRun;
+  dim3 grid(static_cast<unsigned>((a.n_new + per_wg - 1) / per_wg), static_cast<unsigned>(a.n_kv),
+            static_cast<unsigned>(a.batch));
+  hipLaunchKernelGGL((append_bulk_kernel<true, true>), grid, dim3(256), 0, stream, a, rpw);
   return hipGetLastError();
 }
 

@@ -71,7 +71,8 @@ constexpr float kHeadroom = 64.f;
 // are those a separate append followed by reading the cache would have produced.  The loads are
 // a step of their own so that they can be requested together with the workgroup's other first loads.
 struct TokenRegs {
-  int j;
+  double f;
+  bool rot;
   uint16_t kx, ky, v0, v1;
   uint16_t qx[kMaxGroup], qy[kMaxGroup];
 };
@@ -80,7 +81,8 @@ __device__ __forceinline__ void token_load(const DecodeArgs& a, int b, int h, in
   const int P = a.n_pairs;
   const long long nrow = static_cast<long long>(b) * a.n_kv + h;
   const bool hp = lane < P;
-  r.j = hp ? a.keep[h * P + lane] : -1;
+  r.f = 0.0;
+  r.rot = hp && pair_frequency(a.keep, a.pair_freq, a.neg2_log2_theta_over_d, a.d_head, h * P + lane, &r.f);
   r.kx = hp ? a.k_new[nrow * 2 * P + lane] : 0;
   r.ky = hp ? a.k_new[nrow * 2 * P + lane + P] : 0;
   r.v0 = lane < a.d_v ? a.v_new[nrow * a.d_v + lane] : 0;
@@ -102,8 +104,8 @@ __device__ __forceinline__ void token_finish(const DecodeArgs& a, int b, int h, 
   const long long row = nrow * a.cap + t;
   uint16_t kxr = 0, kyr = 0;
   if (lane < P && stored) {
-    if (r.j >= 0 && r.j < a.d_head / 2) {
-      const double phi = static_cast<double>(t) * exp2(static_cast<double>(r.j) * a.neg2_log2_theta_over_d);
+    if (r.rot) {
+      const double phi = static_cast<double>(t) * r.f;
       double sn, cs;
       sincos_f64(phi, &sn, &cs);
       const double x = static_cast<double>(bf16_to_f32(r.kx)), y = static_cast<double>(bf16_to_f32(r.ky));

@@ -68,14 +68,31 @@ __device__ __forceinline__ void sincos_f64(double phi, double* s, double* c) {
   *c = ((n + 1) & 2) ? -b : b;
 }
 
+// Angular frequency of compact pair idx = h * P + c: from the caller's table when there is one
+// (every entry is valid, 0 means "do not rotate"), else theta^(-2j/D) = 2^(j * (-2 log2(theta) / D))
+// at the pair's original index j; false when that index lies outside [0, D/2).
+__device__ __forceinline__ bool pair_frequency(const int32_t* keep, const double* pair_freq, double neg2_log2_theta_over_d,
+                                               int d_head, int idx, double* f) {
+  if (pair_freq != nullptr) {
+    *f = pair_freq[idx];
+    return true;
+  }
+  const int j = keep[idx];
+  const bool ok = j >= 0 && j < d_head / 2;
+  *f = ok ? exp2(static_cast<double>(j) * neg2_log2_theta_over_d) : 0.0;
+  return ok;
+}
+
 struct AppendArgs {
   const uint16_t* k_new;
   const uint16_t* v_new;
   const int32_t* pos;
   const int32_t* keep;
+  const double* pair_freq;          // [H_kv, P] radians per position, or null: theta_j from keep
   uint16_t* k_cache;
   uint16_t* v_cache;
   int32_t batch, n_new, n_kv, d_head, n_pairs, d_v;
+  int32_t group;                    // query rows only: heads per row of keep / pair_freq
   int64_t cap;
   double neg2_log2_theta_over_d;    // -2 log2(theta_base) / D, so that theta_j = 2^(j * this)
 };
@@ -84,6 +101,7 @@ struct DecodeArgs {
   const uint16_t* q;
   const int32_t* q_pos;     // [B] or null: when given, q is un-rotated and is rotated at q_pos[b] first
   const int32_t* keep;      // [H_kv, P] original pair indices (only with q_pos)
+  const double* pair_freq;  // [H_kv, P] radians per position, or null: theta_j from keep
   double neg2_log2_theta_over_d;
   int32_t d_head;
   const uint16_t* k_cache;
@@ -139,10 +157,10 @@ __device__ __forceinline__ void rotate_queries_to_lds(const DecodeArgs& a, int b
   for (int e = tid; e < G * P; e += nthreads) {
     const int g = e / P, c = e - g * P;
     const uint16_t* qrow = a.q + (static_cast<long long>(b) * a.n_q + h * G + g) * (2 * P);
-    const int j = a.keep[h * P + c];
+    double f;
     uint16_t r0 = 0, r1 = 0;
-    if (j >= 0 && j < a.d_head / 2) {
-      const double phi = static_cast<double>(t) * exp2(static_cast<double>(j) * a.neg2_log2_theta_over_d);
+    if (pair_frequency(a.keep, a.pair_freq, a.neg2_log2_theta_over_d, a.d_head, h * P + c, &f)) {
+      const double phi = static_cast<double>(t) * f;
       double sn, cs;
       sincos_f64(phi, &sn, &cs);
       const double x = static_cast<double>(bf16_to_f32(qrow[c]));

@@ -41,9 +41,6 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
 constexpr int kKeysPerTile = 64;     // staged per barrier
 constexpr int kSub = 32;             // keys per matrix-instruction group (two 16-row fragments)
-struct Yes { static constexpr bool value = true; };
-struct No { static constexpr bool value = false; };
-
 // f(integral_constant<int, 0>), ..., f(integral_constant<int, N - 1>): a loop whose index is a
 // constant inside the body (register arrays must never be indexed by a run-time value)
 template <int... Is, class F>

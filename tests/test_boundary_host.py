@@ -29,8 +29,9 @@ def test_every_declared_symbol_is_exported(rap):
 
 
 def test_struct_layout_matches_header():
-    assert C.sizeof(pkg.RapShape) == 40
+    assert C.sizeof(pkg.RapShape) == 48
     assert pkg.RapShape.cache_cap.offset == 24 and pkg.RapShape.rope_theta.offset == 32
+    assert pkg.RapShape.pair_inv_freq.offset == 40
     assert C.sizeof(pkg.RapTuning) == 32 and pkg.RapTuning.ev_main_start.offset == 16
 
 

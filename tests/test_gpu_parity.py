@@ -471,6 +471,121 @@ def test_prefill_cfg2_sampled(rap):
     H.assert_attn_close(np.array(got), np.array(ref), "prefill cfg2 sampled")
 
 
+def test_frequency_table(rap):
+    """rap_shape_t.pair_inv_freq: a scaled frequency table with un-rotated pairs replaces rope_theta
+    and keep_pair_idx in the per-token append, the run-based append, the fused query rotation and
+    the one-call step (keep_pair_idx passed as NULL)."""
+    P, dv, Hq, Hkv, D, theta = 45, 90, 8, 2, 128, 5.0e5
+    _say("frequency table")
+    w = I.scaled(I.WORKLOADS["cfg2"], batch=3, n_q_heads=Hq, n_kv_heads=Hkv, ctx=600, n_new=40, ragged_min=200, peaky_frac=0.0, seed=55)
+    case = I.make_case(w, device=DEV)
+    keep = case.keep.cpu().numpy()
+    table = O.inv_freq(theta, D)[keep]                                   # [H_kv, P]
+    table = table * np.where(table < 0.01, 0.125, 1.0)                   # long wavelengths stretched (a scaled table)
+    table[:, ::7] = 0.0                                                  # some pairs not rotated at all
+    tdev = torch.from_numpy(table).to(DEV)
+    shp = rap.shape(w.batch, Hq, Hkv, D, P, dv, case.cap, 1.0, pair_inv_freq=tdev)   # rope_theta is not used
+    lens = case.seq_lens.cpu().numpy()
+    # run-based append of 40 tokens, then per-token append of 3 more at far rows
+    okc, ovc = I.bits(case.k_cache).copy(), I.bits(case.v_cache).copy()
+    rap.rap_rope_append(shp, w.n_new, case.k_new, case.v_new, case.pos, None, case.k_cache, case.v_cache)
+    O.append_ref(I.bits(case.k_new), I.bits(case.v_new), case.pos.cpu().numpy(), None, okc, ovc, theta, D, pair_freq=table)
+    k3, v3 = case.k_new[:, :3].contiguous(), case.v_new[:, :3].contiguous()
+    pos3 = torch.tensor([[5, 0, case.cap - 1]] * w.batch, dtype=torch.int32, device=DEV)
+    rap.rap_rope_append(shp, 3, k3, v3, pos3, None, case.k_cache, case.v_cache)
+    O.append_ref(I.bits(k3), I.bits(v3), pos3.cpu().numpy(), None, okc, ovc, theta, D, pair_freq=table)
+    torch.cuda.synchronize()
+    dist = H.bf16_ulp_distance(I.bits(case.k_cache), okc)
+    assert dist.max() <= 1 and (dist != 0).sum() <= dist.size // 1000 + 1
+    assert np.array_equal(I.bits(case.v_cache), ovc)
+    # fused query rotation and the one-call step
+    qpos_np = (lens - 1).astype(np.int32)
+    qpos = torch.from_numpy(qpos_np).to(DEV)
+    qrot = O.rope_queries_ref(I.bits(case.q), qpos_np, None, theta, D, Hkv, pair_freq=table)
+    for kernel in (VALU, MFMA):
+        tun = rap.tuning(kernel=kernel)
+        ws = rap.new_workspace(shp, case.cap, tun)
+        out = torch.full((w.batch, Hq, dv), float("nan"), dtype=torch.float32, device=DEV)
+        rap.rap_decode_attn_rope(shp, case.q, qpos, None, case.k_cache, case.v_cache, case.seq_lens, case.cap, out, float(w.scale), ws, tun)
+        torch.cuda.synchronize()
+        ref = O.attn_ref(qrot, I.bits(case.k_cache), I.bits(case.v_cache), lens, w.scale)
+        H.assert_attn_close(out.cpu().numpy(), ref, "table, fused query rotation, kernel %d" % kernel)
+        kc, vc = case.k_cache.clone(), case.v_cache.clone()
+        kn, vn = case.k_new[:, -1].contiguous(), case.v_new[:, -1].contiguous()
+        rap.rap_decode_step(shp, kn, vn, qpos, None, case.q, False, kc, vc, case.seq_lens, case.cap, out, float(w.scale), ws, tun)
+        torch.cuda.synchronize()
+        okc2, ovc2 = I.bits(case.k_cache).copy(), I.bits(case.v_cache).copy()
+        O.append_ref(I.bits(kn)[:, None], I.bits(vn)[:, None], qpos_np[:, None], None, okc2, ovc2, theta, D, pair_freq=table)
+        assert H.bf16_ulp_distance(I.bits(kc), okc2).max() <= 1 and np.array_equal(I.bits(vc), ovc2)
+        ref = O.attn_ref(qrot, I.bits(kc), I.bits(vc), lens, w.scale)
+        H.assert_attn_close(out.cpu().numpy(), ref, "table, one-call step, kernel %d" % kernel)
+
+
+def _rope_queries_oracle(q_bits, pos, keep, theta, d_head, n_kv, pair_freq=None):
+    """Token by token through the oracle's query rotation ([B, n, H_q, 2P])."""
+    out = np.empty_like(q_bits)
+    for n in range(q_bits.shape[1]):
+        out[:, n] = O.rope_queries_ref(q_bits[:, n], pos[:, n], keep, theta, d_head, n_kv, pair_freq=pair_freq)
+    return out
+
+
+@pytest.mark.parametrize("P,Hq,Hkv,n_new", [(45, 8, 2, 100), (58, 8, 2, 37), (32, 10, 2, 16), (64, 4, 1, 7), (3, 3, 1, 65)])
+def test_rope_queries(rap, P, Hq, Hkv, n_new):
+    """rap_rope_queries against the oracle, bit for bit up to the 1-ulp bar: consecutive positions
+    (angle carried along runs), shuffled and far positions, short inputs, a bad pair index (stored
+    as zero), in place."""
+    B, D, theta = 3, 128, 5.0e5
+    _say("rope queries P=%d heads %d/%d n_new=%d" % (P, Hq, Hkv, n_new))
+    rng = np.random.Generator(np.random.PCG64(31 + P))
+    keep = I.draw_keep(rng, Hkv, D // 2, P)
+    if P > 4:
+        keep[0, 3] = D // 2 + 5                                   # bad index
+    gen = torch.Generator(device=DEV); gen.manual_seed(8)
+    q = torch.randn((B, n_new, Hq, 2 * P), generator=gen, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    pos = np.stack([np.arange(n_new) + 1000, rng.permutation(131072)[:n_new], np.arange(n_new) * 3]).astype(np.int32)
+    keep_t = torch.from_numpy(keep.astype(np.int32)).to(DEV)
+    pos_t = torch.from_numpy(pos).to(DEV)
+    shp = rap.shape(B, Hq, Hkv, D, P, 2 * P, 8, theta)
+    out = torch.empty_like(q)
+    rap.rap_rope_queries(shp, n_new, q, pos_t, keep_t, out)
+    inplace = q.clone()
+    rap.rap_rope_queries(shp, n_new, inplace, pos_t, keep_t, inplace)
+    torch.cuda.synchronize()
+    keep_ref = keep.copy()
+    ref = _rope_queries_oracle(I.bits(q), pos, np.where(keep_ref < D // 2, keep_ref, 0), theta, D, Hkv)
+    if P > 4:                                                     # the bad pair reads as zero for the heads of KV head 0
+        G = Hq // Hkv
+        ref[:, :, :G, 3] = 0
+        ref[:, :, :G, 3 + P] = 0
+    dist = H.bf16_ulp_distance(I.bits(out), ref)
+    assert dist.max() <= 1 and (dist != 0).sum() <= dist.size // 1000 + 1, (int(dist.max()), int((dist != 0).sum()))
+    assert torch.equal(out.view(torch.int16), inplace.view(torch.int16))
+
+
+def test_prefill_pipeline(rap):
+    """The three prefill calls in sequence, run-based append of K/V, rotation of the queries and
+    causal attention, against the oracle's composition on un-rotated inputs."""
+    w = I.scaled(I.WORKLOADS["cfg2"], batch=2, n_q_heads=8, n_kv_heads=2, ctx=333, n_new=333, peaky_frac=0.0, seed=99)
+    _say("prefill pipeline")
+    case = I.make_case(w, device=DEV, fill_unused=False)
+    gen = torch.Generator(device=DEV); gen.manual_seed(4)
+    q = torch.randn((w.batch, w.n_new, w.n_q_heads, w.d_k), generator=gen, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    shp = H.shape_of(rap, case)
+    rap.rap_rope_append(shp, w.n_new, case.k_new, case.v_new, case.pos, case.keep, case.k_cache, case.v_cache)
+    qr = torch.empty_like(q)
+    rap.rap_rope_queries(shp, w.n_new, q, case.pos, case.keep, qr)
+    out = torch.empty((w.batch, w.n_new, w.n_q_heads, w.d_v), dtype=torch.float32, device=DEV)
+    rap.rap_prefill_attn(shp, w.n_new, qr, case.k_cache, case.v_cache, case.seq_lens, case.cap, out, float(w.scale))
+    torch.cuda.synchronize()
+    keep = case.keep.cpu().numpy()
+    pos = case.pos.cpu().numpy()
+    okc = np.zeros_like(I.bits(case.k_cache)); ovc = np.zeros_like(I.bits(case.v_cache))
+    O.append_ref(I.bits(case.k_new), I.bits(case.v_new), pos, keep, okc, ovc, w.rope_theta, w.d_head)
+    qref = _rope_queries_oracle(I.bits(q), pos, keep, w.rope_theta, w.d_head, w.n_kv_heads)
+    ref = O.prefill_attn_ref(qref, okc, ovc, case.seq_lens.cpu().numpy(), w.scale)
+    H.assert_attn_close(out.cpu().numpy(), ref, "prefill pipeline")
+
+
 def test_split_invariance(rap):
     """1 range vs many: same result up to fp32 rounding (merge identity on the GPU side)."""
     w = I.scaled(I.WORKLOADS["cfg2"], batch=2, ctx=4000, seed=13)

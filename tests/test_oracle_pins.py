@@ -537,6 +537,33 @@ def test_prefill_brute_force_tiny():
                 assert abs(got[0, i, a_h, c] - want) < 1e-14
 
 
+def test_frequency_table_rotation_pins():
+    """rope_compact_freq: with the table theta^(-2 keep/D) it is rope_compact bit for bit; an entry
+    of 0 leaves its pair untouched whatever the position (hybrid rule: un-rotated kept channels);
+    any table keeps the relative-position invariant of the scores; one pair in closed form."""
+    rng = _rng(77)
+    D, P, theta = 128, 45, 5.0e5
+    keep = np.sort(rng.choice(D // 2, P, replace=False))
+    x = rng.standard_normal((5, 2 * P))
+    t = np.array([0, 1, 17, 4095, 131071])
+    table = O.inv_freq(theta, D)[keep]
+    assert np.array_equal(O.rope_compact_freq(x, t, table), O.rope_compact(x, t, keep, theta, D))
+    # a scaled table with some pairs switched off
+    scaled = table * np.where(np.arange(P) % 3 == 0, 0.25, 1.0)
+    scaled[[2, 7, 40]] = 0.0
+    y = O.rope_compact_freq(x, t, scaled)
+    for c in (2, 7, 40):
+        assert np.array_equal(y[:, c], x[:, c]) and np.array_equal(y[:, c + P], x[:, c + P])
+    q, k = rng.standard_normal(2 * P), rng.standard_normal(2 * P)
+    s0 = O.rope_compact_freq(q, 1000, scaled) @ O.rope_compact_freq(k, 900, scaled)
+    s1 = O.rope_compact_freq(q, 100 + 64, scaled) @ O.rope_compact_freq(k, 64, scaled)
+    assert abs(s0 - s1) < 1e-9
+    # one pair: (a, b) at position t with frequency f is the complex number (a + i b) e^{i t f}
+    z = complex(0.75, -1.5) * cmath.exp(1j * 37 * 0.0123)
+    r = O.rope_compact_freq(np.array([0.75, -1.5]), 37, np.array([0.0123]))
+    assert abs(r[0] - z.real) < 1e-15 and abs(r[1] - z.imag) < 1e-15
+
+
 def test_split_merge_identity():
     """Merging (m, l, acc) partials over any partition of the rows gives the unsplit result."""
     rng = _rng(17)
