@@ -224,6 +224,41 @@ rap_status_t rap_decode_step(const rap_shape_t* shape,
                              void* workspace, size_t workspace_bytes,
                              const rap_tuning_t* tuning, void* stream);
 
+/* Paged caches, as serving stacks keep them (the paper's own measurements sit on such stacks).
+ * K and V live in pools of pages shared by all sequences,
+ *   k_pool  dev bf16 [n_pages, n_kv_heads, page_rows, 2P],  v_pool  dev bf16 [n_pages, n_kv_heads, page_rows, d_v],
+ * and row t of sequence b is row t % page_rows of page block_table[b][t / page_rows].
+ *   page_rows        a power of two, 32 .. 65536 (a 32-row tile then never straddles two pages)
+ *   n_pages          pages in the pools
+ *   max_pages        columns of block_table; shape->cache_cap must equal max_pages * page_rows
+ *   block_table      dev int32 [batch, max_pages]; only the entries that cover rows [0, seq_lens[b])
+ *                    (and appended positions) are read; a page number outside [0, n_pages) is
+ *                    clamped into the pool (wrong result for that sequence, no stray access)
+ * Both pools 16-byte aligned.  Everything else is as for the dense calls of the same name:
+ * the same kernels with another start address per 32-row tile. */
+typedef struct rap_paging {
+  int32_t page_rows;
+  int32_t n_pages;
+  int32_t max_pages;
+  int32_t reserved;
+  const int32_t* block_table;
+} rap_paging_t;
+
+rap_status_t rap_rope_append_paged(const rap_shape_t* shape, const rap_paging_t* paging, int32_t n_new,
+                                   const void* k_new, const void* v_new, const int32_t* pos,
+                                   const int32_t* keep_pair_idx, void* k_pool, void* v_pool, void* stream);
+
+/* rap_decode_attn over paged caches (matrix-core kernel only: tuning->kernel = 1 is
+ * RAP_ERR_UNSUPPORTED); q_pos non-NULL fuses the query rotation as rap_decode_attn_rope does.
+ * Workspace size: rap_decode_attn_workspace_bytes with the same shape. */
+rap_status_t rap_decode_attn_paged(const rap_shape_t* shape, const rap_paging_t* paging, const void* q,
+                                   const int32_t* q_pos, const int32_t* keep_pair_idx,
+                                   const void* k_pool, const void* v_pool,
+                                   const int32_t* seq_lens, int64_t max_seq_len,
+                                   void* out, float scale,
+                                   void* workspace, size_t workspace_bytes,
+                                   const rap_tuning_t* tuning, void* stream);
+
 /* Measurement aids (not part of the method): a read-only streaming pass over `bytes` bytes of
  * `src` (16-byte aligned, bytes % 16 == 0) that folds everything into 16 bytes at `sink`, and a
  * plain copy of `bytes` bytes.  They give the bandwidth a trivial kernel reaches on the same

@@ -355,6 +355,42 @@ def merge_partials_ref(ms, ls, accs):
 
 
 # --------------------------------------------------------------------------
+# Paged caches (serving stacks): a pure re-indexing of the dense cache
+# --------------------------------------------------------------------------
+
+
+def paged_to_dense_ref(pool: np.ndarray, block_table: np.ndarray, n_rows) -> np.ndarray:
+    """pool [n_pages, H, page_rows, d], block_table [B, max_pages], n_rows int or [B] ->
+    dense [B, H, max_pages * page_rows, d] with row t of sequence b = row t % page_rows of page
+    block_table[b][t // page_rows] for t < n_rows[b], zeros elsewhere (those table entries are
+    not looked at)."""
+    pool = np.asarray(pool)
+    block_table = np.asarray(block_table)
+    n_pages, n_heads, page_rows, d = pool.shape
+    bsz, max_pages = block_table.shape
+    n_rows = np.broadcast_to(np.asarray(n_rows), (bsz,))
+    dense = np.zeros((bsz, n_heads, max_pages * page_rows, d), dtype=pool.dtype)
+    for b in range(bsz):
+        for t in range(int(n_rows[b])):
+            dense[b, :, t, :] = pool[block_table[b, t // page_rows], :, t % page_rows, :]
+    return dense
+
+
+def dense_to_paged_ref(dense: np.ndarray, block_table: np.ndarray, page_rows: int, n_pages: int, n_rows, fill=0) -> np.ndarray:
+    """Inverse arrangement: rows [0, n_rows[b]) of dense [B, H, cap, d] stored into a pool of
+    n_pages pages through block_table; everything else in the pool holds `fill`."""
+    dense = np.asarray(dense)
+    block_table = np.asarray(block_table)
+    bsz, n_heads, _, d = dense.shape
+    n_rows = np.broadcast_to(np.asarray(n_rows), (bsz,))
+    pool = np.full((n_pages, n_heads, page_rows, d), fill, dtype=dense.dtype)
+    for b in range(bsz):
+        for t in range(int(n_rows[b])):
+            pool[block_table[b, t // page_rows], :, t % page_rows, :] = dense[b, :, t, :]
+    return pool
+
+
+# --------------------------------------------------------------------------
 # Cost model (byte accounting)
 # --------------------------------------------------------------------------
 

@@ -6,6 +6,6 @@ library has not been built, loading fails with an error that says how to build i
 """
 from __future__ import annotations
 
-from .binding import Rap, RapError, RapShape, RapTuning, load, library_path  # noqa: F401
+from .binding import Rap, RapError, RapPaging, RapShape, RapTuning, load, library_path  # noqa: F401
 
-__all__ = ["Rap", "RapError", "RapShape", "RapTuning", "load", "library_path"]
+__all__ = ["Rap", "RapError", "RapPaging", "RapShape", "RapTuning", "load", "library_path"]

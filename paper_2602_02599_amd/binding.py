@@ -29,6 +29,14 @@ class RapShape(C.Structure):
     ]
 
 
+class RapPaging(C.Structure):
+    """Mirror of rap_paging_t."""
+    _fields_ = [
+        ("page_rows", C.c_int32), ("n_pages", C.c_int32), ("max_pages", C.c_int32), ("reserved", C.c_int32),
+        ("block_table", C.c_void_p),
+    ]
+
+
 class RapTuning(C.Structure):
     """Mirror of rap_tuning_t."""
     _fields_ = [
@@ -95,6 +103,12 @@ class Rap:
         L.rap_prefill_attn.restype = C.c_int
         L.rap_prefill_attn.argtypes = [C.POINTER(RapShape), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_int64, C.c_void_p, C.c_float, C.c_void_p]
+        L.rap_rope_append_paged.restype = C.c_int
+        L.rap_rope_append_paged.argtypes = [C.POINTER(RapShape), C.POINTER(RapPaging), C.c_int32] + [C.c_void_p] * 7
+        L.rap_decode_attn_paged.restype = C.c_int
+        L.rap_decode_attn_paged.argtypes = [C.POINTER(RapShape), C.POINTER(RapPaging), C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_float,
+                                            C.c_void_p, C.c_size_t, C.POINTER(RapTuning), C.c_void_p]
         L.rap_stream_read.restype = C.c_int
         L.rap_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.rap_stream_copy.restype = C.c_int
@@ -125,6 +139,13 @@ class Rap:
                        _ptr(pair_inv_freq, torch.float64, "pair_inv_freq"))
         shp._keep_alive = pair_inv_freq
         return shp
+
+    @staticmethod
+    def paging(page_rows: int, n_pages: int, block_table) -> RapPaging:
+        """block_table: int32 GPU tensor [batch, max_pages]; the returned object keeps a reference."""
+        pg = RapPaging(page_rows, n_pages, int(block_table.shape[1]), 0, _ptr(block_table, torch.int32, "block_table"))
+        pg._keep_alive = block_table
+        return pg
 
     @staticmethod
     def tuning(kernel=0, rows_per_split=0, ev_main_start=None, ev_main_stop=None) -> RapTuning:
@@ -201,6 +222,31 @@ class Rap:
                                        _ptr(k_cache, torch.bfloat16, "k_cache"), _ptr(v_cache, torch.bfloat16, "v_cache"),
                                        _ptr(seq_lens, torch.int32, "seq_lens"), max_seq_len, _ptr(out, torch.float32, "out"),
                                        scale, _stream(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def rap_rope_append_paged(self, shape: RapShape, paging: RapPaging, n_new: int, k_new, v_new, pos, keep_pair_idx,
+                              k_pool, v_pool, stream=None, check=True) -> int:
+        st = self.lib.rap_rope_append_paged(C.byref(shape), C.byref(paging), n_new, _ptr(k_new, torch.bfloat16, "k_new"),
+                                            _ptr(v_new, torch.bfloat16, "v_new"), _ptr(pos, torch.int32, "pos"),
+                                            _ptr(keep_pair_idx, torch.int32, "keep_pair_idx"),
+                                            _ptr(k_pool, torch.bfloat16, "k_pool"), _ptr(v_pool, torch.bfloat16, "v_pool"),
+                                            _stream(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def rap_decode_attn_paged(self, shape: RapShape, paging: RapPaging, q, q_pos, keep_pair_idx, k_pool, v_pool, seq_lens,
+                              max_seq_len: int, out, scale: float, workspace=None, tuning: Optional[RapTuning] = None,
+                              stream=None, check=True) -> int:
+        st = self.lib.rap_decode_attn_paged(C.byref(shape), C.byref(paging), _ptr(q, torch.bfloat16, "q"),
+                                            _ptr(q_pos, torch.int32, "q_pos"), _ptr(keep_pair_idx, torch.int32, "keep_pair_idx"),
+                                            _ptr(k_pool, torch.bfloat16, "k_pool"), _ptr(v_pool, torch.bfloat16, "v_pool"),
+                                            _ptr(seq_lens, torch.int32, "seq_lens"), max_seq_len, _ptr(out, torch.float32, "out"),
+                                            scale, _ptr(workspace, None, "workspace"),
+                                            0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                            C.byref(tuning) if tuning is not None else None, _stream(stream))
         if check:
             self._check(st)
         return st

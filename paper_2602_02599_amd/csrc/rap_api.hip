@@ -79,15 +79,30 @@ size_t part_ml_bytes(const rap_shape_t* s, const Plan& p) {
   return align_up(static_cast<size_t>(s->batch) * s->n_q_heads * (p.n_split + 1) * 2 * sizeof(float), 256);
 }
 
+// page_rows a power of two in [32, 65536], table present, logical capacity consistent
+rap_status_t check_paging(const rap_shape_t* s, const rap_paging_t* pg, int* shift) {
+  if (!pg) return RAP_ERR_NULL;
+  if (pg->page_rows < 32 || pg->page_rows > 65536 || (pg->page_rows & (pg->page_rows - 1)) != 0) return RAP_ERR_SHAPE;
+  if (pg->n_pages <= 0 || pg->max_pages <= 0) return RAP_ERR_SHAPE;
+  if (static_cast<int64_t>(pg->max_pages) * pg->page_rows != s->cache_cap) return RAP_ERR_SHAPE;
+  if (s->batch > 0 && !pg->block_table) return RAP_ERR_NULL;
+  int sh = 0;
+  while ((1 << sh) < pg->page_rows) ++sh;
+  *shift = sh;
+  return RAP_OK;
+}
+
 }  // namespace
 
 extern "C" {
 
-rap_status_t rap_rope_append(const rap_shape_t* shape, int32_t n_new, const void* k_new, const void* v_new,
-                             const int32_t* pos, const int32_t* keep_pair_idx, void* k_cache, void* v_cache,
-                             void* stream) {
+static rap_status_t append_impl(const rap_shape_t* shape, const rap_paging_t* paging, int32_t n_new, const void* k_new,
+                                const void* v_new, const int32_t* pos, const int32_t* keep_pair_idx, void* k_cache,
+                                void* v_cache, void* stream) {
   rap_status_t st = check_shape(shape);
   if (st != RAP_OK) return st;
+  int page_shift = 0;
+  if (paging && (st = check_paging(shape, paging, &page_shift)) != RAP_OK) return st;
   if (n_new < 0) return RAP_ERR_SHAPE;
   if (n_new == 0 || shape->batch == 0) return RAP_OK;
   if (!k_new || !v_new || !pos || (!keep_pair_idx && !shape->pair_inv_freq) || !k_cache || !v_cache) return RAP_ERR_NULL;
@@ -96,6 +111,13 @@ rap_status_t rap_rope_append(const rap_shape_t* shape, int32_t n_new, const void
       (reinterpret_cast<uintptr_t>(k_cache) & 3) || (reinterpret_cast<uintptr_t>(v_cache) & 3))
     return RAP_ERR_SHAPE;
   rap::AppendArgs a;
+  memset(&a, 0, sizeof(a));
+  if (paging) {
+    a.block_table = paging->block_table;
+    a.page_shift = page_shift;
+    a.n_pages = paging->n_pages;
+    a.max_pages = paging->max_pages;
+  }
   a.k_new = static_cast<const uint16_t*>(k_new);
   a.v_new = static_cast<const uint16_t*>(v_new);
   a.pos = pos;
@@ -113,6 +135,19 @@ rap_status_t rap_rope_append(const rap_shape_t* shape, int32_t n_new, const void
   a.cap = shape->cache_cap;
   a.neg2_log2_theta_over_d = -2.0 * log2(shape->rope_theta) / static_cast<double>(shape->d_head);
   return rap::launch_append(a, static_cast<hipStream_t>(stream)) == hipSuccess ? RAP_OK : RAP_ERR_HIP;
+}
+
+rap_status_t rap_rope_append(const rap_shape_t* shape, int32_t n_new, const void* k_new, const void* v_new,
+                             const int32_t* pos, const int32_t* keep_pair_idx, void* k_cache, void* v_cache,
+                             void* stream) {
+  return append_impl(shape, nullptr, n_new, k_new, v_new, pos, keep_pair_idx, k_cache, v_cache, stream);
+}
+
+rap_status_t rap_rope_append_paged(const rap_shape_t* shape, const rap_paging_t* paging, int32_t n_new,
+                                   const void* k_new, const void* v_new, const int32_t* pos,
+                                   const int32_t* keep_pair_idx, void* k_pool, void* v_pool, void* stream) {
+  if (!paging) return RAP_ERR_NULL;
+  return append_impl(shape, paging, n_new, k_new, v_new, pos, keep_pair_idx, k_pool, v_pool, stream);
 }
 
 rap_status_t rap_rope_queries(const rap_shape_t* shape, int32_t n_new, const void* q, const int32_t* pos,
@@ -164,9 +199,11 @@ struct NewToken {          // the append fused into rap_decode_step; all null ot
 rap_status_t decode_impl(const rap_shape_t* shape, const void* q, const int32_t* q_pos, const int32_t* keep,
                          const void* k_cache, const void* v_cache, const int32_t* seq_lens, int64_t max_seq_len,
                          void* out, float scale, void* workspace, size_t workspace_bytes, const rap_tuning_t* tuning,
-                         void* stream, const NewToken& nt = NewToken()) {
+                         void* stream, const NewToken& nt = NewToken(), const rap_paging_t* paging = nullptr) {
   rap_status_t st = check_shape(shape);
   if (st != RAP_OK) return st;
+  int page_shift = 0;
+  if (paging && (st = check_paging(shape, paging, &page_shift)) != RAP_OK) return st;
   if (max_seq_len < 1) return RAP_ERR_SHAPE;
   if (max_seq_len > shape->cache_cap) return RAP_ERR_CAPACITY;
   if (shape->batch == 0) return RAP_OK;
@@ -216,6 +253,13 @@ rap_status_t decode_impl(const rap_shape_t* shape, const void* q, const int32_t*
   a.cap = shape->cache_cap;
   a.scale_log2e = scale * 1.4426950408889634f;
   a.lds_wave_bytes = rap::mfma_lds_wave_bytes(a.d_k, a.d_v);
+  if (paging) {
+    if (p.kernel != 2) return RAP_ERR_UNSUPPORTED;      // the vector-ALU kernel reads dense caches only
+    a.block_table = paging->block_table;
+    a.page_shift = page_shift;
+    a.n_pages = paging->n_pages;
+    a.max_pages = paging->max_pages;
+  }
   a.direct_out = (p.n_split == 1 && !fused_step) ? 1 : 0;
   if (fused_step) {
     a.k_new = static_cast<const uint16_t*>(nt.k_new);
@@ -313,6 +357,20 @@ rap_status_t rap_prefill_attn(const rap_shape_t* shape, int32_t n_new, const voi
   a.cap = shape->cache_cap;
   a.scale_log2e = scale * 1.4426950408889634f;
   return rap::launch_prefill(a, static_cast<hipStream_t>(stream)) == hipSuccess ? RAP_OK : RAP_ERR_HIP;
+}
+
+rap_status_t rap_decode_attn_paged(const rap_shape_t* shape, const rap_paging_t* paging, const void* q,
+                                   const int32_t* q_pos, const int32_t* keep_pair_idx, const void* k_pool,
+                                   const void* v_pool, const int32_t* seq_lens, int64_t max_seq_len, void* out,
+                                   float scale, void* workspace, size_t workspace_bytes, const rap_tuning_t* tuning,
+                                   void* stream) {
+  if (!paging) return RAP_ERR_NULL;
+  if (shape && shape->batch > 0 && max_seq_len >= 1 && q_pos && !keep_pair_idx && !shape->pair_inv_freq) {
+    const rap_status_t st = check_shape(shape);
+    return st != RAP_OK ? st : RAP_ERR_NULL;
+  }
+  return decode_impl(shape, q, q_pos, keep_pair_idx, k_pool, v_pool, seq_lens, max_seq_len, out, scale, workspace,
+                     workspace_bytes, tuning, stream, NewToken(), paging);
 }
 
 rap_status_t rap_stream_read(const void* src, size_t bytes, void* sink, void* stream) {

@@ -38,7 +38,7 @@ __global__ __launch_bounds__(256) void append_kernel(AppendArgs a) {
   const uint16_t v0 = has_v0 ? vsrc[lane] : 0, v1 = has_v1 ? vsrc[lane + kWave] : 0;
   if (t < 0 || t >= a.cap) return;                                        // documented: skipped
 
-  const long long row = (static_cast<long long>(b) * a.n_kv + h) * a.cap + t;
+  const long long row = cache_row(a, b, h, t);
   if (rot) {                                                              // bad index: documented skip
     const double phi = static_cast<double>(t) * f;
     double sn, cs;
@@ -122,8 +122,11 @@ __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs
     const int tv = lane < cnt ? pos[n0 + lane] : 0;
     const int t0 = __builtin_amdgcn_readfirstlane(tv);
     // (a last, shorter run takes the general loop: at most kBulkRun - 1 tokens per sequence and head)
+    // (with paged caches a run must also stay inside one page)
     const bool in_order = cnt == kBulkRun && __all(lane >= kBulkRun || tv == t0 + lane) &&
-                          (QUERY || (t0 >= 0 && static_cast<long long>(t0) + kBulkRun <= a.cap));
+                          (QUERY || (t0 >= 0 && static_cast<long long>(t0) + kBulkRun <= a.cap &&
+                                     (a.block_table == nullptr ||
+                                      (t0 & ((1 << a.page_shift) - 1)) + kBulkRun <= (1 << a.page_shift))));
 
     if (in_order) {
       // Loads are unconditional (straight-line code, all in flight together): lanes with nothing
@@ -142,7 +145,7 @@ __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs
         }
       }
       if (!(anchored && t0 == t_next)) sincos_f64(static_cast<double>(t0) * f, &sn, &cs);   // exact
-      const long long row0 = (static_cast<long long>(b) * a.n_kv + h) * a.cap + t0;
+      const long long row0 = QUERY ? 0 : cache_row(a, b, h, t0);
       uint16_t* kdst0 = QUERY ? a.k_cache + (tok0 * a.n_kv + h) * (2 * P) : a.k_cache + row0 * (2 * P);
       const long long kdstride = QUERY ? kstride : 2 * P;          // consecutive cache rows, or the input's layout
       uint16_t* vdst0 = QUERY ? nullptr : a.v_cache + row0 * a.d_v;
@@ -207,7 +210,7 @@ __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs
       }
       if (t < 0 || t >= a.cap) continue;                         // documented: skipped
       const uint16_t* vsrc = vsrc0 + i * vstride;
-      const long long row = (static_cast<long long>(b) * a.n_kv + h) * a.cap + t;
+      const long long row = cache_row(a, b, h, t);
       if (rot) {
         double s1, c1d;
         sincos_f64(static_cast<double>(t) * f, &s1, &c1d);

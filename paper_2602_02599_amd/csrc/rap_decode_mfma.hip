@@ -148,7 +148,10 @@ __device__ __forceinline__ void token_finish(const DecodeArgs& a, int b, int h, 
 // KCH = ceil(d_k / 32) score k-steps, NT = 16-channel output tiles.  VPAIR (even d_v): a lane
 // reads two adjacent V channels with one 4-byte LDS read and tile nt holds channels
 // 32 (nt / 2) + 2 l16 + (nt & 1); otherwise 2-byte reads and tile nt holds channels 16 nt + l16.
-template <int KCH, int NT, bool VPAIR>
+// PAGED: the caches are pools of pages [n_pages, H_kv, page_rows, d] and row r of sequence b lives
+// in page block_table[b][r / page_rows]; page_rows is a power of two >= 32, so a 32-row tile never
+// straddles two pages and only the start address of a tile changes.
+template <int KCH, int NT, bool VPAIR, bool PAGED>
 __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(DecodeArgs a) {
   constexpr int NLD_K = 2 * KCH;   // 1 KB wave-loads covering a K tile (d_k <= 32 KCH)
   constexpr int NLD_V = NT;        // same for a V tile (d_v <= 16 NT)
@@ -215,8 +218,19 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
   unsigned char* vt = kt + 1024 * NLD_K;
 
   const long long slab = static_cast<long long>(b) * a.n_kv + h;
-  const unsigned char* kslab = reinterpret_cast<const unsigned char*>(a.k_cache) + slab * a.cap * pitch_k;
-  const unsigned char* vslab = reinterpret_cast<const unsigned char*>(a.v_cache) + slab * a.cap * pitch_v;
+  const unsigned char* kslab = reinterpret_cast<const unsigned char*>(a.k_cache) + (PAGED ? 0 : slab * a.cap * pitch_k);
+  const unsigned char* vslab = reinterpret_cast<const unsigned char*>(a.v_cache) + (PAGED ? 0 : slab * a.cap * pitch_v);
+  // row of the pool (paged) or of the (b, h) slab (dense) where logical row `row` starts; a page
+  // number outside the pool is clamped into it, so that a bad table cannot send a load astray
+  auto tile_row = [&](int row) -> long long {
+    if constexpr (PAGED) {
+      int pg = a.block_table[static_cast<long long>(b) * a.max_pages + (row >> a.page_shift)];
+      pg = pg < 0 ? 0 : (pg >= a.n_pages ? a.n_pages - 1 : pg);
+      return ((static_cast<long long>(pg) * a.n_kv + h) << a.page_shift) + (row & ((1 << a.page_shift) - 1));
+    } else {
+      return row;
+    }
+  };
 
   f32x4 acc[NT];
 #pragma unroll
@@ -233,9 +247,9 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
   // does this lane's share of the last whole-KB load belong to the tile?
   const bool k_last = 1024 * (NLD_K - 1) + 16 * lane < kTileRows * pitch_k;
   const bool v_last = 1024 * (NLD_V - 1) + 16 * lane < kTileRows * pitch_v;
-  auto issue_loads = [&](int base) {
-    const unsigned char* kg = kslab + static_cast<long long>(base) * pitch_k + 16 * lane;
-    const unsigned char* vg = vslab + static_cast<long long>(base) * pitch_v + 16 * lane;
+  auto issue_loads = [&](int base, long long trow) {
+    const unsigned char* kg = kslab + trow * pitch_k + 16 * lane;
+    const unsigned char* vg = vslab + trow * pitch_v + 16 * lane;
     if (base + kTileRows <= len8) {
       // common case, a full tile: whole-KB loads, the last one of each run trimmed to the tile's
       // own bytes so that nothing is fetched twice and nothing beyond row len8 is touched
@@ -260,7 +274,9 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
 
   // first tile on its way before anything else is fetched
   const int first = r0 + kTileRows * wave;
-  if (first < r1) issue_loads(first);
+  if (first < r1) issue_loads(first, tile_row(first));
+  // paged: the page of the tile after next is looked up one iteration before its loads are issued
+  long long trow1 = (PAGED && first + 4 * kTileRows < r1) ? tile_row(first + 4 * kTileRows) : 0;
 
   // ---- query rows as the B operand: lane (l16 = head slot, lg = k sub-chunk).  With q_pos the
   // rows arrive un-rotated: the workgroup rotates them into LDS first, while its first tile flies.
@@ -308,7 +324,8 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
 #pragma unroll
     for (int j = 0; j < NLD_V; ++j) *reinterpret_cast<uint4*>(vt + 1024 * j + 16 * lane) = vst[j];
     wave_lds_sync();
-    if (base + 4 * kTileRows < r1) issue_loads(base + 4 * kTileRows);
+    if (base + 4 * kTileRows < r1) issue_loads(base + 4 * kTileRows, PAGED ? trow1 : base + 4 * kTileRows);
+    if (PAGED && base + 8 * kTileRows < r1) trow1 = tile_row(base + 8 * kTileRows);
 
     // ---- scores: sc[rt][r] = q[g = l16] . K[base + 16 rt + 4 lg + r]
     f32x4 sc[2];
@@ -476,8 +493,8 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
   }
 }
 
-template <int KCH, int NT, bool VPAIR>
-hipError_t launch_inst(const DecodeArgs& a, hipStream_t stream) {
+template <int KCH, int NT, bool VPAIR, bool PAGED>
+hipError_t launch_inst2(const DecodeArgs& a, hipStream_t stream) {
   // scanning workgroups, then (decode step: n_slots = n_split + 1) one per (b, h) for the new token
   dim3 grid(static_cast<unsigned>(a.n_slots) * a.n_kv * a.batch), block(256);
   const size_t lds = 4 * static_cast<size_t>(a.lds_wave_bytes);
@@ -485,14 +502,20 @@ hipError_t launch_inst(const DecodeArgs& a, hipStream_t stream) {
     // more than the default dynamic-LDS limit: raise it once per kernel (gfx950 has 160 KB per CU)
     static int raised_to = 0;
     if (raised_to < static_cast<int>(lds)) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_mfma_kernel<KCH, NT, VPAIR>),
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_mfma_kernel<KCH, NT, VPAIR, PAGED>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
       if (e != hipSuccess) return e;
       raised_to = static_cast<int>(lds);
     }
   }
-  hipLaunchKernelGGL((decode_mfma_kernel<KCH, NT, VPAIR>), grid, block, lds, stream, a);
+  hipLaunchKernelGGL((decode_mfma_kernel<KCH, NT, VPAIR, PAGED>), grid, block, lds, stream, a);
   return hipGetLastError();
+}
+
+template <int KCH, int NT, bool VPAIR>
+hipError_t launch_inst(const DecodeArgs& a, hipStream_t stream) {
+  if (a.block_table != nullptr) return launch_inst2<KCH, NT, VPAIR, true>(a, stream);
+  return launch_inst2<KCH, NT, VPAIR, false>(a, stream);
 }
 
 template <int KCH>

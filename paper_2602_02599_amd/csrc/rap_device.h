@@ -89,6 +89,8 @@ struct AppendArgs {
   const int32_t* pos;
   const int32_t* keep;
   const double* pair_freq;          // [H_kv, P] radians per position, or null: theta_j from keep
+  const int32_t* block_table;       // paged caches: [B, max_pages], or null
+  int32_t page_shift, n_pages, max_pages;
   uint16_t* k_cache;
   uint16_t* v_cache;
   int32_t batch, n_new, n_kv, d_head, n_pairs, d_v;
@@ -107,6 +109,9 @@ struct DecodeArgs {
   const uint16_t* k_cache;
   const uint16_t* v_cache;
   const int32_t* seq_lens;
+  // paged caches (block_table null otherwise): pools [n_pages, H_kv, 1 << page_shift, d]
+  const int32_t* block_table;   // [B, max_pages]
+  int32_t page_shift, n_pages, max_pages;
   // one-call decode step (all null otherwise): the new token of every sequence.  The attention
   // kernel leaves cache row new_pos[b] out of its scan; its first workgroup of each (b, h) rotates
   // the new K row, writes it and the V row into the caches and leaves the token's score and V row
@@ -143,6 +148,16 @@ struct PrefillArgs {
   int64_t cap;
   float scale_log2e;
 };
+
+// Row of the K / V cache that holds position t of sequence b for KV head h: a row of the dense
+// [B, H_kv, cap] arrangement, or, with a block table, of the pool [n_pages, H_kv, page_rows] (a page
+// number outside the pool is clamped into it).
+__device__ __forceinline__ long long cache_row(const AppendArgs& a, int b, int h, int t) {
+  if (a.block_table == nullptr) return (static_cast<long long>(b) * a.n_kv + h) * a.cap + t;
+  int pg = a.block_table[static_cast<long long>(b) * a.max_pages + (t >> a.page_shift)];
+  pg = pg < 0 ? 0 : (pg >= a.n_pages ? a.n_pages - 1 : pg);
+  return ((static_cast<long long>(pg) * a.n_kv + h) << a.page_shift) + (t & ((1 << a.page_shift) - 1));
+}
 
 // Index-aware RoPE of the G query rows of KV head h of sequence b, into LDS as bf16 in the
 // compact order (Eq. (latent-score): the query side of RoPE(X W~_q) . RoPE(X W~_k)^T).  Same

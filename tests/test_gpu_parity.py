@@ -586,6 +586,72 @@ def test_prefill_pipeline(rap):
     H.assert_attn_close(out.cpu().numpy(), ref, "prefill pipeline")
 
 
+@pytest.mark.parametrize("P,dv,Hq,Hkv,ctx,page_rows,n_new", [
+    (45, 90, 8, 2, 3000, 256, 1), (58, 115, 8, 2, 1500, 32, 3), (32, 64, 10, 2, 2500, 128, 40), (64, 128, 4, 1, 700, 64, 1),
+    (45, 90, 8, 2, 9000, 1024, 100)])
+def test_paged_caches(rap, P, dv, Hq, Hkv, ctx, page_rows, n_new):
+    """rap_rope_append_paged + rap_decode_attn_paged over pools with a shuffled block table:
+    the pools, gathered back, must be what the dense append gives, and the attention what the
+    oracle gives on the dense cache; also with the fused query rotation and several range sizes.
+    Unused pool pages and the table entries beyond each sequence hold garbage (NaN / wild numbers)."""
+    w = I.scaled(I.WORKLOADS["cfg2"], batch=3, n_q_heads=Hq, n_kv_heads=Hkv, n_pairs=P, d_v=dv, ctx=ctx, n_new=n_new,
+                 ragged_min=max(n_new + 1, ctx // 4), peaky_frac=0.0, seed=400 + P + page_rows)
+    _say("paged P=%d dv=%d ctx=%d page_rows=%d n_new=%d" % (P, dv, ctx, page_rows, n_new))
+    case = I.make_case(w, device=DEV)
+    lens = case.seq_lens.cpu().numpy()
+    max_pages = (int(lens.max()) + page_rows - 1) // page_rows
+    cap = max_pages * page_rows
+    n_pages = w.batch * max_pages + 5
+    rng = np.random.Generator(np.random.PCG64(7))
+    table = rng.permutation(n_pages)[:w.batch * max_pages].reshape(w.batch, max_pages).astype(np.int32)
+    prefill = case.prefill_lens
+    kd, vd = I.bits(case.k_cache), I.bits(case.v_cache)
+    nan = 0x7FC0
+    kp = O.dense_to_paged_ref(kd, table, page_rows, n_pages, prefill, fill=nan)
+    vp = O.dense_to_paged_ref(vd, table, page_rows, n_pages, prefill, fill=nan)
+    table_dev = table.copy()
+    for b in range(w.batch):                                     # entries beyond the sequence: never to be read
+        used = (int(lens[b]) + page_rows - 1) // page_rows
+        table_dev[b, used:] = 2 ** 30
+    k_pool, v_pool = I.from_bits(kp, DEV), I.from_bits(vp, DEV)
+    bt = torch.from_numpy(table_dev).to(DEV)
+    shp = rap.shape(w.batch, Hq, Hkv, w.d_head, P, dv, cap, w.rope_theta)
+    pg = rap.paging(page_rows, n_pages, bt)
+    rap.rap_rope_append_paged(shp, pg, n_new, case.k_new, case.v_new, case.pos, case.keep, k_pool, v_pool)
+    torch.cuda.synchronize()
+    okc = np.zeros((w.batch, Hkv, cap, 2 * P), dtype=np.uint16); ovc = np.zeros((w.batch, Hkv, cap, dv), dtype=np.uint16)
+    for b in range(w.batch):
+        okc[b, :, :prefill[b]] = kd[b, :, :prefill[b]]
+        ovc[b, :, :prefill[b]] = vd[b, :, :prefill[b]]
+    O.append_ref(I.bits(case.k_new), I.bits(case.v_new), case.pos.cpu().numpy(), case.keep.cpu().numpy(), okc, ovc, w.rope_theta, w.d_head)
+    gk = O.paged_to_dense_ref(I.bits(k_pool), table, lens)
+    gv = O.paged_to_dense_ref(I.bits(v_pool), table, lens)
+    for b in range(w.batch):
+        assert H.bf16_ulp_distance(gk[b, :, :lens[b]], okc[b, :, :lens[b]]).max() <= 1, "paged K rows"
+        assert np.array_equal(gv[b, :, :lens[b]], ovc[b, :, :lens[b]]), "paged V rows"
+    ref = O.attn_ref(I.bits(case.q), gk, gv, lens, w.scale)
+    for rps in (0, 128, 512):
+        tun = rap.tuning(kernel=MFMA, rows_per_split=rps)
+        ws = rap.new_workspace(shp, cap, tun)
+        out = torch.full((w.batch, Hq, dv), float("nan"), dtype=torch.float32, device=DEV)
+        rap.rap_decode_attn_paged(shp, pg, case.q, None, None, k_pool, v_pool, case.seq_lens, cap, out, float(w.scale), ws, tun)
+        torch.cuda.synchronize()
+        H.assert_attn_close(out.cpu().numpy(), ref, "paged decode rps=%d" % rps)
+    # fused query rotation over the paged cache
+    qpos_np = (lens - 1).astype(np.int32)
+    qrot = O.rope_queries_ref(I.bits(case.q), qpos_np, case.keep.cpu().numpy(), w.rope_theta, w.d_head, Hkv)
+    ref2 = O.attn_ref(qrot, gk, gv, lens, w.scale)
+    ws = rap.new_workspace(shp, cap, None)
+    rap.rap_decode_attn_paged(shp, pg, case.q, torch.from_numpy(qpos_np).to(DEV), case.keep, k_pool, v_pool, case.seq_lens, cap,
+                              out, float(w.scale), ws, None)
+    torch.cuda.synchronize()
+    H.assert_attn_close(out.cpu().numpy(), ref2, "paged decode with query rotation")
+    # the vector-ALU kernel does not read pools
+    st = rap.rap_decode_attn_paged(shp, pg, case.q, None, None, k_pool, v_pool, case.seq_lens, cap, out, float(w.scale), ws,
+                                   rap.tuning(kernel=VALU), check=False)
+    assert st == 3
+
+
 def test_split_invariance(rap):
     """1 range vs many: same result up to fp32 rounding (merge identity on the GPU side)."""
     w = I.scaled(I.WORKLOADS["cfg2"], batch=2, ctx=4000, seed=13)

@@ -564,6 +564,37 @@ def test_frequency_table_rotation_pins():
     assert abs(r[0] - z.real) < 1e-15 and abs(r[1] - z.imag) < 1e-15
 
 
+def test_paged_arrangement_pins():
+    """Paged caches are a re-indexing: a hand-written 2-page example, the identity table (= a
+    reshape), round trips through a shuffled table, and attention over the gathered rows equal to
+    attention over the dense cache."""
+    pool = np.arange(3 * 1 * 2 * 1).reshape(3, 1, 2, 1)          # 3 pages x 1 head x 2 rows x 1 value: page p holds 2p, 2p+1
+    bt = np.array([[2, 0], [1, 2]])
+    dense = O.paged_to_dense_ref(pool, bt, [3, 4])
+    assert dense[0, 0, :, 0].tolist() == [4, 5, 0, 0]            # rows 0, 1 from page 2, row 2 from page 0, row 3 beyond n_rows
+    assert dense[1, 0, :, 0].tolist() == [2, 3, 4, 5]
+    rng = _rng(91)
+    B, H, page_rows, max_pages, d = 2, 3, 4, 5, 6
+    dense = rng.integers(0, 60000, size=(B, H, max_pages * page_rows, d)).astype(np.uint16)
+    ident = np.arange(B * max_pages).reshape(B, max_pages)
+    pool = O.dense_to_paged_ref(dense, ident, page_rows, B * max_pages, max_pages * page_rows)
+    assert np.array_equal(pool.reshape(B, max_pages, H, page_rows, d).transpose(0, 2, 1, 3, 4).reshape(dense.shape), dense)
+    table = rng.permutation(B * max_pages + 3)[:B * max_pages].reshape(B, max_pages)
+    lens = np.array([17, 9])
+    pool = O.dense_to_paged_ref(dense, table, page_rows, B * max_pages + 3, lens, fill=7)
+    back = O.paged_to_dense_ref(pool, table, lens)
+    for b in range(B):
+        assert np.array_equal(back[b, :, :lens[b]], dense[b, :, :lens[b]]) and np.all(back[b, :, lens[b]:] == 0)
+    kc = _bf16_of(rng.standard_normal((B, H, max_pages * page_rows, d)))
+    vc = _bf16_of(rng.standard_normal((B, H, max_pages * page_rows, 5)))
+    q = _bf16_of(rng.standard_normal((B, 2 * H, d)))
+    kp = O.dense_to_paged_ref(kc, table, page_rows, B * max_pages + 3, lens)
+    vp = O.dense_to_paged_ref(vc, table, page_rows, B * max_pages + 3, lens)
+    a1 = O.attn_ref(q, kc, vc, lens, 0.3)
+    a2 = O.attn_ref(q, O.paged_to_dense_ref(kp, table, lens), O.paged_to_dense_ref(vp, table, lens), lens, 0.3)
+    assert np.array_equal(a1, a2)
+
+
 def test_split_merge_identity():
     """Merging (m, l, acc) partials over any partition of the rows gives the unsplit result."""
     rng = _rng(17)
