@@ -92,6 +92,9 @@ typedef struct rap_tuning {
  *   k_cache[b][h][t][c + P] = bf16( k_new[b][n][h][c] sin phi + k_new[b][n][h][c+P] cos phi )
  *   v_cache[b][h][t][:]     = v_new[b][n][h][:]                   (bit copy)
  * with one round-to-nearest-even to bf16.  Rows not named by pos are left untouched.
+ * From n_new = 16 on, runs of 16 tokens whose positions go up by one take their first angle as
+ * above and advance it by one fp64 rotation per position (a difference of order 1e-16 in the
+ * sine and cosine, far below the rounding to bf16).
  *
  *   k_new          dev  bf16  [batch, n_new, n_kv_heads, 2P]  un-rotated, compact order
  *   v_new          dev  bf16  [batch, n_new, n_kv_heads, d_v]
@@ -224,8 +227,9 @@ rap_status_t rap_decode_step(const rap_shape_t* shape,
                              void* workspace, size_t workspace_bytes,
                              const rap_tuning_t* tuning, void* stream);
 
-/* Paged caches, as serving stacks keep them (the paper's own measurements sit on such stacks).
- * K and V live in pools of pages shared by all sequences,
+/* Paged caches, as batched serving stacks keep them (App. "Limitations", "Serving gains are
+ * context-dependent": turning the smaller cache into throughput there needs a fused attention
+ * kernel over the stack's own cache).  K and V live in pools of pages shared by all sequences,
  *   k_pool  dev bf16 [n_pages, n_kv_heads, page_rows, 2P],  v_pool  dev bf16 [n_pages, n_kv_heads, page_rows, d_v],
  * and row t of sequence b is row t % page_rows of page block_table[b][t / page_rows].
  *   page_rows        a power of two, 32 .. 65536 (a 32-row tile then never straddles two pages)
