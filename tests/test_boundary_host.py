@@ -83,6 +83,36 @@ def test_decode_rejects_bad_arguments(rap):
     assert a > b
 
 
+def test_prefill_and_query_rotation_reject_bad_arguments(rap):
+    pf = lambda shp, n=4, msl=512: rap.rap_prefill_attn(shp, n, None, None, None, None, msl, None, 0.1, check=False)
+    assert pf(_shape(rap)) == 1
+    assert pf(_shape(rap), n=0) == 0 and pf(_shape(rap, batch=0)) == 0
+    assert pf(_shape(rap), n=-1) == 2 and pf(_shape(rap), msl=0) == 2
+    assert pf(_shape(rap), msl=513) == 4
+    assert pf(_shape(rap, n_pairs=65)) == 2
+    rq = lambda shp, n=4: rap.rap_rope_queries(shp, n, None, None, None, None, check=False)
+    assert rq(_shape(rap)) == 1 and rq(_shape(rap), n=0) == 0 and rq(_shape(rap), n=-2) == 2
+    assert rq(_shape(rap, rope_theta=-1.0)) == 2
+
+
+def test_paging_rejects_bad_arguments(rap):
+    def pg(page_rows=128, n_pages=10, max_pages=4, table=0):
+        return pkg.RapPaging(page_rows, n_pages, max_pages, 0, table)
+    ap = lambda shp, paging: rap.rap_rope_append_paged(shp, paging, 1, None, None, None, None, None, None, check=False)
+    dc = lambda shp, paging, tun=None: rap.rap_decode_attn_paged(shp, paging, None, None, None, None, None, None, 512, None,
+                                                                  0.1, None, tun, check=False)
+    ok_shape = _shape(rap, cache_cap=512)
+    for f in (ap, dc):
+        assert f(ok_shape, pg(table=0)) == 1                       # no block table
+        assert f(ok_shape, pg(page_rows=100, table=1)) == 2        # not a power of two
+        assert f(ok_shape, pg(page_rows=16, max_pages=32, table=1)) == 2   # below one tile
+        assert f(ok_shape, pg(max_pages=5, table=1)) == 2          # capacity != max_pages * page_rows
+        assert f(ok_shape, pg(n_pages=0, table=1)) == 2
+        assert f(_shape(rap, cache_cap=512, batch=0), pg(table=1)) == 0
+    # a plausible table pointer gets past the paging checks and stops at the next null pointer
+    assert ap(ok_shape, pg(table=1)) == 1 and dc(ok_shape, pg(table=1)) == 1
+
+
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(pkg.RapError):
         pkg.Rap(str(tmp_path / "librap.so"))
