@@ -24,65 +24,56 @@ __global__ __launch_bounds__(128) void merge_kernel(DecodeArgs a) {
   const float l_tok = tok ? ml[2 * a.n_split + 1] : 0.f;
   const float v_tok = tok ? accc[static_cast<long long>(a.n_split) * a.d_v] : 0.f;
   const int t_new = tok ? a.new_pos[b] : -1;
-  // The first four slots are requested before the sequence length is known (they are allocated,
-  // whatever they hold), so the common case of a few ranges costs one memory round trip.
-  float m[4], l[4], v[4];
-#pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const bool have = u < a.n_split;
-    m[u] = have ? ml[2 * u] : 0.f;
-    l[u] = have ? ml[2 * u + 1] : 0.f;
-    v[u] = have ? accc[static_cast<long long>(u) * a.d_v] : 0.f;
-  }
-  int len = a.seq_lens[b];
-  len = len < 0 ? 0 : (len > a.max_len ? a.max_len : len);
-  if (len > 0 && t_new == len - 1) len -= 1;       // the first stage stopped before the new token's row
-  const int n = (len + a.rows_per_split - 1) / a.rows_per_split;   // ranges that hold rows
-  float mstar = m_tok;
-#pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    if (u >= n) { m[u] = -INFINITY; l[u] = 0.f; v[u] = 0.f; }      // unwritten slot: drop, do not multiply
-    mstar = fmaxf(mstar, m[u]);
-  }
-  int s = 4;
-  for (; s + 4 <= n; s += 4) {
-    const float m0 = ml[2 * s], m1 = ml[2 * s + 2], m2 = ml[2 * s + 4], m3 = ml[2 * s + 6];
-    mstar = fmaxf(fmaxf(mstar, fmaxf(m0, m1)), fmaxf(m2, m3));
-  }
-  for (; s < n; ++s) mstar = fmaxf(mstar, ml[2 * s]);
-  float den = 0.f, num = 0.f;
+  // All slots of a query head are allocated, whatever they hold, so they are requested before the
+  // sequence length is known, eight at a time: up to eight ranges cost one memory round trip (these
+  // reads miss L2, the partials were written through other XCDs; wider groups were measured and
+  // do not help: with 32 ranges the kernel takes 7.4 us either way).  Slots beyond the ranges that
+  // hold rows are dropped by a select, not multiplied.
+  constexpr int kGroup = 8;
+  float mstar = m_tok, den = 0.f, num = 0.f;
   if (m_tok > -INFINITY) {
-    den = exp2f(m_tok - mstar) * l_tok;
-    num = exp2f(m_tok - mstar) * v_tok;
+    den = l_tok;
+    num = v_tok;
   }
-  if (n > 0) {
+  int n = 0;
+  for (int s0 = 0; s0 < a.n_split; s0 += kGroup) {
+    float m[kGroup], l[kGroup], v[kGroup];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const float w = exp2f(m[u] - mstar);                          // 2^-inf = 0 for dropped slots
+    for (int u = 0; u < kGroup; ++u) {
+      const bool have = s0 + u < a.n_split;
+      m[u] = have ? ml[2 * (s0 + u)] : -INFINITY;
+      l[u] = have ? ml[2 * (s0 + u) + 1] : 0.f;
+      v[u] = have ? accc[static_cast<long long>(s0 + u) * a.d_v] : 0.f;
+    }
+    if (s0 == 0) {
+      int len = a.seq_lens[b];
+      len = len < 0 ? 0 : (len > a.max_len ? a.max_len : len);
+      if (len > 0 && t_new == len - 1) len -= 1;   // the first stage stopped before the new token's row
+      n = (len + a.rows_per_split - 1) / a.rows_per_split;   // ranges that hold rows
+    }
+    if (s0 >= n) break;
+    float gmax = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < kGroup; ++u) {
+      if (s0 + u >= n) {                           // unwritten slot: any bits, NaN included
+        m[u] = -INFINITY;
+        l[u] = 0.f;
+        v[u] = 0.f;
+      }
+      gmax = fmaxf(gmax, m[u]);
+    }
+    if (gmax > mstar) {                            // the reference follows the running maximum
+      const float r = mstar > -INFINITY ? exp2f(mstar - gmax) : 0.f;
+      den *= r;
+      num *= r;
+      mstar = gmax;
+    }
+#pragma unroll
+    for (int u = 0; u < kGroup; ++u) {
+      const float w = m[u] > -INFINITY ? exp2f(m[u] - mstar) : 0.f;
       den = fmaf(w, l[u], den);
       num = fmaf(w, v[u], num);
     }
-  }
-  s = 4;
-  for (; s + 4 <= n; s += 4) {
-    float mm[4], ll[4], vv[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      mm[u] = ml[2 * (s + u)];
-      ll[u] = ml[2 * (s + u) + 1];
-      vv[u] = accc[static_cast<long long>(s + u) * a.d_v];
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const float w = exp2f(mm[u] - mstar);
-      den = fmaf(w, ll[u], den);
-      num = fmaf(w, vv[u], num);
-    }
-  }
-  for (; s < n; ++s) {
-    const float w = exp2f(ml[2 * s] - mstar);
-    den = fmaf(w, ml[2 * s + 1], den);
-    num = fmaf(w, accc[static_cast<long long>(s) * a.d_v], num);
   }
   if (live) a.out[hq * a.d_v + c] = den > 0.f ? num / den : 0.f;
 }
