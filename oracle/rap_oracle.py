@@ -355,6 +355,87 @@ def merge_partials_ref(ms, ls, accs):
 
 
 # --------------------------------------------------------------------------
+# fp8 (E4M3, finite-only "fn" flavour of the OCP 8-bit floating point
+# specification) cache codes.  The paper calls KV quantisation orthogonal to
+# RAP and composable with it (Sec. "Introduction", "Related Work") without
+# fixing a format; this is the 8-bit format gfx950 converts natively.
+# --------------------------------------------------------------------------
+
+
+def e4m3_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """uint8 codes -> float64.  1 sign, 4 exponent (bias 7), 3 mantissa bits; exponent field 0 is
+    subnormal (m / 8 * 2^-6); there is no infinity, and S.1111.111 is NaN, so the largest finite
+    magnitude is S.1111.110 = 448."""
+    b = np.asarray(bits).astype(np.int64)
+    sign = np.where(b & 0x80, -1.0, 1.0)
+    e = (b >> 3) & 0xF
+    m = (b & 0x7).astype(np.float64)
+    val = np.where(e == 0, m / 8.0 * 2.0 ** -6, (1.0 + m / 8.0) * np.exp2((e - 7).astype(np.float64)))
+    val = np.where((b & 0x7F) == 0x7F, np.nan, val)
+    return sign * val
+
+
+def f64_to_e4m3_bits(x: np.ndarray) -> np.ndarray:
+    """float64 -> nearest E4M3 code, ties to the code with even mantissa, magnitudes above 448
+    (infinities included) saturate to 448, NaN -> 0x7F.  Written as a search over the 127 finite
+    non-negative codes so that it is the definition, not an algorithm."""
+    x = np.asarray(x, dtype=np.float64)
+    grid = e4m3_bits_to_f64(np.arange(0x7F, dtype=np.uint8))        # ascending: 0, 2^-9, ..., 448
+    a = np.minimum(np.abs(x), 448.0)
+    a = np.where(np.isnan(x), 0.0, a)
+    hi = np.clip(np.searchsorted(grid, a, side="left"), 0, 0x7E)    # first code >= a
+    lo = np.clip(hi - 1, 0, 0x7E)
+    d_hi, d_lo = grid[hi] - a, a - grid[lo]
+    pick_lo = (d_lo < d_hi) | ((d_lo == d_hi) & (lo % 2 == 0))
+    code = np.where(pick_lo, lo, hi).astype(np.uint8)
+    code = np.where(np.signbit(x), code | 0x80, code).astype(np.uint8)
+    return np.where(np.isnan(x), np.uint8(0x7F), code).astype(np.uint8)
+
+
+def append_q8_ref(k_new, v_new, pos, keep, k_cache8, v_cache8, k_scale, v_scale, theta_base, d_head, pair_freq=None):
+    """append_ref into an fp8 cache: the rotated K row (float64) and the V row are divided by the
+    per-KV-head scales k_scale[h], v_scale[h] (float32 values, taken as float64) and rounded once to
+    E4M3.  k_cache8, v_cache8: uint8 [B, H_kv, cap, 2P / d_v], modified in place."""
+    k_new = np.asarray(k_new)
+    v_new = np.asarray(v_new)
+    pos = np.asarray(pos)
+    bsz, n_new, n_kv, _ = k_new.shape
+    kf, vf = bf16_bits_to_f64(k_new), bf16_bits_to_f64(v_new)
+    ks = np.asarray(k_scale, dtype=np.float32).astype(np.float64)
+    vs = np.asarray(v_scale, dtype=np.float32).astype(np.float64)
+    for b in range(bsz):
+        for n in range(n_new):
+            t = int(pos[b, n])
+            for h in range(n_kv):
+                if pair_freq is None:
+                    rot = rope_compact(kf[b, n, h], np.float64(t), np.asarray(keep)[h], theta_base, d_head)
+                else:
+                    rot = rope_compact_freq(kf[b, n, h], np.float64(t), pair_freq[h])
+                k_cache8[b, h, t, :] = f64_to_e4m3_bits(rot / ks[h])
+                v_cache8[b, h, t, :] = f64_to_e4m3_bits(vf[b, n, h] / vs[h])
+
+
+def attn_q8_ref(q, k_cache8, v_cache8, k_scale, v_scale, seq_lens, scale) -> np.ndarray:
+    """attn_ref over an fp8 cache: every code stands for its value times the scale of its KV head."""
+    q = np.asarray(q)
+    bsz, n_q, _ = q.shape
+    n_kv = k_cache8.shape[1]
+    g = n_q // n_kv
+    d_v = v_cache8.shape[3]
+    out = np.zeros((bsz, n_q, d_v), dtype=np.float64)
+    qf = bf16_bits_to_f64(q)
+    ks = np.asarray(k_scale, dtype=np.float32).astype(np.float64)
+    vs = np.asarray(v_scale, dtype=np.float32).astype(np.float64)
+    for b in range(bsz):
+        n = int(seq_lens[b])
+        for h in range(n_kv):
+            kf = e4m3_bits_to_f64(k_cache8[b, h, :n]) * ks[h]
+            vf = e4m3_bits_to_f64(v_cache8[b, h, :n]) * vs[h]
+            out[b, h * g:(h + 1) * g] = attn_rows_ref(qf[b, h * g:(h + 1) * g], kf, vf, scale)
+    return out
+
+
+# --------------------------------------------------------------------------
 # Paged caches (serving stacks): a pure re-indexing of the dense cache
 # --------------------------------------------------------------------------
 

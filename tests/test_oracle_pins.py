@@ -595,6 +595,77 @@ def test_paged_arrangement_pins():
     assert np.array_equal(a1, a2)
 
 
+def test_e4m3_codes_and_rounding():
+    """E4M3 (finite-only) decode against the values the format's specification lists (1.0, the
+    largest finite 448, the smallest subnormal 2^-9, the smallest normal 2^-6, NaN) and the bit
+    layout; encode against an exhaustive nearest search with ties to even, saturation and sign."""
+    assert O.e4m3_bits_to_f64(np.array([0x38]))[0] == 1.0
+    assert O.e4m3_bits_to_f64(np.array([0x7E]))[0] == 448.0 and O.e4m3_bits_to_f64(np.array([0xFE]))[0] == -448.0
+    assert O.e4m3_bits_to_f64(np.array([0x01]))[0] == 2.0 ** -9 and O.e4m3_bits_to_f64(np.array([0x08]))[0] == 2.0 ** -6
+    assert np.isnan(O.e4m3_bits_to_f64(np.array([0x7F, 0xFF]))).all()
+    codes = np.arange(256, dtype=np.uint8)
+    vals = O.e4m3_bits_to_f64(codes)
+    for c in range(256):                                         # bit layout, by hand
+        s_, e, m = c >> 7, (c >> 3) & 15, c & 7
+        if (c & 0x7F) == 0x7F:
+            continue
+        want = (m / 8 * 2.0 ** -6) if e == 0 else (1 + m / 8) * 2.0 ** (e - 7)
+        assert vals[c] == (-want if s_ else want)
+    finite = (codes & 0x7F) != 0x7F
+    back = O.f64_to_e4m3_bits(vals[finite])
+    same = back == codes[finite]
+    assert same[codes[finite] != 0x80].all()                     # every code but -0 returns to itself (-0 too, as 0x80)
+    assert O.f64_to_e4m3_bits(np.array([-0.0]))[0] == 0x80
+    pos = vals[:0x7F]                                            # ascending grid of non-negative finite values
+    rng = _rng(5)
+    x = np.concatenate([rng.uniform(0, 470, 4000), rng.uniform(0, 0.05, 2000), (pos[:-1] + pos[1:]) / 2, pos, [448.0, 464.0, 1e9, np.inf]])
+    got = O.f64_to_e4m3_bits(x)
+    for xi, gi in zip(x, got):
+        a = min(xi, 448.0)
+        d = np.abs(pos - a)
+        best = np.flatnonzero(d == d.min())
+        want = best[0] if len(best) == 1 else (best[0] if best[0] % 2 == 0 else best[1])   # tie: even mantissa
+        assert gi == want, (xi, gi, want)
+    assert O.f64_to_e4m3_bits(np.array([-3.3]))[0] == (O.f64_to_e4m3_bits(np.array([3.3]))[0] | 0x80)
+    assert O.f64_to_e4m3_bits(np.array([np.nan]))[0] == 0x7F and O.f64_to_e4m3_bits(np.array([-np.inf]))[0] == 0xFE
+    # midpoint 1.0625 between 1.0 (mantissa 000) and 1.125 (001) goes to the even one; 1.1875 to 1.25 (010)
+    assert O.f64_to_e4m3_bits(np.array([1.0625, 1.1875])).tolist() == [0x38, 0x3A]
+
+
+def test_q8_cache_pins():
+    """The fp8 cache is the dense path on dequantised values: append codes decode to within half a
+    code step of the rotated row over the scale, V likewise, and attention over the codes equals
+    attn_ref over a bf16 cache holding exactly the dequantised values (every E4M3 value times a
+    power-of-two scale is a bf16 number)."""
+    rng = _rng(6)
+    B, n_new, H, P, dv, cap, D, theta = 2, 3, 2, 4, 5, 16, 16, 1.0e4
+    keep = np.stack([np.sort(rng.choice(D // 2, P, replace=False)) for _ in range(H)])
+    k_new = _bf16_of(rng.standard_normal((B, n_new, H, 2 * P)) * 3)
+    v_new = _bf16_of(rng.standard_normal((B, n_new, H, dv)))
+    pos = np.array([[0, 1, 2], [7, 3, 11]])
+    ks, vs = np.array([0.25, 0.5], dtype=np.float32), np.array([0.125, 1.0], dtype=np.float32)
+    k8 = np.zeros((B, H, cap, 2 * P), dtype=np.uint8); v8 = np.zeros((B, H, cap, dv), dtype=np.uint8)
+    O.append_q8_ref(k_new, v_new, pos, keep, k8, v8, ks, vs, theta, D)
+    kd = np.zeros((B, H, cap, 2 * P), dtype=np.uint16); vd = np.zeros((B, H, cap, dv), dtype=np.uint16)
+    O.append_ref(k_new, v_new, pos, keep, kd, vd, theta, D)       # same rows, bf16
+    for b in range(B):
+        for n in range(n_new):
+            t = pos[b, n]
+            for h in range(H):
+                exact = O.rope_compact(O.bf16_bits_to_f64(k_new[b, n, h]), np.float64(t), keep[h], theta, D)
+                deq = O.e4m3_bits_to_f64(k8[b, h, t]) * ks[h]
+                step = np.maximum(np.abs(exact) / ks[h], 2.0 ** -6) * 2.0 ** -3 * ks[h]   # at most one code step
+                assert np.all(np.abs(deq - exact) <= step / 2 * 1.0000001)
+                assert np.array_equal(v8[b, h, t], O.f64_to_e4m3_bits(O.bf16_bits_to_f64(v_new[b, n, h]) / vs[h]))
+    assert np.all(k8[0, :, 3:] == 0) and np.all(v8[1, :, 0] == 0)   # untouched rows
+    q = _bf16_of(rng.standard_normal((B, 2 * H, 2 * P)))
+    lens = np.array([3, 12])
+    got = O.attn_q8_ref(q, k8, v8, ks, vs, lens, 0.4)
+    kb = _bf16_of(O.e4m3_bits_to_f64(k8) * ks[None, :, None, None].astype(np.float64))
+    vb = _bf16_of(O.e4m3_bits_to_f64(v8) * vs[None, :, None, None].astype(np.float64))
+    assert np.array_equal(got, O.attn_ref(q, kb, vb, lens, 0.4))
+
+
 def test_split_merge_identity():
     """Merging (m, l, acc) partials over any partition of the rows gives the unsplit result."""
     rng = _rng(17)
