@@ -227,6 +227,35 @@ rap_status_t rap_decode_step(const rap_shape_t* shape,
                              void* workspace, size_t workspace_bytes,
                              const rap_tuning_t* tuning, void* stream);
 
+/* fp8 caches.  The paper names KV-cache quantisation as orthogonal to RAP and composable with it
+ * (Sec. "Introduction", Sec. "Related Work") without fixing a format; here both caches hold
+ * one-byte E4M3 codes (the finite-only 8-bit float of the OCP specification: 4 exponent bits,
+ * bias 7, 3 mantissa bits, largest magnitude 448, S.1111.111 = NaN), and a code stands for its
+ * value times the scale of its KV head:
+ *   k_cache8  dev uint8 [batch, n_kv_heads, cache_cap, 2P],  v_cache8  dev uint8 [batch, n_kv_heads, cache_cap, d_v]
+ *   k_scale, v_scale  dev fp32 [n_kv_heads], positive and finite (the caller's calibration)
+ * cache_cap must be a multiple of 16 (keeps every 16-row group 16-byte aligned at any width).
+ * The append rotates exactly as rap_rope_append, divides by the scale in fp64 and rounds once to
+ * the nearest code (ties to the even mantissa, magnitudes above 448 saturate, NaN -> 0x7f); V
+ * rows are divided and rounded the same way.  The attention is rap_decode_attn on the values the
+ * codes stand for (q stays bf16; q_pos non-NULL fuses its rotation as rap_decode_attn_rope does):
+ * the same matrix-core kernel at half the bytes per row.  tuning->kernel = 1 is
+ * RAP_ERR_UNSUPPORTED.  Workspace size as for rap_decode_attn. */
+rap_status_t rap_rope_append_q8(const rap_shape_t* shape, int32_t n_new,
+                                const void* k_new, const void* v_new,
+                                const int32_t* pos, const int32_t* keep_pair_idx,
+                                void* k_cache8, void* v_cache8,
+                                const float* k_scale, const float* v_scale, void* stream);
+
+rap_status_t rap_decode_attn_q8(const rap_shape_t* shape, const void* q, const int32_t* q_pos,
+                                const int32_t* keep_pair_idx,
+                                const void* k_cache8, const void* v_cache8,
+                                const float* k_scale, const float* v_scale,
+                                const int32_t* seq_lens, int64_t max_seq_len,
+                                void* out, float scale,
+                                void* workspace, size_t workspace_bytes,
+                                const rap_tuning_t* tuning, void* stream);
+
 /* Paged caches, as batched serving stacks keep them (App. "Limitations", "Serving gains are
  * context-dependent": turning the smaller cache into throughput there needs a fused attention
  * kernel over the stack's own cache).  K and V live in pools of pages shared by all sequences,

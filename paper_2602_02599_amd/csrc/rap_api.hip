@@ -15,7 +15,7 @@ hipError_t launch_merge(const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream);
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t stream);
 hipError_t launch_stream_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
-int mfma_lds_wave_bytes(int d_k, int d_v);
+int mfma_lds_wave_bytes(int d_k, int d_v, bool q8);
 }  // namespace rap
 
 namespace {
@@ -98,7 +98,8 @@ extern "C" {
 
 static rap_status_t append_impl(const rap_shape_t* shape, const rap_paging_t* paging, int32_t n_new, const void* k_new,
                                 const void* v_new, const int32_t* pos, const int32_t* keep_pair_idx, void* k_cache,
-                                void* v_cache, void* stream) {
+                                void* v_cache, void* stream, const float* k_scale = nullptr,
+                                const float* v_scale = nullptr, bool q8 = false) {
   rap_status_t st = check_shape(shape);
   if (st != RAP_OK) return st;
   int page_shift = 0;
@@ -117,6 +118,12 @@ static rap_status_t append_impl(const rap_shape_t* shape, const rap_paging_t* pa
     a.page_shift = page_shift;
     a.n_pages = paging->n_pages;
     a.max_pages = paging->max_pages;
+  }
+  if (q8) {
+    if (!k_scale || !v_scale) return RAP_ERR_NULL;
+    if (shape->cache_cap % 16 != 0) return RAP_ERR_SHAPE;
+    a.k_scale = k_scale;
+    a.v_scale = v_scale;
   }
   a.k_new = static_cast<const uint16_t*>(k_new);
   a.v_new = static_cast<const uint16_t*>(v_new);
@@ -189,6 +196,11 @@ size_t rap_decode_attn_workspace_bytes(const rap_shape_t* shape, int64_t max_seq
 
 namespace {
 
+struct Fp8Scales {         // fp8 caches: per-KV-head scales of the codes (device); null otherwise
+  const float* k_scale;
+  const float* v_scale;
+};
+
 struct NewToken {          // the append fused into rap_decode_step; all null otherwise
   const void* k_new = nullptr;
   const void* v_new = nullptr;
@@ -199,7 +211,8 @@ struct NewToken {          // the append fused into rap_decode_step; all null ot
 rap_status_t decode_impl(const rap_shape_t* shape, const void* q, const int32_t* q_pos, const int32_t* keep,
                          const void* k_cache, const void* v_cache, const int32_t* seq_lens, int64_t max_seq_len,
                          void* out, float scale, void* workspace, size_t workspace_bytes, const rap_tuning_t* tuning,
-                         void* stream, const NewToken& nt = NewToken(), const rap_paging_t* paging = nullptr) {
+                         void* stream, const NewToken& nt = NewToken(), const rap_paging_t* paging = nullptr,
+                         const Fp8Scales* q8 = nullptr) {
   rap_status_t st = check_shape(shape);
   if (st != RAP_OK) return st;
   int page_shift = 0;
@@ -252,7 +265,14 @@ rap_status_t decode_impl(const rap_shape_t* shape, const void* q, const int32_t*
   a.n_slots = p.n_split;
   a.cap = shape->cache_cap;
   a.scale_log2e = scale * 1.4426950408889634f;
-  a.lds_wave_bytes = rap::mfma_lds_wave_bytes(a.d_k, a.d_v);
+  a.lds_wave_bytes = rap::mfma_lds_wave_bytes(a.d_k, a.d_v, q8 != nullptr);
+  if (q8) {
+    if (p.kernel != 2 || paging || nt.k_new) return RAP_ERR_UNSUPPORTED;   // matrix-core kernel, dense cache, no fused step
+    if (shape->cache_cap % 16 != 0) return RAP_ERR_SHAPE;
+    if (!q8->k_scale || !q8->v_scale) return RAP_ERR_NULL;
+    a.k_scale = q8->k_scale;
+    a.v_scale = q8->v_scale;
+  }
   if (paging) {
     if (p.kernel != 2) return RAP_ERR_UNSUPPORTED;      // the vector-ALU kernel reads dense caches only
     a.block_table = paging->block_table;
@@ -357,6 +377,27 @@ rap_status_t rap_prefill_attn(const rap_shape_t* shape, int32_t n_new, const voi
   a.cap = shape->cache_cap;
   a.scale_log2e = scale * 1.4426950408889634f;
   return rap::launch_prefill(a, static_cast<hipStream_t>(stream)) == hipSuccess ? RAP_OK : RAP_ERR_HIP;
+}
+
+rap_status_t rap_rope_append_q8(const rap_shape_t* shape, int32_t n_new, const void* k_new, const void* v_new,
+                                const int32_t* pos, const int32_t* keep_pair_idx, void* k_cache8, void* v_cache8,
+                                const float* k_scale, const float* v_scale, void* stream) {
+  return append_impl(shape, nullptr, n_new, k_new, v_new, pos, keep_pair_idx, k_cache8, v_cache8, stream, k_scale, v_scale,
+                     true);
+}
+
+rap_status_t rap_decode_attn_q8(const rap_shape_t* shape, const void* q, const int32_t* q_pos,
+                                const int32_t* keep_pair_idx, const void* k_cache8, const void* v_cache8,
+                                const float* k_scale, const float* v_scale, const int32_t* seq_lens,
+                                int64_t max_seq_len, void* out, float scale, void* workspace, size_t workspace_bytes,
+                                const rap_tuning_t* tuning, void* stream) {
+  if (shape && shape->batch > 0 && max_seq_len >= 1 && q_pos && !keep_pair_idx && !shape->pair_inv_freq) {
+    const rap_status_t st = check_shape(shape);
+    return st != RAP_OK ? st : RAP_ERR_NULL;
+  }
+  Fp8Scales sc{k_scale, v_scale};
+  return decode_impl(shape, q, q_pos, keep_pair_idx, k_cache8, v_cache8, seq_lens, max_seq_len, out, scale, workspace,
+                     workspace_bytes, tuning, stream, NewToken(), nullptr, &sc);
 }
 
 rap_status_t rap_decode_attn_paged(const rap_shape_t* shape, const rap_paging_t* paging, const void* q,

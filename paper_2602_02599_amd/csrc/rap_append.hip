@@ -54,6 +54,44 @@ __global__ __launch_bounds__(256) void append_kernel(AppendArgs a) {
   if (has_v1) vdst[lane + kWave] = v1;
 }
 
+// The same append into an fp8 cache: the rotated K value and the V value are divided by the scale
+// of their KV head (fp64) and rounded once to an E4M3 code.  One wavefront per (token, KV head) for
+// any n_new.
+__global__ __launch_bounds__(256) void append_q8_kernel(AppendArgs a) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x >> 6;
+  const int h = blockIdx.y;
+  const long long tok = static_cast<long long>(blockIdx.x) * 4 + wave;   // b * n_new + n
+  const long long n_tok = static_cast<long long>(a.batch) * a.n_new;
+  if (tok >= n_tok) return;
+  const int b = static_cast<int>(tok / a.n_new);
+  const int P = a.n_pairs;
+  const bool has_pair = lane < P;
+  const bool has_v0 = lane < a.d_v, has_v1 = lane + kWave < a.d_v;
+  const uint16_t* ksrc = a.k_new + (tok * a.n_kv + h) * (2 * P);
+  const uint16_t* vsrc = a.v_new + (tok * a.n_kv + h) * a.d_v;
+  const int t = a.pos[tok];
+  double f = 0.0;
+  const bool rot = has_pair && pair_frequency(a.keep, a.pair_freq, a.neg2_log2_theta_over_d, a.d_head, h * P + lane, &f);
+  const uint16_t kx = has_pair ? ksrc[lane] : 0, ky = has_pair ? ksrc[lane + P] : 0;
+  const uint16_t v0 = has_v0 ? vsrc[lane] : 0, v1 = has_v1 ? vsrc[lane + kWave] : 0;
+  const double ks = static_cast<double>(a.k_scale[h]), vs = static_cast<double>(a.v_scale[h]);
+  if (t < 0 || t >= a.cap) return;                                        // documented: skipped
+  const long long row = (static_cast<long long>(b) * a.n_kv + h) * a.cap + t;
+  uint8_t* k8 = reinterpret_cast<uint8_t*>(a.k_cache) + row * (2 * P);
+  uint8_t* v8 = reinterpret_cast<uint8_t*>(a.v_cache) + row * a.d_v;
+  if (rot) {
+    double sn, cs;
+    sincos_f64(static_cast<double>(t) * f, &sn, &cs);
+    const double x = static_cast<double>(bf16_to_f32(kx));
+    const double y = static_cast<double>(bf16_to_f32(ky));
+    k8[lane] = f64_to_e4m3((x * cs - y * sn) / ks);
+    k8[lane + P] = f64_to_e4m3((x * sn + y * cs) / ks);
+  }
+  if (has_v0) v8[lane] = f64_to_e4m3(static_cast<double>(bf16_to_f32(v0)) / vs);
+  if (has_v1) v8[lane + kWave] = f64_to_e4m3(static_cast<double>(bf16_to_f32(v1)) / vs);
+}
+
 // Many tokens per sequence (prefill-sized appends).  The per-token kernel above spends its time in
 // fp64 exp2 and sincos (about 0.6 ms for 131072 tokens x 8 heads, four times the HBM time of the
 // same rows) and in one memory round trip per token.  Here a wavefront takes runs_per_wave runs of
@@ -228,6 +266,12 @@ __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs
 }
 
 hipError_t launch_append(const AppendArgs& a, hipStream_t stream) {
+  if (a.k_scale != nullptr) {
+    const long long n_tok8 = static_cast<long long>(a.batch) * a.n_new;
+    dim3 grid8(static_cast<unsigned>((n_tok8 + 3) / 4), static_cast<unsigned>(a.n_kv), 1);
+    hipLaunchKernelGGL(append_q8_kernel, grid8, dim3(256), 0, stream, a);
+    return hipGetLastError();
+  }
   if (a.n_new >= kBulkRun) {
     // longer walks per wavefront share the per-lane set-up; short jobs keep one run per wavefront
     // so that the chip still gets enough wavefronts

@@ -48,6 +48,13 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
+// eight E4M3 codes (c0: elements 0..3, c1: elements 4..7, lowest byte first) -> eight bf16, exact
+__device__ __forceinline__ uint4 widen_e4m3x8(uint32_t c0, uint32_t c1) {
+  const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(c0), false), b = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(c0), true);
+  const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(c1), false), d = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(c1), true);
+  return make_uint4(pack_bf16(a[0], a[1]), pack_bf16(b[0], b[1]), pack_bf16(c[0], c[1]), pack_bf16(d[0], d[1]));
+}
+
 __device__ __forceinline__ void wave_lds_sync() {
   // LDS operations of one wavefront execute in order; this only stops the compiler from moving
   // LDS accesses of different lanes across the hand-over point.
@@ -151,10 +158,15 @@ __device__ __forceinline__ void token_finish(const DecodeArgs& a, int b, int h, 
 // PAGED: the caches are pools of pages [n_pages, H_kv, page_rows, d] and row r of sequence b lives
 // in page block_table[b][r / page_rows]; page_rows is a power of two >= 32, so a 32-row tile never
 // straddles two pages and only the start address of a tile changes.
-template <int KCH, int NT, bool VPAIR, bool PAGED>
+// Q8: the caches hold one-byte E4M3 codes (value = code value x the scale of the KV head).  Rows
+// are half as long, tiles take half the loads and half the LDS, and a fragment is widened to bf16
+// (exactly: every E4M3 value is a bf16 number) on its way from LDS into the matrix instruction;
+// the two scales fold into the softmax scale and into the partial sums.
+template <int KCH, int NT, bool VPAIR, bool PAGED, bool Q8>
 __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(DecodeArgs a) {
-  constexpr int NLD_K = 2 * KCH;   // 1 KB wave-loads covering a K tile (d_k <= 32 KCH)
-  constexpr int NLD_V = NT;        // same for a V tile (d_v <= 16 NT)
+  constexpr int NLD_K = Q8 ? KCH : 2 * KCH;        // 1 KB wave-loads covering a K tile (d_k <= 32 KCH)
+  constexpr int NLD_V = Q8 ? (NT + 1) / 2 : NT;    // same for a V tile (d_v <= 16 NT)
+  constexpr int EB = Q8 ? 1 : 2;                   // bytes per cache element
   extern __shared__ __align__(16) unsigned char smem[];
 
   const int tid = threadIdx.x;
@@ -208,11 +220,13 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
     return;
   }
   const int r1 = min(r0 + a.rows_per_split, len);
-  const int len8 = (len + 7) & ~7;                 // <= cache_cap: rows below it are readable
+  // rows below len8 are readable: <= cache_cap (a multiple of 8, of 16 for one-byte elements, which
+  // keeps every such group of rows 16-byte aligned whatever the row width)
+  const int len8 = Q8 ? (len + 15) & ~15 : (len + 7) & ~7;
 
   const int G = a.group;
   const int dk = a.d_k, dv = a.d_v;
-  const int pitch_k = 2 * dk, pitch_v = 2 * dv;    // bytes
+  const int pitch_k = EB * dk, pitch_v = EB * dv;  // bytes
   // LDS slice of this wavefront: K area and V area, each a whole number of 1 KB wave-stores
   unsigned char* kt = smem + wave * a.lds_wave_bytes;
   unsigned char* vt = kt + 1024 * NLD_K;
@@ -304,16 +318,24 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
   uint32_t kmask[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) kmask[i] = (32 * (KCH - 1) + 8 * lg + 2 * i) < dk ? 0xffffffffu : 0u;
+  // one-byte elements: the same limit as byte masks of the fragment's two words (d_k is even)
+  uint32_t kmask8[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int left = dk - (32 * (KCH - 1) + 8 * lg + 4 * i);      // elements of word i that exist
+    kmask8[i] = left >= 4 ? 0xffffffffu : (left >= 2 ? 0x0000ffffu : 0u);
+  }
 
+  const float scale_log2e = Q8 ? a.scale_log2e * a.k_scale[h] : a.scale_log2e;
   // LDS byte offsets of this lane's operands inside a tile
   int koff[2];
 #pragma unroll
-  for (int rt = 0; rt < 2; ++rt) koff[rt] = (16 * rt + l16) * pitch_k + 16 * lg;
+  for (int rt = 0; rt < 2; ++rt) koff[rt] = (16 * rt + l16) * pitch_k + 8 * EB * lg;
   int voff[2][4];
 #pragma unroll
   for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) voff[rt][r] = (16 * rt + 4 * lg + r) * pitch_v + (VPAIR ? 4 : 2) * l16;
+    for (int r = 0; r < 4; ++r) voff[rt][r] = (16 * rt + 4 * lg + r) * pitch_v + (VPAIR ? 2 : 1) * EB * l16;
 
 
   for (int base = first; base < r1; base += 4 * kTileRows) {
@@ -334,13 +356,24 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
       sc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int kk = 0; kk < KCH; ++kk) {
-        const uint32_t* p = reinterpret_cast<const uint32_t*>(kt + koff[rt] + 64 * kk);
-        uint4 w = make_uint4(p[0], p[1], p[2], p[3]);
-        if (kk == KCH - 1) {
-          w.x &= kmask[0];
-          w.y &= kmask[1];
-          w.z &= kmask[2];
-          w.w &= kmask[3];
+        uint4 w;
+        if constexpr (Q8) {
+          const uint16_t* p = reinterpret_cast<const uint16_t*>(kt + koff[rt] + 32 * kk);   // rows are 2-byte aligned
+          uint32_t c0 = p[0] | (static_cast<uint32_t>(p[1]) << 16), c1 = p[2] | (static_cast<uint32_t>(p[3]) << 16);
+          if (kk == KCH - 1) {
+            c0 &= kmask8[0];
+            c1 &= kmask8[1];
+          }
+          w = widen_e4m3x8(c0, c1);
+        } else {
+          const uint32_t* p = reinterpret_cast<const uint32_t*>(kt + koff[rt] + 64 * kk);
+          w = make_uint4(p[0], p[1], p[2], p[3]);
+          if (kk == KCH - 1) {
+            w.x &= kmask[0];
+            w.y &= kmask[1];
+            w.z &= kmask[2];
+            w.w &= kmask[3];
+          }
         }
         sc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), qf[kk], sc[rt], 0, 0, 0);
       }
@@ -355,7 +388,7 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
     for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const float s = sc[rt][r] * a.scale_log2e;
+        const float s = sc[rt][r] * scale_log2e;
         x[rt][r] = ((16 * rt + 4 * lg + r) < nv && (16 * rt + 4 * lg + r) != skip_rel) ? s : -INFINITY;
         tmax = fmaxf(tmax, x[rt][r]);
       }
@@ -406,15 +439,27 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const int row = min(16 * (j >> 2) + 4 * lg + (j & 3), nv - 1);
-      vo[j] = nv == kTileRows ? voff[j >> 2][j & 3] : row * pitch_v + (VPAIR ? 4 : 2) * l16;
+      vo[j] = nv == kTileRows ? voff[j >> 2][j & 3] : row * pitch_v + (VPAIR ? 2 : 1) * EB * l16;
     }
     if constexpr (VPAIR) {
 #pragma unroll
       for (int np = 0; np < NT / 2; ++np) {
+        uint4 be, bo;   // even / odd channel of the pair, rows packed two by two
+        if constexpr (Q8) {
+          uint32_t h[8];                 // two adjacent channels of row j: even channel in the low byte
+#pragma unroll
+          for (int j = 0; j < 8; ++j) h[j] = *reinterpret_cast<const uint16_t*>(vt + vo[j] + 32 * np);
+          // bytes of one channel over rows 0..3 and 4..7, then widened
+          const uint32_t lo01 = __builtin_amdgcn_perm(h[1], h[0], 0x0c0c0400u), lo23 = __builtin_amdgcn_perm(h[3], h[2], 0x04000c0cu);
+          const uint32_t lo45 = __builtin_amdgcn_perm(h[5], h[4], 0x0c0c0400u), lo67 = __builtin_amdgcn_perm(h[7], h[6], 0x04000c0cu);
+          const uint32_t hi01 = __builtin_amdgcn_perm(h[1], h[0], 0x0c0c0501u), hi23 = __builtin_amdgcn_perm(h[3], h[2], 0x05010c0cu);
+          const uint32_t hi45 = __builtin_amdgcn_perm(h[5], h[4], 0x0c0c0501u), hi67 = __builtin_amdgcn_perm(h[7], h[6], 0x05010c0cu);
+          be = widen_e4m3x8(lo01 | lo23, lo45 | lo67);
+          bo = widen_e4m3x8(hi01 | hi23, hi45 | hi67);
+        } else {
         uint32_t w[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) w[j] = *reinterpret_cast<const uint32_t*>(vt + vo[j] + 64 * np);
-        uint4 be, bo;   // even / odd channel of the pair, rows packed two by two
         be.x = __builtin_amdgcn_perm(w[1], w[0], 0x05040100u);
         be.y = __builtin_amdgcn_perm(w[3], w[2], 0x05040100u);
         be.z = __builtin_amdgcn_perm(w[5], w[4], 0x05040100u);
@@ -423,6 +468,7 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
         bo.y = __builtin_amdgcn_perm(w[3], w[2], 0x07060302u);
         bo.z = __builtin_amdgcn_perm(w[5], w[4], 0x07060302u);
         bo.w = __builtin_amdgcn_perm(w[7], w[6], 0x07060302u);
+        }
         const bf16x8 vbe = __builtin_bit_cast(bf16x8, be), vbo = __builtin_bit_cast(bf16x8, bo);
         acc[2 * np] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi, vbe, acc[2 * np], 0, 0, 0);
         acc[2 * np + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi, vbo, acc[2 * np + 1], 0, 0, 0);
@@ -433,9 +479,16 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         uint32_t u[8];
+        uint4 bv;
+        if constexpr (Q8) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) u[j] = *reinterpret_cast<const uint16_t*>(vt + vo[j] + 32 * nt);
-        const uint4 bv = make_uint4(u[0] | (u[1] << 16), u[2] | (u[3] << 16), u[4] | (u[5] << 16), u[6] | (u[7] << 16));
+          for (int j = 0; j < 8; ++j) u[j] = *reinterpret_cast<const uint8_t*>(vt + vo[j] + 16 * nt);
+          bv = widen_e4m3x8(u[0] | (u[1] << 8) | (u[2] << 16) | (u[3] << 24), u[4] | (u[5] << 8) | (u[6] << 16) | (u[7] << 24));
+        } else {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) u[j] = *reinterpret_cast<const uint16_t*>(vt + vo[j] + 32 * nt);
+          bv = make_uint4(u[0] | (u[1] << 16), u[2] | (u[3] << 16), u[4] | (u[5] << 16), u[6] | (u[7] << 16));
+        }
         const bf16x8 vb = __builtin_bit_cast(bf16x8, bv);
         acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi, vb, acc[nt], 0, 0, 0);
         acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_lo, vb, acc[nt], 0, 0, 0);
@@ -480,6 +533,7 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
         num = fmaf(wt, pw[32 + g * (16 * NT) + c], num);
       }
     }
+    if constexpr (Q8) num *= a.v_scale[h];          // codes -> values
     const long long hq = static_cast<long long>(b) * a.n_q + h * G + g;
     if (a.direct_out) {
       a.out[hq * dv + c] = den > 0.f ? num / den : 0.f;
@@ -493,7 +547,7 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
   }
 }
 
-template <int KCH, int NT, bool VPAIR, bool PAGED>
+template <int KCH, int NT, bool VPAIR, bool PAGED, bool Q8>
 hipError_t launch_inst2(const DecodeArgs& a, hipStream_t stream) {
   // scanning workgroups, then (decode step: n_slots = n_split + 1) one per (b, h) for the new token
   dim3 grid(static_cast<unsigned>(a.n_slots) * a.n_kv * a.batch), block(256);
@@ -502,20 +556,21 @@ hipError_t launch_inst2(const DecodeArgs& a, hipStream_t stream) {
     // more than the default dynamic-LDS limit: raise it once per kernel (gfx950 has 160 KB per CU)
     static int raised_to = 0;
     if (raised_to < static_cast<int>(lds)) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_mfma_kernel<KCH, NT, VPAIR, PAGED>),
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_mfma_kernel<KCH, NT, VPAIR, PAGED, Q8>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
       if (e != hipSuccess) return e;
       raised_to = static_cast<int>(lds);
     }
   }
-  hipLaunchKernelGGL((decode_mfma_kernel<KCH, NT, VPAIR, PAGED>), grid, block, lds, stream, a);
+  hipLaunchKernelGGL((decode_mfma_kernel<KCH, NT, VPAIR, PAGED, Q8>), grid, block, lds, stream, a);
   return hipGetLastError();
 }
 
 template <int KCH, int NT, bool VPAIR>
 hipError_t launch_inst(const DecodeArgs& a, hipStream_t stream) {
-  if (a.block_table != nullptr) return launch_inst2<KCH, NT, VPAIR, true>(a, stream);
-  return launch_inst2<KCH, NT, VPAIR, false>(a, stream);
+  if (a.k_scale != nullptr) return launch_inst2<KCH, NT, VPAIR, false, true>(a, stream);   // fp8 caches are dense
+  if (a.block_table != nullptr) return launch_inst2<KCH, NT, VPAIR, true, false>(a, stream);
+  return launch_inst2<KCH, NT, VPAIR, false, false>(a, stream);
 }
 
 template <int KCH>
@@ -547,9 +602,9 @@ hipError_t launch_k(const DecodeArgs& a, hipStream_t stream) {
 
 // LDS bytes one wavefront needs: its K tile, its V tile and slack for the fragment reads that run
 // past the last row, or the hand-over area of the final fold, whichever is larger.
-int mfma_lds_wave_bytes(int d_k, int d_v) {
+int mfma_lds_wave_bytes(int d_k, int d_v, bool q8) {
   const int nt = (d_v + 15) / 16;
-  const int tiles = 1024 * (2 * ((d_k + 31) / 32) + nt) + 128;
+  const int tiles = 1024 * (q8 ? (d_k + 31) / 32 + (nt + 1) / 2 : 2 * ((d_k + 31) / 32) + nt) + 128;
   const int fold = (32 + kMaxGroup * 16 * nt) * 4;
   const int need = tiles > fold ? tiles : fold;
   return (need + 127) / 128 * 128;

@@ -90,6 +90,8 @@ struct AppendArgs {
   const int32_t* keep;
   const double* pair_freq;          // [H_kv, P] radians per position, or null: theta_j from keep
   const int32_t* block_table;       // paged caches: [B, max_pages], or null
+  const float* k_scale;             // fp8 caches: [H_kv] scales of the codes, or null
+  const float* v_scale;
   int32_t page_shift, n_pages, max_pages;
   uint16_t* k_cache;
   uint16_t* v_cache;
@@ -109,6 +111,9 @@ struct DecodeArgs {
   const uint16_t* k_cache;
   const uint16_t* v_cache;
   const int32_t* seq_lens;
+  // fp8 caches (null otherwise): per-KV-head scales of the E4M3 codes
+  const float* k_scale;
+  const float* v_scale;
   // paged caches (block_table null otherwise): pools [n_pages, H_kv, 1 << page_shift, d]
   const int32_t* block_table;   // [B, max_pages]
   int32_t page_shift, n_pages, max_pages;
@@ -148,6 +153,30 @@ struct PrefillArgs {
   int64_t cap;
   float scale_log2e;
 };
+
+// fp64 -> E4M3 code (finite-only 8-bit float: 4 exponent bits, bias 7, 3 mantissa bits, no
+// infinity, S.1111.111 = NaN): nearest value, ties to the even mantissa, magnitudes above 448
+// saturate, NaN -> 0x7f.  The mantissa is rounded as an integer in fp64 (rint of the value scaled
+// by a power of two, exact), so there is one rounding and it is the format's.
+__device__ __forceinline__ uint8_t f64_to_e4m3(double y) {
+  if (y != y) return 0x7f;
+  const uint32_t sign = (__double2hiint(y) < 0) ? 0x80u : 0u;
+  double mag = fabs(y);
+  mag = mag > 448.0 ? 448.0 : mag;
+  uint32_t code;
+  if (mag < 0.015625) {                              // subnormal codes: multiples of 2^-9
+    code = static_cast<uint32_t>(rint(mag * 512.0)); // 0..8; 8 is the smallest normal, 0x08
+  } else {
+    int e = ilogb(mag);                              // -6 .. 8
+    int q = static_cast<int>(rint(ldexp(mag, 3 - e)));   // 8 .. 16
+    if (q == 16) {
+      q = 8;
+      e += 1;
+    }
+    code = (static_cast<uint32_t>(e + 7) << 3) | static_cast<uint32_t>(q - 8);
+  }
+  return static_cast<uint8_t>(sign | code);
+}
 
 // Row of the K / V cache that holds position t of sequence b for KV head h: a row of the dense
 // [B, H_kv, cap] arrangement, or, with a block table, of the pool [n_pages, H_kv, page_rows] (a page

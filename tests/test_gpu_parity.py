@@ -652,6 +652,68 @@ def test_paged_caches(rap, P, dv, Hq, Hkv, ctx, page_rows, n_new):
     assert st == 3
 
 
+# ---------------------------------------------------------------- fp8 (E4M3) caches
+
+
+@pytest.mark.parametrize("P,dv,Hq,Hkv,ctx,n_new", [(45, 90, 8, 2, 1200, 1), (58, 115, 8, 2, 700, 5), (32, 64, 10, 2, 2500, 40),
+                                                   (64, 128, 4, 1, 300, 1), (3, 5, 3, 1, 40, 2)])
+def test_q8_cache(rap, P, dv, Hq, Hkv, ctx, n_new):
+    """rap_rope_append_q8 + rap_decode_attn_q8: the appended codes against the oracle's (equal, up
+    to one code step on a vanishing fraction where the fp64 angle arithmetic differs in its last
+    bit), then attention over the GPU-written cache against the oracle on the same codes, with
+    several range sizes, NaN codes beyond the sequences, and the fused query rotation."""
+    w = I.scaled(I.WORKLOADS["cfg2"], batch=3, n_q_heads=Hq, n_kv_heads=Hkv, n_pairs=P, d_v=dv, ctx=ctx, n_new=n_new,
+                 ragged_min=max(n_new + 1, ctx // 3), peaky_frac=0.0, seed=600 + P)
+    _say("q8 cache P=%d dv=%d ctx=%d n_new=%d" % (P, dv, ctx, n_new))
+    case = I.make_case(w, device=DEV)
+    lens = case.seq_lens.cpu().numpy()
+    cap = (int(lens.max()) + 15) // 16 * 16
+    rng = np.random.Generator(np.random.PCG64(11))
+    ks = (rng.uniform(4.0, 6.0, Hkv) / 448.0).astype(np.float32)        # per-head scales: amax about 4.5 sigma
+    vs = (rng.uniform(4.0, 6.0, Hkv) / 448.0).astype(np.float32)
+    kd = O.bf16_bits_to_f64(I.bits(case.k_cache))[:, :, :cap]
+    vd = O.bf16_bits_to_f64(I.bits(case.v_cache))[:, :, :cap]
+    k8 = np.full((w.batch, Hkv, cap, 2 * P), 0x7F, dtype=np.uint8)      # NaN everywhere ...
+    v8 = np.full((w.batch, Hkv, cap, dv), 0xFF, dtype=np.uint8)
+    for b in range(w.batch):                                            # ... but the prefilled rows
+        n0 = int(case.prefill_lens[b])
+        k8[b, :, :n0] = O.f64_to_e4m3_bits(kd[b, :, :n0] / ks[None, :, None, None].astype(np.float64)[0])
+        v8[b, :, :n0] = O.f64_to_e4m3_bits(vd[b, :, :n0] / vs[None, :, None, None].astype(np.float64)[0])
+    k8d, v8d = torch.from_numpy(k8).to(DEV), torch.from_numpy(v8).to(DEV)
+    ksd, vsd = torch.from_numpy(ks).to(DEV), torch.from_numpy(vs).to(DEV)
+    shp = rap.shape(w.batch, Hq, Hkv, w.d_head, P, dv, cap, w.rope_theta)
+    rap.rap_rope_append_q8(shp, n_new, case.k_new, case.v_new, case.pos, case.keep, k8d, v8d, ksd, vsd)
+    torch.cuda.synchronize()
+    ok8, ov8 = k8.copy(), v8.copy()
+    O.append_q8_ref(I.bits(case.k_new), I.bits(case.v_new), case.pos.cpu().numpy(), case.keep.cpu().numpy(), ok8, ov8, ks, vs,
+                    w.rope_theta, w.d_head)
+    gk, gv = k8d.cpu().numpy(), v8d.cpu().numpy()
+    assert np.array_equal(gv, ov8), "V codes differ"
+    diff = gk != ok8
+    assert diff.sum() <= gk.size // 10000 + 1, "%d K codes differ" % diff.sum()
+    if diff.any():
+        step = np.abs(O.e4m3_bits_to_f64(gk[diff]) - O.e4m3_bits_to_f64(ok8[diff]))
+        assert np.all(step <= np.maximum(np.abs(O.e4m3_bits_to_f64(ok8[diff])), 2.0 ** -6) * 0.126)   # one code step
+    ref = O.attn_q8_ref(I.bits(case.q), gk, gv, ks, vs, lens, w.scale)
+    for rps in (0, 128, 512):
+        tun = rap.tuning(kernel=MFMA, rows_per_split=rps)
+        ws = rap.new_workspace(shp, cap, tun)
+        out = torch.full((w.batch, Hq, dv), float("nan"), dtype=torch.float32, device=DEV)
+        rap.rap_decode_attn_q8(shp, case.q, None, None, k8d, v8d, ksd, vsd, case.seq_lens, cap, out, float(w.scale), ws, tun)
+        torch.cuda.synchronize()
+        H.assert_attn_close(out.cpu().numpy(), ref, "q8 decode rps=%d" % rps)
+    qpos_np = (lens - 1).astype(np.int32)
+    qrot = O.rope_queries_ref(I.bits(case.q), qpos_np, case.keep.cpu().numpy(), w.rope_theta, w.d_head, Hkv)
+    ref2 = O.attn_q8_ref(qrot, gk, gv, ks, vs, lens, w.scale)
+    ws = rap.new_workspace(shp, cap, None)
+    rap.rap_decode_attn_q8(shp, case.q, torch.from_numpy(qpos_np).to(DEV), case.keep, k8d, v8d, ksd, vsd, case.seq_lens, cap,
+                           out, float(w.scale), ws, None)
+    torch.cuda.synchronize()
+    H.assert_attn_close(out.cpu().numpy(), ref2, "q8 decode with query rotation")
+    assert rap.rap_decode_attn_q8(shp, case.q, None, None, k8d, v8d, ksd, vsd, case.seq_lens, cap, out, float(w.scale), ws,
+                                  rap.tuning(kernel=VALU), check=False) == 3
+
+
 def test_split_invariance(rap):
     """1 range vs many: same result up to fp32 rounding (merge identity on the GPU side)."""
     w = I.scaled(I.WORKLOADS["cfg2"], batch=2, ctx=4000, seed=13)
