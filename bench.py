@@ -187,6 +187,48 @@ def prefill_figure(rap, torch, w, dev, reps=5):
     return ms, flops
 
 
+def q8_figure(rap, torch, job, steps, warmup):
+    """rap_decode_attn_q8 over fp8 (E4M3) caches of the same shape and lengths (random finite
+    codes), the attention call alone; bytes are the one-byte rows actually read."""
+    w = job.w
+    dev = job.out.device
+    cap = (max(c.cap for c in job.cases) + 15) // 16 * 16
+    shp = rap.shape(w.batch, w.n_q_heads, w.n_kv_heads, w.d_head, w.n_pairs, w.d_v, cap, w.rope_theta)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed + 7)
+    pools = []
+    for _ in job.cases:
+        k8 = torch.randint(0, 0x78, (w.batch, w.n_kv_heads, cap, w.d_k), generator=gen, device=dev, dtype=torch.uint8)
+        k8 |= torch.randint(0, 2, k8.shape, generator=gen, device=dev, dtype=torch.uint8) << 7
+        v8 = torch.randint(0, 0x78, (w.batch, w.n_kv_heads, cap, w.d_v), generator=gen, device=dev, dtype=torch.uint8)
+        pools.append((k8, v8))
+    ks = torch.full((w.n_kv_heads,), 0.0125, dtype=torch.float32, device=dev)
+    vs = ks.clone()
+    ws = rap.new_workspace(shp, job.max_len, None, device=dev)
+    n = len(job.cases)
+
+    def call(i):
+        c = job.cases[i % n]
+        rap.rap_decode_attn_q8(shp, c.q, None, None, pools[i % n][0], pools[i % n][1], ks, vs, c.seq_lens, job.max_len,
+                               job.out, float(w.scale), ws, None)
+
+    def call16(i):
+        c = job.cases[i % n]
+        rap.rap_decode_attn(job.shape, c.q, c.k_cache, c.v_cache, c.seq_lens, job.max_len, job.out, float(w.scale), job.ws, None)
+
+    res = []
+    for fn in (call, call16):
+        for i in range(warmup + 3 * n):
+            fn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            fn(i)
+        torch.cuda.synchronize()
+        res.append((time.perf_counter() - t0) / steps)
+    return res[0], res[1], job.bytes_per_step / 2
+
+
 def read_traffic(path):
     """HBM bytes per launch of the dominant kernel from the committed counter summary, if present."""
     try:
@@ -211,6 +253,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-control", action="store_true", help="skip the rho = 1.0 control")
     ap.add_argument("--no-prefill", action="store_true", help="skip the causal prefill attention figure")
+    ap.add_argument("--no-q8", action="store_true", help="skip the fp8-cache attention figure")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain copies of 256 MiB (known-size reference for hardware byte counters)")
     args = ap.parse_args()
@@ -237,6 +280,15 @@ def main():
     sec_rope = job.timed(args.steps, args.warmup, mode="step_rope")
     k_mean_ms, k_min_ms = job.kernel_ms(args.steps, ev)
     achieved = job.bytes_per_step / (k_mean_ms * 1e-3) / 1e9
+
+    q8 = None
+    if not args.no_q8:
+        # last row of the path's follow-ups (not part of `value`): the same attention over fp8 caches
+        s8, s16, b8 = q8_figure(rap, torch, job, args.steps, args.warmup)
+        q8 = {"call": "rap_decode_attn_q8 (attention call alone, E4M3 caches, half the bytes per row)",
+              "ms": round(s8 * 1e3, 5), "value": round(b8 / s8 / 1e9, 2), "unit": "GB/s",
+              "tokens_per_s": round(w.batch / s8, 1),
+              "bf16_call_ms": round(s16 * 1e3, 5), "speedup_over_bf16_cache": round(s16 / s8, 4)}
 
     # what a trivial read-only kernel reaches over the same bytes, same run
     flat = torch.cat([c.k_cache.view(-1) for c in job.cases] + [c.v_cache.view(-1) for c in job.cases])
@@ -283,6 +335,9 @@ def main():
                      "kernel_ms_mean": round(k_mean_ms, 5), "kernel_ms_min": round(k_min_ms, 5),
                      "algorithmic_bytes_per_launch": int(job.bytes_per_step)},
     }
+
+    if q8 is not None:
+        result["fp8_cache"] = q8
 
     if not args.no_control and (args.workload + "_rho1") in I.WORKLOADS:
         case0 = job.cases[0]
