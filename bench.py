@@ -254,6 +254,8 @@ def main():
     ap.add_argument("--no-control", action="store_true", help="skip the rho = 1.0 control")
     ap.add_argument("--no-prefill", action="store_true", help="skip the causal prefill attention figure")
     ap.add_argument("--no-q8", action="store_true", help="skip the fp8-cache attention figure")
+    ap.add_argument("--only-prefill", action="store_true",
+                    help="run nothing but the causal prefill attention figure (for profiling that kernel)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain copies of 256 MiB (known-size reference for hardware byte counters)")
     args = ap.parse_args()
@@ -271,6 +273,14 @@ def main():
     dev = "cuda:0"
     rap = pkg.load()
     ev = HipEvents()
+
+    if args.only_prefill:
+        w = I.WORKLOADS[args.workload]
+        pms, pflops = prefill_figure(rap, torch, w, dev)
+        print(json.dumps({"metric": "causal prefill attention (rap_prefill_attn), useful TFLOP/s", "workload": w.name,
+                          "ms": round(pms, 4), "value": round(pflops / pms / 1e9, 1), "unit": "TFLOP/s",
+                          "frac_of_mfma_peak": round(pflops / pms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)}))
+        return
 
     job = Job(rap, I, args.workload, args.buffers, dev)
     w = job.w
