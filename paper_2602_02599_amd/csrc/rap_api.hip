@@ -1,5 +1,7 @@
 // C ABI of librap: host-side validation, split planning and kernel dispatch.  See include/rap.h
-// for the contract of every entry point.
+// for the contract of every entry point.  Each exported function fills a request record and hands
+// it to one of the two shared bodies below (append_impl, decode_impl); nothing here allocates,
+// synchronises or keeps state between calls.
 #include <math.h>
 #include <string.h>
 
@@ -20,7 +22,13 @@ int mfma_lds_wave_bytes(int d_k, int d_v, bool q8);
 
 namespace {
 
-constexpr int kCUs = 256;   // MI355X
+constexpr int kCUs = 256;                          // MI355X
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr int64_t kInt32Max = 0x7fffffffLL;
+
+bool misaligned(const void* p, uintptr_t bytes) { return (reinterpret_cast<uintptr_t>(p) & (bytes - 1)) != 0; }
+
+rap_status_t hip_status(hipError_t e) { return e == hipSuccess ? RAP_OK : RAP_ERR_HIP; }
 
 rap_status_t check_shape(const rap_shape_t* s) {
   if (!s) return RAP_ERR_NULL;
@@ -32,8 +40,18 @@ rap_status_t check_shape(const rap_shape_t* s) {
   if (s->cache_cap % 8 != 0) return RAP_ERR_SHAPE;
   if (s->n_pairs > rap::kMaxPairs || s->d_v > rap::kMaxDv || s->n_q_heads / s->n_kv_heads > rap::kMaxGroup)
     return RAP_ERR_UNSUPPORTED;
-  if (s->cache_cap > 0x7fffffffLL - 1024 || s->batch > 65535 || s->n_kv_heads > 65535) return RAP_ERR_UNSUPPORTED;
+  if (s->cache_cap > kInt32Max - 1024 || s->batch > 65535 || s->n_kv_heads > 65535) return RAP_ERR_UNSUPPORTED;
   return RAP_OK;
+}
+
+// Exponent of the rotation frequencies: theta_j = 2^(j * this), Eq. (rope).
+double neg2_log2_theta_over_d(const rap_shape_t* s) {
+  return -2.0 * log2(s->rope_theta) / static_cast<double>(s->d_head);
+}
+
+// A rotation needs either the kept pair indices or the caller's frequency table.
+bool no_rotation_rule(const rap_shape_t* s, const int32_t* keep_pair_idx) {
+  return !keep_pair_idx && !s->pair_inv_freq;
 }
 
 struct Plan {
@@ -42,13 +60,12 @@ struct Plan {
   int kernel;   // 1 vector ALU, 2 matrix core
 };
 
-// Row range per workgroup.  The grid is (n_split, H_kv, B); a workgroup whose range starts at or
-// beyond its sequence's length exits at once, so ragged batches cost only empty launches.
-// Measured on MI355X: a workgroup should stream for a long time (its fixed cost is a few
-// microseconds), and when the whole job fits in one round of resident workgroups their number
-// should be a multiple of the 256 compute units.  So: about 512 workgroups when the (b, h) count
-// allows it, ranges never shorter than 512 rows nor longer than 4096 (longer ranges only lengthen
-// the tail of a ragged batch).
+// Row range per workgroup.  A workgroup whose range starts at or beyond its sequence's length
+// exits at once, so ragged batches cost only empty launches.  Measured on MI355X: a workgroup
+// should stream for a long time (its fixed cost is a few microseconds), and when the whole job
+// fits in one round of resident workgroups their number should be a multiple of the 256 compute
+// units.  So: about 512 workgroups when the (b, h) count allows it, ranges never shorter than 512
+// rows nor longer than 4096 (longer ranges only lengthen the tail of a ragged batch).
 rap_status_t make_plan(const rap_shape_t* s, int64_t max_seq_len, const rap_tuning_t* t, Plan* p) {
   int rps = t ? t->rows_per_split : 0;
   if (rps < 0 || (rps % rap::kSplitQuantum) != 0) return RAP_ERR_SHAPE;
@@ -72,12 +89,16 @@ rap_status_t make_plan(const rap_shape_t* s, int64_t max_seq_len, const rap_tuni
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Workspace = accumulators [B, H_q, n_split + 1, d_v], then (reference, sum) pairs
+// [B, H_q, n_split + 1, 2], fp32, each block rounded up to 256 bytes; the extra slot is the new
+// token's in the one-call step.
 size_t part_acc_bytes(const rap_shape_t* s, const Plan& p) {
   return align_up(static_cast<size_t>(s->batch) * s->n_q_heads * (p.n_split + 1) * s->d_v * sizeof(float), 256);
 }
 size_t part_ml_bytes(const rap_shape_t* s, const Plan& p) {
   return align_up(static_cast<size_t>(s->batch) * s->n_q_heads * (p.n_split + 1) * 2 * sizeof(float), 256);
 }
+size_t workspace_need(const rap_shape_t* s, const Plan& p) { return part_acc_bytes(s, p) + part_ml_bytes(s, p) + 256; }
 
 // page_rows a power of two in [32, 65536], table present, logical capacity consistent
 rap_status_t check_paging(const rap_shape_t* s, const rap_paging_t* pg, int* shift) {
@@ -92,69 +113,271 @@ rap_status_t check_paging(const rap_shape_t* s, const rap_paging_t* pg, int* shi
   return RAP_OK;
 }
 
-}  // namespace
+// ---- append ---------------------------------------------------------------------------------
 
-extern "C" {
+struct AppendRequest {
+  const rap_shape_t* shape = nullptr;
+  const rap_paging_t* paging = nullptr;    // paged pools instead of dense caches
+  int32_t n_new = 0;
+  const void* k_new = nullptr;
+  const void* v_new = nullptr;
+  const int32_t* pos = nullptr;
+  const int32_t* keep_pair_idx = nullptr;
+  void* k_cache = nullptr;
+  void* v_cache = nullptr;
+  bool fp8 = false;                        // caches hold E4M3 codes, scales required
+  const float* k_scale = nullptr;
+  const float* v_scale = nullptr;
+  void* stream = nullptr;
+};
 
-static rap_status_t append_impl(const rap_shape_t* shape, const rap_paging_t* paging, int32_t n_new, const void* k_new,
-                                const void* v_new, const int32_t* pos, const int32_t* keep_pair_idx, void* k_cache,
-                                void* v_cache, void* stream, const float* k_scale = nullptr,
-                                const float* v_scale = nullptr, bool q8 = false) {
+// Shared body of rap_rope_append, rap_rope_append_paged and rap_rope_append_q8.
+rap_status_t append_impl(const AppendRequest& r) {
+  const rap_shape_t* shape = r.shape;
   rap_status_t st = check_shape(shape);
   if (st != RAP_OK) return st;
   int page_shift = 0;
-  if (paging && (st = check_paging(shape, paging, &page_shift)) != RAP_OK) return st;
-  if (n_new < 0) return RAP_ERR_SHAPE;
-  if (n_new == 0 || shape->batch == 0) return RAP_OK;
-  if (!k_new || !v_new || !pos || (!keep_pair_idx && !shape->pair_inv_freq) || !k_cache || !v_cache) return RAP_ERR_NULL;
-  if (static_cast<int64_t>(shape->batch) * n_new > 0x7fffffffLL) return RAP_ERR_UNSUPPORTED;
-  if ((reinterpret_cast<uintptr_t>(k_new) & 3) || (reinterpret_cast<uintptr_t>(v_new) & 3) ||
-      (reinterpret_cast<uintptr_t>(k_cache) & 3) || (reinterpret_cast<uintptr_t>(v_cache) & 3))
+  if (r.paging && (st = check_paging(shape, r.paging, &page_shift)) != RAP_OK) return st;
+  if (r.n_new < 0) return RAP_ERR_SHAPE;
+  if (r.n_new == 0 || shape->batch == 0) return RAP_OK;
+  if (!r.k_new || !r.v_new || !r.pos || no_rotation_rule(shape, r.keep_pair_idx) || !r.k_cache || !r.v_cache)
+    return RAP_ERR_NULL;
+  if (static_cast<int64_t>(shape->batch) * r.n_new > kInt32Max) return RAP_ERR_UNSUPPORTED;
+  if (misaligned(r.k_new, 4) || misaligned(r.v_new, 4) || misaligned(r.k_cache, 4) || misaligned(r.v_cache, 4))
     return RAP_ERR_SHAPE;
   rap::AppendArgs a;
   memset(&a, 0, sizeof(a));
-  if (paging) {
-    a.block_table = paging->block_table;
+  if (r.paging) {
+    a.block_table = r.paging->block_table;
     a.page_shift = page_shift;
-    a.n_pages = paging->n_pages;
-    a.max_pages = paging->max_pages;
+    a.n_pages = r.paging->n_pages;
+    a.max_pages = r.paging->max_pages;
   }
-  if (q8) {
-    if (!k_scale || !v_scale) return RAP_ERR_NULL;
+  if (r.fp8) {
+    if (r.paging) return RAP_ERR_UNSUPPORTED;
+    if (!r.k_scale || !r.v_scale) return RAP_ERR_NULL;
     if (shape->cache_cap % 16 != 0) return RAP_ERR_SHAPE;
-    a.k_scale = k_scale;
-    a.v_scale = v_scale;
+    a.k_scale = r.k_scale;
+    a.v_scale = r.v_scale;
   }
-  a.k_new = static_cast<const uint16_t*>(k_new);
-  a.v_new = static_cast<const uint16_t*>(v_new);
-  a.pos = pos;
-  a.keep = keep_pair_idx;
+  a.k_new = static_cast<const uint16_t*>(r.k_new);
+  a.v_new = static_cast<const uint16_t*>(r.v_new);
+  a.pos = r.pos;
+  a.keep = r.keep_pair_idx;
   a.pair_freq = shape->pair_inv_freq;
-  a.k_cache = static_cast<uint16_t*>(k_cache);
-  a.v_cache = static_cast<uint16_t*>(v_cache);
+  a.k_cache = static_cast<uint16_t*>(r.k_cache);
+  a.v_cache = static_cast<uint16_t*>(r.v_cache);
   a.batch = shape->batch;
-  a.n_new = n_new;
+  a.n_new = r.n_new;
   a.n_kv = shape->n_kv_heads;
   a.d_head = shape->d_head;
   a.n_pairs = shape->n_pairs;
   a.d_v = shape->d_v;
   a.group = 1;
   a.cap = shape->cache_cap;
-  a.neg2_log2_theta_over_d = -2.0 * log2(shape->rope_theta) / static_cast<double>(shape->d_head);
-  return rap::launch_append(a, static_cast<hipStream_t>(stream)) == hipSuccess ? RAP_OK : RAP_ERR_HIP;
+  a.neg2_log2_theta_over_d = neg2_log2_theta_over_d(shape);
+  return hip_status(rap::launch_append(a, static_cast<hipStream_t>(r.stream)));
 }
+
+// ---- decode attention -------------------------------------------------------------------------
+
+struct DecodeRequest {
+  const rap_shape_t* shape = nullptr;
+  const rap_paging_t* paging = nullptr;    // paged pools instead of dense caches
+  const void* q = nullptr;
+  const int32_t* q_pos = nullptr;          // non-null: q arrives un-rotated and is rotated in the prologue
+  const int32_t* keep_pair_idx = nullptr;
+  const void* k_cache = nullptr;
+  const void* v_cache = nullptr;
+  bool fp8 = false;                        // caches hold E4M3 codes, scales required
+  const float* k_scale = nullptr;
+  const float* v_scale = nullptr;
+  const void* k_new = nullptr;             // one-call step: the token to append first (with v_new, new_pos)
+  const void* v_new = nullptr;
+  const int32_t* new_pos = nullptr;
+  const int32_t* seq_lens = nullptr;
+  int64_t max_seq_len = 0;
+  void* out = nullptr;
+  float scale = 0.f;
+  void* workspace = nullptr;
+  size_t workspace_bytes = 0;
+  const rap_tuning_t* tuning = nullptr;
+  void* stream = nullptr;
+};
+
+// Shared body of rap_decode_attn, rap_decode_attn_rope, rap_decode_attn_paged, rap_decode_attn_q8
+// and rap_decode_step.
+rap_status_t decode_impl(const DecodeRequest& r) {
+  const rap_shape_t* shape = r.shape;
+  rap_status_t st = check_shape(shape);
+  if (st != RAP_OK) return st;
+  int page_shift = 0;
+  if (r.paging && (st = check_paging(shape, r.paging, &page_shift)) != RAP_OK) return st;
+  if (r.max_seq_len < 1) return RAP_ERR_SHAPE;
+  if (r.max_seq_len > shape->cache_cap) return RAP_ERR_CAPACITY;
+  if (shape->batch == 0) return RAP_OK;
+  const bool step = r.k_new || r.v_new || r.new_pos;
+  if (!r.q || !r.k_cache || !r.v_cache || !r.seq_lens || !r.out) return RAP_ERR_NULL;
+  if (step && (!r.k_new || !r.v_new || !r.new_pos)) return RAP_ERR_NULL;
+  if ((r.q_pos || step) && no_rotation_rule(shape, r.keep_pair_idx)) return RAP_ERR_NULL;
+  if (misaligned(r.k_cache, 16) || misaligned(r.v_cache, 16) || misaligned(r.q, 4) || misaligned(r.out, 4))
+    return RAP_ERR_SHAPE;
+  Plan p;
+  st = make_plan(shape, r.max_seq_len, r.tuning, &p);
+  if (st != RAP_OK) return st;
+  // the one-call step on the matrix-core kernel hands the new token to the combining kernel, which
+  // therefore always runs
+  const bool fused_step = step && p.kernel == 2;
+  const bool combine = p.n_split > 1 || fused_step;
+  if (combine) {
+    if (!r.workspace || r.workspace_bytes < workspace_need(shape, p)) return RAP_ERR_WORKSPACE;
+    if (misaligned(r.workspace, 256)) return RAP_ERR_WORKSPACE;
+  }
+  if (p.n_split > 65535 || (static_cast<int64_t>(p.n_split) + 1) * shape->n_kv_heads * shape->batch > kInt32Max)
+    return RAP_ERR_UNSUPPORTED;
+  // combinations no kernel is built for
+  if (r.fp8 && (p.kernel != 2 || r.paging || step)) return RAP_ERR_UNSUPPORTED;   // matrix-core kernel, dense, no step
+  if (r.paging && (p.kernel != 2 || step)) return RAP_ERR_UNSUPPORTED;            // the vector-ALU kernel reads dense caches only
+  if (r.fp8) {
+    if (shape->cache_cap % 16 != 0) return RAP_ERR_SHAPE;
+    if (!r.k_scale || !r.v_scale) return RAP_ERR_NULL;
+  }
+
+  rap::DecodeArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = static_cast<const uint16_t*>(r.q);
+  a.q_pos = r.q_pos;
+  a.keep = r.keep_pair_idx;
+  a.pair_freq = shape->pair_inv_freq;
+  a.neg2_log2_theta_over_d = neg2_log2_theta_over_d(shape);
+  a.d_head = shape->d_head;
+  a.k_cache = static_cast<const uint16_t*>(r.k_cache);
+  a.v_cache = static_cast<const uint16_t*>(r.v_cache);
+  a.seq_lens = r.seq_lens;
+  a.out = static_cast<float*>(r.out);
+  a.part_acc = static_cast<float*>(r.workspace);
+  a.part_ml = r.workspace ? reinterpret_cast<float*>(static_cast<char*>(r.workspace) + part_acc_bytes(shape, p)) : nullptr;
+  a.batch = shape->batch;
+  a.n_q = shape->n_q_heads;
+  a.n_kv = shape->n_kv_heads;
+  a.group = shape->n_q_heads / shape->n_kv_heads;
+  a.n_pairs = shape->n_pairs;
+  a.d_k = 2 * shape->n_pairs;
+  a.d_v = shape->d_v;
+  a.max_len = static_cast<int32_t>(r.max_seq_len);
+  a.rows_per_split = p.rows_per_split;
+  a.n_split = p.n_split;
+  a.n_slots = fused_step ? p.n_split + 1 : p.n_split;
+  a.cap = shape->cache_cap;
+  a.scale_log2e = r.scale * kLog2e;
+  a.lds_wave_bytes = rap::mfma_lds_wave_bytes(a.d_k, a.d_v, r.fp8);
+  a.k_scale = r.fp8 ? r.k_scale : nullptr;
+  a.v_scale = r.fp8 ? r.v_scale : nullptr;
+  if (r.paging) {
+    a.block_table = r.paging->block_table;
+    a.page_shift = page_shift;
+    a.n_pages = r.paging->n_pages;
+    a.max_pages = r.paging->max_pages;
+  }
+  a.direct_out = combine ? 0 : 1;
+  if (fused_step) {
+    a.k_new = static_cast<const uint16_t*>(r.k_new);
+    a.v_new = static_cast<const uint16_t*>(r.v_new);
+    a.new_pos = r.new_pos;
+    a.k_cache_w = static_cast<uint16_t*>(const_cast<void*>(r.k_cache));
+    a.v_cache_w = static_cast<uint16_t*>(const_cast<void*>(r.v_cache));
+  }
+
+  hipStream_t s = static_cast<hipStream_t>(r.stream);
+  if (step && !fused_step) {
+    // vector-ALU kernel: the append is a launch of its own ahead of the attention
+    AppendRequest ar;
+    ar.shape = shape;
+    ar.n_new = 1;
+    ar.k_new = r.k_new;
+    ar.v_new = r.v_new;
+    ar.pos = r.new_pos;
+    ar.keep_pair_idx = r.keep_pair_idx;
+    ar.k_cache = const_cast<void*>(r.k_cache);
+    ar.v_cache = const_cast<void*>(r.v_cache);
+    ar.stream = r.stream;
+    if ((st = append_impl(ar)) != RAP_OK) return st;
+  }
+  const rap_tuning_t* t = r.tuning;
+  if (t && t->ev_main_start && hipEventRecord(static_cast<hipEvent_t>(t->ev_main_start), s) != hipSuccess)
+    return RAP_ERR_HIP;
+  const hipError_t e = p.kernel == 1 ? rap::launch_decode_valu(a, s) : rap::launch_decode_mfma(a, s);
+  if (e != hipSuccess) return RAP_ERR_HIP;
+  if (t && t->ev_main_stop && hipEventRecord(static_cast<hipEvent_t>(t->ev_main_stop), s) != hipSuccess)
+    return RAP_ERR_HIP;
+  if (combine && rap::launch_merge(a, s) != hipSuccess) return RAP_ERR_HIP;
+  return RAP_OK;
+}
+
+// rap_decode_attn_rope and its relatives take q_pos and keep_pair_idx as a pair: an argument the
+// call needs and does not get is RAP_ERR_NULL, but only once the shape itself has passed.
+rap_status_t null_after_shape(const rap_shape_t* shape) {
+  const rap_status_t st = check_shape(shape);
+  return st != RAP_OK ? st : RAP_ERR_NULL;
+}
+
+bool live_call(const rap_shape_t* shape, int64_t max_seq_len) { return shape && shape->batch > 0 && max_seq_len >= 1; }
+
+}  // namespace
+
+extern "C" {
 
 rap_status_t rap_rope_append(const rap_shape_t* shape, int32_t n_new, const void* k_new, const void* v_new,
                              const int32_t* pos, const int32_t* keep_pair_idx, void* k_cache, void* v_cache,
                              void* stream) {
-  return append_impl(shape, nullptr, n_new, k_new, v_new, pos, keep_pair_idx, k_cache, v_cache, stream);
+  AppendRequest r;
+  r.shape = shape;
+  r.n_new = n_new;
+  r.k_new = k_new;
+  r.v_new = v_new;
+  r.pos = pos;
+  r.keep_pair_idx = keep_pair_idx;
+  r.k_cache = k_cache;
+  r.v_cache = v_cache;
+  r.stream = stream;
+  return append_impl(r);
 }
 
 rap_status_t rap_rope_append_paged(const rap_shape_t* shape, const rap_paging_t* paging, int32_t n_new,
                                    const void* k_new, const void* v_new, const int32_t* pos,
                                    const int32_t* keep_pair_idx, void* k_pool, void* v_pool, void* stream) {
   if (!paging) return RAP_ERR_NULL;
-  return append_impl(shape, paging, n_new, k_new, v_new, pos, keep_pair_idx, k_pool, v_pool, stream);
+  AppendRequest r;
+  r.shape = shape;
+  r.paging = paging;
+  r.n_new = n_new;
+  r.k_new = k_new;
+  r.v_new = v_new;
+  r.pos = pos;
+  r.keep_pair_idx = keep_pair_idx;
+  r.k_cache = k_pool;
+  r.v_cache = v_pool;
+  r.stream = stream;
+  return append_impl(r);
+}
+
+rap_status_t rap_rope_append_q8(const rap_shape_t* shape, int32_t n_new, const void* k_new, const void* v_new,
+                                const int32_t* pos, const int32_t* keep_pair_idx, void* k_cache8, void* v_cache8,
+                                const float* k_scale, const float* v_scale, void* stream) {
+  AppendRequest r;
+  r.shape = shape;
+  r.n_new = n_new;
+  r.k_new = k_new;
+  r.v_new = v_new;
+  r.pos = pos;
+  r.keep_pair_idx = keep_pair_idx;
+  r.k_cache = k_cache8;
+  r.v_cache = v_cache8;
+  r.fp8 = true;
+  r.k_scale = k_scale;
+  r.v_scale = v_scale;
+  r.stream = stream;
+  return append_impl(r);
 }
 
 rap_status_t rap_rope_queries(const rap_shape_t* shape, int32_t n_new, const void* q, const int32_t* pos,
@@ -163,9 +386,10 @@ rap_status_t rap_rope_queries(const rap_shape_t* shape, int32_t n_new, const voi
   if (st != RAP_OK) return st;
   if (n_new < 0) return RAP_ERR_SHAPE;
   if (n_new == 0 || shape->batch == 0) return RAP_OK;
-  if (!q || !pos || (!keep_pair_idx && !shape->pair_inv_freq) || !q_out) return RAP_ERR_NULL;
-  if (static_cast<int64_t>(shape->batch) * n_new > 0x7fffffffLL) return RAP_ERR_UNSUPPORTED;
-  if ((reinterpret_cast<uintptr_t>(q) & 3) || (reinterpret_cast<uintptr_t>(q_out) & 3)) return RAP_ERR_SHAPE;
+  if (!q || !pos || no_rotation_rule(shape, keep_pair_idx) || !q_out) return RAP_ERR_NULL;
+  if (static_cast<int64_t>(shape->batch) * n_new > kInt32Max) return RAP_ERR_UNSUPPORTED;
+  if (misaligned(q, 4) || misaligned(q_out, 4)) return RAP_ERR_SHAPE;
+  // the append kernel walking query rows: no V, no cache layout, G query heads per row of kept pairs
   rap::AppendArgs a;
   memset(&a, 0, sizeof(a));
   a.k_new = static_cast<const uint16_t*>(q);
@@ -181,169 +405,137 @@ rap_status_t rap_rope_queries(const rap_shape_t* shape, int32_t n_new, const voi
   a.d_v = 0;
   a.group = shape->n_q_heads / shape->n_kv_heads;
   a.cap = shape->cache_cap;
-  a.neg2_log2_theta_over_d = -2.0 * log2(shape->rope_theta) / static_cast<double>(shape->d_head);
-  return rap::launch_rope_queries(a, static_cast<hipStream_t>(stream)) == hipSuccess ? RAP_OK : RAP_ERR_HIP;
+  a.neg2_log2_theta_over_d = neg2_log2_theta_over_d(shape);
+  return hip_status(rap::launch_rope_queries(a, static_cast<hipStream_t>(stream)));
 }
 
 size_t rap_decode_attn_workspace_bytes(const rap_shape_t* shape, int64_t max_seq_len, const rap_tuning_t* tuning) {
   if (check_shape(shape) != RAP_OK || max_seq_len < 1 || max_seq_len > shape->cache_cap) return 0;
   Plan p;
   if (make_plan(shape, max_seq_len, tuning, &p) != RAP_OK) return 0;
-  return part_acc_bytes(shape, p) + part_ml_bytes(shape, p) + 256;
+  return workspace_need(shape, p);
 }
-
-}  // extern "C"
-
-namespace {
-
-struct Fp8Scales {         // fp8 caches: per-KV-head scales of the codes (device); null otherwise
-  const float* k_scale;
-  const float* v_scale;
-};
-
-struct NewToken {          // the append fused into rap_decode_step; all null otherwise
-  const void* k_new = nullptr;
-  const void* v_new = nullptr;
-  const int32_t* pos = nullptr;
-};
-
-// Shared body of rap_decode_attn (q_pos == keep == null), rap_decode_attn_rope and rap_decode_step.
-rap_status_t decode_impl(const rap_shape_t* shape, const void* q, const int32_t* q_pos, const int32_t* keep,
-                         const void* k_cache, const void* v_cache, const int32_t* seq_lens, int64_t max_seq_len,
-                         void* out, float scale, void* workspace, size_t workspace_bytes, const rap_tuning_t* tuning,
-                         void* stream, const NewToken& nt = NewToken(), const rap_paging_t* paging = nullptr,
-                         const Fp8Scales* q8 = nullptr) {
-  rap_status_t st = check_shape(shape);
-  if (st != RAP_OK) return st;
-  int page_shift = 0;
-  if (paging && (st = check_paging(shape, paging, &page_shift)) != RAP_OK) return st;
-  if (max_seq_len < 1) return RAP_ERR_SHAPE;
-  if (max_seq_len > shape->cache_cap) return RAP_ERR_CAPACITY;
-  if (shape->batch == 0) return RAP_OK;
-  if (!q || !k_cache || !v_cache || !seq_lens || !out) return RAP_ERR_NULL;
-  if ((reinterpret_cast<uintptr_t>(k_cache) & 15) || (reinterpret_cast<uintptr_t>(v_cache) & 15) ||
-      (reinterpret_cast<uintptr_t>(q) & 3) || (reinterpret_cast<uintptr_t>(out) & 3))
-    return RAP_ERR_SHAPE;
-  Plan p;
-  st = make_plan(shape, max_seq_len, tuning, &p);
-  if (st != RAP_OK) return st;
-  const size_t need = part_acc_bytes(shape, p) + part_ml_bytes(shape, p) + 256;
-  // the one-call step on the matrix-core kernel hands the new token to the combining kernel, which
-  // therefore always runs
-  const bool fused_step = nt.k_new != nullptr && p.kernel == 2;
-  if (p.n_split > 1 || fused_step) {
-    if (!workspace || workspace_bytes < need) return RAP_ERR_WORKSPACE;
-    if (reinterpret_cast<uintptr_t>(workspace) & 255) return RAP_ERR_WORKSPACE;
-  }
-  if (p.n_split > 65535 ||
-      (static_cast<int64_t>(p.n_split) + 1) * shape->n_kv_heads * shape->batch > 0x7fffffffLL) return RAP_ERR_UNSUPPORTED;
-
-  rap::DecodeArgs a;
-  memset(&a, 0, sizeof(a));
-  a.q = static_cast<const uint16_t*>(q);
-  a.q_pos = q_pos;
-  a.keep = keep;
-  a.pair_freq = shape->pair_inv_freq;
-  a.neg2_log2_theta_over_d = -2.0 * log2(shape->rope_theta) / static_cast<double>(shape->d_head);
-  a.d_head = shape->d_head;
-  a.k_cache = static_cast<const uint16_t*>(k_cache);
-  a.v_cache = static_cast<const uint16_t*>(v_cache);
-  a.seq_lens = seq_lens;
-  a.out = static_cast<float*>(out);
-  a.part_acc = static_cast<float*>(workspace);
-  a.part_ml = workspace ? reinterpret_cast<float*>(static_cast<char*>(workspace) + part_acc_bytes(shape, p)) : nullptr;
-  a.batch = shape->batch;
-  a.n_q = shape->n_q_heads;
-  a.n_kv = shape->n_kv_heads;
-  a.group = shape->n_q_heads / shape->n_kv_heads;
-  a.n_pairs = shape->n_pairs;
-  a.d_k = 2 * shape->n_pairs;
-  a.d_v = shape->d_v;
-  a.max_len = static_cast<int32_t>(max_seq_len);
-  a.rows_per_split = p.rows_per_split;
-  a.n_split = p.n_split;
-  a.n_slots = p.n_split;
-  a.cap = shape->cache_cap;
-  a.scale_log2e = scale * 1.4426950408889634f;
-  a.lds_wave_bytes = rap::mfma_lds_wave_bytes(a.d_k, a.d_v, q8 != nullptr);
-  if (q8) {
-    if (p.kernel != 2 || paging || nt.k_new) return RAP_ERR_UNSUPPORTED;   // matrix-core kernel, dense cache, no fused step
-    if (shape->cache_cap % 16 != 0) return RAP_ERR_SHAPE;
-    if (!q8->k_scale || !q8->v_scale) return RAP_ERR_NULL;
-    a.k_scale = q8->k_scale;
-    a.v_scale = q8->v_scale;
-  }
-  if (paging) {
-    if (p.kernel != 2) return RAP_ERR_UNSUPPORTED;      // the vector-ALU kernel reads dense caches only
-    a.block_table = paging->block_table;
-    a.page_shift = page_shift;
-    a.n_pages = paging->n_pages;
-    a.max_pages = paging->max_pages;
-  }
-  a.direct_out = (p.n_split == 1 && !fused_step) ? 1 : 0;
-  if (fused_step) {
-    a.k_new = static_cast<const uint16_t*>(nt.k_new);
-    a.v_new = static_cast<const uint16_t*>(nt.v_new);
-    a.new_pos = nt.pos;
-    a.n_slots = p.n_split + 1;
-    a.k_cache_w = static_cast<uint16_t*>(const_cast<void*>(k_cache));
-    a.v_cache_w = static_cast<uint16_t*>(const_cast<void*>(v_cache));
-  }
-
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  if (nt.k_new && !fused_step) {
-    // vector-ALU kernel: the append is a launch of its own ahead of the attention
-    const rap_status_t ast = rap_rope_append(shape, 1, nt.k_new, nt.v_new, nt.pos, keep, const_cast<void*>(k_cache),
-                                             const_cast<void*>(v_cache), stream);
-    if (ast != RAP_OK) return ast;
-  }
-  if (tuning && tuning->ev_main_start && hipEventRecord(static_cast<hipEvent_t>(tuning->ev_main_start), s) != hipSuccess)
-    return RAP_ERR_HIP;
-  hipError_t e = p.kernel == 1 ? rap::launch_decode_valu(a, s) : rap::launch_decode_mfma(a, s);
-  if (e != hipSuccess) return RAP_ERR_HIP;
-  if (tuning && tuning->ev_main_stop && hipEventRecord(static_cast<hipEvent_t>(tuning->ev_main_stop), s) != hipSuccess)
-    return RAP_ERR_HIP;
-  if ((p.n_split > 1 || fused_step) && rap::launch_merge(a, s) != hipSuccess) return RAP_ERR_HIP;
-  return RAP_OK;
-}
-
-}  // namespace
-
-extern "C" {
 
 rap_status_t rap_decode_attn(const rap_shape_t* shape, const void* q, const void* k_cache, const void* v_cache,
                              const int32_t* seq_lens, int64_t max_seq_len, void* out, float scale, void* workspace,
                              size_t workspace_bytes, const rap_tuning_t* tuning, void* stream) {
-  return decode_impl(shape, q, nullptr, nullptr, k_cache, v_cache, seq_lens, max_seq_len, out, scale, workspace,
-                     workspace_bytes, tuning, stream);
-}
-
-rap_status_t rap_decode_step(const rap_shape_t* shape, const void* k_new, const void* v_new, const int32_t* pos,
-                             const int32_t* keep_pair_idx, const void* q, int32_t q_is_rotated, void* k_cache,
-                             void* v_cache, const int32_t* seq_lens, int64_t max_seq_len, void* out, float scale,
-                             void* workspace, size_t workspace_bytes, const rap_tuning_t* tuning, void* stream) {
-  if (shape && shape->batch > 0 && max_seq_len >= 1 && (!k_new || !v_new || !pos || (!keep_pair_idx && !shape->pair_inv_freq))) {
-    const rap_status_t st = check_shape(shape);
-    return st != RAP_OK ? st : RAP_ERR_NULL;
-  }
-  NewToken nt;
-  nt.k_new = k_new;
-  nt.v_new = v_new;
-  nt.pos = pos;
-  return decode_impl(shape, q, q_is_rotated ? nullptr : pos, keep_pair_idx, k_cache, v_cache, seq_lens, max_seq_len, out,
-                     scale, workspace, workspace_bytes, tuning, stream, nt);
+  DecodeRequest r;
+  r.shape = shape;
+  r.q = q;
+  r.k_cache = k_cache;
+  r.v_cache = v_cache;
+  r.seq_lens = seq_lens;
+  r.max_seq_len = max_seq_len;
+  r.out = out;
+  r.scale = scale;
+  r.workspace = workspace;
+  r.workspace_bytes = workspace_bytes;
+  r.tuning = tuning;
+  r.stream = stream;
+  return decode_impl(r);
 }
 
 rap_status_t rap_decode_attn_rope(const rap_shape_t* shape, const void* q, const int32_t* q_pos,
                                   const int32_t* keep_pair_idx, const void* k_cache, const void* v_cache,
                                   const int32_t* seq_lens, int64_t max_seq_len, void* out, float scale,
                                   void* workspace, size_t workspace_bytes, const rap_tuning_t* tuning, void* stream) {
-  if (shape && shape->batch > 0 && max_seq_len >= 1 && (!q_pos || (!keep_pair_idx && !shape->pair_inv_freq))) {
-    const rap_status_t st = check_shape(shape);
-    return st != RAP_OK ? st : RAP_ERR_NULL;
-  }
-  return decode_impl(shape, q, q_pos, keep_pair_idx, k_cache, v_cache, seq_lens, max_seq_len, out, scale, workspace,
-                     workspace_bytes, tuning, stream);
+  if (live_call(shape, max_seq_len) && (!q_pos || no_rotation_rule(shape, keep_pair_idx))) return null_after_shape(shape);
+  DecodeRequest r;
+  r.shape = shape;
+  r.q = q;
+  r.q_pos = q_pos;
+  r.keep_pair_idx = keep_pair_idx;
+  r.k_cache = k_cache;
+  r.v_cache = v_cache;
+  r.seq_lens = seq_lens;
+  r.max_seq_len = max_seq_len;
+  r.out = out;
+  r.scale = scale;
+  r.workspace = workspace;
+  r.workspace_bytes = workspace_bytes;
+  r.tuning = tuning;
+  r.stream = stream;
+  return decode_impl(r);
+}
+
+rap_status_t rap_decode_step(const rap_shape_t* shape, const void* k_new, const void* v_new, const int32_t* pos,
+                             const int32_t* keep_pair_idx, const void* q, int32_t q_is_rotated, void* k_cache,
+                             void* v_cache, const int32_t* seq_lens, int64_t max_seq_len, void* out, float scale,
+                             void* workspace, size_t workspace_bytes, const rap_tuning_t* tuning, void* stream) {
+  if (live_call(shape, max_seq_len) && (!k_new || !v_new || !pos || no_rotation_rule(shape, keep_pair_idx)))
+    return null_after_shape(shape);
+  DecodeRequest r;
+  r.shape = shape;
+  r.q = q;
+  r.q_pos = q_is_rotated ? nullptr : pos;
+  r.keep_pair_idx = keep_pair_idx;
+  r.k_cache = k_cache;
+  r.v_cache = v_cache;
+  r.k_new = k_new;
+  r.v_new = v_new;
+  r.new_pos = pos;
+  r.seq_lens = seq_lens;
+  r.max_seq_len = max_seq_len;
+  r.out = out;
+  r.scale = scale;
+  r.workspace = workspace;
+  r.workspace_bytes = workspace_bytes;
+  r.tuning = tuning;
+  r.stream = stream;
+  return decode_impl(r);
+}
+
+rap_status_t rap_decode_attn_q8(const rap_shape_t* shape, const void* q, const int32_t* q_pos,
+                                const int32_t* keep_pair_idx, const void* k_cache8, const void* v_cache8,
+                                const float* k_scale, const float* v_scale, const int32_t* seq_lens,
+                                int64_t max_seq_len, void* out, float scale, void* workspace, size_t workspace_bytes,
+                                const rap_tuning_t* tuning, void* stream) {
+  if (live_call(shape, max_seq_len) && q_pos && no_rotation_rule(shape, keep_pair_idx)) return null_after_shape(shape);
+  DecodeRequest r;
+  r.shape = shape;
+  r.q = q;
+  r.q_pos = q_pos;
+  r.keep_pair_idx = keep_pair_idx;
+  r.k_cache = k_cache8;
+  r.v_cache = v_cache8;
+  r.fp8 = true;
+  r.k_scale = k_scale;
+  r.v_scale = v_scale;
+  r.seq_lens = seq_lens;
+  r.max_seq_len = max_seq_len;
+  r.out = out;
+  r.scale = scale;
+  r.workspace = workspace;
+  r.workspace_bytes = workspace_bytes;
+  r.tuning = tuning;
+  r.stream = stream;
+  return decode_impl(r);
+}
+
+rap_status_t rap_decode_attn_paged(const rap_shape_t* shape, const rap_paging_t* paging, const void* q,
+                                   const int32_t* q_pos, const int32_t* keep_pair_idx, const void* k_pool,
+                                   const void* v_pool, const int32_t* seq_lens, int64_t max_seq_len, void* out,
+                                   float scale, void* workspace, size_t workspace_bytes, const rap_tuning_t* tuning,
+                                   void* stream) {
+  if (!paging) return RAP_ERR_NULL;
+  if (live_call(shape, max_seq_len) && q_pos && no_rotation_rule(shape, keep_pair_idx)) return null_after_shape(shape);
+  DecodeRequest r;
+  r.shape = shape;
+  r.paging = paging;
+  r.q = q;
+  r.q_pos = q_pos;
+  r.keep_pair_idx = keep_pair_idx;
+  r.k_cache = k_pool;
+  r.v_cache = v_pool;
+  r.seq_lens = seq_lens;
+  r.max_seq_len = max_seq_len;
+  r.out = out;
+  r.scale = scale;
+  r.workspace = workspace;
+  r.workspace_bytes = workspace_bytes;
+  r.tuning = tuning;
+  r.stream = stream;
+  return decode_impl(r);
 }
 
 rap_status_t rap_prefill_attn(const rap_shape_t* shape, int32_t n_new, const void* q, const void* k_cache,
@@ -355,10 +547,8 @@ rap_status_t rap_prefill_attn(const rap_shape_t* shape, int32_t n_new, const voi
   if (max_seq_len > shape->cache_cap) return RAP_ERR_CAPACITY;
   if (n_new == 0 || shape->batch == 0) return RAP_OK;
   if (!q || !k_cache || !v_cache || !seq_lens || !out) return RAP_ERR_NULL;
-  if ((reinterpret_cast<uintptr_t>(k_cache) & 15) || (reinterpret_cast<uintptr_t>(v_cache) & 15) ||
-      (reinterpret_cast<uintptr_t>(q) & 3) || (reinterpret_cast<uintptr_t>(out) & 3))
-    return RAP_ERR_SHAPE;
-  if (static_cast<int64_t>(shape->batch) * n_new > 0x7fffffffLL) return RAP_ERR_UNSUPPORTED;
+  if (misaligned(k_cache, 16) || misaligned(v_cache, 16) || misaligned(q, 4) || misaligned(out, 4)) return RAP_ERR_SHAPE;
+  if (static_cast<int64_t>(shape->batch) * n_new > kInt32Max) return RAP_ERR_UNSUPPORTED;
   rap::PrefillArgs a;
   memset(&a, 0, sizeof(a));
   a.q = static_cast<const uint16_t*>(q);
@@ -375,55 +565,20 @@ rap_status_t rap_prefill_attn(const rap_shape_t* shape, int32_t n_new, const voi
   a.d_v = shape->d_v;
   a.max_len = static_cast<int32_t>(max_seq_len);
   a.cap = shape->cache_cap;
-  a.scale_log2e = scale * 1.4426950408889634f;
-  return rap::launch_prefill(a, static_cast<hipStream_t>(stream)) == hipSuccess ? RAP_OK : RAP_ERR_HIP;
-}
-
-rap_status_t rap_rope_append_q8(const rap_shape_t* shape, int32_t n_new, const void* k_new, const void* v_new,
-                                const int32_t* pos, const int32_t* keep_pair_idx, void* k_cache8, void* v_cache8,
-                                const float* k_scale, const float* v_scale, void* stream) {
-  return append_impl(shape, nullptr, n_new, k_new, v_new, pos, keep_pair_idx, k_cache8, v_cache8, stream, k_scale, v_scale,
-                     true);
-}
-
-rap_status_t rap_decode_attn_q8(const rap_shape_t* shape, const void* q, const int32_t* q_pos,
-                                const int32_t* keep_pair_idx, const void* k_cache8, const void* v_cache8,
-                                const float* k_scale, const float* v_scale, const int32_t* seq_lens,
-                                int64_t max_seq_len, void* out, float scale, void* workspace, size_t workspace_bytes,
-                                const rap_tuning_t* tuning, void* stream) {
-  if (shape && shape->batch > 0 && max_seq_len >= 1 && q_pos && !keep_pair_idx && !shape->pair_inv_freq) {
-    const rap_status_t st = check_shape(shape);
-    return st != RAP_OK ? st : RAP_ERR_NULL;
-  }
-  Fp8Scales sc{k_scale, v_scale};
-  return decode_impl(shape, q, q_pos, keep_pair_idx, k_cache8, v_cache8, seq_lens, max_seq_len, out, scale, workspace,
-                     workspace_bytes, tuning, stream, NewToken(), nullptr, &sc);
-}
-
-rap_status_t rap_decode_attn_paged(const rap_shape_t* shape, const rap_paging_t* paging, const void* q,
-                                   const int32_t* q_pos, const int32_t* keep_pair_idx, const void* k_pool,
-                                   const void* v_pool, const int32_t* seq_lens, int64_t max_seq_len, void* out,
-                                   float scale, void* workspace, size_t workspace_bytes, const rap_tuning_t* tuning,
-                                   void* stream) {
-  if (!paging) return RAP_ERR_NULL;
-  if (shape && shape->batch > 0 && max_seq_len >= 1 && q_pos && !keep_pair_idx && !shape->pair_inv_freq) {
-    const rap_status_t st = check_shape(shape);
-    return st != RAP_OK ? st : RAP_ERR_NULL;
-  }
-  return decode_impl(shape, q, q_pos, keep_pair_idx, k_pool, v_pool, seq_lens, max_seq_len, out, scale, workspace,
-                     workspace_bytes, tuning, stream, NewToken(), paging);
+  a.scale_log2e = scale * kLog2e;
+  return hip_status(rap::launch_prefill(a, static_cast<hipStream_t>(stream)));
 }
 
 rap_status_t rap_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
   if (!src || !sink) return RAP_ERR_NULL;
-  if ((bytes & 15) || (reinterpret_cast<uintptr_t>(src) & 15) || (reinterpret_cast<uintptr_t>(sink) & 15)) return RAP_ERR_SHAPE;
-  return rap::launch_stream_read(src, bytes, sink, static_cast<hipStream_t>(stream)) == hipSuccess ? RAP_OK : RAP_ERR_HIP;
+  if ((bytes & 15) || misaligned(src, 16) || misaligned(sink, 16)) return RAP_ERR_SHAPE;
+  return hip_status(rap::launch_stream_read(src, bytes, sink, static_cast<hipStream_t>(stream)));
 }
 
 rap_status_t rap_stream_copy(void* dst, const void* src, size_t bytes, void* stream) {
   if (!src || !dst) return RAP_ERR_NULL;
-  if ((bytes & 15) || (reinterpret_cast<uintptr_t>(src) & 15) || (reinterpret_cast<uintptr_t>(dst) & 15)) return RAP_ERR_SHAPE;
-  return rap::launch_stream_copy(dst, src, bytes, static_cast<hipStream_t>(stream)) == hipSuccess ? RAP_OK : RAP_ERR_HIP;
+  if ((bytes & 15) || misaligned(src, 16) || misaligned(dst, 16)) return RAP_ERR_SHAPE;
+  return hip_status(rap::launch_stream_copy(dst, src, bytes, static_cast<hipStream_t>(stream)));
 }
 
 const char* rap_status_str(rap_status_t status) {
@@ -439,6 +594,6 @@ const char* rap_status_str(rap_status_t status) {
   return "unknown status";
 }
 
-int32_t rap_version(void) { return 100; }
+int32_t rap_version(void) { return 200; }
 
 }  // extern "C"
