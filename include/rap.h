@@ -292,6 +292,22 @@ rap_status_t rap_decode_attn_paged(const rap_shape_t* shape, const rap_paging_t*
                                    void* workspace, size_t workspace_bytes,
                                    const rap_tuning_t* tuning, void* stream);
 
+/* Both together: fp8 (E4M3) codes in paged pools, [n_pages, n_kv_heads, page_rows, d] bytes.
+ * Arguments as in rap_rope_append_q8 / rap_decode_attn_q8 and rap_*_paged; page_rows being a
+ * multiple of 32 keeps every page 16-byte aligned at one byte per element. */
+rap_status_t rap_rope_append_paged_q8(const rap_shape_t* shape, const rap_paging_t* paging, int32_t n_new,
+                                      const void* k_new, const void* v_new, const int32_t* pos,
+                                      const int32_t* keep_pair_idx, void* k_pool8, void* v_pool8,
+                                      const float* k_scale, const float* v_scale, void* stream);
+rap_status_t rap_decode_attn_paged_q8(const rap_shape_t* shape, const rap_paging_t* paging, const void* q,
+                                      const int32_t* q_pos, const int32_t* keep_pair_idx,
+                                      const void* k_pool8, const void* v_pool8,
+                                      const float* k_scale, const float* v_scale,
+                                      const int32_t* seq_lens, int64_t max_seq_len,
+                                      void* out, float scale,
+                                      void* workspace, size_t workspace_bytes,
+                                      const rap_tuning_t* tuning, void* stream);
+
 /* Measurement aids (not part of the method): a read-only streaming pass over `bytes` bytes of
  * `src` (16-byte aligned, bytes % 16 == 0) that folds everything into 16 bytes at `sink`, and a
  * plain copy of `bytes` bytes.  They give the bandwidth a trivial kernel reaches on the same

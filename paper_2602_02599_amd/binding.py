@@ -115,6 +115,11 @@ class Rap:
         L.rap_decode_attn_q8.argtypes = [C.POINTER(RapShape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_float,
                                          C.c_void_p, C.c_size_t, C.POINTER(RapTuning), C.c_void_p]
+        L.rap_rope_append_paged_q8.restype = C.c_int
+        L.rap_rope_append_paged_q8.argtypes = [C.POINTER(RapShape), C.POINTER(RapPaging), C.c_int32] + [C.c_void_p] * 9
+        L.rap_decode_attn_paged_q8.restype = C.c_int
+        L.rap_decode_attn_paged_q8.argtypes = [C.POINTER(RapShape), C.POINTER(RapPaging)] + [C.c_void_p] * 8 + [
+            C.c_int64, C.c_void_p, C.c_float, C.c_void_p, C.c_size_t, C.POINTER(RapTuning), C.c_void_p]
         L.rap_stream_read.restype = C.c_int
         L.rap_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.rap_stream_copy.restype = C.c_int
@@ -280,6 +285,33 @@ class Rap:
                                          scale, _ptr(workspace, None, "workspace"),
                                          0 if workspace is None else workspace.numel() * workspace.element_size(),
                                          C.byref(tuning) if tuning is not None else None, _stream(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def rap_rope_append_paged_q8(self, shape: RapShape, paging: RapPaging, n_new: int, k_new, v_new, pos, keep_pair_idx,
+                                 k_pool8, v_pool8, k_scale, v_scale, stream=None, check=True) -> int:
+        st = self.lib.rap_rope_append_paged_q8(C.byref(shape), C.byref(paging), n_new, _ptr(k_new, torch.bfloat16, "k_new"),
+                                               _ptr(v_new, torch.bfloat16, "v_new"), _ptr(pos, torch.int32, "pos"),
+                                               _ptr(keep_pair_idx, torch.int32, "keep_pair_idx"),
+                                               _ptr(k_pool8, torch.uint8, "k_pool8"), _ptr(v_pool8, torch.uint8, "v_pool8"),
+                                               _ptr(k_scale, torch.float32, "k_scale"), _ptr(v_scale, torch.float32, "v_scale"),
+                                               _stream(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def rap_decode_attn_paged_q8(self, shape: RapShape, paging: RapPaging, q, q_pos, keep_pair_idx, k_pool8, v_pool8,
+                                 k_scale, v_scale, seq_lens, max_seq_len: int, out, scale: float, workspace=None,
+                                 tuning: Optional[RapTuning] = None, stream=None, check=True) -> int:
+        st = self.lib.rap_decode_attn_paged_q8(C.byref(shape), C.byref(paging), _ptr(q, torch.bfloat16, "q"),
+                                               _ptr(q_pos, torch.int32, "q_pos"), _ptr(keep_pair_idx, torch.int32, "keep_pair_idx"),
+                                               _ptr(k_pool8, torch.uint8, "k_pool8"), _ptr(v_pool8, torch.uint8, "v_pool8"),
+                                               _ptr(k_scale, torch.float32, "k_scale"), _ptr(v_scale, torch.float32, "v_scale"),
+                                               _ptr(seq_lens, torch.int32, "seq_lens"), max_seq_len,
+                                               _ptr(out, torch.float32, "out"), scale, _ptr(workspace, None, "workspace"),
+                                               0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                               C.byref(tuning) if tuning is not None else None, _stream(stream))
         if check:
             self._check(st)
         return st

@@ -131,7 +131,7 @@ struct AppendRequest {
   void* stream = nullptr;
 };
 
-// Shared body of rap_rope_append, rap_rope_append_paged and rap_rope_append_q8.
+// Shared body of rap_rope_append and its paged and fp8 variants.
 rap_status_t append_impl(const AppendRequest& r) {
   const rap_shape_t* shape = r.shape;
   rap_status_t st = check_shape(shape);
@@ -154,7 +154,6 @@ rap_status_t append_impl(const AppendRequest& r) {
     a.max_pages = r.paging->max_pages;
   }
   if (r.fp8) {
-    if (r.paging) return RAP_ERR_UNSUPPORTED;
     if (!r.k_scale || !r.v_scale) return RAP_ERR_NULL;
     if (shape->cache_cap % 16 != 0) return RAP_ERR_SHAPE;
     a.k_scale = r.k_scale;
@@ -205,8 +204,8 @@ struct DecodeRequest {
   void* stream = nullptr;
 };
 
-// Shared body of rap_decode_attn, rap_decode_attn_rope, rap_decode_attn_paged, rap_decode_attn_q8
-// and rap_decode_step.
+// Shared body of rap_decode_attn, rap_decode_attn_rope, the paged and fp8 variants and
+// rap_decode_step.
 rap_status_t decode_impl(const DecodeRequest& r) {
   const rap_shape_t* shape = r.shape;
   rap_status_t st = check_shape(shape);
@@ -236,7 +235,7 @@ rap_status_t decode_impl(const DecodeRequest& r) {
   if (p.n_split > 65535 || (static_cast<int64_t>(p.n_split) + 1) * shape->n_kv_heads * shape->batch > kInt32Max)
     return RAP_ERR_UNSUPPORTED;
   // combinations no kernel is built for
-  if (r.fp8 && (p.kernel != 2 || r.paging || step)) return RAP_ERR_UNSUPPORTED;   // matrix-core kernel, dense, no step
+  if (r.fp8 && (p.kernel != 2 || step)) return RAP_ERR_UNSUPPORTED;               // matrix-core kernel, no fused step
   if (r.paging && (p.kernel != 2 || step)) return RAP_ERR_UNSUPPORTED;            // the vector-ALU kernel reads dense caches only
   if (r.fp8) {
     if (shape->cache_cap % 16 != 0) return RAP_ERR_SHAPE;
@@ -538,6 +537,57 @@ rap_status_t rap_decode_attn_paged(const rap_shape_t* shape, const rap_paging_t*
   return decode_impl(r);
 }
 
+rap_status_t rap_rope_append_paged_q8(const rap_shape_t* shape, const rap_paging_t* paging, int32_t n_new,
+                                      const void* k_new, const void* v_new, const int32_t* pos,
+                                      const int32_t* keep_pair_idx, void* k_pool8, void* v_pool8, const float* k_scale,
+                                      const float* v_scale, void* stream) {
+  if (!paging) return RAP_ERR_NULL;
+  AppendRequest r;
+  r.shape = shape;
+  r.paging = paging;
+  r.n_new = n_new;
+  r.k_new = k_new;
+  r.v_new = v_new;
+  r.pos = pos;
+  r.keep_pair_idx = keep_pair_idx;
+  r.k_cache = k_pool8;
+  r.v_cache = v_pool8;
+  r.fp8 = true;
+  r.k_scale = k_scale;
+  r.v_scale = v_scale;
+  r.stream = stream;
+  return append_impl(r);
+}
+
+rap_status_t rap_decode_attn_paged_q8(const rap_shape_t* shape, const rap_paging_t* paging, const void* q,
+                                      const int32_t* q_pos, const int32_t* keep_pair_idx, const void* k_pool8,
+                                      const void* v_pool8, const float* k_scale, const float* v_scale,
+                                      const int32_t* seq_lens, int64_t max_seq_len, void* out, float scale,
+                                      void* workspace, size_t workspace_bytes, const rap_tuning_t* tuning, void* stream) {
+  if (!paging) return RAP_ERR_NULL;
+  if (live_call(shape, max_seq_len) && q_pos && no_rotation_rule(shape, keep_pair_idx)) return null_after_shape(shape);
+  DecodeRequest r;
+  r.shape = shape;
+  r.paging = paging;
+  r.q = q;
+  r.q_pos = q_pos;
+  r.keep_pair_idx = keep_pair_idx;
+  r.k_cache = k_pool8;
+  r.v_cache = v_pool8;
+  r.fp8 = true;
+  r.k_scale = k_scale;
+  r.v_scale = v_scale;
+  r.seq_lens = seq_lens;
+  r.max_seq_len = max_seq_len;
+  r.out = out;
+  r.scale = scale;
+  r.workspace = workspace;
+  r.workspace_bytes = workspace_bytes;
+  r.tuning = tuning;
+  r.stream = stream;
+  return decode_impl(r);
+}
+
 rap_status_t rap_prefill_attn(const rap_shape_t* shape, int32_t n_new, const void* q, const void* k_cache,
                               const void* v_cache, const int32_t* seq_lens, int64_t max_seq_len, void* out, float scale,
                               void* stream) {
@@ -594,6 +644,6 @@ const char* rap_status_str(rap_status_t status) {
   return "unknown status";
 }
 
-int32_t rap_version(void) { return 200; }
+int32_t rap_version(void) { return 300; }
 
 }  // extern "C"

@@ -77,7 +77,7 @@ __global__ __launch_bounds__(256) void append_q8_kernel(AppendArgs a) {
   const uint16_t v0 = has_v0 ? vsrc[lane] : 0, v1 = has_v1 ? vsrc[lane + kWave] : 0;
   const double ks = static_cast<double>(a.k_scale[h]), vs = static_cast<double>(a.v_scale[h]);
   if (t < 0 || t >= a.cap) return;                                        // documented: skipped
-  const long long row = (static_cast<long long>(b) * a.n_kv + h) * a.cap + t;
+  const long long row = cache_row(a, b, h, t);                            // dense or paged
   uint8_t* k8 = reinterpret_cast<uint8_t*>(a.k_cache) + row * (2 * P);
   uint8_t* v8 = reinterpret_cast<uint8_t*>(a.v_cache) + row * a.d_v;
   if (rot) {

@@ -568,7 +568,8 @@ hipError_t launch_inst2(const DecodeArgs& a, hipStream_t stream) {
 
 template <int KCH, int NT, bool VPAIR>
 hipError_t launch_inst(const DecodeArgs& a, hipStream_t stream) {
-  if (a.k_scale != nullptr) return launch_inst2<KCH, NT, VPAIR, false, true>(a, stream);   // fp8 caches are dense
+  if (a.k_scale != nullptr && a.block_table != nullptr) return launch_inst2<KCH, NT, VPAIR, true, true>(a, stream);
+  if (a.k_scale != nullptr) return launch_inst2<KCH, NT, VPAIR, false, true>(a, stream);
   if (a.block_table != nullptr) return launch_inst2<KCH, NT, VPAIR, true, false>(a, stream);
   return launch_inst2<KCH, NT, VPAIR, false, false>(a, stream);
 }

@@ -714,6 +714,83 @@ def test_q8_cache(rap, P, dv, Hq, Hkv, ctx, n_new):
                                   rap.tuning(kernel=VALU), check=False) == 3
 
 
+@pytest.mark.parametrize("P,dv,Hq,Hkv,ctx,page_rows,n_new", [(45, 90, 8, 2, 2100, 128, 1), (58, 115, 8, 2, 900, 32, 4),
+                                                             (32, 64, 10, 2, 1500, 64, 30), (64, 128, 4, 1, 600, 256, 1)])
+def test_q8_paged_caches(rap, P, dv, Hq, Hkv, ctx, page_rows, n_new):
+    """fp8 codes in paged pools: rap_rope_append_paged_q8 + rap_decode_attn_paged_q8.  The oracle
+    side is the dense fp8 oracle plus pure re-indexing; unused pages hold NaN codes and the table
+    entries beyond each sequence hold wild page numbers."""
+    w = I.scaled(I.WORKLOADS["cfg2"], batch=3, n_q_heads=Hq, n_kv_heads=Hkv, n_pairs=P, d_v=dv, ctx=ctx, n_new=n_new,
+                 ragged_min=max(n_new + 1, ctx // 3), peaky_frac=0.0, seed=800 + P + page_rows)
+    _say("q8 paged P=%d dv=%d ctx=%d page_rows=%d n_new=%d" % (P, dv, ctx, page_rows, n_new))
+    case = I.make_case(w, device=DEV)
+    lens = case.seq_lens.cpu().numpy()
+    prefill = case.prefill_lens
+    max_pages = (int(lens.max()) + page_rows - 1) // page_rows
+    cap = max_pages * page_rows
+    n_pages = w.batch * max_pages + 3
+    rng = np.random.Generator(np.random.PCG64(19))
+    table = rng.permutation(n_pages)[:w.batch * max_pages].reshape(w.batch, max_pages).astype(np.int32)
+    ks = (rng.uniform(4.0, 6.0, Hkv) / 448.0).astype(np.float32)
+    vs = (rng.uniform(4.0, 6.0, Hkv) / 448.0).astype(np.float32)
+    kd = O.bf16_bits_to_f64(I.bits(case.k_cache))
+    vd = O.bf16_bits_to_f64(I.bits(case.v_cache))
+    k8 = np.full((w.batch, Hkv, cap, 2 * P), 0x7F, dtype=np.uint8)
+    v8 = np.full((w.batch, Hkv, cap, dv), 0xFF, dtype=np.uint8)
+    for b in range(w.batch):
+        n0 = int(prefill[b])
+        k8[b, :, :n0] = O.f64_to_e4m3_bits(kd[b, :, :n0] / ks.astype(np.float64)[:, None, None])
+        v8[b, :, :n0] = O.f64_to_e4m3_bits(vd[b, :, :n0] / vs.astype(np.float64)[:, None, None])
+    kp = O.dense_to_paged_ref(k8, table, page_rows, n_pages, prefill, fill=0x7F)
+    vp = O.dense_to_paged_ref(v8, table, page_rows, n_pages, prefill, fill=0xFF)
+    table_dev = table.copy()
+    for b in range(w.batch):
+        used = (int(lens[b]) + page_rows - 1) // page_rows
+        table_dev[b, used:] = -(2 ** 30)
+    k_pool, v_pool = torch.from_numpy(kp).to(DEV), torch.from_numpy(vp).to(DEV)
+    bt = torch.from_numpy(table_dev).to(DEV)
+    ksd, vsd = torch.from_numpy(ks).to(DEV), torch.from_numpy(vs).to(DEV)
+    shp = rap.shape(w.batch, Hq, Hkv, w.d_head, P, dv, cap, w.rope_theta)
+    pg = rap.paging(page_rows, n_pages, bt)
+    rap.rap_rope_append_paged_q8(shp, pg, n_new, case.k_new, case.v_new, case.pos, case.keep, k_pool, v_pool, ksd, vsd)
+    torch.cuda.synchronize()
+    ok8, ov8 = k8.copy(), v8.copy()
+    O.append_q8_ref(I.bits(case.k_new), I.bits(case.v_new), case.pos.cpu().numpy(), case.keep.cpu().numpy(), ok8, ov8, ks, vs,
+                    w.rope_theta, w.d_head)
+    gk = O.paged_to_dense_ref(k_pool.cpu().numpy(), table, lens)
+    gv = O.paged_to_dense_ref(v_pool.cpu().numpy(), table, lens)
+    n_diff = 0
+    for b in range(w.batch):
+        n = int(lens[b])
+        assert np.array_equal(gv[b, :, :n], ov8[b, :, :n]), "paged V codes"
+        n_diff += int((gk[b, :, :n] != ok8[b, :, :n]).sum())
+    assert n_diff <= gk.size // 10000 + 1, "%d K codes differ" % n_diff
+    ref = O.attn_q8_ref(I.bits(case.q), gk, gv, ks, vs, lens, w.scale)
+    for rps in (0, 128, 512):
+        tun = rap.tuning(kernel=MFMA, rows_per_split=rps)
+        ws = rap.new_workspace(shp, cap, tun)
+        out = torch.full((w.batch, Hq, dv), float("nan"), dtype=torch.float32, device=DEV)
+        rap.rap_decode_attn_paged_q8(shp, pg, case.q, None, None, k_pool, v_pool, ksd, vsd, case.seq_lens, cap, out,
+                                     float(w.scale), ws, tun)
+        torch.cuda.synchronize()
+        H.assert_attn_close(out.cpu().numpy(), ref, "q8 paged decode rps=%d" % rps)
+    qpos_np = (lens - 1).astype(np.int32)
+    qrot = O.rope_queries_ref(I.bits(case.q), qpos_np, case.keep.cpu().numpy(), w.rope_theta, w.d_head, Hkv)
+    ref2 = O.attn_q8_ref(qrot, gk, gv, ks, vs, lens, w.scale)
+    ws = rap.new_workspace(shp, cap, None)
+    rap.rap_decode_attn_paged_q8(shp, pg, case.q, torch.from_numpy(qpos_np).to(DEV), case.keep, k_pool, v_pool, ksd, vsd,
+                                 case.seq_lens, cap, out, float(w.scale), ws, None)
+    torch.cuda.synchronize()
+    H.assert_attn_close(out.cpu().numpy(), ref2, "q8 paged decode with query rotation")
+    # identical to the dense fp8 call on the gathered cache
+    gk_d, gv_d = torch.from_numpy(gk).to(DEV), torch.from_numpy(gv).to(DEV)
+    out_d = torch.full_like(out, float("nan"))
+    rap.rap_decode_attn_q8(shp, case.q, torch.from_numpy(qpos_np).to(DEV), case.keep, gk_d, gv_d, ksd, vsd, case.seq_lens, cap,
+                           out_d, float(w.scale), ws, None)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out_d), "paged and dense fp8 attention differ"
+
+
 def test_split_invariance(rap):
     """1 range vs many: same result up to fp32 rounding (merge identity on the GPU side)."""
     w = I.scaled(I.WORKLOADS["cfg2"], batch=2, ctx=4000, seed=13)
