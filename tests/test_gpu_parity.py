@@ -791,6 +791,71 @@ def test_q8_paged_caches(rap, P, dv, Hq, Hkv, ctx, page_rows, n_new):
     assert torch.equal(out, out_d), "paged and dense fp8 attention differ"
 
 
+@pytest.mark.parametrize("one_call", [False, True])
+def test_graph_replay(rap, one_call):
+    """A decode loop recorded once into a HIP graph (append + attention, or the one-call step) and
+    replayed for four tokens with new inputs in the same buffers: every replay must leave the
+    caches and give the outputs of the same calls made directly, and the last one is checked
+    against the oracle.  The library launches kernels only (no allocation, no memset, no
+    synchronisation), which is what makes it recordable; eager work and synchronisations lie
+    between the replays."""
+    n_steps = 4
+    w = I.scaled(I.WORKLOADS["cfg2"], batch=3, n_q_heads=8, n_kv_heads=2, n_pairs=45, d_v=90, ctx=1500, n_new=n_steps,
+                 ragged_min=600, peaky_frac=0.0, seed=4242)
+    _say("graph replay one_call=%s" % one_call)
+    case = I.make_case(w, device=DEV)
+    shp = H.shape_of(rap, case)
+    cap = int(case.cap)
+    prefill = torch.from_numpy(np.asarray(case.prefill_lens, dtype=np.int32)).to(DEV)
+    qs = [torch.randn((w.batch, w.n_q_heads, w.d_k), generator=torch.Generator().manual_seed(50 + i)).to(torch.bfloat16).to(DEV)
+          for i in range(n_steps)]
+    ws = rap.new_workspace(shp, cap, None)
+
+    def step(k1, v1, p1, q, kc, vc, sl, out):
+        if one_call:
+            rap.rap_decode_step(shp, k1, v1, p1, case.keep, q, True, kc, vc, sl, cap, out, float(w.scale), ws, None)
+        else:
+            rap.rap_rope_append(shp, 1, k1, v1, p1, case.keep, kc, vc)
+            rap.rap_decode_attn(shp, q, kc, vc, sl, cap, out, float(w.scale), ws, None)
+
+    def inputs(i):
+        return (case.k_new[:, i:i + 1].contiguous(), case.v_new[:, i:i + 1].contiguous(), case.pos[:, i].contiguous(),
+                qs[i], (prefill + i + 1).to(torch.int32))
+
+    # the calls made directly
+    kc_e, vc_e = case.k_cache.clone(), case.v_cache.clone()
+    outs_e, caches_e = [], []
+    for i in range(n_steps):
+        k1, v1, p1, q, sl = inputs(i)
+        out = torch.full((w.batch, w.n_q_heads, w.d_v), float("nan"), dtype=torch.float32, device=DEV)
+        step(k1, v1, p1, q, kc_e, vc_e, sl, out)
+        torch.cuda.synchronize()
+        outs_e.append(out)
+        caches_e.append((kc_e.clone(), vc_e.clone()))
+
+    # the same calls recorded once over fixed buffers
+    kc_g, vc_g = case.k_cache.clone(), case.v_cache.clone()
+    k1_s, v1_s, p1_s, q_s, sl_s = [t.clone() for t in inputs(0)]
+    out_s = torch.full((w.batch, w.n_q_heads, w.d_v), float("nan"), dtype=torch.float32, device=DEV)
+    step(k1_s, v1_s, p1_s, q_s, kc_g, vc_g, sl_s, out_s)            # warm-up outside the recording (same token: idempotent)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step(k1_s, v1_s, p1_s, q_s, kc_g, vc_g, sl_s, out_s)
+    for i in range(n_steps):
+        for dst, src in zip((k1_s, v1_s, p1_s, q_s, sl_s), inputs(i)):
+            dst.copy_(src)
+        out_s.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_s, outs_e[i]), "replay %d: output differs from the direct calls" % i
+        assert torch.equal(kc_g, caches_e[i][0]) and torch.equal(vc_g, caches_e[i][1]), "replay %d: caches differ" % i
+    lens = (np.asarray(case.prefill_lens) + n_steps).astype(np.int64)
+    ref = O.attn_ref(I.bits(qs[-1]), I.bits(kc_g), I.bits(vc_g), lens, w.scale)
+    H.assert_attn_close(out_s.cpu().numpy(), ref, "last replay against the oracle")
+
+
 def test_split_invariance(rap):
     """1 range vs many: same result up to fp32 rounding (merge identity on the GPU side)."""
     w = I.scaled(I.WORKLOADS["cfg2"], batch=2, ctx=4000, seed=13)
