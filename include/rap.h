@@ -308,6 +308,26 @@ rap_status_t rap_decode_attn_paged_q8(const rap_shape_t* shape, const rap_paging
                                       void* workspace, size_t workspace_bytes,
                                       const rap_tuning_t* tuning, void* stream);
 
+/* The one-call decode step over any kind of cache.  k, v: the dense caches or, with paging, the
+ * pools (dev, updated in place); k_scale, v_scale (dev fp32 [n_kv_heads]): both non-NULL when the
+ * caches hold one-byte E4M3 codes, both NULL for bf16; paging: NULL for dense caches.  Everything
+ * else as in rap_decode_step; matrix-core kernel only for paged or fp8 caches. */
+typedef struct rap_kv_cache {
+  void* k;
+  void* v;
+  const float* k_scale;
+  const float* v_scale;
+  const rap_paging_t* paging;
+} rap_kv_cache_t;
+
+rap_status_t rap_decode_step_ex(const rap_shape_t* shape, const rap_kv_cache_t* cache,
+                                const void* k_new, const void* v_new, const int32_t* pos,
+                                const int32_t* keep_pair_idx, const void* q, int32_t q_is_rotated,
+                                const int32_t* seq_lens, int64_t max_seq_len,
+                                void* out, float scale,
+                                void* workspace, size_t workspace_bytes,
+                                const rap_tuning_t* tuning, void* stream);
+
 /* Measurement aids (not part of the method): a read-only streaming pass over `bytes` bytes of
  * `src` (16-byte aligned, bytes % 16 == 0) that folds everything into 16 bytes at `sink`, and a
  * plain copy of `bytes` bytes.  They give the bandwidth a trivial kernel reaches on the same

@@ -37,6 +37,12 @@ class RapPaging(C.Structure):
     ]
 
 
+class RapKvCache(C.Structure):
+    """Mirror of rap_kv_cache_t."""
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("k_scale", C.c_void_p), ("v_scale", C.c_void_p),
+                ("paging", C.POINTER(RapPaging))]
+
+
 class RapTuning(C.Structure):
     """Mirror of rap_tuning_t."""
     _fields_ = [
@@ -120,6 +126,9 @@ class Rap:
         L.rap_decode_attn_paged_q8.restype = C.c_int
         L.rap_decode_attn_paged_q8.argtypes = [C.POINTER(RapShape), C.POINTER(RapPaging)] + [C.c_void_p] * 8 + [
             C.c_int64, C.c_void_p, C.c_float, C.c_void_p, C.c_size_t, C.POINTER(RapTuning), C.c_void_p]
+        L.rap_decode_step_ex.restype = C.c_int
+        L.rap_decode_step_ex.argtypes = [C.POINTER(RapShape), C.POINTER(RapKvCache)] + [C.c_void_p] * 5 + [
+            C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_float, C.c_void_p, C.c_size_t, C.POINTER(RapTuning), C.c_void_p]
         L.rap_stream_read.restype = C.c_int
         L.rap_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.rap_stream_copy.restype = C.c_int
@@ -312,6 +321,24 @@ class Rap:
                                                _ptr(out, torch.float32, "out"), scale, _ptr(workspace, None, "workspace"),
                                                0 if workspace is None else workspace.numel() * workspace.element_size(),
                                                C.byref(tuning) if tuning is not None else None, _stream(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def rap_decode_step_ex(self, shape: RapShape, k, v, k_scale, v_scale, paging: Optional[RapPaging], k_new, v_new, pos,
+                           keep_pair_idx, q, q_is_rotated: bool, seq_lens, max_seq_len: int, out, scale: float,
+                           workspace=None, tuning: Optional[RapTuning] = None, stream=None, check=True) -> int:
+        """k, v: bf16 caches or pools, or uint8 ones with k_scale / v_scale; paging None for dense caches."""
+        el = torch.uint8 if k_scale is not None else torch.bfloat16
+        cache = RapKvCache(_ptr(k, el, "k"), _ptr(v, el, "v"), _ptr(k_scale, torch.float32, "k_scale"),
+                           _ptr(v_scale, torch.float32, "v_scale"), C.pointer(paging) if paging is not None else None)
+        st = self.lib.rap_decode_step_ex(C.byref(shape), C.byref(cache), _ptr(k_new, torch.bfloat16, "k_new"),
+                                         _ptr(v_new, torch.bfloat16, "v_new"), _ptr(pos, torch.int32, "pos"),
+                                         _ptr(keep_pair_idx, torch.int32, "keep_pair_idx"), _ptr(q, torch.bfloat16, "q"),
+                                         1 if q_is_rotated else 0, _ptr(seq_lens, torch.int32, "seq_lens"), max_seq_len,
+                                         _ptr(out, torch.float32, "out"), scale, _ptr(workspace, None, "workspace"),
+                                         0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                         C.byref(tuning) if tuning is not None else None, _stream(stream))
         if check:
             self._check(st)
         return st

@@ -235,8 +235,7 @@ rap_status_t decode_impl(const DecodeRequest& r) {
   if (p.n_split > 65535 || (static_cast<int64_t>(p.n_split) + 1) * shape->n_kv_heads * shape->batch > kInt32Max)
     return RAP_ERR_UNSUPPORTED;
   // combinations no kernel is built for
-  if (r.fp8 && (p.kernel != 2 || step)) return RAP_ERR_UNSUPPORTED;               // matrix-core kernel, no fused step
-  if (r.paging && (p.kernel != 2 || step)) return RAP_ERR_UNSUPPORTED;            // the vector-ALU kernel reads dense caches only
+  if ((r.fp8 || r.paging) && p.kernel != 2) return RAP_ERR_UNSUPPORTED;   // the vector-ALU kernel reads dense bf16 caches only
   if (r.fp8) {
     if (shape->cache_cap % 16 != 0) return RAP_ERR_SHAPE;
     if (!r.k_scale || !r.v_scale) return RAP_ERR_NULL;
@@ -484,6 +483,39 @@ rap_status_t rap_decode_step(const rap_shape_t* shape, const void* k_new, const 
   return decode_impl(r);
 }
 
+rap_status_t rap_decode_step_ex(const rap_shape_t* shape, const rap_kv_cache_t* cache, const void* k_new,
+                                const void* v_new, const int32_t* pos, const int32_t* keep_pair_idx, const void* q,
+                                int32_t q_is_rotated, const int32_t* seq_lens, int64_t max_seq_len, void* out, float scale,
+                                void* workspace, size_t workspace_bytes, const rap_tuning_t* tuning, void* stream) {
+  if (!cache) return RAP_ERR_NULL;
+  if ((cache->k_scale == nullptr) != (cache->v_scale == nullptr)) return null_after_shape(shape);
+  if (live_call(shape, max_seq_len) && (!k_new || !v_new || !pos || no_rotation_rule(shape, keep_pair_idx)))
+    return null_after_shape(shape);
+  DecodeRequest r;
+  r.shape = shape;
+  r.paging = cache->paging;
+  r.q = q;
+  r.q_pos = q_is_rotated ? nullptr : pos;
+  r.keep_pair_idx = keep_pair_idx;
+  r.k_cache = cache->k;
+  r.v_cache = cache->v;
+  r.fp8 = cache->k_scale != nullptr;
+  r.k_scale = cache->k_scale;
+  r.v_scale = cache->v_scale;
+  r.k_new = k_new;
+  r.v_new = v_new;
+  r.new_pos = pos;
+  r.seq_lens = seq_lens;
+  r.max_seq_len = max_seq_len;
+  r.out = out;
+  r.scale = scale;
+  r.workspace = workspace;
+  r.workspace_bytes = workspace_bytes;
+  r.tuning = tuning;
+  r.stream = stream;
+  return decode_impl(r);
+}
+
 rap_status_t rap_decode_attn_q8(const rap_shape_t* shape, const void* q, const int32_t* q_pos,
                                 const int32_t* keep_pair_idx, const void* k_cache8, const void* v_cache8,
                                 const float* k_scale, const float* v_scale, const int32_t* seq_lens,
@@ -644,6 +676,6 @@ const char* rap_status_str(rap_status_t status) {
   return "unknown status";
 }
 
-int32_t rap_version(void) { return 300; }
+int32_t rap_version(void) { return 400; }
 
 }  // extern "C"

@@ -103,33 +103,67 @@ __device__ __forceinline__ void token_load(const DecodeArgs& a, int b, int h, in
   }
 }
 
+// value of one E4M3 code
+__device__ __forceinline__ float e4m3_to_f32(uint8_t code) {
+  return __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(code), false)[0];
+}
+
 __device__ __forceinline__ void token_finish(const DecodeArgs& a, int b, int h, int lane, int t, bool attended,
                                              const uint16_t* s_q, const TokenRegs& r) {
   const int P = a.n_pairs;
   const bool stored = t >= 0 && t < a.cap;
-  const long long nrow = static_cast<long long>(b) * a.n_kv + h;
-  const long long row = nrow * a.cap + t;
-  uint16_t kxr = 0, kyr = 0;
+  const bool q8 = a.k_scale != nullptr;             // caches of E4M3 codes: value = code value x scale of the head
+  // row of the cache (dense) or of the pool (paged) that holds position t
+  long long row = (static_cast<long long>(b) * a.n_kv + h) * a.cap + t;
+  if (a.block_table != nullptr && stored) {
+    int pg = a.block_table[static_cast<long long>(b) * a.max_pages + (t >> a.page_shift)];
+    pg = pg < 0 ? 0 : (pg >= a.n_pages ? a.n_pages - 1 : pg);
+    row = ((static_cast<long long>(pg) * a.n_kv + h) << a.page_shift) + (t & ((1 << a.page_shift) - 1));
+  }
+  uint8_t* k8 = reinterpret_cast<uint8_t*>(a.k_cache_w) + row * 2 * P;
+  uint8_t* v8 = reinterpret_cast<uint8_t*>(a.v_cache_w) + row * a.d_v;
+  // the new K pair and V elements as the scan would read them back from the cache (fp32, exact)
+  float kxf = 0.f, kyf = 0.f, v0f = bf16_to_f32(r.v0), v1f = bf16_to_f32(r.v1);
   if (lane < P && stored) {
     if (r.rot) {
       const double phi = static_cast<double>(t) * r.f;
       double sn, cs;
       sincos_f64(phi, &sn, &cs);
       const double x = static_cast<double>(bf16_to_f32(r.kx)), y = static_cast<double>(bf16_to_f32(r.ky));
-      kxr = f64_to_bf16_rne(x * cs - y * sn);
-      kyr = f64_to_bf16_rne(x * sn + y * cs);
-      a.k_cache_w[row * 2 * P + lane] = kxr;
-      a.k_cache_w[row * 2 * P + lane + P] = kyr;
-    } else {   // bad pair index: the append leaves these two elements as they are
-      kxr = a.k_cache_w[row * 2 * P + lane];
-      kyr = a.k_cache_w[row * 2 * P + lane + P];
+      if (q8) {
+        const double ks = static_cast<double>(a.k_scale[h]);
+        const uint8_t cx = f64_to_e4m3((x * cs - y * sn) / ks), cy = f64_to_e4m3((x * sn + y * cs) / ks);
+        k8[lane] = cx;
+        k8[lane + P] = cy;
+        kxf = e4m3_to_f32(cx);
+        kyf = e4m3_to_f32(cy);
+      } else {
+        const uint16_t kxr = f64_to_bf16_rne(x * cs - y * sn), kyr = f64_to_bf16_rne(x * sn + y * cs);
+        a.k_cache_w[row * 2 * P + lane] = kxr;
+        a.k_cache_w[row * 2 * P + lane + P] = kyr;
+        kxf = bf16_to_f32(kxr);
+        kyf = bf16_to_f32(kyr);
+      }
+    } else if (q8) {   // bad pair index: the append leaves these two elements as they are
+      kxf = e4m3_to_f32(k8[lane]);
+      kyf = e4m3_to_f32(k8[lane + P]);
+    } else {
+      kxf = bf16_to_f32(a.k_cache_w[row * 2 * P + lane]);
+      kyf = bf16_to_f32(a.k_cache_w[row * 2 * P + lane + P]);
     }
   }
-  if (stored) {
+  if (q8) {
+    const double vs = static_cast<double>(a.v_scale[h]);
+    const uint8_t c0 = f64_to_e4m3(static_cast<double>(v0f) / vs), c1 = f64_to_e4m3(static_cast<double>(v1f) / vs);
+    if (stored && lane < a.d_v) v8[lane] = c0;
+    if (stored && lane + kWave < a.d_v) v8[lane + kWave] = c1;
+    v0f = e4m3_to_f32(c0) * a.v_scale[h];
+    v1f = e4m3_to_f32(c1) * a.v_scale[h];
+  } else if (stored) {
     if (lane < a.d_v) a.v_cache_w[row * a.d_v + lane] = r.v0;
     if (lane + kWave < a.d_v) a.v_cache_w[row * a.d_v + lane + kWave] = r.v1;
   }
-  const float kxf = bf16_to_f32(kxr), kyf = bf16_to_f32(kyr);
+  const float score_scale = q8 ? a.scale_log2e * a.k_scale[h] : a.scale_log2e;
 #pragma unroll
   for (int g = 0; g < kMaxGroup; ++g) {
     if (g < a.group) {
@@ -143,11 +177,11 @@ __device__ __forceinline__ void token_finish(const DecodeArgs& a, int b, int h, 
       for (int o = 32; o >= 1; o >>= 1) part += __shfl_xor(part, o);
       const long long slot = (static_cast<long long>(b) * a.n_q + h * a.group + g) * a.n_slots + a.n_split;
       if (lane == 0) {
-        a.part_ml[slot * 2 + 0] = attended ? part * a.scale_log2e : -INFINITY;
+        a.part_ml[slot * 2 + 0] = attended ? part * score_scale : -INFINITY;
         a.part_ml[slot * 2 + 1] = attended ? 1.f : 0.f;
       }
-      if (lane < a.d_v) a.part_acc[slot * a.d_v + lane] = attended ? bf16_to_f32(r.v0) : 0.f;
-      if (lane + kWave < a.d_v) a.part_acc[slot * a.d_v + lane + kWave] = attended ? bf16_to_f32(r.v1) : 0.f;
+      if (lane < a.d_v) a.part_acc[slot * a.d_v + lane] = attended ? v0f : 0.f;
+      if (lane + kWave < a.d_v) a.part_acc[slot * a.d_v + lane + kWave] = attended ? v1f : 0.f;
     }
   }
 }

@@ -791,6 +791,91 @@ def test_q8_paged_caches(rap, P, dv, Hq, Hkv, ctx, page_rows, n_new):
     assert torch.equal(out, out_d), "paged and dense fp8 attention differ"
 
 
+@pytest.mark.parametrize("fp8,paged", [(False, True), (True, False), (True, True), (False, False)])
+@pytest.mark.parametrize("P,dv,Hq,Hkv,ctx,page_rows", [(45, 90, 8, 2, 1300, 128), (58, 115, 8, 2, 500, 32), (32, 64, 10, 2, 900, 64)])
+def test_decode_step_any_cache(rap, fp8, paged, P, dv, Hq, Hkv, ctx, page_rows):
+    """rap_decode_step_ex over bf16 / fp8 caches, dense or paged, against the two calls for the same
+    kind of cache (caches bit for bit, outputs to fp32 rounding) and against the oracle on the
+    resulting cache.  One token sits in the middle of its sequence, one just beyond the attended rows."""
+    w = I.scaled(I.WORKLOADS["cfg2"], batch=4, n_q_heads=Hq, n_kv_heads=Hkv, n_pairs=P, d_v=dv, ctx=ctx, n_new=1,
+                 ragged_min=max(2, ctx // 3), peaky_frac=0.0, seed=900 + P + page_rows)
+    _say("step any cache fp8=%s paged=%s P=%d dv=%d ctx=%d" % (fp8, paged, P, dv, ctx))
+    case = I.make_case(w, device=DEV)
+    lens = case.seq_lens.cpu().numpy().copy()
+    max_pages = (int(lens.max()) + 1 + page_rows - 1) // page_rows
+    cap = max_pages * page_rows
+    pos_np = (lens - 1).astype(np.int32)
+    pos_np[1] = lens[1] // 2
+    pos_np[2] = lens[2]
+    pos = torch.from_numpy(pos_np).to(DEV)
+    k_new, v_new = case.k_new[:, 0].contiguous(), case.v_new[:, 0].contiguous()
+    keep_np = case.keep.cpu().numpy()
+    rng = np.random.Generator(np.random.PCG64(23))
+    ks = (rng.uniform(4.0, 6.0, Hkv) / 448.0).astype(np.float32)
+    vs = (rng.uniform(4.0, 6.0, Hkv) / 448.0).astype(np.float32)
+    ksd, vsd = (torch.from_numpy(ks).to(DEV), torch.from_numpy(vs).to(DEV)) if fp8 else (None, None)
+    # dense cache contents of this kind: bf16 bits or E4M3 codes, rows [0, len) valid
+    kb, vb = I.bits(case.k_cache)[:, :, :cap], I.bits(case.v_cache)[:, :, :cap]
+    if kb.shape[2] < cap:
+        kb = np.concatenate([kb, np.zeros((w.batch, Hkv, cap - kb.shape[2], 2 * P), kb.dtype)], axis=2)
+        vb = np.concatenate([vb, np.zeros((w.batch, Hkv, cap - vb.shape[2], dv), vb.dtype)], axis=2)
+    if fp8:
+        kd = O.f64_to_e4m3_bits(O.bf16_bits_to_f64(kb) / ks.astype(np.float64)[None, :, None, None])
+        vd = O.f64_to_e4m3_bits(O.bf16_bits_to_f64(vb) / vs.astype(np.float64)[None, :, None, None])
+    else:
+        kd, vd = kb.copy(), vb.copy()
+    n_pages = w.batch * max_pages + 2
+    table = rng.permutation(n_pages)[:w.batch * max_pages].reshape(w.batch, max_pages).astype(np.int32)
+    full = np.full(w.batch, cap)
+    def to_dev(x):
+        t = torch.from_numpy(x if fp8 else x.view(np.int16)).to(DEV)
+        return t if fp8 else t.view(torch.bfloat16)
+    def fresh():
+        if paged:
+            return to_dev(O.dense_to_paged_ref(kd, table, page_rows, n_pages, full)), to_dev(O.dense_to_paged_ref(vd, table, page_rows, n_pages, full))
+        return to_dev(kd.copy()), to_dev(vd.copy())
+    def to_dense(t):
+        x = t.cpu().numpy() if fp8 else I.bits(t)
+        return O.paged_to_dense_ref(x, table, full) if paged else x
+    shp = rap.shape(w.batch, Hq, Hkv, w.d_head, P, dv, cap, w.rope_theta)
+    pg = rap.paging(page_rows, n_pages, torch.from_numpy(table).to(DEV)) if paged else None
+    for q_is_rotated in (True, False):
+        for rps in (0, 256):
+            tun = rap.tuning(kernel=MFMA, rows_per_split=rps)
+            ws = rap.new_workspace(shp, cap, tun)
+            k1, v1 = fresh()
+            out1 = torch.full((w.batch, Hq, dv), float("nan"), dtype=torch.float32, device=DEV)
+            rap.rap_decode_step_ex(shp, k1, v1, ksd, vsd, pg, k_new, v_new, pos, case.keep, case.q, q_is_rotated,
+                                   case.seq_lens, cap, out1, float(w.scale), ws, tun)
+            k2, v2 = fresh()
+            out2 = torch.full_like(out1, float("nan"))
+            qp = None if q_is_rotated else pos
+            kp = None if q_is_rotated else case.keep
+            if fp8 and paged:
+                rap.rap_rope_append_paged_q8(shp, pg, 1, k_new, v_new, pos, case.keep, k2, v2, ksd, vsd)
+                rap.rap_decode_attn_paged_q8(shp, pg, case.q, qp, kp, k2, v2, ksd, vsd, case.seq_lens, cap, out2, float(w.scale), ws, tun)
+            elif fp8:
+                rap.rap_rope_append_q8(shp, 1, k_new, v_new, pos, case.keep, k2, v2, ksd, vsd)
+                rap.rap_decode_attn_q8(shp, case.q, qp, kp, k2, v2, ksd, vsd, case.seq_lens, cap, out2, float(w.scale), ws, tun)
+            elif paged:
+                rap.rap_rope_append_paged(shp, pg, 1, k_new, v_new, pos, case.keep, k2, v2)
+                rap.rap_decode_attn_paged(shp, pg, case.q, qp, kp, k2, v2, case.seq_lens, cap, out2, float(w.scale), ws, tun)
+            else:
+                rap.rap_rope_append(shp, 1, k_new, v_new, pos, case.keep, k2, v2)
+                if q_is_rotated:
+                    rap.rap_decode_attn(shp, case.q, k2, v2, case.seq_lens, cap, out2, float(w.scale), ws, tun)
+                else:
+                    rap.rap_decode_attn_rope(shp, case.q, pos, case.keep, k2, v2, case.seq_lens, cap, out2, float(w.scale), ws, tun)
+            torch.cuda.synchronize()
+            assert torch.equal(k1.view(torch.uint8), k2.view(torch.uint8)) and torch.equal(v1.view(torch.uint8), v2.view(torch.uint8)), "caches differ"
+            rel = (out1 - out2).abs().max().item() / out2.abs().max().item()
+            assert rel <= 2e-5, "step differs from the two calls (rps=%d): %.3g" % (rps, rel)
+            gk, gv = to_dense(k1), to_dense(v1)
+            qb = I.bits(case.q) if q_is_rotated else O.rope_queries_ref(I.bits(case.q), pos_np, keep_np, w.rope_theta, w.d_head, Hkv)
+            ref = O.attn_q8_ref(qb, gk, gv, ks, vs, lens, w.scale) if fp8 else O.attn_ref(qb, gk, gv, lens, w.scale)
+            H.assert_attn_close(out1.cpu().numpy(), ref, "step fp8=%s paged=%s rps=%d rotated=%s" % (fp8, paged, rps, q_is_rotated))
+
+
 @pytest.mark.parametrize("one_call", [False, True])
 def test_graph_replay(rap, one_call):
     """A decode loop recorded once into a HIP graph (append + attention, or the one-call step) and
