@@ -292,6 +292,13 @@ rap_status_t rap_decode_attn_paged(const rap_shape_t* shape, const rap_paging_t*
                                    void* workspace, size_t workspace_bytes,
                                    const rap_tuning_t* tuning, void* stream);
 
+/* rap_prefill_attn over paged bf16 pools; page_rows must be at least 64 (smaller pages are
+ * RAP_ERR_UNSUPPORTED).  Everything else as in rap_prefill_attn. */
+rap_status_t rap_prefill_attn_paged(const rap_shape_t* shape, const rap_paging_t* paging, int32_t n_new,
+                                    const void* q, const void* k_pool, const void* v_pool,
+                                    const int32_t* seq_lens, int64_t max_seq_len,
+                                    void* out, float scale, void* stream);
+
 /* Both together: fp8 (E4M3) codes in paged pools, [n_pages, n_kv_heads, page_rows, d] bytes.
  * Arguments as in rap_rope_append_q8 / rap_decode_attn_q8 and rap_*_paged; page_rows being a
  * multiple of 32 keeps every page 16-byte aligned at one byte per element. */

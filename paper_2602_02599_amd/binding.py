@@ -109,6 +109,9 @@ class Rap:
         L.rap_prefill_attn.restype = C.c_int
         L.rap_prefill_attn.argtypes = [C.POINTER(RapShape), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_int64, C.c_void_p, C.c_float, C.c_void_p]
+        L.rap_prefill_attn_paged.restype = C.c_int
+        L.rap_prefill_attn_paged.argtypes = [C.POINTER(RapShape), C.POINTER(RapPaging), C.c_int32, C.c_void_p, C.c_void_p,
+                                             C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_float, C.c_void_p]
         L.rap_rope_append_paged.restype = C.c_int
         L.rap_rope_append_paged.argtypes = [C.POINTER(RapShape), C.POINTER(RapPaging), C.c_int32] + [C.c_void_p] * 7
         L.rap_decode_attn_paged.restype = C.c_int
@@ -242,6 +245,16 @@ class Rap:
                                        _ptr(k_cache, torch.bfloat16, "k_cache"), _ptr(v_cache, torch.bfloat16, "v_cache"),
                                        _ptr(seq_lens, torch.int32, "seq_lens"), max_seq_len, _ptr(out, torch.float32, "out"),
                                        scale, _stream(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def rap_prefill_attn_paged(self, shape: RapShape, paging: RapPaging, n_new: int, q, k_pool, v_pool, seq_lens,
+                               max_seq_len: int, out, scale: float, stream=None, check=True) -> int:
+        st = self.lib.rap_prefill_attn_paged(C.byref(shape), C.byref(paging), n_new, _ptr(q, torch.bfloat16, "q"),
+                                             _ptr(k_pool, torch.bfloat16, "k_pool"), _ptr(v_pool, torch.bfloat16, "v_pool"),
+                                             _ptr(seq_lens, torch.int32, "seq_lens"), max_seq_len,
+                                             _ptr(out, torch.float32, "out"), scale, _stream(stream))
         if check:
             self._check(st)
         return st

@@ -321,6 +321,51 @@ rap_status_t null_after_shape(const rap_shape_t* shape) {
 
 bool live_call(const rap_shape_t* shape, int64_t max_seq_len) { return shape && shape->batch > 0 && max_seq_len >= 1; }
 
+// ---- prefill attention ----------------------------------------------------------------------------
+
+// Shared body of rap_prefill_attn and rap_prefill_attn_paged.
+rap_status_t prefill_impl(const rap_shape_t* shape, const rap_paging_t* paging, int32_t n_new, const void* q,
+                          const void* k_cache, const void* v_cache, const int32_t* seq_lens, int64_t max_seq_len,
+                          void* out, float scale, void* stream) {
+  rap_status_t st = check_shape(shape);
+  if (st != RAP_OK) return st;
+  int page_shift = 0;
+  if (paging) {
+    if ((st = check_paging(shape, paging, &page_shift)) != RAP_OK) return st;
+    if (paging->page_rows < 64) return RAP_ERR_UNSUPPORTED;     // a 64-row tile must not straddle pages
+  }
+  if (n_new < 0 || max_seq_len < 1) return RAP_ERR_SHAPE;
+  if (max_seq_len > shape->cache_cap) return RAP_ERR_CAPACITY;
+  if (n_new == 0 || shape->batch == 0) return RAP_OK;
+  if (!q || !k_cache || !v_cache || !seq_lens || !out) return RAP_ERR_NULL;
+  if (misaligned(k_cache, 16) || misaligned(v_cache, 16) || misaligned(q, 4) || misaligned(out, 4)) return RAP_ERR_SHAPE;
+  if (static_cast<int64_t>(shape->batch) * n_new > kInt32Max) return RAP_ERR_UNSUPPORTED;
+  rap::PrefillArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = static_cast<const uint16_t*>(q);
+  a.k_cache = static_cast<const uint16_t*>(k_cache);
+  a.v_cache = static_cast<const uint16_t*>(v_cache);
+  a.seq_lens = seq_lens;
+  a.out = static_cast<float*>(out);
+  a.batch = shape->batch;
+  a.n_new = n_new;
+  a.n_q = shape->n_q_heads;
+  a.n_kv = shape->n_kv_heads;
+  a.group = shape->n_q_heads / shape->n_kv_heads;
+  a.d_k = 2 * shape->n_pairs;
+  a.d_v = shape->d_v;
+  a.max_len = static_cast<int32_t>(max_seq_len);
+  a.cap = shape->cache_cap;
+  a.scale_log2e = scale * kLog2e;
+  if (paging) {
+    a.block_table = paging->block_table;
+    a.page_shift = page_shift;
+    a.n_pages = paging->n_pages;
+    a.max_pages = paging->max_pages;
+  }
+  return hip_status(rap::launch_prefill(a, static_cast<hipStream_t>(stream)));
+}
+
 }  // namespace
 
 extern "C" {
@@ -623,32 +668,14 @@ rap_status_t rap_decode_attn_paged_q8(const rap_shape_t* shape, const rap_paging
 rap_status_t rap_prefill_attn(const rap_shape_t* shape, int32_t n_new, const void* q, const void* k_cache,
                               const void* v_cache, const int32_t* seq_lens, int64_t max_seq_len, void* out, float scale,
                               void* stream) {
-  rap_status_t st = check_shape(shape);
-  if (st != RAP_OK) return st;
-  if (n_new < 0 || max_seq_len < 1) return RAP_ERR_SHAPE;
-  if (max_seq_len > shape->cache_cap) return RAP_ERR_CAPACITY;
-  if (n_new == 0 || shape->batch == 0) return RAP_OK;
-  if (!q || !k_cache || !v_cache || !seq_lens || !out) return RAP_ERR_NULL;
-  if (misaligned(k_cache, 16) || misaligned(v_cache, 16) || misaligned(q, 4) || misaligned(out, 4)) return RAP_ERR_SHAPE;
-  if (static_cast<int64_t>(shape->batch) * n_new > kInt32Max) return RAP_ERR_UNSUPPORTED;
-  rap::PrefillArgs a;
-  memset(&a, 0, sizeof(a));
-  a.q = static_cast<const uint16_t*>(q);
-  a.k_cache = static_cast<const uint16_t*>(k_cache);
-  a.v_cache = static_cast<const uint16_t*>(v_cache);
-  a.seq_lens = seq_lens;
-  a.out = static_cast<float*>(out);
-  a.batch = shape->batch;
-  a.n_new = n_new;
-  a.n_q = shape->n_q_heads;
-  a.n_kv = shape->n_kv_heads;
-  a.group = shape->n_q_heads / shape->n_kv_heads;
-  a.d_k = 2 * shape->n_pairs;
-  a.d_v = shape->d_v;
-  a.max_len = static_cast<int32_t>(max_seq_len);
-  a.cap = shape->cache_cap;
-  a.scale_log2e = scale * kLog2e;
-  return hip_status(rap::launch_prefill(a, static_cast<hipStream_t>(stream)));
+  return prefill_impl(shape, nullptr, n_new, q, k_cache, v_cache, seq_lens, max_seq_len, out, scale, stream);
+}
+
+rap_status_t rap_prefill_attn_paged(const rap_shape_t* shape, const rap_paging_t* paging, int32_t n_new, const void* q,
+                                    const void* k_pool, const void* v_pool, const int32_t* seq_lens, int64_t max_seq_len,
+                                    void* out, float scale, void* stream) {
+  if (!paging) return RAP_ERR_NULL;
+  return prefill_impl(shape, paging, n_new, q, k_pool, v_pool, seq_lens, max_seq_len, out, scale, stream);
 }
 
 rap_status_t rap_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
@@ -676,6 +703,6 @@ const char* rap_status_str(rap_status_t status) {
   return "unknown status";
 }
 
-int32_t rap_version(void) { return 400; }
+int32_t rap_version(void) { return 500; }
 
 }  // extern "C"

@@ -144,6 +144,10 @@ struct PrefillArgs {
   const uint16_t* v_cache;
   const int32_t* seq_lens;
   float* out;               // [B, n_new, H_q, d_v]
+  // paged caches (block_table null otherwise): pools [n_pages, H_kv, 1 << page_shift, d], pages of
+  // at least 64 rows so that a staged tile never straddles two of them
+  const int32_t* block_table;   // [B, max_pages]
+  int32_t page_shift, n_pages, max_pages;
   int32_t batch, n_new, n_q, n_kv, group, d_k, d_v, max_len;
   int32_t tok_per_wg;       // query tokens per workgroup: (64 NQ) / G
   int32_t n_qblk;           // ceil(n_new / tok_per_wg)

@@ -21,6 +21,9 @@
 //    diagonal of the wavefront's columns, later tiles are skipped by the wavefront, earlier ones
 //    need no mask.
 //
+// Paged caches: with a block table the caches are pools of pages of at least 64 rows, a staged
+// tile never straddles two pages, and only its start address changes (looked up a tile ahead).
+//
 // Garbage safety: rows at or beyond the sequence length may hold any bits; their scores are never
 // visible (a select to -inf), their V rows are cleared on the way into LDS, K fragments are masked
 // beyond d_k, and loads never touch rows >= round-up-8(len) <= cap.
@@ -144,19 +147,28 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   // rows a fragment read touches would all start in the same bank.
   const int lpk = pitch_k + a.pad_k, lpv = pitch_v + a.pad_v;
   const long long slab = static_cast<long long>(b) * a.n_kv + h;
-  const unsigned char* kslab = reinterpret_cast<const unsigned char*>(a.k_cache) + slab * a.cap * pitch_k;
-  const unsigned char* vslab = reinterpret_cast<const unsigned char*>(a.v_cache) + slab * a.cap * pitch_v;
+  const bool paged = a.block_table != nullptr;
+  const unsigned char* kslab = reinterpret_cast<const unsigned char*>(a.k_cache) + (paged ? 0 : slab * a.cap * pitch_k);
+  const unsigned char* vslab = reinterpret_cast<const unsigned char*>(a.v_cache) + (paged ? 0 : slab * a.cap * pitch_v);
+  // row of the (b, h) slab, or of the pool, where the tile that starts at logical row `row` lies
+  // (a page number outside the pool is clamped into it)
+  auto tile_row = [&](int row) -> long long {
+    if (!paged) return row;
+    int pg = a.block_table[static_cast<long long>(b) * a.max_pages + (row >> a.page_shift)];
+    pg = pg < 0 ? 0 : (pg >= a.n_pages ? a.n_pages - 1 : pg);
+    return ((static_cast<long long>(pg) * a.n_kv + h) << a.page_shift) + (row & ((1 << a.page_shift) - 1));
+  };
   const int len8 = (len + 7) & ~7;                 // <= cache_cap: rows below it are readable
   const int kbytes = kKeysPerTile * pitch_k, vbytes = kKeysPerTile * pitch_v;   // bytes fetched per tile
   const int v_off = (kKeysPerTile * lpk + 64 + 127) & ~127;   // slack: the last K fragment read runs past the tile
 
   uint4 kst[DIRECT ? 1 : NCK], vst[DIRECT ? 1 : NCV];
-  auto issue = [&](int t) {
+  auto issue = [&](int t, long long trow) {
     const int base = t * kKeysPerTile;
     const int rows = min(kKeysPerTile, len8 - base);           // multiple of 8, >= 8
     const int kval = rows * pitch_k, vval = rows * pitch_v;    // multiples of 16
-    const unsigned char* kg = kslab + static_cast<long long>(base) * pitch_k;
-    const unsigned char* vg = vslab + static_cast<long long>(base) * pitch_v;
+    const unsigned char* kg = kslab + trow * pitch_k;
+    const unsigned char* vg = vslab + trow * pitch_v;
 #pragma unroll
     for (int j = 0; j < NCK; ++j) {
       const int off = (j * 256 + tid) * 16;
@@ -185,12 +197,12 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 
   // Without LDS padding the tile is a flat copy, and the 16-byte loads can write LDS themselves
   // (lane i of a wavefront lands at the wavefront's LDS base + 16 i): no staging registers.
-  auto issue_direct = [&](int t) {
+  auto issue_direct = [&](int t, long long trow) {
     const int base = t * kKeysPerTile;
     const int rows = min(kKeysPerTile, len8 - base);
     const int kval = rows * pitch_k, vval = rows * pitch_v;
-    const unsigned char* kg = kslab + static_cast<long long>(base) * pitch_k;
-    const unsigned char* vg = vslab + static_cast<long long>(base) * pitch_v;
+    const unsigned char* kg = kslab + trow * pitch_k;
+    const unsigned char* vg = vslab + trow * pitch_v;
     unsigned char* kt = smem + (t & 1) * a.lds_buf_bytes;
     unsigned char* vt = kt + v_off;
 #pragma unroll
@@ -230,13 +242,18 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     for (int r = 0; r < 4; ++r) voff[rt][r] = (16 * rt + 4 * lg + r) * lpv + (VPAIR ? 4 : 2) * l16;
 
   const int n_tiles = (n_keys + kKeysPerTile - 1) / kKeysPerTile;
+  // start row of the tile whose loads are issued next, looked up (paged) one tile ahead of them
+  long long trow_next;
+  auto row_of_tile = [&](int t) -> long long { return t < n_tiles ? tile_row(t * kKeysPerTile) : 0; };
   if constexpr (DIRECT) {
-    issue_direct(0);
+    issue_direct(0, row_of_tile(0));
+    trow_next = row_of_tile(1);
   } else {
-    issue(0);
+    issue(0, row_of_tile(0));
     park(0);
     __syncthreads();
-    if (n_tiles > 1) issue(1);
+    if (n_tiles > 1) issue(1, row_of_tile(1));
+    trow_next = row_of_tile(2);
   }
 
   for (int t = 0; t < n_tiles; ++t) {
@@ -245,7 +262,8 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     if constexpr (DIRECT) {
       __builtin_amdgcn_s_waitcnt(0);       // this wavefront's share of tile t has landed
       __syncthreads();                     // everybody's has, and nobody still reads the other buffer
-      if (t + 1 < n_tiles) issue_direct(t + 1);
+      if (t + 1 < n_tiles) issue_direct(t + 1, trow_next);
+      trow_next = row_of_tile(t + 2);
     }
     if ((t + 1) * kKeysPerTile > len) {
       // The V rows at or beyond the sequence length may hold anything (NaN included) and a zero
@@ -414,7 +432,8 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
       // ---- next tile into the other buffer (its last readers passed the previous barrier)
       if (t + 1 < n_tiles) park((t + 1) & 1);
       __syncthreads();
-      if (t + 2 < n_tiles) issue(t + 2);
+      if (t + 2 < n_tiles) issue(t + 2, trow_next);
+      trow_next = row_of_tile(t + 3);
     }
   }
 
@@ -492,12 +511,13 @@ hipError_t launch_prefill_inst(PrefillArgs a, hipStream_t stream) {
 template <int KCH, int NQ>
 hipError_t launch_prefill_k(const PrefillArgs& a, hipStream_t stream) {
   const int nt = (a.d_v + 15) / 16;
+  constexpr int NQW = NQ > 2 ? 2 : NQ;   // d_v > 96: four column blocks of accumulators do not fit the registers
   if ((a.d_v & 1) == 0 && (nt & 1) == 0) {
     switch (nt) {
       case 2: return launch_prefill_inst<KCH, 2, true, NQ>(a, stream);
       case 4: return launch_prefill_inst<KCH, 4, true, NQ>(a, stream);
       case 6: return launch_prefill_inst<KCH, 6, true, NQ>(a, stream);
-      case 8: return launch_prefill_inst<KCH, 8, true, NQ>(a, stream);
+      case 8: return launch_prefill_inst<KCH, 8, true, NQW>(a, stream);
       default: return hipErrorInvalidValue;
     }
   }
@@ -508,8 +528,8 @@ hipError_t launch_prefill_k(const PrefillArgs& a, hipStream_t stream) {
     case 4: return launch_prefill_inst<KCH, 4, false, NQ>(a, stream);
     case 5: return launch_prefill_inst<KCH, 5, false, NQ>(a, stream);
     case 6: return launch_prefill_inst<KCH, 6, false, NQ>(a, stream);
-    case 7: return launch_prefill_inst<KCH, 7, false, NQ>(a, stream);
-    case 8: return launch_prefill_inst<KCH, 8, false, NQ>(a, stream);
+    case 7: return launch_prefill_inst<KCH, 7, false, NQW>(a, stream);
+    case 8: return launch_prefill_inst<KCH, 8, false, NQW>(a, stream);
     default: return hipErrorInvalidValue;
   }
 }

@@ -428,6 +428,44 @@ def test_prefill_small(rap, P, dv, Hq, Hkv, n_new, lens):
     H.assert_attn_close(out.cpu().numpy(), ref, "prefill")
 
 
+@pytest.mark.parametrize("P,dv,Hq,Hkv,n_new,lens,page_rows", [
+    (45, 90, 8, 2, 200, [200, 333, 150], 64), (58, 115, 8, 2, 130, [130, 517], 128),
+    (32, 64, 10, 2, 97, [97, 400, 1], 64), (64, 128, 4, 1, 150, [150, 700], 256)])
+def test_prefill_paged(rap, P, dv, Hq, Hkv, n_new, lens, page_rows):
+    """rap_prefill_attn_paged over pools with a shuffled block table: bit for bit the dense call on
+    the same rows, and the oracle's bar; unused pages and the rows beyond each sequence hold NaN,
+    table entries beyond the sequences hold wild page numbers; pages of 32 rows are refused."""
+    q, kc, vc, sl, cap0, scale = _prefill_case(P, dv, Hq, Hkv, n_new, lens, seed=1200 + P + page_rows, nan_beyond=True)
+    _say("prefill paged P=%d dv=%d n_new=%d page_rows=%d" % (P, dv, n_new, page_rows))
+    lens_np = np.asarray(lens)
+    B = len(lens)
+    max_pages = (int(lens_np.max()) + page_rows - 1) // page_rows
+    cap = max_pages * page_rows
+    n_pages = B * max_pages + 3
+    rng = np.random.Generator(np.random.PCG64(31))
+    table = rng.permutation(n_pages)[:B * max_pages].reshape(B, max_pages).astype(np.int32)
+    nan = 0x7FC0
+    kp = O.dense_to_paged_ref(I.bits(kc), table, page_rows, n_pages, lens_np, fill=nan)
+    vp = O.dense_to_paged_ref(I.bits(vc), table, page_rows, n_pages, lens_np, fill=nan)
+    table_dev = table.copy()
+    for b in range(B):
+        table_dev[b, (int(lens_np[b]) + page_rows - 1) // page_rows:] = 2 ** 30
+    pg = rap.paging(page_rows, n_pages, torch.from_numpy(table_dev).to(DEV))
+    shp_p = rap.shape(B, Hq, Hkv, 128, P, dv, cap, 5e5)
+    out_p = torch.full((B, n_new, Hq, dv), float("nan"), dtype=torch.float32, device=DEV)
+    rap.rap_prefill_attn_paged(shp_p, pg, n_new, q, I.from_bits(kp, DEV), I.from_bits(vp, DEV), sl, cap, out_p, scale)
+    shp_d = rap.shape(B, Hq, Hkv, 128, P, dv, cap0, 5e5)
+    out_d = torch.full_like(out_p, float("nan"))
+    rap.rap_prefill_attn(shp_d, n_new, q, kc, vc, sl, cap0, out_d, scale)
+    torch.cuda.synchronize()
+    assert torch.equal(out_p, out_d), "paged and dense prefill differ"
+    ref = O.prefill_attn_ref(I.bits(q), I.bits(kc), I.bits(vc), lens_np, scale)
+    H.assert_attn_close(out_p.cpu().numpy(), ref, "paged prefill")
+    small = rap.paging(32, n_pages * (page_rows // 32), torch.zeros((B, cap // 32), dtype=torch.int32, device=DEV))
+    assert rap.rap_prefill_attn_paged(shp_p, small, n_new, q, I.from_bits(kp, DEV), I.from_bits(vp, DEV), sl, cap, out_p, scale,
+                                      check=False) == 3
+
+
 def test_prefill_last_row_is_decode(rap):
     """The last query of a prefill is the decode case: same numbers as rap_decode_attn (to fp32
     rounding: other tiling of the same sums)."""
