@@ -1058,6 +1058,60 @@ def test_cfg3_sampled(rap):
     _append_then_decode(rap, case, sample=_sampled(w, 6, 3) + [(0, 0), (w.batch - 1, w.n_kv_heads - 1)])
 
 
+@pytest.mark.parametrize("fp8", [False, True])
+def test_cfg3_paged_full(rap, fp8):
+    """The cfg3 shape in paged pools (pages of 256 rows, shuffled table; pool offsets beyond 2^31
+    bytes), bf16 and fp8: the attention over the pools must equal, bit for bit, the attention over
+    the same rows in dense caches, which test_cfg3_sampled and test_q8_cache hold to the oracle."""
+    _say("cfg3 paged full fp8=%s" % fp8)
+    w = I.WORKLOADS["cfg3"]
+    case = I.make_case(w, device=DEV)
+    page_rows = 256
+    B, Hkv = w.batch, w.n_kv_heads
+    max_pages = (int(case.cap) + page_rows - 1) // page_rows
+    cap = max_pages * page_rows
+    n_pages = B * max_pages + 7
+    gen = torch.Generator().manual_seed(5)
+    table = torch.randperm(n_pages, generator=gen)[:B * max_pages].reshape(B, max_pages).to(torch.int32)
+    def dense_of(t, d):      # [B, Hkv, case.cap, d] -> [B, Hkv, cap, d], what lies beyond stays zero
+        x = torch.zeros((B, Hkv, cap, d), dtype=t.dtype, device=DEV)
+        x[:, :, :t.shape[2]] = t
+        return x
+    if fp8:
+        g = torch.Generator(device=DEV); g.manual_seed(9)
+        kd = dense_of(torch.randint(0, 0x78, (B, Hkv, int(case.cap), w.d_k), generator=g, device=DEV, dtype=torch.uint8), w.d_k)
+        vd = dense_of(torch.randint(0, 0x78, (B, Hkv, int(case.cap), w.d_v), generator=g, device=DEV, dtype=torch.uint8), w.d_v)
+        ks = torch.full((Hkv,), 0.011, dtype=torch.float32, device=DEV); vs = ks.clone()
+    else:
+        kd, vd = dense_of(case.k_cache, w.d_k), dense_of(case.v_cache, w.d_v)
+    del case.k_cache, case.v_cache
+    torch.cuda.empty_cache()
+    def pool_of(x):          # [B, Hkv, cap, d] -> [n_pages, Hkv, page_rows, d] through the table
+        pool = torch.zeros((n_pages, Hkv, page_rows, x.shape[3]), dtype=x.dtype, device=DEV)
+        for b in range(B):
+            pages = x[b].reshape(Hkv, max_pages, page_rows, x.shape[3]).permute(1, 0, 2, 3)
+            pool[table[b].to(DEV).long()] = pages
+        return pool
+    kp, vp = pool_of(kd), pool_of(vd)
+    shp = rap.shape(B, w.n_q_heads, Hkv, w.d_head, w.n_pairs, w.d_v, cap, w.rope_theta)
+    pg = rap.paging(page_rows, n_pages, table.to(DEV))
+    msl = int(case.seq_lens.max().item())
+    ws = rap.new_workspace(shp, msl, None)
+    out_d = torch.full((B, w.n_q_heads, w.d_v), float("nan"), dtype=torch.float32, device=DEV)
+    out_p = torch.full_like(out_d, float("nan"))
+    if fp8:
+        rap.rap_decode_attn_q8(shp, case.q, None, None, kd, vd, ks, vs, case.seq_lens, msl, out_d, float(w.scale), ws, None)
+        rap.rap_decode_attn_paged_q8(shp, pg, case.q, None, None, kp, vp, ks, vs, case.seq_lens, msl, out_p, float(w.scale), ws, None)
+    else:
+        rap.rap_decode_attn(shp, case.q, kd, vd, case.seq_lens, msl, out_d, float(w.scale), ws, None)
+        rap.rap_decode_attn_paged(shp, pg, case.q, None, None, kp, vp, case.seq_lens, msl, out_p, float(w.scale), ws, None)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out_d).all()
+    assert torch.equal(out_d, out_p), "paged and dense attention differ at full size"
+    del kd, vd, kp, vp
+    torch.cuda.empty_cache()
+
+
 def test_cfg4_sampled(rap):
     _say("cfg4 sampled")
     w = I.WORKLOADS["cfg4"]
