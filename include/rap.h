@@ -335,6 +335,22 @@ rap_status_t rap_decode_step_ex(const rap_shape_t* shape, const rap_kv_cache_t* 
                                 void* workspace, size_t workspace_bytes,
                                 const rap_tuning_t* tuning, void* stream);
 
+/* A look at the device-side inputs whose values the host never sees, for callers who want to
+ * know before trusting a result.  ORs into *flags (dev, one uint32 the caller has set to 0):
+ *   RAP_FLAG_POS        a pos[b][n] outside [0, cache_cap): rap_rope_append skips that token
+ *   RAP_FLAG_PAIR       a keep_pair_idx entry outside [0, d_head / 2): that pair is left alone
+ *   RAP_FLAG_PAIR_ORDER a row of keep_pair_idx that is not strictly ascending (a pair kept twice)
+ *   RAP_FLAG_SEQ_LEN    a seq_lens[b] outside [0, max_seq_len]: the attention clamps it
+ * pos [batch, n_new], keep_pair_idx [n_kv_heads, P] and seq_lens [batch] may each be NULL (not
+ * looked at).  One small launch on `stream`; nothing is synchronised. */
+#define RAP_FLAG_POS 1u
+#define RAP_FLAG_PAIR 2u
+#define RAP_FLAG_PAIR_ORDER 4u
+#define RAP_FLAG_SEQ_LEN 8u
+rap_status_t rap_check_inputs(const rap_shape_t* shape, int32_t n_new, const int32_t* pos,
+                              const int32_t* keep_pair_idx, const int32_t* seq_lens,
+                              int64_t max_seq_len, uint32_t* flags, void* stream);
+
 /* Measurement aids (not part of the method): a read-only streaming pass over `bytes` bytes of
  * `src` (16-byte aligned, bytes % 16 == 0) that folds everything into 16 bytes at `sink`, and a
  * plain copy of `bytes` bytes.  They give the bandwidth a trivial kernel reaches on the same

@@ -132,6 +132,9 @@ class Rap:
         L.rap_decode_step_ex.restype = C.c_int
         L.rap_decode_step_ex.argtypes = [C.POINTER(RapShape), C.POINTER(RapKvCache)] + [C.c_void_p] * 5 + [
             C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_float, C.c_void_p, C.c_size_t, C.POINTER(RapTuning), C.c_void_p]
+        L.rap_check_inputs.restype = C.c_int
+        L.rap_check_inputs.argtypes = [C.POINTER(RapShape), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                       C.c_void_p, C.c_void_p]
         L.rap_stream_read.restype = C.c_int
         L.rap_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.rap_stream_copy.restype = C.c_int
@@ -352,6 +355,17 @@ class Rap:
                                          _ptr(out, torch.float32, "out"), scale, _ptr(workspace, None, "workspace"),
                                          0 if workspace is None else workspace.numel() * workspace.element_size(),
                                          C.byref(tuning) if tuning is not None else None, _stream(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def rap_check_inputs(self, shape: RapShape, n_new: int, pos, keep_pair_idx, seq_lens, max_seq_len: int, flags,
+                         stream=None, check=True) -> int:
+        """flags: one int32/uint32 word on the device, zeroed by the caller; bits as RAP_FLAG_* in rap.h."""
+        st = self.lib.rap_check_inputs(C.byref(shape), n_new, _ptr(pos, torch.int32, "pos"),
+                                       _ptr(keep_pair_idx, torch.int32, "keep_pair_idx"),
+                                       _ptr(seq_lens, torch.int32, "seq_lens"), max_seq_len, _ptr(flags, torch.int32, "flags"),
+                                       _stream(stream))
         if check:
             self._check(st)
         return st

@@ -17,6 +17,8 @@ hipError_t launch_merge(const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream);
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t stream);
 hipError_t launch_stream_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
+hipError_t launch_validate(const int32_t* pos, long long n_pos, long long cap, const int32_t* keep, int n_kv, int n_pairs,
+                           int half, const int32_t* seq_lens, int batch, long long max_len, uint32_t* flags, hipStream_t stream);
 int mfma_lds_wave_bytes(int d_k, int d_v, bool q8);
 }  // namespace rap
 
@@ -678,6 +680,20 @@ rap_status_t rap_prefill_attn_paged(const rap_shape_t* shape, const rap_paging_t
   return prefill_impl(shape, paging, n_new, q, k_pool, v_pool, seq_lens, max_seq_len, out, scale, stream);
 }
 
+rap_status_t rap_check_inputs(const rap_shape_t* shape, int32_t n_new, const int32_t* pos, const int32_t* keep_pair_idx,
+                              const int32_t* seq_lens, int64_t max_seq_len, uint32_t* flags, void* stream) {
+  const rap_status_t st = check_shape(shape);
+  if (st != RAP_OK) return st;
+  if (!flags) return RAP_ERR_NULL;
+  if (n_new < 0 || max_seq_len < 0 || max_seq_len > shape->cache_cap) return RAP_ERR_SHAPE;
+  if (misaligned(flags, 4)) return RAP_ERR_SHAPE;
+  const long long n_pos = pos ? static_cast<long long>(shape->batch) * n_new : 0;
+  if (n_pos > kInt32Max) return RAP_ERR_UNSUPPORTED;
+  return hip_status(rap::launch_validate(pos, n_pos, shape->cache_cap, keep_pair_idx, shape->n_kv_heads, shape->n_pairs,
+                                         shape->d_head / 2, seq_lens, shape->batch, max_seq_len, flags,
+                                         static_cast<hipStream_t>(stream)));
+}
+
 rap_status_t rap_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
   if (!src || !sink) return RAP_ERR_NULL;
   if ((bytes & 15) || misaligned(src, 16) || misaligned(sink, 16)) return RAP_ERR_SHAPE;
@@ -703,6 +719,6 @@ const char* rap_status_str(rap_status_t status) {
   return "unknown status";
 }
 
-int32_t rap_version(void) { return 500; }
+int32_t rap_version(void) { return 600; }
 
 }  // extern "C"

@@ -1,6 +1,7 @@
-// Measurement aids: a read-only streaming pass and a plain copy, 16 bytes per lane per step,
-// grid-stride.  They show what bandwidth a trivial kernel reaches on this device and give the
-// known-size reference that hardware byte counters are scaled by.
+// Small kernels beside the method.  Measurement aids: a read-only streaming pass and a plain copy,
+// 16 bytes per lane per step, grid-stride; they show what bandwidth a trivial kernel reaches on
+// this device and give the known-size reference that hardware byte counters are scaled by.  And a
+// check of the device-side inputs whose values the host never sees.
 #include "rap_device.h"
 
 namespace rap {
@@ -19,6 +20,38 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restric
 __global__ __launch_bounds__(256) void stream_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
   const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
   for (size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+// Device-side look at the inputs the host cannot see: ORs into *flags
+//   1  a position outside [0, cache_cap)            (the append skips such a token)
+//   2  a kept pair index outside [0, d_head / 2)     (the append leaves that pair alone)
+//   4  a row of kept pair indices not strictly ascending
+//   8  a sequence length outside [0, max_seq_len]    (the attention clamps it)
+// One thread per element of the longest array; atomics only where something is wrong.
+__global__ __launch_bounds__(256) void validate_kernel(const int32_t* pos, long long n_pos, long long cap, const int32_t* keep,
+                                                       int n_kv, int n_pairs, int half, const int32_t* seq_lens, int batch,
+                                                       long long max_len, uint32_t* flags) {
+  const long long i = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+  uint32_t f = 0;
+  if (pos != nullptr && i < n_pos && (pos[i] < 0 || pos[i] >= cap)) f |= 1u;
+  if (keep != nullptr && i < static_cast<long long>(n_kv) * n_pairs) {
+    const int v = keep[i];
+    if (v < 0 || v >= half) f |= 2u;
+    if (i % n_pairs != 0 && keep[i - 1] >= v) f |= 4u;
+  }
+  if (seq_lens != nullptr && i < batch && (seq_lens[i] < 0 || seq_lens[i] > max_len)) f |= 8u;
+  if (f != 0) atomicOr(flags, f);
+}
+
+hipError_t launch_validate(const int32_t* pos, long long n_pos, long long cap, const int32_t* keep, int n_kv, int n_pairs,
+                           int half, const int32_t* seq_lens, int batch, long long max_len, uint32_t* flags, hipStream_t stream) {
+  long long n = n_pos;
+  if (static_cast<long long>(n_kv) * n_pairs > n) n = static_cast<long long>(n_kv) * n_pairs;
+  if (batch > n) n = batch;
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(validate_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, stream, pos, n_pos, cap, keep,
+                     n_kv, n_pairs, half, seq_lens, batch, max_len, flags);
+  return hipGetLastError();
 }
 
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t stream) {

@@ -979,6 +979,37 @@ def test_graph_replay(rap, one_call):
     H.assert_attn_close(out_s.cpu().numpy(), ref, "last replay against the oracle")
 
 
+def test_check_inputs(rap):
+    """rap_check_inputs: clean inputs leave the flag word at zero; each kind of bad value sets its bit."""
+    w = I.scaled(I.WORKLOADS["cfg2"], batch=3, n_q_heads=8, n_kv_heads=2, ctx=300, n_new=5, ragged_min=100, seed=77)
+    case = I.make_case(w, device=DEV)
+    shp = H.shape_of(rap, case)
+    cap = int(case.cap)
+    def flags_of(pos, keep, sl, msl=cap):
+        f = torch.zeros(1, dtype=torch.int32, device=DEV)
+        rap.rap_check_inputs(shp, w.n_new, pos, keep, sl, msl, f)
+        torch.cuda.synchronize()
+        return int(f.item())
+    assert flags_of(case.pos, case.keep, case.seq_lens) == 0
+    assert flags_of(None, None, None) == 0
+    pos = case.pos.clone(); pos[1, 2] = cap
+    assert flags_of(pos, case.keep, case.seq_lens) == 1
+    pos[1, 2] = -1
+    assert flags_of(pos, None, None) == 1
+    keep = case.keep.clone(); keep[1, w.n_pairs - 1] = w.d_head // 2
+    assert flags_of(case.pos, keep, case.seq_lens) == 2
+    keep = case.keep.clone(); keep[0, 3] = keep[0, 2]
+    assert flags_of(case.pos, keep, case.seq_lens) == 4
+    keep = case.keep.clone(); keep[1, 0] = -5                     # out of range; the row still ascends
+    assert flags_of(None, keep, None) == 2
+    sl = case.seq_lens.clone(); sl[2] = cap + 1
+    assert flags_of(case.pos, case.keep, sl) == 8
+    assert flags_of(case.pos, case.keep, case.seq_lens, msl=int(case.seq_lens.max().item()) - 1) == 8
+    sl[0] = -1; pos[0, 0] = 2 ** 30
+    assert flags_of(pos, case.keep, sl) == 9
+    assert rap.rap_check_inputs(shp, w.n_new, case.pos, case.keep, case.seq_lens, cap, None, check=False) == 1
+
+
 def test_split_invariance(rap):
     """1 range vs many: same result up to fp32 rounding (merge identity on the GPU side)."""
     w = I.scaled(I.WORKLOADS["cfg2"], batch=2, ctx=4000, seed=13)
