@@ -113,6 +113,45 @@ def test_paging_rejects_bad_arguments(rap):
     assert ap(ok_shape, pg(table=1)) == 1 and dc(ok_shape, pg(table=1)) == 1
 
 
+def test_later_entry_points_reject_bad_arguments(rap):
+    """fp8, paged fp8, paged prefill, the general step, workspace-free helpers: host-side rejections only."""
+    def pg(page_rows=128, n_pages=10, max_pages=4, table=1):
+        return pkg.RapPaging(page_rows, n_pages, max_pages, 0, table)
+    shp = _shape(rap, cache_cap=512)
+    # fp8 append / attention: null scales are null pointers, capacity must be a multiple of 16
+    a8 = lambda s: rap.rap_rope_append_q8(s, 1, None, None, None, None, None, None, None, None, check=False)
+    d8 = lambda s: rap.rap_decode_attn_q8(s, None, None, None, None, None, None, None, None, 8, None, 0.1, None, None, check=False)
+    assert a8(shp) == 1 and d8(shp) == 1
+    assert a8(_shape(rap, cache_cap=511)) == 2 and d8(_shape(rap, n_q_heads=7)) == 2
+    assert a8(_shape(rap, batch=0)) == 0 and d8(_shape(rap, batch=0)) == 0
+    # paged fp8
+    ap8 = lambda s, p: rap.rap_rope_append_paged_q8(s, p, 1, None, None, None, None, None, None, None, None, check=False)
+    dp8 = lambda s, p: rap.rap_decode_attn_paged_q8(s, p, None, None, None, None, None, None, None, None, 512, None, 0.1, None,
+                                                    None, check=False)
+    assert ap8(shp, pg(page_rows=100)) == 2 and dp8(shp, pg(page_rows=100)) == 2
+    assert ap8(shp, pg(table=0)) == 1 and dp8(shp, pg(table=0)) == 1
+    assert ap8(shp, pg()) == 1 and dp8(shp, pg()) == 1           # past the paging checks, stops at a null tensor
+    # paged prefill: pages below 64 rows are not supported
+    pf = lambda s, p, n=4: rap.rap_prefill_attn_paged(s, p, n, None, None, None, None, 512, None, 0.1, check=False)
+    assert pf(shp, pg(page_rows=32, max_pages=16)) == 3
+    assert pf(shp, pg(page_rows=64, max_pages=8)) == 1
+    assert pf(shp, pg(), n=0) == 0 and pf(shp, pg(max_pages=5)) == 2
+    # the general step: a cache descriptor is required, scales come as a pair
+    lib = rap.lib
+    def step_ex(cache, s=shp, msl=512):
+        return lib.rap_decode_step_ex(C.byref(s), cache, None, None, None, None, None, 1, None, msl, None, 0.1, None, 0, None, None)
+    assert step_ex(None) == 1
+    assert step_ex(C.byref(pkg.binding.RapKvCache(None, None, 1, None, None))) == 1
+    assert step_ex(C.byref(pkg.binding.RapKvCache(None, None, None, None, None))) == 1
+    assert step_ex(C.byref(pkg.binding.RapKvCache(None, None, None, None, None)), s=_shape(rap, n_pairs=65)) == 2
+    assert step_ex(C.byref(pkg.binding.RapKvCache(None, None, None, None, None)), s=_shape(rap, batch=0)) == 0
+    assert step_ex(C.byref(pkg.binding.RapKvCache(None, None, None, None, None)), msl=0) == 2
+    # input check and workspace of the attention
+    ci = lambda s, flags, n=1, msl=512: lib.rap_check_inputs(C.byref(s), n, None, None, None, msl, flags, None)
+    assert ci(shp, None) == 1 and ci(_shape(rap, d_v=0), 1) == 2
+    assert ci(shp, 4, n=-1) == 2 and ci(shp, 4, msl=513) == 2 and ci(shp, 2) == 2      # misaligned flag word
+
+
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(pkg.RapError):
         pkg.Rap(str(tmp_path / "librap.so"))
