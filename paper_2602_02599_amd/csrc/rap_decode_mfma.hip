@@ -588,13 +588,8 @@ hipError_t launch_inst2(const DecodeArgs& a, hipStream_t stream) {
   const size_t lds = 4 * static_cast<size_t>(a.lds_wave_bytes);
   if (lds > 64 * 1024) {
     // more than the default dynamic-LDS limit: raise it once per kernel (gfx950 has 160 KB per CU)
-    static int raised_to = 0;
-    if (raised_to < static_cast<int>(lds)) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_mfma_kernel<KCH, NT, VPAIR, PAGED, Q8>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-      if (e != hipSuccess) return e;
-      raised_to = static_cast<int>(lds);
-    }
+    const hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(&decode_mfma_kernel<KCH, NT, VPAIR, PAGED, Q8>), static_cast<int>(lds));
+    if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL((decode_mfma_kernel<KCH, NT, VPAIR, PAGED, Q8>), grid, block, lds, stream, a);
   return hipGetLastError();

@@ -3,6 +3,8 @@
 #define RAP_DEVICE_H_
 
 #include <hip/hip_runtime.h>
+
+#include <atomic>
 #include <stdint.h>
 
 namespace rap {
@@ -220,6 +222,26 @@ __device__ __forceinline__ void rotate_queries_to_lds(const DecodeArgs& a, int b
     s_q[g * 2 * P + c + P] = r1;
   }
 }
+
+// Host side: a kernel that wants more than the default 64 KB of dynamic LDS has its limit raised
+// before the launch.  The setting belongs to the (kernel, device) pair, so what has been done is
+// remembered per device, one slot per call site (a template instantiation each); a lost race
+// between two host threads only repeats the call.
+constexpr int kMaxDevicesRemembered = 64;
+inline hipError_t raise_lds_limit_impl(const void* kernel, int bytes, std::atomic<int>* done) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) dev = -1;
+  const bool remembered = dev >= 0 && dev < kMaxDevicesRemembered;
+  if (remembered && done[dev].load(std::memory_order_relaxed) >= bytes) return hipSuccess;
+  const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && remembered) done[dev].store(bytes, std::memory_order_relaxed);
+  return e;
+}
+#define raise_lds_limit(kernel, bytes)                                \
+  ([&]() -> hipError_t {                                              \
+    static std::atomic<int> done_[::rap::kMaxDevicesRemembered];      \
+    return ::rap::raise_lds_limit_impl((kernel), (bytes), done_);     \
+  }())
 
 }  // namespace rap
 #endif  // RAP_DEVICE_H_

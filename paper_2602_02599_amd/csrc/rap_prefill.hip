@@ -466,13 +466,8 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 template <int KCH, int NT, bool VPAIR, int NQ, bool DIRECT, bool ONES>
 hipError_t launch_prefill_go2(const PrefillArgs& a, size_t lds, long long n_wg, hipStream_t stream) {
   if (lds > 64 * 1024) {
-    static int raised_to = 0;
-    if (raised_to < static_cast<int>(lds)) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<KCH, NT, VPAIR, NQ, DIRECT, ONES>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-      if (e != hipSuccess) return e;
-      raised_to = static_cast<int>(lds);
-    }
+    const hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(&prefill_kernel<KCH, NT, VPAIR, NQ, DIRECT, ONES>), static_cast<int>(lds));
+    if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL((prefill_kernel<KCH, NT, VPAIR, NQ, DIRECT, ONES>), dim3(static_cast<unsigned>(n_wg)), dim3(256), lds, stream, a);
   return hipGetLastError();
