@@ -115,7 +115,10 @@ __device__ __forceinline__ uint32_t lane_read(int byte_addr, uint32_t v) {
 // QUERY: the same walk over query rows (rap_rope_queries): no V, no cache; row (b, n, head) of
 // the input is rotated at pos[b][n] with the kept pairs of KV head head / G and stored at the same
 // place of the output; a pair with a bad index is stored as zero.
-template <bool VDWORD, bool QUERY>
+// Q8: the caches hold E4M3 codes (rap_rope_append_q8): every rotated element and every V element is
+// divided by its head's scale in fp64 and rounded once to the nearest code; a lane stores the two
+// code bytes of its own pair, so nothing travels back between lanes.
+template <bool VDWORD, bool QUERY, bool Q8>
 __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs_per_wave) {
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -145,6 +148,14 @@ __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs
   const bool has_v1 = !QUERY && !VDWORD && lane + kWave < a.d_v;
   const int kl = has_k ? lane : 0;
   const int vl0 = has_v0 ? lane : 0, vl1 = has_v1 ? lane + kWave : 0;
+
+  double ks8 = 1.0, vs8 = 1.0;
+  if constexpr (Q8) {
+    ks8 = static_cast<double>(a.k_scale[h]);
+    vs8 = static_cast<double>(a.v_scale[h]);
+  }
+  uint8_t* const k8 = reinterpret_cast<uint8_t*>(a.k_cache);
+  uint8_t* const v8 = reinterpret_cast<uint8_t*>(a.v_cache);
 
   double cs = 1.0, sn = 0.0;
   bool anchored = false;                                         // (cs, sn) is the angle of position t_next
@@ -193,11 +204,28 @@ __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs
           const uint32_t xw = lane_read(x_lane, kw[i]), yw = lane_read(y_lane, kw[i]);
           const double x = static_cast<double>(bf16_to_f32(static_cast<uint16_t>(x_half ? xw >> 16 : xw & 0xffffu)));
           const double y = static_cast<double>(bf16_to_f32(static_cast<uint16_t>(y_half ? yw >> 16 : yw & 0xffffu)));
-          const uint32_t o = static_cast<uint32_t>(f64_to_bf16_rne(x * cs - y * sn)) |
-                             static_cast<uint32_t>(f64_to_bf16_rne(x * sn + y * cs)) << 16;
+          const double xr = x * cs - y * sn, yr = x * sn + y * cs;
           const double c2 = cs * cf - sn * sf;                   // angle advances by theta_j
           sn = sn * cf + cs * sf;
           cs = c2;
+          if constexpr (Q8) {
+            const long long row = row0 + i;                      // the run lies in one slab (or page)
+            if (rot) {
+              k8[row * (2 * P) + lane] = f64_to_e4m3(xr / ks8);
+              k8[row * (2 * P) + lane + P] = f64_to_e4m3(yr / ks8);
+            }
+            const double v0 = static_cast<double>(bf16_to_f32(static_cast<uint16_t>(vw[i] & 0xffffu)));
+            const double v1 = static_cast<double>(bf16_to_f32(static_cast<uint16_t>(vw[i] >> 16)));
+            const uint8_t q0 = f64_to_e4m3(v0 / vs8), q1 = f64_to_e4m3(v1 / vs8);
+            if (VDWORD) {
+              if (has_v0) reinterpret_cast<uint16_t*>(v8 + row * a.d_v)[lane] = static_cast<uint16_t>(q0 | (q1 << 8));
+            } else {
+              if (has_v0) v8[row * a.d_v + lane] = q0;
+              if (has_v1) v8[row * a.d_v + lane + kWave] = q1;
+            }
+            continue;
+          }
+          const uint32_t o = static_cast<uint32_t>(f64_to_bf16_rne(xr)) | static_cast<uint32_t>(f64_to_bf16_rne(yr)) << 16;
           const uint32_t p0 = lane_read(c0, o), p1 = lane_read(c1, o);
           const uint32_t o0 = x0 ? p0 & 0xffffu : p0 >> 16, o1 = x1 ? p1 & 0xffffu : p1 >> 16;
           uint16_t* kdst = kdst0 + i * kdstride;
@@ -249,6 +277,20 @@ __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs
       if (t < 0 || t >= a.cap) continue;                         // documented: skipped
       const uint16_t* vsrc = vsrc0 + i * vstride;
       const long long row = cache_row(a, b, h, t);
+      if constexpr (Q8) {
+        if (rot) {
+          double s1, c1d;
+          sincos_f64(static_cast<double>(t) * f, &s1, &c1d);
+          const double x = static_cast<double>(bf16_to_f32(ksrc[lane]));
+          const double y = static_cast<double>(bf16_to_f32(ksrc[lane + P]));
+          k8[row * (2 * P) + lane] = f64_to_e4m3((x * c1d - y * s1) / ks8);
+          k8[row * (2 * P) + lane + P] = f64_to_e4m3((x * s1 + y * c1d) / ks8);
+        }
+        if (lane < a.d_v) v8[row * a.d_v + lane] = f64_to_e4m3(static_cast<double>(bf16_to_f32(vsrc[lane])) / vs8);
+        if (lane + kWave < a.d_v)
+          v8[row * a.d_v + lane + kWave] = f64_to_e4m3(static_cast<double>(bf16_to_f32(vsrc[lane + kWave])) / vs8);
+        continue;
+      }
       if (rot) {
         double s1, c1d;
         sincos_f64(static_cast<double>(t) * f, &s1, &c1d);
@@ -266,6 +308,16 @@ __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs
 }
 
 hipError_t launch_append(const AppendArgs& a, hipStream_t stream) {
+  if (a.k_scale != nullptr && a.n_new >= kBulkRun) {
+    const long long runs = static_cast<long long>((a.n_new + kBulkRun - 1) / kBulkRun) * a.n_kv * a.batch;
+    const int rpw = runs >= 32768 ? 4 : runs >= 16384 ? 2 : 1;
+    const int per_wg = 4 * rpw * kBulkRun;
+    dim3 grid(static_cast<unsigned>((a.n_new + per_wg - 1) / per_wg), static_cast<unsigned>(a.n_kv),
+              static_cast<unsigned>(a.batch));
+    if ((a.d_v & 1) == 0) hipLaunchKernelGGL((append_bulk_kernel<true, false, true>), grid, dim3(256), 0, stream, a, rpw);
+    else hipLaunchKernelGGL((append_bulk_kernel<false, false, true>), grid, dim3(256), 0, stream, a, rpw);
+    return hipGetLastError();
+  }
   if (a.k_scale != nullptr) {
     const long long n_tok8 = static_cast<long long>(a.batch) * a.n_new;
     dim3 grid8(static_cast<unsigned>((n_tok8 + 3) / 4), static_cast<unsigned>(a.n_kv), 1);
@@ -280,8 +332,8 @@ hipError_t launch_append(const AppendArgs& a, hipStream_t stream) {
     const int per_wg = 4 * rpw * kBulkRun;
     dim3 grid(static_cast<unsigned>((a.n_new + per_wg - 1) / per_wg), static_cast<unsigned>(a.n_kv),
               static_cast<unsigned>(a.batch));
-    if ((a.d_v & 1) == 0) hipLaunchKernelGGL((append_bulk_kernel<true, false>), grid, dim3(256), 0, stream, a, rpw);
-    else hipLaunchKernelGGL((append_bulk_kernel<false, false>), grid, dim3(256), 0, stream, a, rpw);
+    if ((a.d_v & 1) == 0) hipLaunchKernelGGL((append_bulk_kernel<true, false, false>), grid, dim3(256), 0, stream, a, rpw);
+    else hipLaunchKernelGGL((append_bulk_kernel<false, false, false>), grid, dim3(256), 0, stream, a, rpw);
     return hipGetLastError();
   }
   const long long n_tok = static_cast<long long>(a.batch) * a.n_new;
@@ -297,7 +349,7 @@ hipError_t launch_rope_queries(const AppendArgs& a, hipStream_t stream) {
   const int per_wg = 4 * rpw * kBulkRun;
   dim3 grid(static_cast<unsigned>((a.n_new + per_wg - 1) / per_wg), static_cast<unsigned>(a.n_kv),
             static_cast<unsigned>(a.batch));
-  hipLaunchKernelGGL((append_bulk_kernel<true, true>), grid, dim3(256), 0, stream, a, rpw);
+  hipLaunchKernelGGL((append_bulk_kernel<true, true, false>), grid, dim3(256), 0, stream, a, rpw);
   return hipGetLastError();
 }
 

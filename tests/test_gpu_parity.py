@@ -694,7 +694,8 @@ def test_paged_caches(rap, P, dv, Hq, Hkv, ctx, page_rows, n_new):
 
 
 @pytest.mark.parametrize("P,dv,Hq,Hkv,ctx,n_new", [(45, 90, 8, 2, 1200, 1), (58, 115, 8, 2, 700, 5), (32, 64, 10, 2, 2500, 40),
-                                                   (64, 128, 4, 1, 300, 1), (3, 5, 3, 1, 40, 2)])
+                                                   (64, 128, 4, 1, 300, 1), (3, 5, 3, 1, 40, 2),
+                                                   (45, 90, 8, 2, 2600, 700), (58, 115, 4, 2, 900, 333)])   # run-based append
 def test_q8_cache(rap, P, dv, Hq, Hkv, ctx, n_new):
     """rap_rope_append_q8 + rap_decode_attn_q8: the appended codes against the oracle's (equal, up
     to one code step on a vanishing fraction where the fp64 angle arithmetic differs in its last
