@@ -435,6 +435,31 @@ def attn_q8_ref(q, k_cache8, v_cache8, k_scale, v_scale, seq_lens, scale) -> np.
     return out
 
 
+def prefill_attn_q8_ref(q, k_cache8, v_cache8, k_scale, v_scale, seq_lens, scale) -> np.ndarray:
+    """prefill_attn_ref over an fp8 cache: the same causal attention on the values the codes stand
+    for (code value times the scale of its KV head).  q uint16 [B, n_new, H_q, d_k] bf16 bits."""
+    q = np.asarray(q)
+    bsz, n_new, n_q, _ = q.shape
+    n_kv = k_cache8.shape[1]
+    g = n_q // n_kv
+    d_v = v_cache8.shape[3]
+    out = np.zeros((bsz, n_new, n_q, d_v), dtype=np.float64)
+    qf = bf16_bits_to_f64(q)
+    ks = np.asarray(k_scale, dtype=np.float32).astype(np.float64)
+    vs = np.asarray(v_scale, dtype=np.float32).astype(np.float64)
+    for b in range(bsz):
+        n = max(int(seq_lens[b]), 0)
+        for h in range(n_kv):
+            kf = e4m3_bits_to_f64(k_cache8[b, h, :n]) * ks[h]
+            vf = e4m3_bits_to_f64(v_cache8[b, h, :n]) * vs[h]
+            for i in range(n_new):
+                p = n - n_new + i
+                if p < 0:
+                    continue
+                out[b, i, h * g:(h + 1) * g] = attn_rows_ref(qf[b, i, h * g:(h + 1) * g], kf[:p + 1], vf[:p + 1], scale)
+    return out
+
+
 # --------------------------------------------------------------------------
 # Paged caches (serving stacks): a pure re-indexing of the dense cache
 # --------------------------------------------------------------------------

@@ -666,6 +666,25 @@ def test_q8_cache_pins():
     assert np.array_equal(got, O.attn_ref(q, kb, vb, lens, 0.4))
 
 
+def test_prefill_q8_pins():
+    """Causal prefill over fp8 codes: equal to the bf16 prefill oracle on a cache that holds exactly
+    the dequantised values (power-of-two scales), its last row equal to the fp8 decode oracle, and
+    rows of a sequence shorter than n_new zero."""
+    rng = _rng(23)
+    B, n_new, Hq, H, dk, dv, cap = 2, 5, 4, 2, 6, 5, 12
+    k8 = rng.integers(0, 0x7E, (B, H, cap, dk)).astype(np.uint8) | (rng.integers(0, 2, (B, H, cap, dk)).astype(np.uint8) << 7)
+    v8 = rng.integers(0, 0x7E, (B, H, cap, dv)).astype(np.uint8) | (rng.integers(0, 2, (B, H, cap, dv)).astype(np.uint8) << 7)
+    ks, vs = np.array([2.0 ** -5, 2.0 ** -4], dtype=np.float32), np.array([2.0 ** -6, 0.5], dtype=np.float32)
+    q = _bf16_of(rng.standard_normal((B, n_new, Hq, dk)))
+    lens = np.array([9, 3])
+    got = O.prefill_attn_q8_ref(q, k8, v8, ks, vs, lens, 0.3)
+    kb = _bf16_of(O.e4m3_bits_to_f64(k8) * ks[None, :, None, None].astype(np.float64))
+    vb = _bf16_of(O.e4m3_bits_to_f64(v8) * vs[None, :, None, None].astype(np.float64))
+    assert np.array_equal(got, O.prefill_attn_ref(q, kb, vb, lens, 0.3))
+    assert np.array_equal(got[:, -1], O.attn_q8_ref(q[:, -1], k8, v8, ks, vs, lens, 0.3))
+    assert np.all(got[1, :2] == 0) and np.any(got[1, 2] != 0)      # positions -2, -1 do not exist; position 0 does
+
+
 def test_split_merge_identity():
     """Merging (m, l, acc) partials over any partition of the rows gives the unsplit result."""
     rng = _rng(17)
