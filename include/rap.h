@@ -335,6 +335,13 @@ rap_status_t rap_decode_step_ex(const rap_shape_t* shape, const rap_kv_cache_t* 
                                 void* workspace, size_t workspace_bytes,
                                 const rap_tuning_t* tuning, void* stream);
 
+/* rap_prefill_attn over any kind of cache (bf16 or E4M3 codes with scales, dense or paged pools of
+ * at least 64 rows per page), described as for rap_decode_step_ex; the caches are only read.
+ * fp8 caches need cache_cap % 16 == 0. */
+rap_status_t rap_prefill_attn_ex(const rap_shape_t* shape, const rap_kv_cache_t* cache, int32_t n_new,
+                                 const void* q, const int32_t* seq_lens, int64_t max_seq_len,
+                                 void* out, float scale, void* stream);
+
 /* A look at the device-side inputs whose values the host never sees, for callers who want to
  * know before trusting a result.  ORs into *flags (dev, one uint32 the caller has set to 0):
  *   RAP_FLAG_POS        a pos[b][n] outside [0, cache_cap): rap_rope_append skips that token

@@ -132,6 +132,9 @@ class Rap:
         L.rap_decode_step_ex.restype = C.c_int
         L.rap_decode_step_ex.argtypes = [C.POINTER(RapShape), C.POINTER(RapKvCache)] + [C.c_void_p] * 5 + [
             C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_float, C.c_void_p, C.c_size_t, C.POINTER(RapTuning), C.c_void_p]
+        L.rap_prefill_attn_ex.restype = C.c_int
+        L.rap_prefill_attn_ex.argtypes = [C.POINTER(RapShape), C.POINTER(RapKvCache), C.c_int32, C.c_void_p, C.c_void_p,
+                                          C.c_int64, C.c_void_p, C.c_float, C.c_void_p]
         L.rap_check_inputs.restype = C.c_int
         L.rap_check_inputs.argtypes = [C.POINTER(RapShape), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                        C.c_void_p, C.c_void_p]
@@ -355,6 +358,19 @@ class Rap:
                                          _ptr(out, torch.float32, "out"), scale, _ptr(workspace, None, "workspace"),
                                          0 if workspace is None else workspace.numel() * workspace.element_size(),
                                          C.byref(tuning) if tuning is not None else None, _stream(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def rap_prefill_attn_ex(self, shape: RapShape, k, v, k_scale, v_scale, paging: Optional[RapPaging], n_new: int, q,
+                            seq_lens, max_seq_len: int, out, scale: float, stream=None, check=True) -> int:
+        """k, v: bf16 caches or pools, or uint8 ones with k_scale / v_scale; paging None for dense caches."""
+        el = torch.uint8 if k_scale is not None else torch.bfloat16
+        cache = RapKvCache(_ptr(k, el, "k"), _ptr(v, el, "v"), _ptr(k_scale, torch.float32, "k_scale"),
+                           _ptr(v_scale, torch.float32, "v_scale"), C.pointer(paging) if paging is not None else None)
+        st = self.lib.rap_prefill_attn_ex(C.byref(shape), C.byref(cache), n_new, _ptr(q, torch.bfloat16, "q"),
+                                          _ptr(seq_lens, torch.int32, "seq_lens"), max_seq_len,
+                                          _ptr(out, torch.float32, "out"), scale, _stream(stream))
         if check:
             self._check(st)
         return st

@@ -325,12 +325,16 @@ bool live_call(const rap_shape_t* shape, int64_t max_seq_len) { return shape && 
 
 // ---- prefill attention ----------------------------------------------------------------------------
 
-// Shared body of rap_prefill_attn and rap_prefill_attn_paged.
+// Shared body of rap_prefill_attn, rap_prefill_attn_paged and rap_prefill_attn_ex (k_scale and
+// v_scale non-null: the caches hold E4M3 codes).
 rap_status_t prefill_impl(const rap_shape_t* shape, const rap_paging_t* paging, int32_t n_new, const void* q,
                           const void* k_cache, const void* v_cache, const int32_t* seq_lens, int64_t max_seq_len,
-                          void* out, float scale, void* stream) {
+                          void* out, float scale, void* stream, const float* k_scale = nullptr,
+                          const float* v_scale = nullptr) {
   rap_status_t st = check_shape(shape);
   if (st != RAP_OK) return st;
+  if ((k_scale == nullptr) != (v_scale == nullptr)) return RAP_ERR_NULL;
+  if (k_scale && shape->cache_cap % 16 != 0) return RAP_ERR_SHAPE;
   int page_shift = 0;
   if (paging) {
     if ((st = check_paging(shape, paging, &page_shift)) != RAP_OK) return st;
@@ -359,6 +363,8 @@ rap_status_t prefill_impl(const rap_shape_t* shape, const rap_paging_t* paging, 
   a.max_len = static_cast<int32_t>(max_seq_len);
   a.cap = shape->cache_cap;
   a.scale_log2e = scale * kLog2e;
+  a.k_scale = k_scale;
+  a.v_scale = v_scale;
   if (paging) {
     a.block_table = paging->block_table;
     a.page_shift = page_shift;
@@ -673,6 +679,13 @@ rap_status_t rap_prefill_attn(const rap_shape_t* shape, int32_t n_new, const voi
   return prefill_impl(shape, nullptr, n_new, q, k_cache, v_cache, seq_lens, max_seq_len, out, scale, stream);
 }
 
+rap_status_t rap_prefill_attn_ex(const rap_shape_t* shape, const rap_kv_cache_t* cache, int32_t n_new, const void* q,
+                                 const int32_t* seq_lens, int64_t max_seq_len, void* out, float scale, void* stream) {
+  if (!cache) return RAP_ERR_NULL;
+  return prefill_impl(shape, cache->paging, n_new, q, cache->k, cache->v, seq_lens, max_seq_len, out, scale, stream,
+                      cache->k_scale, cache->v_scale);
+}
+
 rap_status_t rap_prefill_attn_paged(const rap_shape_t* shape, const rap_paging_t* paging, int32_t n_new, const void* q,
                                     const void* k_pool, const void* v_pool, const int32_t* seq_lens, int64_t max_seq_len,
                                     void* out, float scale, void* stream) {
@@ -719,6 +732,6 @@ const char* rap_status_str(rap_status_t status) {
   return "unknown status";
 }
 
-int32_t rap_version(void) { return 600; }
+int32_t rap_version(void) { return 700; }
 
 }  // extern "C"

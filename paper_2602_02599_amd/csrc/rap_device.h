@@ -146,6 +146,9 @@ struct PrefillArgs {
   const uint16_t* v_cache;
   const int32_t* seq_lens;
   float* out;               // [B, n_new, H_q, d_v]
+  // fp8 caches (null otherwise): per-KV-head scales of the E4M3 codes
+  const float* k_scale;
+  const float* v_scale;
   // paged caches (block_table null otherwise): pools [n_pages, H_kv, 1 << page_shift, d], pages of
   // at least 64 rows so that a staged tile never straddles two of them
   const int32_t* block_table;   // [B, max_pages]

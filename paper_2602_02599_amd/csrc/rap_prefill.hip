@@ -53,15 +53,27 @@ __device__ __forceinline__ void static_for(std::integer_sequence<int, Is...>, F&
 
 constexpr float kHeadroomP = 64.f;   // log2 units a score may exceed the reference before a rescale
 
+// eight E4M3 codes (c0: elements 0..3, c1: elements 4..7, lowest byte first) -> eight bf16, exact
+__device__ __forceinline__ uint4 widen_codes(uint32_t c0, uint32_t c1) {
+  const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(c0), false), b = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(c0), true);
+  const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(c1), false), d = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(c1), true);
+  return make_uint4(__builtin_bit_cast(uint32_t, __builtin_convertvector(a, bf16x2)), __builtin_bit_cast(uint32_t, __builtin_convertvector(b, bf16x2)),
+                    __builtin_bit_cast(uint32_t, __builtin_convertvector(c, bf16x2)), __builtin_bit_cast(uint32_t, __builtin_convertvector(d, bf16x2)));
+}
+
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
   const f32x2 v = {lo, hi};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-template <int KCH, int NT, bool VPAIR, int NQ, bool DIRECT, bool ONES>
+// Q8: the caches hold one-byte E4M3 codes (value = code value x the scale of the KV head): rows and
+// tiles are half as long, a fragment is widened to bf16 (exactly) between LDS and the matrix
+// instruction, k_scale folds into the softmax scale and v_scale into the final normalisation.
+template <int KCH, int NT, bool VPAIR, int NQ, bool DIRECT, bool ONES, bool Q8>
 __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
-  constexpr int NCK = (kKeysPerTile * 64 * KCH + 4095) / 4096;   // 16-byte chunks per thread, K tile
-  constexpr int NCV = (kKeysPerTile * 32 * NT + 4095) / 4096;    // same, V tile
+  constexpr int EB = Q8 ? 1 : 2;                                      // bytes per cache element
+  constexpr int NCK = (kKeysPerTile * 32 * EB * KCH + 4095) / 4096;   // 16-byte chunks per thread, K tile
+  constexpr int NCV = (kKeysPerTile * 16 * EB * NT + 4095) / 4096;    // same, V tile
   extern __shared__ __align__(16) unsigned char smem[];
 
   int tid = threadIdx.x;
@@ -142,7 +154,8 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     }
   }
 
-  const int pitch_k = 2 * dk, pitch_v = 2 * dv;    // bytes, in the cache
+  const int pitch_k = EB * dk, pitch_v = EB * dv;  // bytes, in the cache
+  const float scale_l2e = Q8 ? a.scale_log2e * a.k_scale[h] : a.scale_log2e;
   // In LDS a row pitch that is a multiple of 128 bytes gets 16 bytes of padding: otherwise the 16
   // rows a fragment read touches would all start in the same bank.
   const int lpk = pitch_k + a.pad_k, lpv = pitch_v + a.pad_v;
@@ -158,7 +171,9 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     pg = pg < 0 ? 0 : (pg >= a.n_pages ? a.n_pages - 1 : pg);
     return ((static_cast<long long>(pg) * a.n_kv + h) << a.page_shift) + (row & ((1 << a.page_shift) - 1));
   };
-  const int len8 = (len + 7) & ~7;                 // <= cache_cap: rows below it are readable
+  // rows below len8 are readable: <= cache_cap (a multiple of 8, of 16 for one-byte elements, which
+  // keeps every such group of rows 16-byte aligned whatever the row width)
+  const int len8 = Q8 ? (len + 15) & ~15 : (len + 7) & ~7;
   const int kbytes = kKeysPerTile * pitch_k, vbytes = kKeysPerTile * pitch_v;   // bytes fetched per tile
   const int v_off = (kKeysPerTile * lpk + 64 + 127) & ~127;   // slack: the last K fragment read runs past the tile
 
@@ -232,14 +247,21 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   // A spare channel slot (d_v not a multiple of 16) carries the constant 1, so that the row sums
   // of the probabilities come out of the P.V product: slot l16 = 15 of the last channel tile.
   const int klim = dk - 32 * (KCH - 1) - 8 * lg;   // elements of this lane's last K fragment that exist
+  // one-byte elements: the same limit as byte masks of the fragment's two words (d_k is even)
+  uint32_t kmask8[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int left = klim - 4 * i;
+    kmask8[i] = left >= 4 ? 0xffffffffu : (left >= 2 ? 0x0000ffffu : 0u);
+  }
   int koff[2];
 #pragma unroll
-  for (int rt = 0; rt < 2; ++rt) koff[rt] = (16 * rt + l16) * lpk + 16 * lg;
+  for (int rt = 0; rt < 2; ++rt) koff[rt] = (16 * rt + l16) * lpk + 8 * EB * lg;
   int voff[2][4];
 #pragma unroll
   for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) voff[rt][r] = (16 * rt + 4 * lg + r) * lpv + (VPAIR ? 4 : 2) * l16;
+    for (int r = 0; r < 4; ++r) voff[rt][r] = (16 * rt + 4 * lg + r) * lpv + (VPAIR ? 2 : 1) * EB * l16;
 
   const int n_tiles = (n_keys + kKeysPerTile - 1) / kKeysPerTile;
   // start row of the tile whose loads are issued next, looked up (paged) one tile ahead of them
@@ -289,13 +311,24 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
       for (int rt = 0; rt < 2; ++rt) {
 #pragma unroll
         for (int kk = 0; kk < KCH; ++kk) {
-          const uint32_t* p = reinterpret_cast<const uint32_t*>(kt + koff[rt] + 64 * kk);
-          uint4 w = make_uint4(p[0], p[1], p[2], p[3]);
-          if (kk == KCH - 1) {                      // beyond d_k lies the next row (or stale LDS)
-            w.x = klim > 0 ? w.x : 0u;
-            w.y = klim > 2 ? w.y : 0u;
-            w.z = klim > 4 ? w.z : 0u;
-            w.w = klim > 6 ? w.w : 0u;
+          uint4 w;
+          if constexpr (Q8) {
+            const uint16_t* p = reinterpret_cast<const uint16_t*>(kt + koff[rt] + 32 * kk);   // rows are 2-byte aligned
+            uint32_t c0 = p[0] | (static_cast<uint32_t>(p[1]) << 16), c1 = p[2] | (static_cast<uint32_t>(p[3]) << 16);
+            if (kk == KCH - 1) {
+              c0 &= kmask8[0];
+              c1 &= kmask8[1];
+            }
+            w = widen_codes(c0, c1);
+          } else {
+            const uint32_t* p = reinterpret_cast<const uint32_t*>(kt + koff[rt] + 64 * kk);
+            w = make_uint4(p[0], p[1], p[2], p[3]);
+            if (kk == KCH - 1) {                      // beyond d_k lies the next row (or stale LDS)
+              w.x = klim > 0 ? w.x : 0u;
+              w.y = klim > 2 ? w.y : 0u;
+              w.z = klim > 4 ? w.z : 0u;
+              w.w = klim > 6 ? w.w : 0u;
+            }
           }
           const bf16x8 kf = __builtin_bit_cast(bf16x8, w);
 #pragma unroll
@@ -308,8 +341,8 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
       // non-negative scale the raw scores stay as they are: scale and reference then fold into
       // one multiply-add per score (mul), and the maximum is scaled instead of the scores.
       bool grow = false;
-      const bool raw = no_mask && a.scale_log2e >= 0.f;
-      const float mul = raw ? a.scale_log2e : 1.f;
+      const bool raw = no_mask && scale_l2e >= 0.f;
+      const float mul = raw ? scale_l2e : 1.f;
       if (!raw) {
 #pragma unroll
         for (int nq = 0; nq < NQ; ++nq) {
@@ -318,7 +351,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
           for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-              sc[nq][rt][r] = (16 * rt + 4 * lg + r) <= rel ? sc[nq][rt][r] * a.scale_log2e : -INFINITY;
+              sc[nq][rt][r] = (16 * rt + 4 * lg + r) <= rel ? sc[nq][rt][r] * scale_l2e : -INFINITY;
         }
       }
       float tmax[NQ];
@@ -386,18 +419,31 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
       if constexpr (VPAIR) {
 #pragma unroll
         for (int np = 0; np < NT / 2; ++np) {
-          uint32_t w[8];
-#pragma unroll
-          for (int j = 0; j < 8; ++j) w[j] = *reinterpret_cast<const uint32_t*>(vt + voff[j >> 2][j & 3] + 64 * np);
           uint4 be, bo;   // even / odd channel of the pair, rows packed two by two
-          be.x = __builtin_amdgcn_perm(w[1], w[0], 0x05040100u);
-          be.y = __builtin_amdgcn_perm(w[3], w[2], 0x05040100u);
-          be.z = __builtin_amdgcn_perm(w[5], w[4], 0x05040100u);
-          be.w = __builtin_amdgcn_perm(w[7], w[6], 0x05040100u);
-          bo.x = __builtin_amdgcn_perm(w[1], w[0], 0x07060302u);
-          bo.y = __builtin_amdgcn_perm(w[3], w[2], 0x07060302u);
-          bo.z = __builtin_amdgcn_perm(w[5], w[4], 0x07060302u);
-          bo.w = __builtin_amdgcn_perm(w[7], w[6], 0x07060302u);
+          if constexpr (Q8) {
+            uint32_t hw[8];                // two adjacent channels of row j: even channel in the low byte
+#pragma unroll
+            for (int j = 0; j < 8; ++j) hw[j] = *reinterpret_cast<const uint16_t*>(vt + voff[j >> 2][j & 3] + 32 * np);
+            // bytes of one channel over rows 0..3 and 4..7, then widened
+            const uint32_t lo01 = __builtin_amdgcn_perm(hw[1], hw[0], 0x0c0c0400u), lo23 = __builtin_amdgcn_perm(hw[3], hw[2], 0x04000c0cu);
+            const uint32_t lo45 = __builtin_amdgcn_perm(hw[5], hw[4], 0x0c0c0400u), lo67 = __builtin_amdgcn_perm(hw[7], hw[6], 0x04000c0cu);
+            const uint32_t hi01 = __builtin_amdgcn_perm(hw[1], hw[0], 0x0c0c0501u), hi23 = __builtin_amdgcn_perm(hw[3], hw[2], 0x05010c0cu);
+            const uint32_t hi45 = __builtin_amdgcn_perm(hw[5], hw[4], 0x0c0c0501u), hi67 = __builtin_amdgcn_perm(hw[7], hw[6], 0x05010c0cu);
+            be = widen_codes(lo01 | lo23, lo45 | lo67);
+            bo = widen_codes(hi01 | hi23, hi45 | hi67);
+          } else {
+            uint32_t w[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) w[j] = *reinterpret_cast<const uint32_t*>(vt + voff[j >> 2][j & 3] + 64 * np);
+            be.x = __builtin_amdgcn_perm(w[1], w[0], 0x05040100u);
+            be.y = __builtin_amdgcn_perm(w[3], w[2], 0x05040100u);
+            be.z = __builtin_amdgcn_perm(w[5], w[4], 0x05040100u);
+            be.w = __builtin_amdgcn_perm(w[7], w[6], 0x05040100u);
+            bo.x = __builtin_amdgcn_perm(w[1], w[0], 0x07060302u);
+            bo.y = __builtin_amdgcn_perm(w[3], w[2], 0x07060302u);
+            bo.z = __builtin_amdgcn_perm(w[5], w[4], 0x07060302u);
+            bo.w = __builtin_amdgcn_perm(w[7], w[6], 0x07060302u);
+          }
           if (ONES && np == NT / 2 - 1 && l16 == 15) bo = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
           const bf16x8 vbe = __builtin_bit_cast(bf16x8, be), vbo = __builtin_bit_cast(bf16x8, bo);
 #pragma unroll
@@ -413,9 +459,16 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
           uint32_t u[8];
+          uint4 bv;
+          if constexpr (Q8) {
 #pragma unroll
-          for (int j = 0; j < 8; ++j) u[j] = *reinterpret_cast<const uint16_t*>(vt + voff[j >> 2][j & 3] + 32 * nt);
-          uint4 bv = make_uint4(u[0] | (u[1] << 16), u[2] | (u[3] << 16), u[4] | (u[5] << 16), u[6] | (u[7] << 16));
+            for (int j = 0; j < 8; ++j) u[j] = *reinterpret_cast<const uint8_t*>(vt + voff[j >> 2][j & 3] + 16 * nt);
+            bv = widen_codes(u[0] | (u[1] << 8) | (u[2] << 16) | (u[3] << 24), u[4] | (u[5] << 8) | (u[6] << 16) | (u[7] << 24));
+          } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) u[j] = *reinterpret_cast<const uint16_t*>(vt + voff[j >> 2][j & 3] + 32 * nt);
+            bv = make_uint4(u[0] | (u[1] << 16), u[2] | (u[3] << 16), u[4] | (u[5] << 16), u[6] | (u[7] << 16));
+          }
           if (ONES && nt == NT - 1 && l16 == 15) bv = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
           const bf16x8 vb = __builtin_bit_cast(bf16x8, bv);
 #pragma unroll
@@ -451,7 +504,8 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
       const int tl = cw / G, g = cw - (cw / G) * G;
       const int i = i0 + tl;
       if (tl < BT && i < a.n_new) {
-        const float inv = (shift + i >= 0 && lc > 0.f) ? 1.f / lc : 0.f;
+        float inv = (shift + i >= 0 && lc > 0.f) ? 1.f / lc : 0.f;
+        if constexpr (Q8) inv *= a.v_scale[h];       // codes -> values
         float* orow = a.out + (out_row0 + static_cast<long long>(i) * a.n_q + g) * dv;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
@@ -463,14 +517,20 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   }
 }
 
-template <int KCH, int NT, bool VPAIR, int NQ, bool DIRECT, bool ONES>
-hipError_t launch_prefill_go2(const PrefillArgs& a, size_t lds, long long n_wg, hipStream_t stream) {
+template <int KCH, int NT, bool VPAIR, int NQ, bool DIRECT, bool ONES, bool Q8>
+hipError_t launch_prefill_go3(const PrefillArgs& a, size_t lds, long long n_wg, hipStream_t stream) {
   if (lds > 64 * 1024) {
-    const hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(&prefill_kernel<KCH, NT, VPAIR, NQ, DIRECT, ONES>), static_cast<int>(lds));
+    const hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(&prefill_kernel<KCH, NT, VPAIR, NQ, DIRECT, ONES, Q8>), static_cast<int>(lds));
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((prefill_kernel<KCH, NT, VPAIR, NQ, DIRECT, ONES>), dim3(static_cast<unsigned>(n_wg)), dim3(256), lds, stream, a);
+  hipLaunchKernelGGL((prefill_kernel<KCH, NT, VPAIR, NQ, DIRECT, ONES, Q8>), dim3(static_cast<unsigned>(n_wg)), dim3(256), lds, stream, a);
   return hipGetLastError();
+}
+
+template <int KCH, int NT, bool VPAIR, int NQ, bool DIRECT, bool ONES>
+hipError_t launch_prefill_go2(const PrefillArgs& a, size_t lds, long long n_wg, hipStream_t stream) {
+  if (a.k_scale != nullptr) return launch_prefill_go3<KCH, NT, VPAIR, NQ, DIRECT, ONES, true>(a, lds, n_wg, stream);
+  return launch_prefill_go3<KCH, NT, VPAIR, NQ, DIRECT, ONES, false>(a, lds, n_wg, stream);
 }
 
 // a spare channel slot exists exactly when d_v is not a multiple of 16
@@ -485,7 +545,8 @@ hipError_t launch_prefill_inst(PrefillArgs a, hipStream_t stream) {
   a.tok_per_wg = (64 * NQ) / a.group;
   a.n_qblk = (a.n_new + a.tok_per_wg - 1) / a.tok_per_wg;
   // padded LDS rows for pitches of 128 or 256 bytes (the shift turns a byte offset into its row)
-  const int pk = 2 * a.d_k, pv = 2 * a.d_v;
+  const int eb = a.k_scale != nullptr ? 1 : 2;        // bytes per cache element
+  const int pk = eb * a.d_k, pv = eb * a.d_v;
   a.pad_k = (pk % 128 == 0) ? 16 : 0;
   a.pad_v = (pv % 128 == 0) ? 16 : 0;
   a.shift_k = a.pad_k ? (pk == 128 ? 7 : 8) : 31;

@@ -466,6 +466,59 @@ def test_prefill_paged(rap, P, dv, Hq, Hkv, n_new, lens, page_rows):
                                       check=False) == 3
 
 
+@pytest.mark.parametrize("P,dv,Hq,Hkv,n_new,lens,page_rows", [
+    (45, 90, 8, 2, 200, [200, 333, 150], 0), (58, 115, 8, 2, 130, [130, 517], 0), (32, 64, 10, 2, 97, [97, 400, 1], 0),
+    (64, 128, 4, 1, 150, [150, 260], 0), (3, 5, 3, 1, 33, [33, 40, 5], 0), (45, 90, 8, 1, 40, [40, 1000], 0),
+    (45, 90, 8, 2, 200, [200, 333, 150], 64), (58, 115, 8, 2, 130, [130, 517], 128)])
+def test_prefill_q8(rap, P, dv, Hq, Hkv, n_new, lens, page_rows):
+    """rap_prefill_attn_ex over fp8 (E4M3) caches, dense and paged, against the fp8 prefill oracle:
+    several key tiles, ragged tails, chunked and too-short sequences, NaN codes beyond the
+    sequences and in unused pages; the paged result equals the dense one bit for bit."""
+    _say("prefill q8 P=%d dv=%d n_new=%d page_rows=%d" % (P, dv, n_new, page_rows))
+    lens_np = np.asarray(lens, dtype=np.int64)
+    B = len(lens)
+    unit = page_rows if page_rows else 16
+    cap = (int(lens_np.max()) + unit - 1) // unit * unit
+    rng = np.random.Generator(np.random.PCG64(1300 + P + n_new))
+    ks = (rng.uniform(4.0, 6.0, Hkv) / 448.0).astype(np.float32)
+    vs = (rng.uniform(4.0, 6.0, Hkv) / 448.0).astype(np.float32)
+    k8 = np.full((B, Hkv, cap, 2 * P), 0x7F, dtype=np.uint8)
+    v8 = np.full((B, Hkv, cap, dv), 0xFF, dtype=np.uint8)
+    for b in range(B):
+        n = int(lens_np[b])
+        k8[b, :, :n] = O.f64_to_e4m3_bits(rng.standard_normal((Hkv, n, 2 * P)) / ks.astype(np.float64)[:, None, None])
+        v8[b, :, :n] = O.f64_to_e4m3_bits(rng.standard_normal((Hkv, n, dv)) / vs.astype(np.float64)[:, None, None])
+    gen = torch.Generator(device=DEV); gen.manual_seed(7)
+    q = torch.randn((B, n_new, Hq, 2 * P), generator=gen, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    sl = torch.from_numpy(lens_np.astype(np.int32)).to(DEV)
+    ksd, vsd = torch.from_numpy(ks).to(DEV), torch.from_numpy(vs).to(DEV)
+    scale = 1.0 / math.sqrt(2 * P)
+    shp = rap.shape(B, Hq, Hkv, 128, P, dv, cap, 5e5)
+    out = torch.full((B, n_new, Hq, dv), float("nan"), dtype=torch.float32, device=DEV)
+    k8d, v8d = torch.from_numpy(k8).to(DEV), torch.from_numpy(v8).to(DEV)
+    rap.rap_prefill_attn_ex(shp, k8d, v8d, ksd, vsd, None, n_new, q, sl, cap, out, scale)
+    torch.cuda.synchronize()
+    ref = O.prefill_attn_q8_ref(I.bits(q), k8, v8, ks, vs, lens_np, scale)
+    H.assert_attn_close(out.cpu().numpy(), ref, "fp8 prefill")
+    if page_rows:
+        max_pages = cap // page_rows
+        n_pages = B * max_pages + 3
+        table = rng.permutation(n_pages)[:B * max_pages].reshape(B, max_pages).astype(np.int32)
+        kp = O.dense_to_paged_ref(k8, table, page_rows, n_pages, lens_np, fill=0x7F)
+        vp = O.dense_to_paged_ref(v8, table, page_rows, n_pages, lens_np, fill=0xFF)
+        table_dev = table.copy()
+        for b in range(B):
+            table_dev[b, (int(lens_np[b]) + page_rows - 1) // page_rows:] = 2 ** 30
+        pg = rap.paging(page_rows, n_pages, torch.from_numpy(table_dev).to(DEV))
+        out_p = torch.full_like(out, float("nan"))
+        rap.rap_prefill_attn_ex(shp, torch.from_numpy(kp).to(DEV), torch.from_numpy(vp).to(DEV), ksd, vsd, pg, n_new, q, sl, cap,
+                                out_p, scale)
+        torch.cuda.synchronize()
+        assert torch.equal(out_p, out), "paged and dense fp8 prefill differ"
+    # scales come as a pair
+    assert rap.rap_prefill_attn_ex(shp, k8d, v8d, ksd, None, None, n_new, q, sl, cap, out, scale, check=False) == 1
+
+
 def test_prefill_last_row_is_decode(rap):
     """The last query of a prefill is the decode case: same numbers as rap_decode_attn (to fp32
     rounding: other tiling of the same sums)."""
