@@ -146,6 +146,16 @@ def test_later_entry_points_reject_bad_arguments(rap):
     assert step_ex(C.byref(pkg.binding.RapKvCache(None, None, None, None, None)), s=_shape(rap, n_pairs=65)) == 2
     assert step_ex(C.byref(pkg.binding.RapKvCache(None, None, None, None, None)), s=_shape(rap, batch=0)) == 0
     assert step_ex(C.byref(pkg.binding.RapKvCache(None, None, None, None, None)), msl=0) == 2
+    # the general prefill: descriptor required, scales as a pair, fp8 wants cap % 16, small pages refused
+    def pf_ex(cache, s=shp, n=4, msl=512):
+        return lib.rap_prefill_attn_ex(C.byref(s), cache, n, None, None, msl, None, 0.1, None)
+    KV = pkg.binding.RapKvCache
+    assert pf_ex(None) == 1
+    assert pf_ex(C.byref(KV(None, None, 1, None, None))) == 1
+    assert pf_ex(C.byref(KV(None, None, 1, 1, None)), s=_shape(rap, cache_cap=520)) == 2
+    assert pf_ex(C.byref(KV(None, None, None, None, None)), n=0) == 0
+    assert pf_ex(C.byref(KV(None, None, None, None, C.pointer(pg(page_rows=32, max_pages=16))))) == 3
+    assert pf_ex(C.byref(KV(None, None, None, None, None)), msl=513) == 4
     # input check and workspace of the attention
     ci = lambda s, flags, n=1, msl=512: lib.rap_check_inputs(C.byref(s), n, None, None, None, msl, flags, None)
     assert ci(shp, None) == 1 and ci(_shape(rap, d_v=0), 1) == 2
