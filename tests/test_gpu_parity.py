@@ -889,16 +889,37 @@ def test_decode_step_any_cache(rap, fp8, paged, P, dv, Hq, Hkv, ctx, page_rows):
     """rap_decode_step_ex over bf16 / fp8 caches, dense or paged, against the two calls for the same
     kind of cache (caches bit for bit, outputs to fp32 rounding) and against the oracle on the
     resulting cache.  One token sits in the middle of its sequence, one just beyond the attended rows."""
-    w = I.scaled(I.WORKLOADS["cfg2"], batch=4, n_q_heads=Hq, n_kv_heads=Hkv, n_pairs=P, d_v=dv, ctx=ctx, n_new=1,
-                 ragged_min=max(2, ctx // 3), peaky_frac=0.0, seed=900 + P + page_rows)
-    _say("step any cache fp8=%s paged=%s P=%d dv=%d ctx=%d" % (fp8, paged, P, dv, ctx))
+    _check_any_cache(rap, fp8, paged, P, dv, Hq, Hkv, ctx, page_rows, seed=900 + P + page_rows)
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_random_shapes(rap, seed):
+    """The same comparison (append, attention with and without the fused query rotation, one-call
+    step; against each other and against the oracle) on shapes, cache kinds and page sizes drawn
+    from a seed: widths from 2 to 128, any d_v, G from 1 to 8, contexts from one tile to ~80."""
+    rng = np.random.Generator(np.random.PCG64(5000 + seed))
+    P = int(rng.integers(1, 65))
+    dv = int(rng.integers(1, 129))
+    Hkv = int(rng.integers(1, 4))
+    G = int(rng.integers(1, 9))
+    ctx = int(rng.integers(40, 2600))
+    page_rows = int(rng.choice([32, 64, 128, 256]))
+    fp8, paged = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+    _check_any_cache(rap, fp8, paged, P, dv, G * Hkv, Hkv, ctx, page_rows, seed=6000 + seed, batch=int(rng.integers(2, 5)))
+
+
+def _check_any_cache(rap, fp8, paged, P, dv, Hq, Hkv, ctx, page_rows, seed, batch=4):
+    w = I.scaled(I.WORKLOADS["cfg2"], batch=batch, n_q_heads=Hq, n_kv_heads=Hkv, n_pairs=P, d_v=dv, ctx=ctx, n_new=1,
+                 ragged_min=max(2, ctx // 3), peaky_frac=0.0, seed=seed)
+    _say("any cache fp8=%s paged=%s P=%d dv=%d Hq=%d Hkv=%d ctx=%d page_rows=%d batch=%d" % (fp8, paged, P, dv, Hq, Hkv, ctx, page_rows, batch))
     case = I.make_case(w, device=DEV)
     lens = case.seq_lens.cpu().numpy().copy()
     max_pages = (int(lens.max()) + 1 + page_rows - 1) // page_rows
     cap = max_pages * page_rows
     pos_np = (lens - 1).astype(np.int32)
     pos_np[1] = lens[1] // 2
-    pos_np[2] = lens[2]
+    if w.batch > 2:
+        pos_np[2] = lens[2]
     pos = torch.from_numpy(pos_np).to(DEV)
     k_new, v_new = case.k_new[:, 0].contiguous(), case.v_new[:, 0].contiguous()
     keep_np = case.keep.cpu().numpy()
