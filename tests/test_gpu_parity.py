@@ -519,6 +519,64 @@ def test_prefill_q8(rap, P, dv, Hq, Hkv, n_new, lens, page_rows):
     assert rap.rap_prefill_attn_ex(shp, k8d, v8d, ksd, None, None, n_new, q, sl, cap, out, scale, check=False) == 1
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_prefill_random_shapes(rap, seed):
+    """rap_prefill_attn_ex on shapes, cache kinds and page sizes drawn from a seed (widths 2 to 128,
+    any d_v, G from 1 to 8, whole, chunked and too-short sequences), against the oracle."""
+    rng = np.random.Generator(np.random.PCG64(7000 + seed))
+    P, dv = int(rng.integers(1, 65)), int(rng.integers(1, 129))
+    Hkv, G = int(rng.integers(1, 4)), int(rng.integers(1, 9))
+    n_new = int(rng.integers(1, 400))
+    B = int(rng.integers(1, 4))
+    lens = [int(rng.integers(max(1, n_new // 2), n_new + 700)) for _ in range(B)]
+    fp8 = bool(rng.integers(0, 2))
+    page_rows = int(rng.choice([0, 64, 128, 256]))
+    Hq = G * Hkv
+    _say("prefill random fp8=%s page_rows=%d P=%d dv=%d Hq=%d Hkv=%d n_new=%d lens=%s" % (fp8, page_rows, P, dv, Hq, Hkv, n_new, lens))
+    lens_np = np.asarray(lens, dtype=np.int64)
+    unit = page_rows if page_rows else 16
+    cap = (int(lens_np.max()) + unit - 1) // unit * unit
+    scale = 1.0 / math.sqrt(2 * P)
+    gen = torch.Generator(device=DEV); gen.manual_seed(seed)
+    q = torch.randn((B, n_new, Hq, 2 * P), generator=gen, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    sl = torch.from_numpy(lens_np.astype(np.int32)).to(DEV)
+    if fp8:
+        ks = (rng.uniform(4.0, 6.0, Hkv) / 448.0).astype(np.float32)
+        vs = (rng.uniform(4.0, 6.0, Hkv) / 448.0).astype(np.float32)
+        kd = np.full((B, Hkv, cap, 2 * P), 0x7F, dtype=np.uint8); vd = np.full((B, Hkv, cap, dv), 0xFF, dtype=np.uint8)
+        for b in range(B):
+            n = int(lens_np[b])
+            kd[b, :, :n] = O.f64_to_e4m3_bits(rng.standard_normal((Hkv, n, 2 * P)) / ks.astype(np.float64)[:, None, None])
+            vd[b, :, :n] = O.f64_to_e4m3_bits(rng.standard_normal((Hkv, n, dv)) / vs.astype(np.float64)[:, None, None])
+        ksd, vsd = torch.from_numpy(ks).to(DEV), torch.from_numpy(vs).to(DEV)
+        ref = O.prefill_attn_q8_ref(I.bits(q), kd, vd, ks, vs, lens_np, scale)
+        fill_k, fill_v = 0x7F, 0xFF
+        to_dev = lambda x: torch.from_numpy(x).to(DEV)
+    else:
+        kd = np.full((B, Hkv, cap, 2 * P), 0x7FC0, dtype=np.uint16); vd = np.full((B, Hkv, cap, dv), 0x7FC0, dtype=np.uint16)
+        for b in range(B):
+            n = int(lens_np[b])
+            kd[b, :, :n] = O.f64_to_bf16_bits_rne(rng.standard_normal((Hkv, n, 2 * P)))
+            vd[b, :, :n] = O.f64_to_bf16_bits_rne(rng.standard_normal((Hkv, n, dv)))
+        ksd = vsd = None
+        ref = O.prefill_attn_ref(I.bits(q), kd, vd, lens_np, scale)
+        fill_k = fill_v = 0x7FC0
+        to_dev = lambda x: I.from_bits(x, DEV)
+    shp = rap.shape(B, Hq, Hkv, 128, P, dv, cap, 5e5)
+    pg = None
+    if page_rows:
+        max_pages = cap // page_rows
+        n_pages = B * max_pages + 2
+        table = rng.permutation(n_pages)[:B * max_pages].reshape(B, max_pages).astype(np.int32)
+        kd = O.dense_to_paged_ref(kd, table, page_rows, n_pages, lens_np, fill=fill_k)
+        vd = O.dense_to_paged_ref(vd, table, page_rows, n_pages, lens_np, fill=fill_v)
+        pg = rap.paging(page_rows, n_pages, torch.from_numpy(table).to(DEV))
+    out = torch.full((B, n_new, Hq, dv), float("nan"), dtype=torch.float32, device=DEV)
+    rap.rap_prefill_attn_ex(shp, to_dev(kd), to_dev(vd), ksd, vsd, pg, n_new, q, sl, cap, out, scale)
+    torch.cuda.synchronize()
+    H.assert_attn_close(out.cpu().numpy(), ref, "random prefill")
+
+
 def test_prefill_last_row_is_decode(rap):
     """The last query of a prefill is the decode case: same numbers as rap_decode_attn (to fp32
     rounding: other tiling of the same sums)."""
