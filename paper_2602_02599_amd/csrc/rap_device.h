@@ -165,26 +165,24 @@ struct PrefillArgs {
 
 // fp64 -> E4M3 code (finite-only 8-bit float: 4 exponent bits, bias 7, 3 mantissa bits, no
 // infinity, S.1111.111 = NaN): nearest value, ties to the even mantissa, magnitudes above 448
-// saturate, NaN -> 0x7f.  The mantissa is rounded as an integer in fp64 (rint of the value scaled
-// by a power of two, exact), so there is one rounding and it is the format's.
+// saturate, NaN -> 0x7f.  Two steps that together round once: the fp64 value is first brought to
+// fp32 by rounding to odd (truncate towards zero, then set the last mantissa bit if anything was
+// cut off), which keeps every fact a later rounding to a format at least two bits shorter needs;
+// the conversion instruction of the part then rounds that fp32 to E4M3, nearest-even, subnormal
+// codes included.  The instruction agrees with a bit-by-bit software rounding on every fp32
+// pattern of magnitude up to 464 (checked exhaustively on the device); above that it no longer
+// saturates, hence the clamp to 448 in front of it.
 __device__ __forceinline__ uint8_t f64_to_e4m3(double y) {
   if (y != y) return 0x7f;
-  const uint32_t sign = (__double2hiint(y) < 0) ? 0x80u : 0u;
-  double mag = fabs(y);
-  mag = mag > 448.0 ? 448.0 : mag;
-  uint32_t code;
-  if (mag < 0.015625) {                              // subnormal codes: multiples of 2^-9
-    code = static_cast<uint32_t>(rint(mag * 512.0)); // 0..8; 8 is the smallest normal, 0x08
-  } else {
-    int e = ilogb(mag);                              // -6 .. 8
-    int q = static_cast<int>(rint(ldexp(mag, 3 - e)));   // 8 .. 16
-    if (q == 16) {
-      q = 8;
-      e += 1;
-    }
-    code = (static_cast<uint32_t>(e + 7) << 3) | static_cast<uint32_t>(q - 8);
+  y = y > 448.0 ? 448.0 : (y < -448.0 ? -448.0 : y);
+  const float f = static_cast<float>(y);            // nearest-even; repaired to round-to-odd below
+  uint32_t bits = __float_as_uint(f);
+  const double d = static_cast<double>(f);
+  if (d != y) {
+    if (fabs(d) > fabs(y)) bits -= 1u;              // went away from zero: step back to the truncation
+    bits |= 1u;
   }
-  return static_cast<uint8_t>(sign | code);
+  return static_cast<uint8_t>(__builtin_amdgcn_cvt_pk_fp8_f32(__uint_as_float(bits), 0.f, 0, false) & 0xff);
 }
 
 // Row of the K / V cache that holds position t of sequence b for KV head h: a row of the dense
