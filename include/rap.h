@@ -342,6 +342,24 @@ rap_status_t rap_prefill_attn_ex(const rap_shape_t* shape, const rap_kv_cache_t*
                                  const void* q, const int32_t* seq_lens, int64_t max_seq_len,
                                  void* out, float scale, void* stream);
 
+/* Attention of a few query tokens per sequence at the speed of a decode step (verification of
+ * drafted tokens, short chunks): the same result as rap_prefill_attn_ex with n_new = n_tok, i.e.
+ * Eq. (attn) with the causal mask for the last n_tok rows of every sequence, which the append has
+ * already written (token i sits at row seq_lens[b] - n_tok + i and attends rows 0 .. its own; a
+ * token in front of the start of its sequence gives a zero row).  The cache in front of the new
+ * rows is read once for all n_tok * (n_q_heads / n_kv_heads) query rows of a KV head, which ride
+ * side by side through the matrix instruction: that product must not exceed 16, else
+ * RAP_ERR_UNSUPPORTED (use rap_prefill_attn_ex).  n_tok = 1 is rap_decode_attn over `cache`.
+ *   q   dev bf16 [batch, n_tok, n_q_heads, d_k] rotated;  out dev fp32 [batch, n_tok, n_q_heads, d_v]
+ *   workspace: at least n_tok * rap_decode_attn_workspace_bytes(shape, max_seq_len, tuning) bytes,
+ *   256-byte aligned, always needed when n_tok > 1; tuning->kernel must be 0 or 2.
+ * Everything else as in rap_decode_attn / rap_decode_step_ex; the caches are only read. */
+rap_status_t rap_decode_attn_multi(const rap_shape_t* shape, const rap_kv_cache_t* cache, int32_t n_tok,
+                                   const void* q, const int32_t* seq_lens, int64_t max_seq_len,
+                                   void* out, float scale,
+                                   void* workspace, size_t workspace_bytes,
+                                   const rap_tuning_t* tuning, void* stream);
+
 /* A look at the device-side inputs whose values the host never sees, for callers who want to
  * know before trusting a result.  ORs into *flags (dev, one uint32 the caller has set to 0):
  *   RAP_FLAG_POS        a pos[b][n] outside [0, cache_cap): rap_rope_append skips that token

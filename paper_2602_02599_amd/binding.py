@@ -135,6 +135,10 @@ class Rap:
         L.rap_prefill_attn_ex.restype = C.c_int
         L.rap_prefill_attn_ex.argtypes = [C.POINTER(RapShape), C.POINTER(RapKvCache), C.c_int32, C.c_void_p, C.c_void_p,
                                           C.c_int64, C.c_void_p, C.c_float, C.c_void_p]
+        L.rap_decode_attn_multi.restype = C.c_int
+        L.rap_decode_attn_multi.argtypes = [C.POINTER(RapShape), C.POINTER(RapKvCache), C.c_int32, C.c_void_p, C.c_void_p,
+                                            C.c_int64, C.c_void_p, C.c_float, C.c_void_p, C.c_size_t,
+                                            C.POINTER(RapTuning), C.c_void_p]
         L.rap_check_inputs.restype = C.c_int
         L.rap_check_inputs.argtypes = [C.POINTER(RapShape), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                        C.c_void_p, C.c_void_p]
@@ -375,6 +379,22 @@ class Rap:
             self._check(st)
         return st
 
+    def rap_decode_attn_multi(self, shape: RapShape, k, v, k_scale, v_scale, paging: Optional[RapPaging], n_tok: int, q,
+                              seq_lens, max_seq_len: int, out, scale: float, workspace, tuning=None, stream=None,
+                              check=True) -> int:
+        """k, v: bf16 caches or pools, or uint8 ones with k_scale / v_scale; paging None for dense caches."""
+        el = torch.uint8 if k_scale is not None else torch.bfloat16
+        cache = RapKvCache(_ptr(k, el, "k"), _ptr(v, el, "v"), _ptr(k_scale, torch.float32, "k_scale"),
+                           _ptr(v_scale, torch.float32, "v_scale"), C.pointer(paging) if paging is not None else None)
+        st = self.lib.rap_decode_attn_multi(C.byref(shape), C.byref(cache), n_tok, _ptr(q, torch.bfloat16, "q"),
+                                            _ptr(seq_lens, torch.int32, "seq_lens"), max_seq_len,
+                                            _ptr(out, torch.float32, "out"), scale, _ptr(workspace, None, "workspace"),
+                                            0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                            C.byref(tuning) if tuning is not None else None, _stream(stream))
+        if check:
+            self._check(st)
+        return st
+
     def rap_check_inputs(self, shape: RapShape, n_new: int, pos, keep_pair_idx, seq_lens, max_seq_len: int, flags,
                          stream=None, check=True) -> int:
         """flags: one int32/uint32 word on the device, zeroed by the caller; bits as RAP_FLAG_* in rap.h."""
@@ -393,11 +413,11 @@ class Rap:
         self._check(self.lib.rap_stream_copy(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream(stream)))
 
     # -- convenience on top of the entry points (allocation of scratch and output only)
-    def new_workspace(self, shape: RapShape, max_seq_len: int, tuning=None, device="cuda") -> torch.Tensor:
+    def new_workspace(self, shape: RapShape, max_seq_len: int, tuning=None, device="cuda", n_tok: int = 1) -> torch.Tensor:
         n = self.rap_decode_attn_workspace_bytes(shape, max_seq_len, tuning)
         if n == 0:
             raise RapError(2, "workspace query rejected the shape")
-        return torch.empty(n, dtype=torch.uint8, device=device)
+        return torch.empty(n * n_tok, dtype=torch.uint8, device=device)
 
 
 _LOADED: Optional[Rap] = None

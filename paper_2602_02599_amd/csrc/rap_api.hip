@@ -19,7 +19,7 @@ hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStre
 hipError_t launch_stream_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 hipError_t launch_validate(const int32_t* pos, long long n_pos, long long cap, const int32_t* keep, int n_kv, int n_pairs,
                            int half, const int32_t* seq_lens, int batch, long long max_len, uint32_t* flags, hipStream_t stream);
-int mfma_lds_wave_bytes(int d_k, int d_v, bool q8);
+int mfma_lds_wave_bytes(int d_k, int d_v, bool q8, int n_tok);
 }  // namespace rap
 
 namespace {
@@ -94,13 +94,16 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // Workspace = accumulators [B, H_q, n_split + 1, d_v], then (reference, sum) pairs
 // [B, H_q, n_split + 1, 2], fp32, each block rounded up to 256 bytes; the extra slot is the new
 // token's in the one-call step.
-size_t part_acc_bytes(const rap_shape_t* s, const Plan& p) {
-  return align_up(static_cast<size_t>(s->batch) * s->n_q_heads * (p.n_split + 1) * s->d_v * sizeof(float), 256);
+// With n_tok query tokens per sequence there are n_tok times as many query rows.
+size_t part_acc_bytes(const rap_shape_t* s, const Plan& p, int n_tok = 1) {
+  return align_up(static_cast<size_t>(s->batch) * n_tok * s->n_q_heads * (p.n_split + 1) * s->d_v * sizeof(float), 256);
 }
-size_t part_ml_bytes(const rap_shape_t* s, const Plan& p) {
-  return align_up(static_cast<size_t>(s->batch) * s->n_q_heads * (p.n_split + 1) * 2 * sizeof(float), 256);
+size_t part_ml_bytes(const rap_shape_t* s, const Plan& p, int n_tok = 1) {
+  return align_up(static_cast<size_t>(s->batch) * n_tok * s->n_q_heads * (p.n_split + 1) * 2 * sizeof(float), 256);
 }
-size_t workspace_need(const rap_shape_t* s, const Plan& p) { return part_acc_bytes(s, p) + part_ml_bytes(s, p) + 256; }
+size_t workspace_need(const rap_shape_t* s, const Plan& p, int n_tok = 1) {
+  return part_acc_bytes(s, p, n_tok) + part_ml_bytes(s, p, n_tok) + 256;
+}
 
 // page_rows a power of two in [32, 65536], table present, logical capacity consistent
 rap_status_t check_paging(const rap_shape_t* s, const rap_paging_t* pg, int* shift) {
@@ -196,6 +199,7 @@ struct DecodeRequest {
   const void* k_new = nullptr;             // one-call step: the token to append first (with v_new, new_pos)
   const void* v_new = nullptr;
   const int32_t* new_pos = nullptr;
+  int32_t n_tok = 1;                       // query tokens per sequence: the last n_tok rows, already appended
   const int32_t* seq_lens = nullptr;
   int64_t max_seq_len = 0;
   void* out = nullptr;
@@ -206,8 +210,8 @@ struct DecodeRequest {
   void* stream = nullptr;
 };
 
-// Shared body of rap_decode_attn, rap_decode_attn_rope, the paged and fp8 variants and
-// rap_decode_step.
+// Shared body of rap_decode_attn, rap_decode_attn_rope, the paged and fp8 variants,
+// rap_decode_step and rap_decode_attn_multi.
 rap_status_t decode_impl(const DecodeRequest& r) {
   const rap_shape_t* shape = r.shape;
   rap_status_t st = check_shape(shape);
@@ -218,6 +222,8 @@ rap_status_t decode_impl(const DecodeRequest& r) {
   if (r.max_seq_len > shape->cache_cap) return RAP_ERR_CAPACITY;
   if (shape->batch == 0) return RAP_OK;
   const bool step = r.k_new || r.v_new || r.new_pos;
+  const bool multi = r.n_tok > 1;
+  if (r.n_tok < 1) return RAP_ERR_SHAPE;
   if (!r.q || !r.k_cache || !r.v_cache || !r.seq_lens || !r.out) return RAP_ERR_NULL;
   if (step && (!r.k_new || !r.v_new || !r.new_pos)) return RAP_ERR_NULL;
   if ((r.q_pos || step) && no_rotation_rule(shape, r.keep_pair_idx)) return RAP_ERR_NULL;
@@ -229,9 +235,14 @@ rap_status_t decode_impl(const DecodeRequest& r) {
   // the one-call step on the matrix-core kernel hands the new token to the combining kernel, which
   // therefore always runs
   const bool fused_step = step && p.kernel == 2;
-  const bool combine = p.n_split > 1 || fused_step;
+  // several query tokens: their rows are the columns of the matrix instruction, 16 at most, and
+  // the part among the tokens themselves is added by the combining kernel, which always runs
+  if (multi && (p.kernel != 2 || step || r.q_pos ||
+                static_cast<int64_t>(r.n_tok) * (shape->n_q_heads / shape->n_kv_heads) > 16))
+    return RAP_ERR_UNSUPPORTED;
+  const bool combine = p.n_split > 1 || fused_step || multi;
   if (combine) {
-    if (!r.workspace || r.workspace_bytes < workspace_need(shape, p)) return RAP_ERR_WORKSPACE;
+    if (!r.workspace || r.workspace_bytes < workspace_need(shape, p, r.n_tok)) return RAP_ERR_WORKSPACE;
     if (misaligned(r.workspace, 256)) return RAP_ERR_WORKSPACE;
   }
   if (p.n_split > 65535 || (static_cast<int64_t>(p.n_split) + 1) * shape->n_kv_heads * shape->batch > kInt32Max)
@@ -256,7 +267,8 @@ rap_status_t decode_impl(const DecodeRequest& r) {
   a.seq_lens = r.seq_lens;
   a.out = static_cast<float*>(r.out);
   a.part_acc = static_cast<float*>(r.workspace);
-  a.part_ml = r.workspace ? reinterpret_cast<float*>(static_cast<char*>(r.workspace) + part_acc_bytes(shape, p)) : nullptr;
+  a.part_ml = r.workspace ? reinterpret_cast<float*>(static_cast<char*>(r.workspace) + part_acc_bytes(shape, p, r.n_tok)) : nullptr;
+  a.n_tok = r.n_tok;
   a.batch = shape->batch;
   a.n_q = shape->n_q_heads;
   a.n_kv = shape->n_kv_heads;
@@ -270,7 +282,7 @@ rap_status_t decode_impl(const DecodeRequest& r) {
   a.n_slots = fused_step ? p.n_split + 1 : p.n_split;
   a.cap = shape->cache_cap;
   a.scale_log2e = r.scale * kLog2e;
-  a.lds_wave_bytes = rap::mfma_lds_wave_bytes(a.d_k, a.d_v, r.fp8);
+  a.lds_wave_bytes = rap::mfma_lds_wave_bytes(a.d_k, a.d_v, r.fp8, r.n_tok);
   a.k_scale = r.fp8 ? r.k_scale : nullptr;
   a.v_scale = r.fp8 ? r.v_scale : nullptr;
   if (r.paging) {
@@ -569,6 +581,32 @@ rap_status_t rap_decode_step_ex(const rap_shape_t* shape, const rap_kv_cache_t* 
   return decode_impl(r);
 }
 
+rap_status_t rap_decode_attn_multi(const rap_shape_t* shape, const rap_kv_cache_t* cache, int32_t n_tok, const void* q,
+                                   const int32_t* seq_lens, int64_t max_seq_len, void* out, float scale,
+                                   void* workspace, size_t workspace_bytes, const rap_tuning_t* tuning, void* stream) {
+  if (!cache) return RAP_ERR_NULL;
+  if ((cache->k_scale == nullptr) != (cache->v_scale == nullptr)) return null_after_shape(shape);
+  DecodeRequest r;
+  r.shape = shape;
+  r.paging = cache->paging;
+  r.q = q;
+  r.k_cache = cache->k;
+  r.v_cache = cache->v;
+  r.fp8 = cache->k_scale != nullptr;
+  r.k_scale = cache->k_scale;
+  r.v_scale = cache->v_scale;
+  r.n_tok = n_tok;
+  r.seq_lens = seq_lens;
+  r.max_seq_len = max_seq_len;
+  r.out = out;
+  r.scale = scale;
+  r.workspace = workspace;
+  r.workspace_bytes = workspace_bytes;
+  r.tuning = tuning;
+  r.stream = stream;
+  return decode_impl(r);
+}
+
 rap_status_t rap_decode_attn_q8(const rap_shape_t* shape, const void* q, const int32_t* q_pos,
                                 const int32_t* keep_pair_idx, const void* k_cache8, const void* v_cache8,
                                 const float* k_scale, const float* v_scale, const int32_t* seq_lens,
@@ -732,6 +770,6 @@ const char* rap_status_str(rap_status_t status) {
   return "unknown status";
 }
 
-int32_t rap_version(void) { return 700; }
+int32_t rap_version(void) { return 800; }
 
 }  // extern "C"

@@ -103,11 +103,6 @@ __device__ __forceinline__ void token_load(const DecodeArgs& a, int b, int h, in
   }
 }
 
-// value of one E4M3 code
-__device__ __forceinline__ float e4m3_to_f32(uint8_t code) {
-  return __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(code), false)[0];
-}
-
 __device__ __forceinline__ void token_finish(const DecodeArgs& a, int b, int h, int lane, int t, bool attended,
                                              const uint16_t* s_q, const TokenRegs& r) {
   const int P = a.n_pairs;
@@ -186,6 +181,8 @@ __device__ __forceinline__ void token_finish(const DecodeArgs& a, int b, int h, 
   }
 }
 
+constexpr int kMaxCols = 16;   // columns of the matrix instruction: query rows of one (b, h) with several tokens
+
 // KCH = ceil(d_k / 32) score k-steps, NT = 16-channel output tiles.  VPAIR (even d_v): a lane
 // reads two adjacent V channels with one 4-byte LDS read and tile nt holds channels
 // 32 (nt / 2) + 2 l16 + (nt & 1); otherwise 2-byte reads and tile nt holds channels 16 nt + l16.
@@ -234,6 +231,9 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
     tok_attended = t_skip >= 0 && t_skip < len;
     if (len > 0 && t_skip == len - 1) len -= 1;
   }
+  // several query tokens: the scan stops in front of their rows; the combining kernel adds the
+  // causal part among the tokens themselves
+  if (a.n_tok > 1) len = len > a.n_tok ? len - a.n_tok : 0;
   if (split == a.n_split) {                            // the workgroup of the new token (decode step only)
     TokenRegs tk;
     if (wave == 0) token_load(a, b, h, lane, rope_q, tk);
@@ -259,6 +259,7 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
   const int len8 = Q8 ? (len + 15) & ~15 : (len + 7) & ~7;
 
   const int G = a.group;
+  const int cols = G * a.n_tok;                    // query rows of this (b, h): columns of the matrix instruction
   const int dk = a.d_k, dv = a.d_v;
   const int pitch_k = EB * dk, pitch_v = EB * dv;  // bytes
   // LDS slice of this wavefront: K area and V area, each a whole number of 1 KB wave-stores
@@ -334,16 +335,18 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
   }
   bf16x8 qf[KCH];
   {
-    const uint32_t* qrow = rope_q ? reinterpret_cast<const uint32_t*>(s_q) + (l16 < G ? l16 : 0) * a.n_pairs
+    // column c = token * G + head of the group (one token: c = head)
+    const int qc = l16 < cols ? l16 : 0, qt = a.n_tok > 1 ? qc / G : 0;
+    const uint32_t* qrow = rope_q ? reinterpret_cast<const uint32_t*>(s_q) + qc * a.n_pairs
                                   : reinterpret_cast<const uint32_t*>(a.q) +
-                                        (static_cast<long long>(b) * a.n_q + h * G + (l16 < G ? l16 : 0)) * a.n_pairs;
+                                        ((static_cast<long long>(b) * a.n_tok + qt) * a.n_q + h * G + (qc - qt * G)) * a.n_pairs;
 #pragma unroll
     for (int kk = 0; kk < KCH; ++kk) {
       uint32_t w[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int e = 32 * kk + 8 * lg + 2 * i;
-        w[i] = (l16 < G && e < dk) ? qrow[e >> 1] : 0u;
+        w[i] = (l16 < cols && e < dk) ? qrow[e >> 1] : 0u;
       }
       qf[kk] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
     }
@@ -542,15 +545,15 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
 #pragma unroll
   for (int reg = 0; reg < 4; ++reg) {
     const int g = 4 * lg + reg;
-    if (g < kMaxGroup) {
+    if (g < (a.n_tok > 1 ? kMaxCols : kMaxGroup)) {   // the hand-over area holds 8 columns, 16 with several tokens
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
         wm[32 + g * (16 * NT) + (VPAIR ? 32 * (nt >> 1) + 2 * l16 + (nt & 1) : 16 * nt + l16)] = acc[nt][reg];
     }
   }
   __syncthreads();
-  for (int e = tid; e < G * dv; e += 256) {
-    const int g = e / dv, c = e - g * dv;
+  for (int e = tid; e < cols * dv; e += 256) {
+    const int g = e / dv, c = e - g * dv;             // g: column
     float mw[4], mstar = -INFINITY;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
@@ -568,7 +571,8 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
       }
     }
     if constexpr (Q8) num *= a.v_scale[h];          // codes -> values
-    const long long hq = static_cast<long long>(b) * a.n_q + h * G + g;
+    const int qt = a.n_tok > 1 ? g / G : 0;
+    const long long hq = (static_cast<long long>(b) * a.n_tok + qt) * a.n_q + h * G + (g - qt * G);
     if (a.direct_out) {
       a.out[hq * dv + c] = den > 0.f ? num / den : 0.f;
     } else {
@@ -632,10 +636,10 @@ hipError_t launch_k(const DecodeArgs& a, hipStream_t stream) {
 
 // LDS bytes one wavefront needs: its K tile, its V tile and slack for the fragment reads that run
 // past the last row, or the hand-over area of the final fold, whichever is larger.
-int mfma_lds_wave_bytes(int d_k, int d_v, bool q8) {
+int mfma_lds_wave_bytes(int d_k, int d_v, bool q8, int n_tok) {
   const int nt = (d_v + 15) / 16;
   const int tiles = 1024 * (q8 ? (d_k + 31) / 32 + (nt + 1) / 2 : 2 * ((d_k + 31) / 32) + nt) + 128;
-  const int fold = (32 + kMaxGroup * 16 * nt) * 4;
+  const int fold = (32 + (n_tok > 1 ? kMaxCols : kMaxGroup) * 16 * nt) * 4;
   const int need = tiles > fold ? tiles : fold;
   return (need + 127) / 128 * 128;
 }

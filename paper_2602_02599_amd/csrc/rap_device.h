@@ -129,9 +129,16 @@ struct DecodeArgs {
   uint16_t* k_cache_w;
   uint16_t* v_cache_w;
   int32_t direct_out;       // one range and no combining kernel: the attention kernel writes out itself
+  // Several query tokens per sequence (n_tok > 1, n_tok * group <= 16; matrix-core kernel only):
+  // q is [B, n_tok, H_q, d_k], out [B, n_tok, H_q, d_v], the tokens are the last n_tok rows of
+  // their sequence and are already in the cache.  The scan covers the rows in front of them, which
+  // every token attends, with the n_tok * group query rows side by side as the columns of the
+  // matrix instruction; the causal part among the tokens themselves is added by the combining
+  // kernel, which always runs.  "Query row" below is then (b * n_tok + token) * H_q + head.
+  int32_t n_tok;
   float* out;          // [B, H_q, d_v]
-  float* part_acc;     // [B, H_q, n_split, d_v]   un-normalised accumulators
-  float* part_ml;      // [B, H_q, n_split, 2]     (running max in log2 units, running sum)
+  float* part_acc;     // [query rows, n_slots, d_v]   un-normalised accumulators
+  float* part_ml;      // [query rows, n_slots, 2]     (running max in log2 units, running sum)
   int32_t batch, n_q, n_kv, group, n_pairs, d_k, d_v;
   int32_t max_len, rows_per_split, n_split;
   int32_t n_slots;          // partial slots per query head: n_split, plus one in the decode step
@@ -183,6 +190,11 @@ __device__ __forceinline__ uint8_t f64_to_e4m3(double y) {
     bits |= 1u;
   }
   return static_cast<uint8_t>(__builtin_amdgcn_cvt_pk_fp8_f32(__uint_as_float(bits), 0.f, 0, false) & 0xff);
+}
+
+// value of one E4M3 code
+__device__ __forceinline__ float e4m3_to_f32(uint8_t code) {
+  return __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(code), false)[0];
 }
 
 // Row of the K / V cache that holds position t of sequence b for KV head h: a row of the dense

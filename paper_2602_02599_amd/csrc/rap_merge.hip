@@ -8,22 +8,103 @@
 // (ceil(len / rows_per_split) of them) were written by the first stage and only those are read.
 // In the one-call decode step there is one more slot behind the ranges, always written: the new
 // token on its own (m = its score, l = 1, acc = its V row, or m = -inf when it is not attended).
+// MULTI, several query tokens per sequence: the ranges stop in front of the new tokens' rows, and
+// the causal part among the tokens themselves (token t attends the new rows 0 .. t, at most 16) is
+// worked out here, by the workgroup of the query row: each thread multiplies one element of the
+// query row with the same element of the new K rows, the products are summed over the workgroup,
+// and the weighted new V rows enter the combination like one more range.
 #include "rap_device.h"
 
 namespace rap {
 
+constexpr int kMaxTok = 16;
+
+template <bool MULTI>
 __global__ __launch_bounds__(128) void merge_kernel(DecodeArgs a) {
-  const long long hq = blockIdx.x;                 // b * n_q + query head
-  const int b = static_cast<int>(hq / a.n_q);
+  const long long hq = blockIdx.x;                 // query row: (b * n_tok + token) * n_q + query head
+  const int b = static_cast<int>(hq / (static_cast<long long>(a.n_q) * a.n_tok));
   const int c = threadIdx.x;
   const bool live = c < a.d_v;
   const float* ml = a.part_ml + hq * a.n_slots * 2;
   const float* accc = a.part_acc + hq * a.n_slots * a.d_v + (live ? c : 0);
-  const bool tok = a.new_pos != nullptr;
-  const float m_tok = tok ? ml[2 * a.n_split] : -INFINITY;
-  const float l_tok = tok ? ml[2 * a.n_split + 1] : 0.f;
-  const float v_tok = tok ? accc[static_cast<long long>(a.n_split) * a.d_v] : 0.f;
-  const int t_new = tok ? a.new_pos[b] : -1;
+  const bool tok = a.n_slots > a.n_split;          // the slot behind the ranges is in use
+  float m_tok = tok ? ml[2 * a.n_split] : -INFINITY;
+  float l_tok = tok ? ml[2 * a.n_split + 1] : 0.f;
+  float v_tok = tok ? accc[static_cast<long long>(a.n_split) * a.d_v] : 0.f;
+  const int t_new = a.new_pos != nullptr ? a.new_pos[b] : -1;
+  if constexpr (MULTI) {
+    __shared__ float s_dot[2][kMaxTok];
+    const int T = a.n_tok, G = a.group;
+    const int t = static_cast<int>((hq / a.n_q) % T);           // this query row's token
+    const int h = static_cast<int>(hq % a.n_q) / G;             // and KV head
+    int len = a.seq_lens[b];
+    len = len < 0 ? 0 : (len > a.max_len ? a.max_len : len);
+    const int p0 = len - T;                                     // position of new token 0, may be negative
+    const bool q8 = a.k_scale != nullptr;
+    // row of the cache (dense) or of the pool (paged) that holds position pos >= 0
+    auto row_of = [&](int pos) -> long long {
+      if (a.block_table == nullptr) return (static_cast<long long>(b) * a.n_kv + h) * a.cap + pos;
+      int pg = a.block_table[static_cast<long long>(b) * a.max_pages + (pos >> a.page_shift)];
+      pg = pg < 0 ? 0 : (pg >= a.n_pages ? a.n_pages - 1 : pg);
+      return ((static_cast<long long>(pg) * a.n_kv + h) << a.page_shift) + (pos & ((1 << a.page_shift) - 1));
+    };
+    const bool have_k = c < a.d_k;
+    const float qv = have_k ? bf16_to_f32(a.q[hq * a.d_k + c]) : 0.f;
+    float prod[kMaxTok], vnew[kMaxTok];
+    // Every thread reads all 16 slots without a branch, so that the loads travel together: slot j
+    // beyond this token's own row repeats that row, a position in front of the sequence reads
+    // row 0; what such a slot holds is dropped below by a select.
+    const int ck = have_k ? c : 0, cv = live ? c : 0;
+    if (q8) {
+      const uint8_t* k8 = reinterpret_cast<const uint8_t*>(a.k_cache);
+      const uint8_t* v8 = reinterpret_cast<const uint8_t*>(a.v_cache);
+#pragma unroll
+      for (int j = 0; j < kMaxTok; ++j) {
+        const int pos = p0 + (j < t ? j : t);
+        const long long row = row_of(pos < 0 ? 0 : pos);
+        prod[j] = have_k ? qv * e4m3_to_f32(k8[row * a.d_k + ck]) : 0.f;
+        vnew[j] = e4m3_to_f32(v8[row * a.d_v + cv]);
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < kMaxTok; ++j) {
+        const int pos = p0 + (j < t ? j : t);
+        const long long row = row_of(pos < 0 ? 0 : pos);
+        prod[j] = have_k ? qv * bf16_to_f32(a.k_cache[row * a.d_k + ck]) : 0.f;
+        vnew[j] = bf16_to_f32(a.v_cache[row * a.d_v + cv]);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < kMaxTok; ++j) {
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) prod[j] += __shfl_xor(prod[j], o);
+    }
+    if ((c & 63) == 0) {
+#pragma unroll
+      for (int j = 0; j < kMaxTok; ++j) s_dot[c >> 6][j] = prod[j];
+    }
+    __syncthreads();
+    const float sc = q8 ? a.scale_log2e * a.k_scale[h] : a.scale_log2e;
+    float x[kMaxTok];
+    m_tok = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < kMaxTok; ++j) {
+      x[j] = (j <= t && p0 + j >= 0) ? (s_dot[0][j] + s_dot[1][j]) * sc : -INFINITY;
+      m_tok = fmaxf(m_tok, x[j]);
+    }
+    l_tok = 0.f;
+    v_tok = 0.f;
+    if (m_tok > -INFINITY) {
+#pragma unroll
+      for (int j = 0; j < kMaxTok; ++j) {
+        const bool in = j <= t && p0 + j >= 0;
+        const float pj = in ? exp2f(x[j] - m_tok) : 0.f;
+        l_tok += pj;
+        v_tok = fmaf(pj, in ? vnew[j] : 0.f, v_tok);            // a left-out slot may hold NaN or inf
+      }
+      if (q8) v_tok *= a.v_scale[h];
+    }
+  }
   // All slots of a query head are allocated, whatever they hold, so they are requested before the
   // sequence length is known, eight at a time: up to eight ranges cost one memory round trip (these
   // reads miss L2, the partials were written through other XCDs; wider groups were measured and
@@ -49,6 +130,7 @@ __global__ __launch_bounds__(128) void merge_kernel(DecodeArgs a) {
       int len = a.seq_lens[b];
       len = len < 0 ? 0 : (len > a.max_len ? a.max_len : len);
       if (len > 0 && t_new == len - 1) len -= 1;   // the first stage stopped before the new token's row
+      if (a.n_tok > 1) len = len > a.n_tok ? len - a.n_tok : 0;   // or before the new tokens' rows
       n = (len + a.rows_per_split - 1) / a.rows_per_split;   // ranges that hold rows
     }
     if (s0 >= n) break;
@@ -79,8 +161,11 @@ __global__ __launch_bounds__(128) void merge_kernel(DecodeArgs a) {
 }
 
 hipError_t launch_merge(const DecodeArgs& a, hipStream_t stream) {
-  dim3 grid(static_cast<unsigned>(a.batch) * a.n_q), block(128);
-  hipLaunchKernelGGL(merge_kernel, grid, block, 0, stream, a);
+  dim3 grid(static_cast<unsigned>(a.batch) * a.n_tok * a.n_q), block(128);
+  if (a.n_tok > 1)
+    hipLaunchKernelGGL(merge_kernel<true>, grid, block, 0, stream, a);
+  else
+    hipLaunchKernelGGL(merge_kernel<false>, grid, block, 0, stream, a);
   return hipGetLastError();
 }
 

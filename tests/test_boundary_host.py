@@ -156,6 +156,16 @@ def test_later_entry_points_reject_bad_arguments(rap):
     assert pf_ex(C.byref(KV(None, None, None, None, None)), n=0) == 0
     assert pf_ex(C.byref(KV(None, None, None, None, C.pointer(pg(page_rows=32, max_pages=16))))) == 3
     assert pf_ex(C.byref(KV(None, None, None, None, None)), msl=513) == 4
+    # several query tokens through the decode kernel: descriptor required, token count positive,
+    # at most 16 query rows per KV head (the default shape has 4 query heads per KV head)
+    def multi(cache, s=shp, n=2, msl=512):
+        return lib.rap_decode_attn_multi(C.byref(s), cache, n, None, None, msl, None, 0.1, None, 0, None, None)
+    assert multi(None) == 1
+    assert multi(C.byref(KV(None, None, 1, None, None))) == 1
+    assert multi(C.byref(KV(None, None, None, None, None)), n=0) == 2
+    assert multi(C.byref(KV(None, None, None, None, None)), s=_shape(rap, batch=0)) == 0
+    assert multi(C.byref(KV(None, None, None, None, None)), msl=513) == 4
+    assert multi(C.byref(KV(None, None, None, None, None))) == 1                  # stops at the null tensors
     # input check and workspace of the attention
     ci = lambda s, flags, n=1, msl=512: lib.rap_check_inputs(C.byref(s), n, None, None, None, msl, flags, None)
     assert ci(shp, None) == 1 and ci(_shape(rap, d_v=0), 1) == 2

@@ -577,6 +577,115 @@ def test_prefill_random_shapes(rap, seed):
     H.assert_attn_close(out.cpu().numpy(), ref, "random prefill")
 
 
+def _cache_of_any_kind(rap, rng, B, Hkv, P, dv, lens_np, fp8, page_rows):
+    """Seeded K / V caches of the asked kind (bf16 or E4M3 codes with scales, dense or pools with a
+    shuffled block table), NaN beyond every sequence and in unused pages.  Returns the dense numpy
+    arrays for the oracle and what the *_ex / *_multi calls take."""
+    unit = page_rows if page_rows else 16
+    cap = max(unit, (int(lens_np.max()) + unit - 1) // unit * unit)
+    if fp8:
+        ks = (rng.uniform(4.0, 6.0, Hkv) / 448.0).astype(np.float32)
+        vs = (rng.uniform(4.0, 6.0, Hkv) / 448.0).astype(np.float32)
+        kd = np.full((B, Hkv, cap, 2 * P), 0x7F, dtype=np.uint8); vd = np.full((B, Hkv, cap, dv), 0xFF, dtype=np.uint8)
+        for b in range(B):
+            n = int(lens_np[b])
+            kd[b, :, :n] = O.f64_to_e4m3_bits(rng.standard_normal((Hkv, n, 2 * P)) / ks.astype(np.float64)[:, None, None])
+            vd[b, :, :n] = O.f64_to_e4m3_bits(rng.standard_normal((Hkv, n, dv)) / vs.astype(np.float64)[:, None, None])
+        ksd, vsd = torch.from_numpy(ks).to(DEV), torch.from_numpy(vs).to(DEV)
+        fill_k, fill_v = 0x7F, 0xFF
+        to_dev = lambda x: torch.from_numpy(x).to(DEV)
+    else:
+        ks = vs = ksd = vsd = None
+        kd = np.full((B, Hkv, cap, 2 * P), 0x7FC0, dtype=np.uint16); vd = np.full((B, Hkv, cap, dv), 0x7FC0, dtype=np.uint16)
+        for b in range(B):
+            n = int(lens_np[b])
+            kd[b, :, :n] = O.f64_to_bf16_bits_rne(rng.standard_normal((Hkv, n, 2 * P)))
+            vd[b, :, :n] = O.f64_to_bf16_bits_rne(rng.standard_normal((Hkv, n, dv)))
+        fill_k = fill_v = 0x7FC0
+        to_dev = lambda x: I.from_bits(x, DEV)
+    pg, kdev, vdev = None, to_dev(kd), to_dev(vd)
+    if page_rows:
+        max_pages = cap // page_rows
+        n_pages = B * max_pages + 2
+        table = rng.permutation(n_pages)[:B * max_pages].reshape(B, max_pages).astype(np.int32)
+        kdev = to_dev(O.dense_to_paged_ref(kd, table, page_rows, n_pages, lens_np, fill=fill_k))
+        vdev = to_dev(O.dense_to_paged_ref(vd, table, page_rows, n_pages, lens_np, fill=fill_v))
+        pg = rap.paging(page_rows, n_pages, torch.from_numpy(table).to(DEV))
+    return cap, kd, vd, ks, vs, kdev, vdev, ksd, vsd, pg
+
+
+@pytest.mark.parametrize("fp8", [False, True])
+@pytest.mark.parametrize("P,dv,Hkv,G,n_tok,lens,page_rows", [
+    (45, 90, 2, 4, 4, [1300, 700, 3, 4, 0], 0), (58, 115, 2, 4, 3, [2100, 33], 32), (32, 64, 2, 5, 3, [900, 600], 64),
+    (64, 128, 1, 1, 16, [5000, 17, 16, 15], 128), (45, 90, 1, 8, 2, [4100, 2], 0), (3, 5, 3, 2, 7, [40, 100, 6], 0)])
+def test_decode_multi(rap, fp8, P, dv, Hkv, G, n_tok, lens, page_rows):
+    """rap_decode_attn_multi (a few query tokens per sequence through the decode kernel) against
+    the causal prefill oracle: token-times-group products up to 16, one and several row ranges,
+    sequences shorter than, as long as and longer than the token count, an empty one, every
+    cache kind; and against the prefill kernel's result for the same inputs (to fp32 rounding)."""
+    _say("decode multi fp8=%s P=%d dv=%d G=%d n_tok=%d lens=%s page_rows=%d" % (fp8, P, dv, G, n_tok, lens, page_rows))
+    lens_np = np.asarray(lens, dtype=np.int64)
+    B, Hq = len(lens), G * Hkv
+    rng = np.random.Generator(np.random.PCG64(9100 + P + n_tok))
+    cap, kd, vd, ks, vs, kdev, vdev, ksd, vsd, pg = _cache_of_any_kind(rap, rng, B, Hkv, P, dv, lens_np, fp8, page_rows)
+    gen = torch.Generator(device=DEV); gen.manual_seed(n_tok)
+    q = torch.randn((B, n_tok, Hq, 2 * P), generator=gen, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    sl = torch.from_numpy(lens_np.astype(np.int32)).to(DEV)
+    scale = 1.0 / math.sqrt(2 * P)
+    shp = rap.shape(B, Hq, Hkv, 128, P, dv, cap, 5e5)
+    ws = rap.new_workspace(shp, cap, n_tok=n_tok)
+    ws.fill_(0xFF)                                   # NaN bit patterns in every partial slot
+    out = torch.full((B, n_tok, Hq, dv), float("nan"), dtype=torch.float32, device=DEV)
+    rap.rap_decode_attn_multi(shp, kdev, vdev, ksd, vsd, pg, n_tok, q, sl, cap, out, scale, ws)
+    torch.cuda.synchronize()
+    if fp8:
+        ref = O.prefill_attn_q8_ref(I.bits(q), kd, vd, ks, vs, lens_np, scale)
+    else:
+        ref = O.prefill_attn_ref(I.bits(q), kd, vd, lens_np, scale)
+    H.assert_attn_close(out.cpu().numpy(), ref, "multi-token decode")
+    if page_rows == 0 or page_rows >= 64:
+        pre = torch.full_like(out, float("nan"))
+        rap.rap_prefill_attn_ex(shp, kdev, vdev, ksd, vsd, pg, n_tok, q, sl, cap, pre, scale)
+        torch.cuda.synchronize()
+        assert (out - pre).abs().max().item() <= 2e-5 * max(1.0, pre.abs().max().item())
+    # the same call twice gives the same bits
+    again = torch.full_like(out, float("nan"))
+    rap.rap_decode_attn_multi(shp, kdev, vdev, ksd, vsd, pg, n_tok, q, sl, cap, again, scale, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out, again)
+
+
+def test_decode_multi_one_token_and_rejections(rap):
+    """n_tok = 1 is rap_decode_attn bit for bit; more than 16 query rows per KV head, the
+    vector-ALU kernel and a workspace sized for one token are refused."""
+    _say("decode multi: one token, refusals")
+    P, dv, Hq, Hkv, lens = 45, 90, 8, 2, [1500, 64]
+    lens_np = np.asarray(lens, dtype=np.int64)
+    B = len(lens)
+    rng = np.random.Generator(np.random.PCG64(9200))
+    cap, kd, vd, _, _, kdev, vdev, _, _, _ = _cache_of_any_kind(rap, rng, B, Hkv, P, dv, lens_np, False, 0)
+    gen = torch.Generator(device=DEV); gen.manual_seed(3)
+    q = torch.randn((B, 1, Hq, 2 * P), generator=gen, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    sl = torch.from_numpy(lens_np.astype(np.int32)).to(DEV)
+    shp = rap.shape(B, Hq, Hkv, 128, P, dv, cap, 5e5)
+    ws = rap.new_workspace(shp, cap)
+    a = torch.full((B, 1, Hq, dv), float("nan"), dtype=torch.float32, device=DEV)
+    b = torch.full((B, Hq, dv), float("nan"), dtype=torch.float32, device=DEV)
+    rap.rap_decode_attn_multi(shp, kdev, vdev, None, None, None, 1, q, sl, cap, a, 0.1, ws)
+    rap.rap_decode_attn(shp, q[:, 0].contiguous(), kdev, vdev, sl, cap, b, 0.1, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(a[:, 0], b)
+    q5 = torch.zeros((B, 5, Hq, 2 * P), dtype=torch.bfloat16, device=DEV)
+    o5 = torch.zeros((B, 5, Hq, dv), dtype=torch.float32, device=DEV)
+    ws5 = rap.new_workspace(shp, cap, n_tok=5)
+    assert rap.rap_decode_attn_multi(shp, kdev, vdev, None, None, None, 5, q5, sl, cap, o5, 0.1, ws5, check=False) == 3   # 5 x 4 > 16
+    assert rap.rap_decode_attn_multi(shp, kdev, vdev, None, None, None, 4, q5, sl, cap, o5, 0.1, ws, check=False) == 5    # workspace of one token
+    assert rap.rap_decode_attn_multi(shp, kdev, vdev, None, None, None, 4, q5, sl, cap, o5, 0.1, ws5,
+                                     tuning=rap.tuning(kernel=1), check=False) == 3
+    assert rap.rap_decode_attn_multi(shp, kdev, vdev, None, None, None, 0, q5, sl, cap, o5, 0.1, ws5, check=False) == 2
+    assert rap.rap_decode_attn_multi(shp, kdev, vdev, None, None, None, 4, q5, sl, cap, o5, 0.1, ws5, check=False) == 0
+
+
 def test_prefill_last_row_is_decode(rap):
     """The last query of a prefill is the decode case: same numbers as rap_decode_attn (to fp32
     rounding: other tiling of the same sums)."""
