@@ -51,33 +51,39 @@ __global__ __launch_bounds__(128) void merge_kernel(DecodeArgs a) {
     const bool have_k = c < a.d_k;
     const float qv = have_k ? bf16_to_f32(a.q[hq * a.d_k + c]) : 0.f;
     float prod[kMaxTok], vnew[kMaxTok];
-    // Every thread reads all 16 slots without a branch, so that the loads travel together: slot j
-    // beyond this token's own row repeats that row, a position in front of the sequence reads
-    // row 0; what such a slot holds is dropped below by a select.
+    // The loads of all n_tok slots are issued first and used afterwards, so that they travel
+    // together: slot j beyond this token's own row repeats that row, a position in front of the
+    // sequence reads row 0; what such a slot holds is dropped below by a select.
     const int ck = have_k ? c : 0, cv = live ? c : 0;
-    if (q8) {
-      const uint8_t* k8 = reinterpret_cast<const uint8_t*>(a.k_cache);
-      const uint8_t* v8 = reinterpret_cast<const uint8_t*>(a.v_cache);
+    uint32_t kraw[kMaxTok], vraw[kMaxTok];
 #pragma unroll
-      for (int j = 0; j < kMaxTok; ++j) {
+    for (int j = 0; j < kMaxTok; ++j) {
+      kraw[j] = 0;
+      vraw[j] = 0;
+      if (j < T) {
         const int pos = p0 + (j < t ? j : t);
         const long long row = row_of(pos < 0 ? 0 : pos);
-        prod[j] = have_k ? qv * e4m3_to_f32(k8[row * a.d_k + ck]) : 0.f;
-        vnew[j] = e4m3_to_f32(v8[row * a.d_v + cv]);
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < kMaxTok; ++j) {
-        const int pos = p0 + (j < t ? j : t);
-        const long long row = row_of(pos < 0 ? 0 : pos);
-        prod[j] = have_k ? qv * bf16_to_f32(a.k_cache[row * a.d_k + ck]) : 0.f;
-        vnew[j] = bf16_to_f32(a.v_cache[row * a.d_v + cv]);
+        if (q8) {
+          kraw[j] = reinterpret_cast<const uint8_t*>(a.k_cache)[row * a.d_k + ck];
+          vraw[j] = reinterpret_cast<const uint8_t*>(a.v_cache)[row * a.d_v + cv];
+        } else {
+          kraw[j] = a.k_cache[row * a.d_k + ck];
+          vraw[j] = a.v_cache[row * a.d_v + cv];
+        }
       }
     }
 #pragma unroll
     for (int j = 0; j < kMaxTok; ++j) {
+      const float kf = q8 ? e4m3_to_f32(static_cast<uint8_t>(kraw[j])) : bf16_to_f32(static_cast<uint16_t>(kraw[j]));
+      vnew[j] = q8 ? e4m3_to_f32(static_cast<uint8_t>(vraw[j])) : bf16_to_f32(static_cast<uint16_t>(vraw[j]));
+      prod[j] = have_k ? qv * kf : 0.f;
+    }
 #pragma unroll
-      for (int o = 32; o >= 1; o >>= 1) prod[j] += __shfl_xor(prod[j], o);
+    for (int j = 0; j < kMaxTok; ++j) {
+      if (j < T) {
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) prod[j] += __shfl_xor(prod[j], o);
+      }
     }
     if ((c & 63) == 0) {
 #pragma unroll
