@@ -229,6 +229,34 @@ def q8_figure(rap, torch, job, steps, warmup):
     return res[0], res[1], job.bytes_per_step / 2
 
 
+def multi_figure(rap, torch, job, steps, warmup):
+    """rap_decode_attn_multi over the job's caches: the causal attention of the last n_tok rows of
+    every sequence, n_tok = 16 // G of them (the most one launch takes), the attention call alone."""
+    w = job.w
+    dev = job.out.device
+    n_tok = max(1, 16 // (w.n_q_heads // w.n_kv_heads))
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed + 11)
+    q = torch.randn((w.batch, n_tok, w.n_q_heads, w.d_k), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    out = torch.empty((w.batch, n_tok, w.n_q_heads, w.d_v), dtype=torch.float32, device=dev)
+    ws = rap.new_workspace(job.shape, job.max_len, None, device=dev, n_tok=n_tok)
+    n = len(job.cases)
+
+    def call(i):
+        c = job.cases[i % n]
+        rap.rap_decode_attn_multi(job.shape, c.k_cache, c.v_cache, None, None, None, n_tok, q, c.seq_lens, job.max_len, out,
+                                  float(w.scale), ws)
+
+    for i in range(warmup + 3 * n):
+        call(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        call(i)
+    torch.cuda.synchronize()
+    return n_tok, (time.perf_counter() - t0) / steps
+
+
 def read_traffic(path):
     """HBM bytes per launch of the dominant kernel from the committed counter summary, if present."""
     try:
@@ -291,7 +319,7 @@ def main():
     k_mean_ms, k_min_ms = job.kernel_ms(args.steps, ev)
     achieved = job.bytes_per_step / (k_mean_ms * 1e-3) / 1e9
 
-    q8 = None
+    q8 = multi = None
     if not args.no_q8:
         # last row of the path's follow-ups (not part of `value`): the same attention over fp8 caches
         s8, s16, b8 = q8_figure(rap, torch, job, args.steps, args.warmup)
@@ -299,6 +327,12 @@ def main():
               "ms": round(s8 * 1e3, 5), "value": round(b8 / s8 / 1e9, 2), "unit": "GB/s",
               "tokens_per_s": round(w.batch / s8, 1),
               "bf16_call_ms": round(s16 * 1e3, 5), "speedup_over_bf16_cache": round(s16 / s8, 4)}
+
+        # and a few query tokens per sequence (drafted tokens, short chunks) through the decode kernel
+        n_tok, sm = multi_figure(rap, torch, job, args.steps, args.warmup)
+        multi = {"call": "rap_decode_attn_multi (attention call alone, %d query tokens per sequence)" % n_tok,
+                 "n_tok": n_tok, "ms": round(sm * 1e3, 5), "one_token_call_ms": round(s16 * 1e3, 5),
+                 "query_tokens_per_s": round(w.batch * n_tok / sm, 1)}
 
     # what a trivial read-only kernel reaches over the same bytes, same run
     flat = torch.cat([c.k_cache.view(-1) for c in job.cases] + [c.v_cache.view(-1) for c in job.cases])
@@ -348,6 +382,7 @@ def main():
 
     if q8 is not None:
         result["fp8_cache"] = q8
+        result["multi_token"] = multi
 
     if not args.no_control and (args.workload + "_rho1") in I.WORKLOADS:
         case0 = job.cases[0]

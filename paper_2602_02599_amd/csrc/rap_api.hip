@@ -269,6 +269,7 @@ rap_status_t decode_impl(const DecodeRequest& r) {
   a.part_acc = static_cast<float*>(r.workspace);
   a.part_ml = r.workspace ? reinterpret_cast<float*>(static_cast<char*>(r.workspace) + part_acc_bytes(shape, p, r.n_tok)) : nullptr;
   a.n_tok = r.n_tok;
+  a.group_inv16 = (65536 + (shape->n_q_heads / shape->n_kv_heads) - 1) / (shape->n_q_heads / shape->n_kv_heads);
   a.batch = shape->batch;
   a.n_q = shape->n_q_heads;
   a.n_kv = shape->n_kv_heads;

@@ -336,10 +336,12 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
   bf16x8 qf[KCH];
   {
     // column c = token * G + head of the group (one token: c = head)
-    const int qc = l16 < cols ? l16 : 0, qt = a.n_tok > 1 ? qc / G : 0;
+    // (wave-uniform base, 32-bit lane offset)
+    const int qc = l16 < cols ? l16 : 0, qt = (qc * a.group_inv16) >> 16;   // qc / G, exact below 16
+    const uint32_t* qbase = reinterpret_cast<const uint32_t*>(a.q) +
+                            (static_cast<long long>(b) * a.n_tok * a.n_q + h * G) * a.n_pairs;
     const uint32_t* qrow = rope_q ? reinterpret_cast<const uint32_t*>(s_q) + qc * a.n_pairs
-                                  : reinterpret_cast<const uint32_t*>(a.q) +
-                                        ((static_cast<long long>(b) * a.n_tok + qt) * a.n_q + h * G + (qc - qt * G)) * a.n_pairs;
+                                  : qbase + (qt * a.n_q + (qc - qt * G)) * a.n_pairs;
 #pragma unroll
     for (int kk = 0; kk < KCH; ++kk) {
       uint32_t w[4];
@@ -571,8 +573,8 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
       }
     }
     if constexpr (Q8) num *= a.v_scale[h];          // codes -> values
-    const int qt = a.n_tok > 1 ? g / G : 0;
-    const long long hq = (static_cast<long long>(b) * a.n_tok + qt) * a.n_q + h * G + (g - qt * G);
+    const int qt = (g * a.group_inv16) >> 16;         // g / G
+    const long long hq = static_cast<long long>(b) * a.n_tok * a.n_q + h * G + (qt * a.n_q + (g - qt * G));
     if (a.direct_out) {
       a.out[hq * dv + c] = den > 0.f ? num / den : 0.f;
     } else {

@@ -136,6 +136,7 @@ struct DecodeArgs {
   // matrix instruction; the causal part among the tokens themselves is added by the combining
   // kernel, which always runs.  "Query row" below is then (b * n_tok + token) * H_q + head.
   int32_t n_tok;
+  int32_t group_inv16;      // ceil(65536 / group): (c * group_inv16) >> 16 == c / group for c < 16
   float* out;          // [B, H_q, d_v]
   float* part_acc;     // [query rows, n_slots, d_v]   un-normalised accumulators
   float* part_ml;      // [query rows, n_slots, 2]     (running max in log2 units, running sum)

@@ -655,6 +655,42 @@ def test_decode_multi(rap, fp8, P, dv, Hkv, G, n_tok, lens, page_rows):
     assert torch.equal(out, again)
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_decode_multi_random_shapes(rap, seed):
+    """rap_decode_attn_multi on shapes, token counts, cache kinds and page sizes drawn from a seed
+    (token count x group up to 16, lengths from empty to several row ranges), against the oracle."""
+    rng = np.random.Generator(np.random.PCG64(9300 + seed))
+    P, dv = int(rng.integers(1, 65)), int(rng.integers(1, 129))
+    G = int(rng.integers(1, 9))
+    n_tok = int(rng.integers(2, 16 // G + 1)) if 16 // G >= 2 else 1
+    Hkv, B = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+    lens = [int(rng.choice([0, 1, n_tok - 1, n_tok, n_tok + 1, int(rng.integers(2, 3000))])) for _ in range(B)]
+    lens[0] = int(rng.integers(600, 3000))
+    fp8 = bool(rng.integers(0, 2))
+    page_rows = int(rng.choice([0, 32, 64, 256]))
+    _say("multi random fp8=%s page_rows=%d P=%d dv=%d G=%d Hkv=%d n_tok=%d lens=%s" % (fp8, page_rows, P, dv, G, Hkv, n_tok, lens))
+    lens_np = np.asarray(lens, dtype=np.int64)
+    Hq = G * Hkv
+    cap, kd, vd, ks, vs, kdev, vdev, ksd, vsd, pg = _cache_of_any_kind(rap, rng, B, Hkv, P, dv, lens_np, fp8, page_rows)
+    gen = torch.Generator(device=DEV); gen.manual_seed(seed)
+    q = torch.randn((B, n_tok, Hq, 2 * P), generator=gen, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    sl = torch.from_numpy(lens_np.astype(np.int32)).to(DEV)
+    scale = 1.0 / math.sqrt(2 * P)
+    shp = rap.shape(B, Hq, Hkv, 128, P, dv, cap, 5e5)
+    rps = int(rng.choice([0, 128, 512]))
+    tun = rap.tuning(rows_per_split=rps)
+    ws = rap.new_workspace(shp, cap, tun, n_tok=n_tok)
+    ws.fill_(0xFF)
+    out = torch.full((B, n_tok, Hq, dv), float("nan"), dtype=torch.float32, device=DEV)
+    rap.rap_decode_attn_multi(shp, kdev, vdev, ksd, vsd, pg, n_tok, q, sl, cap, out, scale, ws, tuning=tun)
+    torch.cuda.synchronize()
+    if fp8:
+        ref = O.prefill_attn_q8_ref(I.bits(q), kd, vd, ks, vs, lens_np, scale)
+    else:
+        ref = O.prefill_attn_ref(I.bits(q), kd, vd, lens_np, scale)
+    H.assert_attn_close(out.cpu().numpy(), ref, "random multi-token decode")
+
+
 def test_decode_multi_one_token_and_rejections(rap):
     """n_tok = 1 is rap_decode_attn bit for bit; more than 16 query rows per KV head, the
     vector-ALU kernel and a workspace sized for one token are refused."""
