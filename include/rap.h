@@ -342,6 +342,20 @@ rap_status_t rap_prefill_attn_ex(const rap_shape_t* shape, const rap_kv_cache_t*
                                  const void* q, const int32_t* seq_lens, int64_t max_seq_len,
                                  void* out, float scale, void* stream);
 
+/* rap_prefill_attn_ex for launches that would otherwise leave most of the chip idle (a short chunk
+ * of new tokens at the end of long sequences, few sequences): with a workspace the rows a query
+ * block sees are cut into key ranges as well, each range a workgroup of its own, and a combining
+ * launch (the one of rap_decode_attn) follows.  Whether and how a launch is cut depends on the
+ * shape, n_new and max_seq_len alone: rap_prefill_attn_split_workspace_bytes returns the bytes
+ * needed, 0 when the launch is not cut (then workspace may be NULL and the call is
+ * rap_prefill_attn_ex).  A missing, misaligned (256 bytes) or too small workspace is
+ * RAP_ERR_WORKSPACE.  Results equal those of rap_prefill_attn_ex up to fp32 rounding. */
+size_t rap_prefill_attn_split_workspace_bytes(const rap_shape_t* shape, int32_t n_new, int64_t max_seq_len);
+rap_status_t rap_prefill_attn_split(const rap_shape_t* shape, const rap_kv_cache_t* cache, int32_t n_new,
+                                    const void* q, const int32_t* seq_lens, int64_t max_seq_len,
+                                    void* out, float scale,
+                                    void* workspace, size_t workspace_bytes, void* stream);
+
 /* Attention of a few query tokens per sequence at the speed of a decode step (verification of
  * drafted tokens, short chunks): the same result as rap_prefill_attn_ex with n_new = n_tok, i.e.
  * Eq. (attn) with the causal mask for the last n_tok rows of every sequence, which the append has

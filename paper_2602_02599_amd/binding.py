@@ -135,6 +135,11 @@ class Rap:
         L.rap_prefill_attn_ex.restype = C.c_int
         L.rap_prefill_attn_ex.argtypes = [C.POINTER(RapShape), C.POINTER(RapKvCache), C.c_int32, C.c_void_p, C.c_void_p,
                                           C.c_int64, C.c_void_p, C.c_float, C.c_void_p]
+        L.rap_prefill_attn_split_workspace_bytes.restype = C.c_size_t
+        L.rap_prefill_attn_split_workspace_bytes.argtypes = [C.POINTER(RapShape), C.c_int32, C.c_int64]
+        L.rap_prefill_attn_split.restype = C.c_int
+        L.rap_prefill_attn_split.argtypes = [C.POINTER(RapShape), C.POINTER(RapKvCache), C.c_int32, C.c_void_p, C.c_void_p,
+                                             C.c_int64, C.c_void_p, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]
         L.rap_decode_attn_multi.restype = C.c_int
         L.rap_decode_attn_multi.argtypes = [C.POINTER(RapShape), C.POINTER(RapKvCache), C.c_int32, C.c_void_p, C.c_void_p,
                                             C.c_int64, C.c_void_p, C.c_float, C.c_void_p, C.c_size_t,
@@ -375,6 +380,24 @@ class Rap:
         st = self.lib.rap_prefill_attn_ex(C.byref(shape), C.byref(cache), n_new, _ptr(q, torch.bfloat16, "q"),
                                           _ptr(seq_lens, torch.int32, "seq_lens"), max_seq_len,
                                           _ptr(out, torch.float32, "out"), scale, _stream(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def rap_prefill_attn_split_workspace_bytes(self, shape: RapShape, n_new: int, max_seq_len: int) -> int:
+        return int(self.lib.rap_prefill_attn_split_workspace_bytes(C.byref(shape), n_new, max_seq_len))
+
+    def rap_prefill_attn_split(self, shape: RapShape, k, v, k_scale, v_scale, paging: Optional[RapPaging], n_new: int, q,
+                               seq_lens, max_seq_len: int, out, scale: float, workspace, stream=None, check=True) -> int:
+        """rap_prefill_attn_ex with a workspace (uint8 tensor of rap_prefill_attn_split_workspace_bytes, or None)."""
+        el = torch.uint8 if k_scale is not None else torch.bfloat16
+        cache = RapKvCache(_ptr(k, el, "k"), _ptr(v, el, "v"), _ptr(k_scale, torch.float32, "k_scale"),
+                           _ptr(v_scale, torch.float32, "v_scale"), C.pointer(paging) if paging is not None else None)
+        st = self.lib.rap_prefill_attn_split(C.byref(shape), C.byref(cache), n_new, _ptr(q, torch.bfloat16, "q"),
+                                             _ptr(seq_lens, torch.int32, "seq_lens"), max_seq_len,
+                                             _ptr(out, torch.float32, "out"), scale, _ptr(workspace, None, "workspace"),
+                                             0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                             _stream(stream))
         if check:
             self._check(st)
         return st

@@ -340,10 +340,29 @@ bool live_call(const rap_shape_t* shape, int64_t max_seq_len) { return shape && 
 
 // Shared body of rap_prefill_attn, rap_prefill_attn_paged and rap_prefill_attn_ex (k_scale and
 // v_scale non-null: the caches hold E4M3 codes).
+// Workspace of the prefill attention with key ranges: partial accumulators [B * n_new * H_q,
+// n_ksplit, d_v] and (reference, sum) pairs, fp32, each block rounded up to 256 bytes; nothing
+// when the launch is not split.
+size_t prefill_part_acc_bytes(const rap_shape_t* s, int32_t n_new, const rap::PrefillPlan& p) {
+  return align_up(static_cast<size_t>(s->batch) * n_new * s->n_q_heads * p.n_ksplit * s->d_v * sizeof(float), 256);
+}
+size_t prefill_workspace_need(const rap_shape_t* s, int32_t n_new, const rap::PrefillPlan& p) {
+  if (p.n_ksplit <= 1) return 0;
+  return prefill_part_acc_bytes(s, n_new, p) +
+         align_up(static_cast<size_t>(s->batch) * n_new * s->n_q_heads * p.n_ksplit * 2 * sizeof(float), 256) + 256;
+}
+rap::PrefillPlan prefill_plan_of(const rap_shape_t* s, int32_t n_new, int64_t max_seq_len) {
+  return rap::prefill_plan(s->batch, s->n_kv_heads, s->n_q_heads / s->n_kv_heads, 2 * s->n_pairs, s->d_v, n_new,
+                           static_cast<int>(max_seq_len));
+}
+
+// `split`: the caller offers a workspace, so a launch whose query blocks would not fill the chip
+// is cut into key ranges as well and combined by a second launch.
 rap_status_t prefill_impl(const rap_shape_t* shape, const rap_paging_t* paging, int32_t n_new, const void* q,
                           const void* k_cache, const void* v_cache, const int32_t* seq_lens, int64_t max_seq_len,
                           void* out, float scale, void* stream, const float* k_scale = nullptr,
-                          const float* v_scale = nullptr) {
+                          const float* v_scale = nullptr, bool split = false, void* workspace = nullptr,
+                          size_t workspace_bytes = 0) {
   rap_status_t st = check_shape(shape);
   if (st != RAP_OK) return st;
   if ((k_scale == nullptr) != (v_scale == nullptr)) return RAP_ERR_NULL;
@@ -359,6 +378,13 @@ rap_status_t prefill_impl(const rap_shape_t* shape, const rap_paging_t* paging, 
   if (!q || !k_cache || !v_cache || !seq_lens || !out) return RAP_ERR_NULL;
   if (misaligned(k_cache, 16) || misaligned(v_cache, 16) || misaligned(q, 4) || misaligned(out, 4)) return RAP_ERR_SHAPE;
   if (static_cast<int64_t>(shape->batch) * n_new > kInt32Max) return RAP_ERR_UNSUPPORTED;
+  rap::PrefillPlan plan = prefill_plan_of(shape, n_new, max_seq_len);
+  if (!split) plan.n_ksplit = 1;
+  if (plan.n_ksplit > 1) {
+    if (!workspace || workspace_bytes < prefill_workspace_need(shape, n_new, plan) || misaligned(workspace, 256))
+      return RAP_ERR_WORKSPACE;
+    if (static_cast<int64_t>(shape->batch) * n_new * shape->n_q_heads > kInt32Max) return RAP_ERR_UNSUPPORTED;
+  }
   rap::PrefillArgs a;
   memset(&a, 0, sizeof(a));
   a.q = static_cast<const uint16_t*>(q);
@@ -384,7 +410,38 @@ rap_status_t prefill_impl(const rap_shape_t* shape, const rap_paging_t* paging, 
     a.n_pages = paging->n_pages;
     a.max_pages = paging->max_pages;
   }
-  return hip_status(rap::launch_prefill(a, static_cast<hipStream_t>(stream)));
+  a.n_ksplit = plan.n_ksplit;
+  if (plan.n_ksplit > 1) {
+    a.tiles_per_split = plan.tiles_per_split;
+    a.tok_per_wg = plan.tok_per_wg;
+    a.part_acc = static_cast<float*>(workspace);
+    a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + prefill_part_acc_bytes(shape, n_new, plan));
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (rap::launch_prefill(a, s) != hipSuccess) return RAP_ERR_HIP;
+  if (plan.n_ksplit > 1) {
+    // the combining kernel of the decode path, one block per (b, token, query head), every slot read
+    rap::DecodeArgs m;
+    memset(&m, 0, sizeof(m));
+    m.seq_lens = seq_lens;
+    m.out = a.out;
+    m.part_acc = a.part_acc;
+    m.part_ml = a.part_ml;
+    m.batch = a.batch;
+    m.n_tok = n_new;
+    m.n_q = a.n_q;
+    m.n_kv = a.n_kv;
+    m.group = a.group;
+    m.d_k = a.d_k;
+    m.d_v = a.d_v;
+    m.max_len = a.max_len;
+    m.rows_per_split = plan.tiles_per_split * 64;
+    m.n_split = plan.n_ksplit;
+    m.n_slots = plan.n_ksplit;
+    m.all_slots = 1;
+    if (rap::launch_merge(m, s) != hipSuccess) return RAP_ERR_HIP;
+  }
+  return RAP_OK;
 }
 
 }  // namespace
@@ -723,6 +780,20 @@ rap_status_t rap_prefill_attn_ex(const rap_shape_t* shape, const rap_kv_cache_t*
   if (!cache) return RAP_ERR_NULL;
   return prefill_impl(shape, cache->paging, n_new, q, cache->k, cache->v, seq_lens, max_seq_len, out, scale, stream,
                       cache->k_scale, cache->v_scale);
+}
+
+size_t rap_prefill_attn_split_workspace_bytes(const rap_shape_t* shape, int32_t n_new, int64_t max_seq_len) {
+  if (check_shape(shape) != RAP_OK || n_new < 1 || max_seq_len < 1 || max_seq_len > shape->cache_cap) return 0;
+  if (shape->batch == 0) return 0;
+  return prefill_workspace_need(shape, n_new, prefill_plan_of(shape, n_new, max_seq_len));
+}
+
+rap_status_t rap_prefill_attn_split(const rap_shape_t* shape, const rap_kv_cache_t* cache, int32_t n_new, const void* q,
+                                    const int32_t* seq_lens, int64_t max_seq_len, void* out, float scale,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
+  if (!cache) return RAP_ERR_NULL;
+  return prefill_impl(shape, cache->paging, n_new, q, cache->k, cache->v, seq_lens, max_seq_len, out, scale, stream,
+                      cache->k_scale, cache->v_scale, true, workspace, workspace_bytes);
 }
 
 rap_status_t rap_prefill_attn_paged(const rap_shape_t* shape, const rap_paging_t* paging, int32_t n_new, const void* q,

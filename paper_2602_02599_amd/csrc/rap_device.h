@@ -136,6 +136,7 @@ struct DecodeArgs {
   // matrix instruction; the causal part among the tokens themselves is added by the combining
   // kernel, which always runs.  "Query row" below is then (b * n_tok + token) * H_q + head.
   int32_t n_tok;
+  int32_t all_slots;        // combining kernel: every slot of every query row was written (prefill key ranges)
   int32_t group_inv16;      // ceil(65536 / group): (c * group_inv16) >> 16 == c / group for c < 16
   float* out;          // [B, H_q, d_v]
   float* part_acc;     // [query rows, n_slots, d_v]   un-normalised accumulators
@@ -169,7 +170,23 @@ struct PrefillArgs {
   int32_t shift_k, shift_v; // log2 of the cache row pitch when padded, else 31
   int64_t cap;
   float scale_log2e;
+  // Key ranges (n_ksplit > 1, for launches whose query blocks alone would not fill the chip): a
+  // query block is served by n_ksplit workgroups, each over tiles_per_split 64-row tiles of the
+  // rows it sees, which leave partials in the form of the decode kernel's (every slot of every
+  // query row is written, an empty range as reference -inf and sum 0); a combining launch follows.
+  int32_t n_ksplit;
+  int32_t tiles_per_split;
+  float* part_acc;          // [B * n_new * H_q, n_ksplit, d_v] un-normalised accumulators
+  float* part_ml;           // [B * n_new * H_q, n_ksplit, 2]   (reference in log2 units, sum)
 };
+
+// Key ranges per query block of a prefill launch, a function of the shape alone: none while the
+// query blocks number at least one and a half per CU or the context is short, else enough for
+// about 512 workgroups, none shorter than four tiles.
+struct PrefillPlan {
+  int tok_per_wg, n_qblk, n_ksplit, tiles_per_split;
+};
+PrefillPlan prefill_plan(int batch, int n_kv, int group, int d_k, int d_v, int n_new, int max_len);
 
 // fp64 -> E4M3 code (finite-only 8-bit float: 4 exponent bits, bias 7, 3 mantissa bits, no
 // infinity, S.1111.111 = NaN): nearest value, ties to the even mantissa, magnitudes above 448

@@ -132,7 +132,9 @@ __global__ __launch_bounds__(128) void merge_kernel(DecodeArgs a) {
       l[u] = have ? ml[2 * (s0 + u) + 1] : 0.f;
       v[u] = have ? accc[static_cast<long long>(s0 + u) * a.d_v] : 0.f;
     }
-    if (s0 == 0) {
+    if (s0 == 0 && a.all_slots) {
+      n = a.n_split;                               // prefill key ranges: every slot was written
+    } else if (s0 == 0) {
       int len = a.seq_lens[b];
       len = len < 0 ? 0 : (len > a.max_len ? a.max_len : len);
       if (len > 0 && t_new == len - 1) len -= 1;   // the first stage stopped before the new token's row
@@ -158,9 +160,10 @@ __global__ __launch_bounds__(128) void merge_kernel(DecodeArgs a) {
     }
 #pragma unroll
     for (int u = 0; u < kGroup; ++u) {
-      const float w = m[u] > -INFINITY ? exp2f(m[u] - mstar) : 0.f;
+      const bool has = m[u] > -INFINITY;           // an empty range leaves only its reference and sum
+      const float w = has ? exp2f(m[u] - mstar) : 0.f;
       den = fmaf(w, l[u], den);
-      num = fmaf(w, v[u], num);
+      num = fmaf(w, has ? v[u] : 0.f, num);
     }
   }
   if (live) a.out[hq * a.d_v + c] = den > 0.f ? num / den : 0.f;
@@ -168,7 +171,7 @@ __global__ __launch_bounds__(128) void merge_kernel(DecodeArgs a) {
 
 hipError_t launch_merge(const DecodeArgs& a, hipStream_t stream) {
   dim3 grid(static_cast<unsigned>(a.batch) * a.n_tok * a.n_q), block(128);
-  if (a.n_tok > 1)
+  if (a.n_tok > 1 && !a.all_slots)
     hipLaunchKernelGGL(merge_kernel<true>, grid, block, 0, stream, a);
   else
     hipLaunchKernelGGL(merge_kernel<false>, grid, block, 0, stream, a);

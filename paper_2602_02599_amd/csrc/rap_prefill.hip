@@ -83,8 +83,10 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   const int lg = lane >> 4;
 
   // heaviest query blocks (the last tokens, which see the most rows) first
+  // (with key ranges: consecutive workgroups are the ranges of one query block)
   const int slabs = a.n_kv * a.batch;
-  const int wg = blockIdx.x;
+  const int ks = a.n_ksplit > 1 ? static_cast<int>(blockIdx.x % a.n_ksplit) : 0;
+  const int wg = a.n_ksplit > 1 ? static_cast<int>(blockIdx.x / a.n_ksplit) : static_cast<int>(blockIdx.x);
   const int qb = a.n_qblk - 1 - wg / slabs;
   const int slab_id = wg - (wg / slabs) * slabs;
   const int h = slab_id % a.n_kv;
@@ -101,6 +103,20 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   const int n_keys = min(len, shift + i_end);      // rows the block's last token sees
   const long long out_row0 = (static_cast<long long>(b) * a.n_new) * a.n_q + h * G;   // + i * n_q + g
 
+  const int n_tiles_all = (n_keys + kKeysPerTile - 1) / kKeysPerTile;
+  const int t_first = ks * a.tiles_per_split;                       // key range of this workgroup, in tiles
+  const int n_tiles = a.n_ksplit > 1 ? min(n_tiles_all, t_first + a.tiles_per_split) : n_tiles_all;
+  if (a.n_ksplit > 1 && t_first >= n_tiles) {
+    // nothing of this range is visible to the block (or the block lies before the start of its
+    // sequence): empty partials, which the combining kernel drops
+    for (int r = tid; r < (i_end - i0) * G; r += 256) {
+      const int g = r % G, i = i0 + r / G;
+      const long long slot = (out_row0 + static_cast<long long>(i) * a.n_q + g) * a.n_ksplit + ks;
+      a.part_ml[slot * 2 + 0] = -INFINITY;
+      a.part_ml[slot * 2 + 1] = 0.f;
+    }
+    return;
+  }
   if (n_keys <= 0) {
     // every token of this block lies before the start of its sequence: zero rows
     for (int e = tid; e < (i_end - i0) * G * dv; e += 256) {
@@ -263,22 +279,21 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) voff[rt][r] = (16 * rt + 4 * lg + r) * lpv + (VPAIR ? 2 : 1) * EB * l16;
 
-  const int n_tiles = (n_keys + kKeysPerTile - 1) / kKeysPerTile;
   // start row of the tile whose loads are issued next, looked up (paged) one tile ahead of them
   long long trow_next;
   auto row_of_tile = [&](int t) -> long long { return t < n_tiles ? tile_row(t * kKeysPerTile) : 0; };
   if constexpr (DIRECT) {
-    issue_direct(0, row_of_tile(0));
-    trow_next = row_of_tile(1);
+    issue_direct(t_first, row_of_tile(t_first));
+    trow_next = row_of_tile(t_first + 1);
   } else {
-    issue(0, row_of_tile(0));
-    park(0);
+    issue(t_first, row_of_tile(t_first));
+    park(t_first & 1);
     __syncthreads();
-    if (n_tiles > 1) issue(1, row_of_tile(1));
-    trow_next = row_of_tile(2);
+    if (t_first + 1 < n_tiles) issue(t_first + 1, row_of_tile(t_first + 1));
+    trow_next = row_of_tile(t_first + 2);
   }
 
-  for (int t = 0; t < n_tiles; ++t) {
+  for (int t = t_first; t < n_tiles; ++t) {
     unsigned char* kt0 = smem + (t & 1) * a.lds_buf_bytes;
     unsigned char* vt0 = kt0 + v_off;
     if constexpr (DIRECT) {
@@ -503,7 +518,25 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
       const int cw = (wave * NQ + nq) * 16 + col;
       const int tl = cw / G, g = cw - (cw / G) * G;
       const int i = i0 + tl;
-      if (tl < BT && i < a.n_new) {
+      if (a.n_ksplit > 1) {
+        // partial of this key range: reference (log2 units), sum, un-normalised accumulators
+        const float mc = __shfl(m_run[nq], col);
+        if (tl < BT && i < a.n_new) {
+          const bool seen = shift + i >= 0 && mc > -INFINITY;
+          const long long slot = (out_row0 + static_cast<long long>(i) * a.n_q + g) * a.n_ksplit + ks;
+          if (l16 == 0) {
+            a.part_ml[slot * 2 + 0] = seen ? mc : -INFINITY;
+            a.part_ml[slot * 2 + 1] = seen ? lc : 0.f;
+          }
+          const float vsc = Q8 ? a.v_scale[h] : 1.f;      // codes -> values
+          float* prow = a.part_acc + slot * dv;
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            const int c = VPAIR ? 32 * (nt >> 1) + 2 * l16 + (nt & 1) : 16 * nt + l16;
+            if (c < dv) prow[c] = seen ? acc[nq][nt][reg] * vsc : 0.f;
+          }
+        }
+      } else if (tl < BT && i < a.n_new) {
         float inv = (shift + i >= 0 && lc > 0.f) ? 1.f / lc : 0.f;
         if constexpr (Q8) inv *= a.v_scale[h];       // codes -> values
         float* orow = a.out + (out_row0 + static_cast<long long>(i) * a.n_q + g) * dv;
@@ -542,6 +575,8 @@ hipError_t launch_prefill_go(const PrefillArgs& a, size_t lds, long long n_wg, h
 
 template <int KCH, int NT, bool VPAIR, int NQ>
 hipError_t launch_prefill_inst(PrefillArgs a, hipStream_t stream) {
+  // key ranges were planned for a block size: it has to be this instantiation's
+  if (a.n_ksplit > 1 && a.tok_per_wg != (64 * NQ) / a.group) return hipErrorInvalidValue;
   a.tok_per_wg = (64 * NQ) / a.group;
   a.n_qblk = (a.n_new + a.tok_per_wg - 1) / a.tok_per_wg;
   // padded LDS rows for pitches of 128 or 256 bytes (the shift turns a byte offset into its row)
@@ -554,7 +589,7 @@ hipError_t launch_prefill_inst(PrefillArgs a, hipStream_t stream) {
   const int kbytes = kKeysPerTile * (pk + a.pad_k), vbytes = kKeysPerTile * (pv + a.pad_v);
   a.lds_buf_bytes = ((kbytes + 64 + 127) & ~127) + ((vbytes + 64 + 127) & ~127);
   const size_t lds = 2 * static_cast<size_t>(a.lds_buf_bytes);
-  const long long n_wg = static_cast<long long>(a.n_qblk) * a.n_kv * a.batch;
+  const long long n_wg = static_cast<long long>(a.n_qblk) * a.n_kv * a.batch * (a.n_ksplit > 1 ? a.n_ksplit : 1);
   if (n_wg > 0x7fffffffLL) return hipErrorInvalidValue;
   // padded rows only occur at 128- and 256-byte pitches (d = 64, 128), where the kernel also has
   // registers to spare for staging
@@ -591,6 +626,27 @@ hipError_t launch_prefill_k(const PrefillArgs& a, hipStream_t stream) {
 }
 
 }  // namespace
+
+PrefillPlan prefill_plan(int batch, int n_kv, int group, int d_k, int d_v, int n_new, int max_len) {
+  // column blocks per wavefront as the instantiation table below picks them
+  const int kch = (d_k + 31) / 32, nt = (d_v + 15) / 16;
+  const int nq = (kch == 4 || nt >= 7) ? 2 : 4;
+  PrefillPlan p;
+  p.tok_per_wg = (64 * nq) / group;
+  p.n_qblk = (n_new + p.tok_per_wg - 1) / p.tok_per_wg;
+  p.n_ksplit = 1;
+  p.tiles_per_split = 0;
+  const long long base = static_cast<long long>(p.n_qblk) * n_kv * batch;
+  const int tiles = (max_len + kKeysPerTile - 1) / kKeysPerTile;
+  if (base > 0 && base < 384 && tiles >= 8) {
+    const int want = static_cast<int>((512 + base - 1) / base);
+    int per = (tiles + want - 1) / want;
+    if (per < 4) per = 4;
+    p.tiles_per_split = per;
+    p.n_ksplit = (tiles + per - 1) / per;
+  }
+  return p;
+}
 
 hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream) {
   switch ((a.d_k + 31) / 32) {

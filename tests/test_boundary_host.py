@@ -166,6 +166,18 @@ def test_later_entry_points_reject_bad_arguments(rap):
     assert multi(C.byref(KV(None, None, None, None, None)), s=_shape(rap, batch=0)) == 0
     assert multi(C.byref(KV(None, None, None, None, None)), msl=513) == 4
     assert multi(C.byref(KV(None, None, None, None, None))) == 1                  # stops at the null tensors
+    # prefill with key ranges: descriptor required; the size query answers 0 for what is not cut or not valid
+    def pf_split(cache, s=shp, n=4, msl=512, ws=None, nbytes=0):
+        return lib.rap_prefill_attn_split(C.byref(s), cache, n, None, None, msl, None, 0.1, ws, nbytes, None)
+    assert pf_split(None) == 1
+    assert pf_split(C.byref(KV(None, None, None, None, None)), n=0) == 0
+    assert pf_split(C.byref(KV(None, None, None, None, None)), msl=513) == 4
+    assert pf_split(C.byref(KV(None, None, None, None, None))) == 1                 # null tensors come first
+    assert rap.rap_prefill_attn_split_workspace_bytes(shp, 4, 512) > 0             # 2 x 2 query blocks, 8 tiles: cut
+    assert rap.rap_prefill_attn_split_workspace_bytes(shp, 4, 256) == 0            # short context: whole
+    assert rap.rap_prefill_attn_split_workspace_bytes(shp, 0, 512) == 0
+    assert rap.rap_prefill_attn_split_workspace_bytes(shp, 4, 513) == 0            # beyond the capacity
+    assert rap.rap_prefill_attn_split_workspace_bytes(_shape(rap, n_pairs=65), 4, 512) == 0
     # input check and workspace of the attention
     ci = lambda s, flags, n=1, msl=512: lib.rap_check_inputs(C.byref(s), n, None, None, None, msl, flags, None)
     assert ci(shp, None) == 1 and ci(_shape(rap, d_v=0), 1) == 2

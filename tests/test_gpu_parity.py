@@ -722,6 +722,62 @@ def test_decode_multi_one_token_and_rejections(rap):
     assert rap.rap_decode_attn_multi(shp, kdev, vdev, None, None, None, 4, q5, sl, cap, o5, 0.1, ws5, check=False) == 0
 
 
+@pytest.mark.parametrize("fp8", [False, True])
+@pytest.mark.parametrize("P,dv,Hkv,G,n_new,lens,page_rows", [
+    (45, 90, 2, 4, 100, [3000, 700, 40], 0),          # 12 key ranges; a short and a too-short sequence
+    (58, 115, 1, 4, 33, [5000, 4999], 64),            # odd d_v, pages of 64 rows
+    (64, 128, 2, 2, 300, [2500, 2100], 128),          # padded LDS rows, two column blocks
+    (32, 64, 1, 5, 17, [1100, 1], 0), (3, 5, 1, 1, 70, [777, 650, 0], 0),
+    (45, 90, 8, 4, 512, [4096], 0)])                  # a chunk at the end of one long sequence
+def test_prefill_split(rap, fp8, P, dv, Hkv, G, n_new, lens, page_rows):
+    """rap_prefill_attn_split (key ranges + combining launch) against the prefill oracle and
+    against the unsplit kernel, on launches small enough to be cut: every cache kind, ranges that
+    are empty for some or all tokens of a block, sequences shorter than the chunk."""
+    _say("prefill split fp8=%s P=%d dv=%d G=%d n_new=%d lens=%s page_rows=%d" % (fp8, P, dv, G, n_new, lens, page_rows))
+    lens_np = np.asarray(lens, dtype=np.int64)
+    B, Hq = len(lens), G * Hkv
+    rng = np.random.Generator(np.random.PCG64(9400 + P + n_new))
+    cap, kd, vd, ks, vs, kdev, vdev, ksd, vsd, pg = _cache_of_any_kind(rap, rng, B, Hkv, P, dv, lens_np, fp8, page_rows)
+    gen = torch.Generator(device=DEV); gen.manual_seed(n_new)
+    q = torch.randn((B, n_new, Hq, 2 * P), generator=gen, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    sl = torch.from_numpy(lens_np.astype(np.int32)).to(DEV)
+    scale = 1.0 / math.sqrt(2 * P)
+    shp = rap.shape(B, Hq, Hkv, 128, P, dv, cap, 5e5)
+    need = rap.rap_prefill_attn_split_workspace_bytes(shp, n_new, cap)
+    assert need > 0, "this case was meant to be cut into key ranges"
+    ws = torch.full((need,), 0xFF, dtype=torch.uint8, device=DEV)      # NaN bit patterns in every slot
+    out = torch.full((B, n_new, Hq, dv), float("nan"), dtype=torch.float32, device=DEV)
+    rap.rap_prefill_attn_split(shp, kdev, vdev, ksd, vsd, pg, n_new, q, sl, cap, out, scale, ws)
+    torch.cuda.synchronize()
+    if fp8:
+        ref = O.prefill_attn_q8_ref(I.bits(q), kd, vd, ks, vs, lens_np, scale)
+    else:
+        ref = O.prefill_attn_ref(I.bits(q), kd, vd, lens_np, scale)
+    H.assert_attn_close(out.cpu().numpy(), ref, "split prefill")
+    one = torch.full_like(out, float("nan"))
+    rap.rap_prefill_attn_ex(shp, kdev, vdev, ksd, vsd, pg, n_new, q, sl, cap, one, scale)
+    torch.cuda.synchronize()
+    assert (out - one).abs().max().item() <= 2e-5 * max(1.0, one.abs().max().item())
+    # a workspace one byte short, or none, is refused; a launch that is not cut needs none
+    assert rap.rap_prefill_attn_split(shp, kdev, vdev, ksd, vsd, pg, n_new, q, sl, cap, out, scale, ws[:need - 1], check=False) == 5
+    assert rap.rap_prefill_attn_split(shp, kdev, vdev, ksd, vsd, pg, n_new, q, sl, cap, out, scale, None, check=False) == 5
+
+
+def test_prefill_split_not_cut(rap):
+    """A launch with enough query blocks is not cut: no workspace asked for, same bits as rap_prefill_attn."""
+    _say("prefill split: large launch stays whole")
+    P, dv, Hq, Hkv, n_new, lens = 45, 90, 8, 2, 6200, [6200, 6200]
+    q, kc, vc, sl, cap, scale = _prefill_case(P, dv, Hq, Hkv, n_new, lens, seed=78)
+    shp = rap.shape(len(lens), Hq, Hkv, 128, P, dv, cap, 5.0e5)
+    assert rap.rap_prefill_attn_split_workspace_bytes(shp, n_new, cap) == 0
+    a = torch.full((len(lens), n_new, Hq, dv), float("nan"), dtype=torch.float32, device=DEV)
+    b = torch.full_like(a, float("nan"))
+    rap.rap_prefill_attn_split(shp, kc, vc, None, None, None, n_new, q, sl, cap, a, scale, None)
+    rap.rap_prefill_attn(shp, n_new, q, kc, vc, sl, cap, b, scale)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
 def test_prefill_last_row_is_decode(rap):
     """The last query of a prefill is the decode case: same numbers as rap_decode_attn (to fp32
     rounding: other tiling of the same sums)."""
