@@ -8,7 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librap.so")
-SOURCES = ["rap_api.hip", "rap_append.hip", "rap_decode_valu.hip", "rap_decode_mfma.hip", "rap_merge.hip", "rap_stream.hip", "rap_prefill.hip"]
+SOURCES = ["rap_api.hip", "rap_append.hip", "rap_decode_valu.hip", "rap_decode_mfma.hip", "rap_merge.hip", "rap_stream.hip", "rap_prefill.hip",
+           "rap_prefill_k1.hip", "rap_prefill_k2.hip", "rap_prefill_k3.hip", "rap_prefill_k4.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -20,7 +21,7 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose: bool = False, jobs: int = 6) -> str:
+def build(verbose: bool = False, jobs: int = 8) -> str:
     """Compile every source (in parallel) and link the shared library; returns its path."""
     bdir = os.path.join(HERE, "_build")
     os.makedirs(bdir, exist_ok=True)
