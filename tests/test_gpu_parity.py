@@ -1313,6 +1313,73 @@ def test_graph_replay(rap, one_call):
     H.assert_attn_close(out_s.cpu().numpy(), ref, "last replay against the oracle")
 
 
+def test_graph_replay_several_tokens(rap):
+    """The calls for several new tokens per step (append of the tokens, rap_decode_attn_multi, and
+    rap_prefill_attn_split over the same tokens) recorded once into a HIP graph and replayed three
+    times with new inputs in the same buffers: every replay gives the bits of the direct calls,
+    and the two attention calls agree with each other and, at the end, with the oracle."""
+    n_steps, n_tok = 3, 2
+    w = I.scaled(I.WORKLOADS["cfg2"], batch=3, n_q_heads=8, n_kv_heads=2, n_pairs=45, d_v=90, ctx=1500, n_new=n_steps * n_tok,
+                 ragged_min=600, peaky_frac=0.0, seed=4343)
+    _say("graph replay, two tokens per step")
+    case = I.make_case(w, device=DEV)
+    shp = H.shape_of(rap, case)
+    cap = int(case.cap)
+    prefill = torch.from_numpy(np.asarray(case.prefill_lens, dtype=np.int32)).to(DEV)
+    qs = [torch.randn((w.batch, n_tok, w.n_q_heads, w.d_k), generator=torch.Generator().manual_seed(60 + i)).to(torch.bfloat16).to(DEV)
+          for i in range(n_steps)]
+    ws = rap.new_workspace(shp, cap, None, n_tok=n_tok)
+    need = rap.rap_prefill_attn_split_workspace_bytes(shp, n_tok, cap)
+    assert need > 0
+    ws2 = torch.empty(need, dtype=torch.uint8, device=DEV)
+
+    def step(k2, v2, p2, q, kc, vc, sl, out_m, out_p):
+        rap.rap_rope_append(shp, n_tok, k2, v2, p2, case.keep, kc, vc)
+        rap.rap_decode_attn_multi(shp, kc, vc, None, None, None, n_tok, q, sl, cap, out_m, float(w.scale), ws)
+        rap.rap_prefill_attn_split(shp, kc, vc, None, None, None, n_tok, q, sl, cap, out_p, float(w.scale), ws2)
+
+    def inputs(i):
+        lo, hi = i * n_tok, (i + 1) * n_tok
+        return (case.k_new[:, lo:hi].contiguous(), case.v_new[:, lo:hi].contiguous(), case.pos[:, lo:hi].contiguous(),
+                qs[i], (prefill + hi).to(torch.int32))
+
+    def blank():
+        return torch.full((w.batch, n_tok, w.n_q_heads, w.d_v), float("nan"), dtype=torch.float32, device=DEV)
+
+    kc_e, vc_e = case.k_cache.clone(), case.v_cache.clone()
+    outs_e = []
+    for i in range(n_steps):
+        om, op = blank(), blank()
+        step(*inputs(i)[:4], kc_e, vc_e, inputs(i)[4], om, op)
+        torch.cuda.synchronize()
+        outs_e.append((om, op))
+        assert (om - op).abs().max().item() <= 2e-5 * max(1.0, op.abs().max().item())
+
+    kc_g, vc_g = case.k_cache.clone(), case.v_cache.clone()
+    k_s, v_s, p_s, q_s, sl_s = [t.clone() for t in inputs(0)]
+    om_s, op_s = blank(), blank()
+    step(k_s, v_s, p_s, q_s, kc_g, vc_g, sl_s, om_s, op_s)          # warm-up outside the recording (same tokens: idempotent)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step(k_s, v_s, p_s, q_s, kc_g, vc_g, sl_s, om_s, op_s)
+    for i in range(n_steps):
+        for dst, src in zip((k_s, v_s, p_s, q_s, sl_s), inputs(i)):
+            dst.copy_(src)
+        om_s.fill_(float("nan"))
+        op_s.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(om_s, outs_e[i][0]), "replay %d: multi-token output differs from the direct call" % i
+        assert torch.equal(op_s, outs_e[i][1]), "replay %d: split prefill output differs from the direct call" % i
+    assert torch.equal(kc_g, kc_e) and torch.equal(vc_g, vc_e)
+    lens = (np.asarray(case.prefill_lens) + n_steps * n_tok).astype(np.int64)
+    ref = O.prefill_attn_ref(I.bits(qs[-1]), I.bits(kc_g), I.bits(vc_g), lens, w.scale)
+    H.assert_attn_close(om_s.cpu().numpy(), ref, "last replay (multi-token decode) against the oracle")
+    H.assert_attn_close(op_s.cpu().numpy(), ref, "last replay (split prefill) against the oracle")
+
+
 def test_check_inputs(rap):
     """rap_check_inputs: clean inputs leave the flag word at zero; each kind of bad value sets its bit."""
     w = I.scaled(I.WORKLOADS["cfg2"], batch=3, n_q_heads=8, n_kv_heads=2, ctx=300, n_new=5, ragged_min=100, seed=77)
