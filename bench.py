@@ -187,6 +187,42 @@ def prefill_figure(rap, torch, w, dev, reps=5):
     return ms, flops
 
 
+def chunk_figure(rap, torch, w, dev, n_new=64, reps=10):
+    """A chunk of n_new tokens at the end of every sequence of the workload (chunked prefill,
+    drafted tokens beyond what rap_decode_attn_multi takes): rap_prefill_attn_ex as one launch
+    against rap_prefill_attn_split, which also cuts the context into key ranges."""
+    B, S = w.batch, w.ctx
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed + 3)
+    kc = torch.randn((B, w.n_kv_heads, S, w.d_k), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    vc = torch.randn((B, w.n_kv_heads, S, w.d_v), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    q = torch.randn((B, n_new, w.n_q_heads, w.d_k), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    sl = torch.full((B,), S, dtype=torch.int32, device=dev)
+    out = torch.empty((B, n_new, w.n_q_heads, w.d_v), dtype=torch.float32, device=dev)
+    shp = rap.shape(B, w.n_q_heads, w.n_kv_heads, w.d_head, w.n_pairs, w.d_v, S, w.rope_theta)
+    need = rap.rap_prefill_attn_split_workspace_bytes(shp, n_new, S)
+    ws = torch.empty(max(need, 1), dtype=torch.uint8, device=dev)
+    calls = (lambda: rap.rap_prefill_attn_ex(shp, kc, vc, None, None, None, n_new, q, sl, S, out, float(w.scale)),
+             lambda: rap.rap_prefill_attn_split(shp, kc, vc, None, None, None, n_new, q, sl, S, out, float(w.scale),
+                                                ws if need else None))
+    ms = []
+    for fn in calls:
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        ms.append(a.elapsed_time(b) / reps)
+    del kc, vc, q, out, ws
+    torch.cuda.empty_cache()
+    return {"call": "rap_prefill_attn_split", "tokens_per_sequence": n_new, "rows_per_sequence": S,
+            "ms_one_launch": round(ms[0], 4), "ms_key_ranges": round(ms[1], 4), "workspace_bytes": int(need)}
+
+
 def q8_figure(rap, torch, job, steps, warmup):
     """rap_decode_attn_q8 over fp8 (E4M3) caches of the same shape and lengths (random finite
     codes), the attention call alone; bytes are the one-byte rows actually read."""
@@ -413,6 +449,7 @@ def main():
             cms, cflops = prefill_figure(rap, torch, I.WORKLOADS[args.workload + "_rho1"], dev)
             pf["rho1_control"] = {"ms": round(cms, 4), "achieved": round(cflops / cms / 1e9, 1), "unit": "TFLOP/s",
                                   "speedup_of_pruned": round(cms / pms, 4), "flop_ratio": round(cflops / pflops, 4)}
+        pf["chunk"] = chunk_figure(rap, torch, w, dev)
         result["prefill"] = pf
 
     if not args.no_cpu:
