@@ -184,6 +184,30 @@ def test_later_entry_points_reject_bad_arguments(rap):
     assert ci(shp, 4, n=-1) == 2 and ci(shp, 4, msl=513) == 2 and ci(shp, 2) == 2      # misaligned flag word
 
 
+def test_prefill_split_plan_from_the_outside(rap):
+    """rap_prefill_attn_split_workspace_bytes over a grid of shapes: nothing while the query blocks
+    alone give at least 384 workgroups or the context is below 8 tiles of 64 rows, else room for
+    two or more ranges of partials (d_v + 2 floats per query row and range)."""
+    for batch, hq, hkv, n_pairs, dv in [(1, 32, 8, 45, 90), (2, 8, 2, 58, 115), (16, 32, 8, 64, 128), (3, 5, 1, 3, 5)]:
+        group = hq // hkv
+        nq = 2 if (2 * n_pairs > 96 or dv > 96) else 4            # column blocks per wavefront at these widths
+        tok_per_wg = 64 * nq // group
+        for n_new in (1, 16, 100, 512, 5000):
+            for max_len in (64, 448, 449, 512, 4096, 65536):
+                shp = _shape(rap, batch=batch, n_q_heads=hq, n_kv_heads=hkv, n_pairs=n_pairs, d_v=dv, cache_cap=65536)
+                need = rap.rap_prefill_attn_split_workspace_bytes(shp, n_new, max_len)
+                blocks = -(-n_new // tok_per_wg) * hkv * batch
+                tiles = -(-max_len // 64)
+                if blocks >= 384 or tiles < 8:
+                    assert need == 0, (batch, hq, n_new, max_len, need)
+                    continue
+                rows = batch * n_new * hq
+                per_range = rows * (dv + 2) * 4
+                # at most about 512 workgroups, and no range shorter than four tiles
+                most = min(-(-512 // blocks), -(-tiles // 4))
+                assert need % 256 == 0 and 2 * per_range <= need <= most * per_range + 1024, (batch, hq, n_new, max_len, need)
+
+
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(pkg.RapError):
         pkg.Rap(str(tmp_path / "librap.so"))
