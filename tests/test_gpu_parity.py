@@ -821,6 +821,44 @@ def test_prefill_cfg2_sampled(rap):
     H.assert_attn_close(np.array(got), np.array(ref), "prefill cfg2 sampled")
 
 
+@pytest.mark.parametrize("call,n_new", [("multi", 4), ("split", 64)])
+def test_cfg2_several_tokens_sampled(rap, call, n_new):
+    """The two calls for several new tokens at the sizes bench.py times them at (cfg2 shape: 16
+    sequences of 8192 rows, 32/8 heads, d = 90; four tokens through rap_decode_attn_multi, a chunk
+    of 64 through rap_prefill_attn_split), in the launch configuration of the bench: sampled
+    (b, token, head) rows against the oracle computed one by one, plus every token of one head."""
+    w = I.WORKLOADS["cfg2"]
+    B, S, Hq, Hkv, P, dv = w.batch, w.ctx, w.n_q_heads, w.n_kv_heads, w.n_pairs, w.d_v
+    _say("cfg2 full size, %s, %d tokens" % (call, n_new))
+    q, kc, vc, sl, cap, scale = _prefill_case(P, dv, Hq, Hkv, n_new, [S] * B, seed=6)
+    shp = rap.shape(B, Hq, Hkv, w.d_head, P, dv, cap, w.rope_theta)
+    out = torch.full((B, n_new, Hq, dv), float("nan"), dtype=torch.float32, device=DEV)
+    if call == "multi":
+        ws = rap.new_workspace(shp, cap, None, n_tok=n_new)
+        rap.rap_decode_attn_multi(shp, kc, vc, None, None, None, n_new, q, sl, cap, out, scale, ws)
+    else:
+        need = rap.rap_prefill_attn_split_workspace_bytes(shp, n_new, cap)
+        assert need > 0
+        ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+        rap.rap_prefill_attn_split(shp, kc, vc, None, None, None, n_new, q, sl, cap, out, scale, ws)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    rng = np.random.Generator(np.random.PCG64(4))
+    G = Hq // Hkv
+    picks = [(int(rng.integers(B)), int(rng.integers(n_new)), int(rng.integers(Hq))) for _ in range(40)]
+    picks += [(0, 0, 0), (B - 1, n_new - 1, Hq - 1)] + [(5, i, 9) for i in range(n_new)]
+    got, ref = [], []
+    for b, i, a_h in picks:
+        h = a_h // G
+        n_vis = S - n_new + i + 1                   # rows token i sees
+        kf = O.bf16_bits_to_f64(I.bits(kc[b, h, :n_vis]))
+        vf = O.bf16_bits_to_f64(I.bits(vc[b, h, :n_vis]))
+        qf = O.bf16_bits_to_f64(I.bits(q[b, i, a_h]))[None, :]
+        ref.append(O.attn_rows_ref(qf, kf, vf, scale)[0])
+        got.append(out[b, i, a_h].cpu().numpy())
+    H.assert_attn_close(np.array(got), np.array(ref), "cfg2 %s sampled" % call)
+
+
 def test_frequency_table(rap):
     """rap_shape_t.pair_inv_freq: a scaled frequency table with un-rotated pairs replaces rope_theta
     and keep_pair_idx in the per-token append, the run-based append, the fused query rotation and
