@@ -46,7 +46,8 @@ typedef enum rap_status {
  * (the half-apart pairing of Eq. (rope), restricted to the kept pairs: the row order of the
  * selection matrix E_k of Eq. (pruned-decomposition)).
  * Limits: 1 <= n_pairs <= d_head / 2, n_pairs <= 64, 1 <= d_v <= 128, G = n_q_heads / n_kv_heads
- * integral and <= 8, cache_cap a positive multiple of 8 (keeps every 8-row group of either
+ * integral and <= 16 (<= 8 for the vector-ALU kernel, the fused query rotation and the one-call
+ * step: RAP_ERR_UNSUPPORTED otherwise), cache_cap a positive multiple of 8 (keeps every 8-row group of either
  * cache 16-byte aligned, whatever the row width).
  */
 typedef struct rap_shape {

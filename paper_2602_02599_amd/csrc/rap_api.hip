@@ -19,7 +19,7 @@ hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStre
 hipError_t launch_stream_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 hipError_t launch_validate(const int32_t* pos, long long n_pos, long long cap, const int32_t* keep, int n_kv, int n_pairs,
                            int half, const int32_t* seq_lens, int batch, long long max_len, uint32_t* flags, hipStream_t stream);
-int mfma_lds_wave_bytes(int d_k, int d_v, bool q8, int n_tok);
+int mfma_lds_wave_bytes(int d_k, int d_v, bool q8, int cols);
 }  // namespace rap
 
 namespace {
@@ -40,7 +40,7 @@ rap_status_t check_shape(const rap_shape_t* s) {
   if (s->n_q_heads % s->n_kv_heads != 0) return RAP_ERR_SHAPE;
   if (s->n_pairs > s->d_head / 2) return RAP_ERR_SHAPE;
   if (s->cache_cap % 8 != 0) return RAP_ERR_SHAPE;
-  if (s->n_pairs > rap::kMaxPairs || s->d_v > rap::kMaxDv || s->n_q_heads / s->n_kv_heads > rap::kMaxGroup)
+  if (s->n_pairs > rap::kMaxPairs || s->d_v > rap::kMaxDv || s->n_q_heads / s->n_kv_heads > rap::kMaxGroupWide)
     return RAP_ERR_UNSUPPORTED;
   if (s->cache_cap > kInt32Max - 1024 || s->batch > 65535 || s->n_kv_heads > 65535) return RAP_ERR_UNSUPPORTED;
   return RAP_OK;
@@ -249,6 +249,8 @@ rap_status_t decode_impl(const DecodeRequest& r) {
     return RAP_ERR_UNSUPPORTED;
   // combinations no kernel is built for
   if ((r.fp8 || r.paging) && p.kernel != 2) return RAP_ERR_UNSUPPORTED;   // the vector-ALU kernel reads dense bf16 caches only
+  // more than 8 query heads per KV head: the matrix-core kernel with rotated queries only
+  if (shape->n_q_heads / shape->n_kv_heads > rap::kMaxGroup && (p.kernel != 2 || step || r.q_pos)) return RAP_ERR_UNSUPPORTED;
   if (r.fp8) {
     if (shape->cache_cap % 16 != 0) return RAP_ERR_SHAPE;
     if (!r.k_scale || !r.v_scale) return RAP_ERR_NULL;
@@ -283,7 +285,7 @@ rap_status_t decode_impl(const DecodeRequest& r) {
   a.n_slots = fused_step ? p.n_split + 1 : p.n_split;
   a.cap = shape->cache_cap;
   a.scale_log2e = r.scale * kLog2e;
-  a.lds_wave_bytes = rap::mfma_lds_wave_bytes(a.d_k, a.d_v, r.fp8, r.n_tok);
+  a.lds_wave_bytes = rap::mfma_lds_wave_bytes(a.d_k, a.d_v, r.fp8, r.n_tok * a.group);
   a.k_scale = r.fp8 ? r.k_scale : nullptr;
   a.v_scale = r.fp8 ? r.v_scale : nullptr;
   if (r.paging) {

@@ -547,7 +547,7 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
 #pragma unroll
   for (int reg = 0; reg < 4; ++reg) {
     const int g = 4 * lg + reg;
-    if (g < (a.n_tok > 1 ? kMaxCols : kMaxGroup)) {   // the hand-over area holds 8 columns, 16 with several tokens
+    if (g < (cols > kMaxGroup ? kMaxCols : kMaxGroup)) {   // the hand-over area holds 8 columns, or all 16 when more are in use
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
         wm[32 + g * (16 * NT) + (VPAIR ? 32 * (nt >> 1) + 2 * l16 + (nt & 1) : 16 * nt + l16)] = acc[nt][reg];
@@ -638,10 +638,10 @@ hipError_t launch_k(const DecodeArgs& a, hipStream_t stream) {
 
 // LDS bytes one wavefront needs: its K tile, its V tile and slack for the fragment reads that run
 // past the last row, or the hand-over area of the final fold, whichever is larger.
-int mfma_lds_wave_bytes(int d_k, int d_v, bool q8, int n_tok) {
+int mfma_lds_wave_bytes(int d_k, int d_v, bool q8, int cols) {
   const int nt = (d_v + 15) / 16;
   const int tiles = 1024 * (q8 ? (d_k + 31) / 32 + (nt + 1) / 2 : 2 * ((d_k + 31) / 32) + nt) + 128;
-  const int fold = (32 + (n_tok > 1 ? kMaxCols : kMaxGroup) * 16 * nt) * 4;
+  const int fold = (32 + (cols > kMaxGroup ? kMaxCols : kMaxGroup) * 16 * nt) * 4;
   const int need = tiles > fold ? tiles : fold;
   return (need + 127) / 128 * 128;
 }

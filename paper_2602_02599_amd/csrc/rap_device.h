@@ -12,7 +12,8 @@ namespace rap {
 constexpr int kWave = 64;            // CDNA wavefront width
 constexpr int kMaxPairs = 64;        // P <= 64  (d_k <= 128)
 constexpr int kMaxDv = 128;
-constexpr int kMaxGroup = 8;
+constexpr int kMaxGroup = 8;         // query heads per KV head: vector-ALU kernel, fused query rotation, one-call step
+constexpr int kMaxGroupWide = 16;    // the same for the matrix-core attention kernels (16 columns per instruction)
 constexpr int kSplitQuantum = 128;   // rows_per_split granularity
 
 // bf16 bit pattern -> fp32 (a bf16 is the upper half of a binary32)

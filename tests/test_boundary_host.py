@@ -58,7 +58,8 @@ def test_append_rejects_bad_arguments(rap):
     assert f(_shape(rap, rope_theta=0.0)) == 2
     assert f(_shape(rap, d_head=256, n_pairs=100)) == 3          # consistent but not built
     assert f(_shape(rap, d_v=200)) == 3
-    assert f(_shape(rap, n_q_heads=32, n_kv_heads=2)) == 3       # G = 16
+    assert f(_shape(rap, n_q_heads=34, n_kv_heads=2)) == 3       # G = 17
+    assert f(_shape(rap, n_q_heads=32, n_kv_heads=2)) == 1       # G = 16 is within the limits: stops at the null pointers
     assert f(_shape(rap), n=-1) == 2
 
 

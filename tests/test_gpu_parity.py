@@ -691,6 +691,65 @@ def test_decode_multi_random_shapes(rap, seed):
     H.assert_attn_close(out.cpu().numpy(), ref, "random multi-token decode")
 
 
+@pytest.mark.parametrize("fp8,page_rows", [(False, 0), (True, 0), (False, 64), (True, 128)])
+@pytest.mark.parametrize("P,dv,Hkv,G,lens", [(45, 90, 2, 16, [1700, 300, 0]), (58, 115, 1, 12, [2300, 5]), (64, 128, 2, 9, [900, 899])])
+def test_wide_groups(rap, fp8, page_rows, P, dv, Hkv, G, lens):
+    """More than eight query heads per KV head (up to 16: the columns of the matrix instruction):
+    rap_decode_attn over every cache kind and the prefill attention against their oracles; the
+    paths that stop at eight (vector-ALU kernel, fused query rotation, one-call step) say so."""
+    _say("wide groups fp8=%s page_rows=%d P=%d dv=%d G=%d lens=%s" % (fp8, page_rows, P, dv, G, lens))
+    lens_np = np.asarray(lens, dtype=np.int64)
+    B, Hq = len(lens), G * Hkv
+    rng = np.random.Generator(np.random.PCG64(9500 + P + G))
+    cap, kd, vd, ks, vs, kdev, vdev, ksd, vsd, pg = _cache_of_any_kind(rap, rng, B, Hkv, P, dv, lens_np, fp8, page_rows)
+    gen = torch.Generator(device=DEV); gen.manual_seed(G)
+    n_new = 40
+    q = torch.randn((B, n_new, Hq, 2 * P), generator=gen, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    sl = torch.from_numpy(lens_np.astype(np.int32)).to(DEV)
+    scale = 1.0 / math.sqrt(2 * P)
+    shp = rap.shape(B, Hq, Hkv, 128, P, dv, cap, 5e5)
+    # decode: the last token's queries
+    q1 = q[:, -1].contiguous()
+    for rps in (0, 256):
+        tun = rap.tuning(rows_per_split=rps)
+        ws = rap.new_workspace(shp, cap, tun)
+        ws.fill_(0xFF)
+        out = torch.full((B, 1, Hq, dv), float("nan"), dtype=torch.float32, device=DEV)
+        rap.rap_decode_attn_multi(shp, kdev, vdev, ksd, vsd, pg, 1, q1, sl, cap, out, scale, ws, tuning=tun)
+        torch.cuda.synchronize()
+        if fp8:
+            ref = O.attn_q8_ref(I.bits(q1), kd, vd, ks, vs, lens_np, scale)
+        else:
+            ref = O.attn_ref(I.bits(q1), kd, vd, lens_np, scale)
+        H.assert_attn_close(out[:, 0].cpu().numpy(), ref, "decode, G = %d, rows_per_split %d" % (G, rps))
+    # prefill of the last 40 tokens, whole and cut into key ranges
+    if page_rows == 0 or page_rows >= 64:
+        pre = torch.full((B, n_new, Hq, dv), float("nan"), dtype=torch.float32, device=DEV)
+        rap.rap_prefill_attn_ex(shp, kdev, vdev, ksd, vsd, pg, n_new, q, sl, cap, pre, scale)
+        need = rap.rap_prefill_attn_split_workspace_bytes(shp, n_new, cap)
+        pre2 = torch.full_like(pre, float("nan"))
+        rap.rap_prefill_attn_split(shp, kdev, vdev, ksd, vsd, pg, n_new, q, sl, cap, pre2, scale,
+                                   torch.empty(need, dtype=torch.uint8, device=DEV) if need else None)
+        torch.cuda.synchronize()
+        if fp8:
+            refp = O.prefill_attn_q8_ref(I.bits(q), kd, vd, ks, vs, lens_np, scale)
+        else:
+            refp = O.prefill_attn_ref(I.bits(q), kd, vd, lens_np, scale)
+        H.assert_attn_close(pre.cpu().numpy(), refp, "prefill, G = %d" % G)
+        H.assert_attn_close(pre2.cpu().numpy(), refp, "split prefill, G = %d" % G)
+    if not fp8 and page_rows == 0:
+        ws = rap.new_workspace(shp, cap)
+        out = torch.zeros((B, Hq, dv), dtype=torch.float32, device=DEV)
+        keep = torch.arange(P, dtype=torch.int32, device=DEV).repeat(Hkv, 1).contiguous()
+        pos = torch.zeros(B, dtype=torch.int32, device=DEV)
+        assert rap.rap_decode_attn(shp, q1, kdev, vdev, sl, cap, out, scale, ws, rap.tuning(kernel=1), check=False) == 3
+        assert rap.rap_decode_attn_rope(shp, q1, pos, keep, kdev, vdev, sl, cap, out, scale, ws, check=False) == 3
+        k1 = torch.zeros((B, Hkv, 2 * P), dtype=torch.bfloat16, device=DEV)
+        v1 = torch.zeros((B, Hkv, dv), dtype=torch.bfloat16, device=DEV)
+        assert rap.rap_decode_step(shp, k1, v1, pos, keep, q1, True, kdev, vdev, sl, cap, out, scale, ws, check=False) == 3
+        assert rap.rap_decode_attn(shp, q1, kdev, vdev, sl, cap, out, scale, ws) == 0
+
+
 def test_decode_multi_one_token_and_rejections(rap):
     """n_tok = 1 is rap_decode_attn bit for bit; more than 16 query rows per KV head, the
     vector-ALU kernel and a workspace sized for one token are refused."""
