@@ -13,6 +13,12 @@
  * other than RAP_OK is returned, no kernel has been enqueued by that call (except RAP_ERR_HIP,
  * which reports a launch failure of the HIP runtime).
  *
+ * Stream capture: the calls enqueue kernels only (no allocation, no memset, no copy), so a sequence
+ * of them can be recorded into a HIP graph.  One thing happens outside the stream: the first launch
+ * of a kernel variant that needs more than 64 KB of LDS raises that kernel's limit with
+ * hipFuncSetAttribute (once per device and variant), so make every call once, directly, with the
+ * shapes to be recorded, before recording it.
+ *
  * Element type of q, k_new, v_new and both caches is bfloat16 (upper half of an IEEE binary32),
  * arithmetic is fp32 (fp64 for the rotation angle), `out` is fp32.
  */
