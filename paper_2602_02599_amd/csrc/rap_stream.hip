@@ -6,12 +6,15 @@
 
 namespace rap {
 
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
+
+// (non-temporal loads, like the attention kernel's: the bytes are used once)
 __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ src, size_t n16, uint4* sink) {
   const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
   uint4 acc = make_uint4(0, 0, 0, 0);
   for (size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n16; i += stride) {
-    const uint4 v = src[i];
-    acc.x ^= v.x; acc.y ^= v.y; acc.z ^= v.z; acc.w ^= v.w;
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(src) + i);
+    acc.x ^= v[0]; acc.y ^= v[1]; acc.z ^= v[2]; acc.w ^= v[3];
   }
   // data-dependent store so the loads cannot be dropped; practically never taken for real data
   if ((acc.x & acc.y & acc.z & acc.w) == 0x9e3779b9u) *sink = acc;
