@@ -75,6 +75,8 @@ class Job:
         self.torch = torch
         self.rap = rap
         self.w = I.WORKLOADS[name]
+        if self.w.ragged_min is not None:
+            n_buf = 1     # ragged lengths differ from copy to copy (and so do the capacities); one copy is far beyond any cache
         self.cases = [I.make_case(I.scaled(self.w, seed=self.w.seed + 100 * i), device=device) for i in range(n_buf)]
         c0 = self.cases[0]
         w = self.w
@@ -400,7 +402,7 @@ def main():
         "dtype": "bf16 storage, f32 accumulate", "data": "synthetic",
         "config": {"workload": "%s: B=%d, %d/%d heads, ctx=%d, d_k=%d, d_v=%d, rho=%.1f, one layer; step = rap_rope_append(%d token/seq) + rap_decode_attn"
                                % (w.name, w.batch, w.n_q_heads, w.n_kv_heads, w.ctx, w.d_k, w.d_v, w.n_pairs / (w.d_head / 2), w.n_new),
-                   "cache_copies_rotated": args.buffers, "kv_bytes_per_step": int(job.bytes_per_step)},
+                   "cache_copies_rotated": len(job.cases), "kv_bytes_per_step": int(job.bytes_per_step)},
         "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
         "tokens_per_s": round(w.batch / sec, 1),
         "stream_read_GBps": round(stream_gbps, 1),
