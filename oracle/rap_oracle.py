@@ -15,6 +15,9 @@ Passages of the paper each function follows:
                            pair (j, j') rotated by R(t, theta_j),
                            theta_j = theta_base^(-2j/D), half-apart pairing
                            (x, x + D/2).
+  rope_full_adjacent,      the other pairing named under Eq. (rope): neighbouring dims
+  select_pairs_adjacent    (2x-1, 2x) in the paper's 1-based count, (2x, 2x+1) from 0; the
+                           selection E_k for that pairing in the compact order.
   rope_compact             Sec. "RAP", index-aware rotation on the compressed
                            matrices (original indices of the retained pairs);
                            App. "Method", Eq. (selection-rope-intertwine),
@@ -162,6 +165,31 @@ def rope_compact_freq(x: np.ndarray, t, pair_freq: np.ndarray) -> np.ndarray:
     c, s_ = np.cos(phi), np.sin(phi)
     a, b = x[..., :p], x[..., p:]
     return np.concatenate([a * c - b * s_, a * s_ + b * c], axis=-1)
+
+
+def rope_full_adjacent(x: np.ndarray, t, theta_base: float) -> np.ndarray:
+    """Full-width rotation of x[..., D] at position(s) t for models that pair NEIGHBOURING dims.
+
+    Pair j couples dims (2j, 2j + 1) counted from 0 (the paper counts from 1: (2x - 1, 2x)); the
+    block and the angle t * theta_j are those of Eq. (rope).  The result keeps the input's order.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    d = x.shape[-1]
+    phi = np.asarray(t, dtype=np.float64)[..., None] * inv_freq(theta_base, d)
+    c, s = np.cos(phi), np.sin(phi)
+    a, b = x[..., 0::2], x[..., 1::2]
+    out = np.empty(np.broadcast_shapes(x.shape, phi.shape[:-1] + (d,)), dtype=np.float64)
+    out[..., 0::2] = a * c - b * s
+    out[..., 1::2] = a * s + b * c
+    return out
+
+
+def select_pairs_adjacent(x_full: np.ndarray, keep: np.ndarray) -> np.ndarray:
+    """E_k for the neighbouring pairing, in the compact order of this library: the first members
+    of the kept pairs (dims 2 keep[c]), then their partners (dims 2 keep[c] + 1)."""
+    keep = np.asarray(keep)
+    idx = np.concatenate([2 * keep, 2 * keep + 1])
+    return np.asarray(x_full)[..., idx]
 
 
 def select_pairs(x_full: np.ndarray, keep: np.ndarray) -> np.ndarray:

@@ -177,6 +177,62 @@ def test_selection_matrix_facts():
     assert np.allclose(O.rope_full(x * np.diag(M), t, 1e4), O.rope_full(x, t, 1e4) * np.diag(M), atol=0)
 
 
+def test_adjacent_pairing_equals_complex_rotation():
+    """Sec. "Motivation", the other pairing named under Eq. (rope): neighbouring dims, (2x - 1, 2x)
+    counted from 1, i.e. (2j, 2j + 1) from 0, pair j at theta_j.  One pair at a time with cmath.
+    Catches half-apart pairing used by mistake, a 1-based frequency index, a flipped sine."""
+    rng = _rng(31)
+    d, theta = 16, 1.0e4
+    x = rng.standard_normal(d)
+    for t in [0, 1, 7, 1000, 131071]:
+        y = O.rope_full_adjacent(x, np.float64(t), theta)
+        for j in range(d // 2):
+            z = complex(x[2 * j], x[2 * j + 1]) * cmath.exp(1j * t * theta ** (-2.0 * j / d))
+            assert math.isclose(y[2 * j], z.real, rel_tol=0, abs_tol=1e-12)
+            assert math.isclose(y[2 * j + 1], z.imag, rel_tol=0, abs_tol=1e-12)
+    # (1, 0) in pair 0 (frequency 1) at angle pi/2 becomes (0, 1): the partner is the NEXT dim
+    y = O.rope_full_adjacent(np.array([1.0, 0.0, 0.0, 0.0]), np.float64(math.pi / 2), theta)
+    assert abs(y[0]) < 1e-15 and abs(y[1] - 1.0) < 1e-15 and y[2] == 0.0 and y[3] == 0.0
+    # and it differs from the half-apart rotation of the same row
+    assert np.max(np.abs(O.rope_full_adjacent(x, np.float64(7), theta) - O.rope_full(x, np.float64(7), theta))) > 1e-2
+
+
+def test_adjacent_pairing_needs_no_other_compact_rotation():
+    """A model that pairs neighbouring dims reaches the same compact row: rotate the full row with
+    the neighbouring pairing, select the kept pairs into [first members | partners], and the result
+    is, bit for bit, rope_compact of the selected un-rotated row (E_k R_t = R_{t,S} E_k for that
+    pairing's E_k).  So the library's compact layout and index-aware rotation serve both pairings;
+    only the offline selection differs.  Also: scores between two such rows equal the full-width
+    scores with the removed pairs zeroed."""
+    rng = _rng(32)
+    d, p = 128, 45
+    for trial in range(5):
+        keep = np.sort(rng.choice(d // 2, p, replace=False))
+        x = rng.standard_normal((3, d))
+        t = rng.integers(0, 131072, 3).astype(np.float64)
+        lhs = O.select_pairs_adjacent(O.rope_full_adjacent(x, t, 1.0e6), keep)
+        rhs = O.rope_compact(O.select_pairs_adjacent(x, keep), t, keep, 1.0e6, d)
+        assert np.array_equal(lhs, rhs)
+    # wrong frequency index (position in the compact row instead of the original pair) must differ
+    wrong = O.rope_compact(O.select_pairs_adjacent(x, keep), t, np.arange(p), 1.0e6, d)
+    assert np.max(np.abs(wrong - rhs)) > 1e-3
+    # selection facts for this E_k: a 0/1 matrix with orthonormal rows that keeps pairs together
+    E = O.select_pairs_adjacent(np.eye(16), np.array([1, 4, 6])).T
+    assert np.array_equal(E @ E.T, np.eye(6))
+    kept_dims = sorted(int(np.argmax(r)) for r in E)
+    assert kept_dims == [2, 3, 8, 9, 12, 13]
+    # masked-logit equivalence for the neighbouring pairing
+    q, k = rng.standard_normal(d), rng.standard_normal((6, d))
+    tq, tk = np.float64(900), np.arange(6, dtype=np.float64) + 890
+    mask = np.zeros(d)
+    mask[2 * keep] = 1.0
+    mask[2 * keep + 1] = 1.0
+    full = (O.rope_full_adjacent(q, tq, 5.0e5) * mask) @ (O.rope_full_adjacent(k, tk, 5.0e5) * mask).T
+    comp = O.rope_compact(O.select_pairs_adjacent(q, keep), tq, keep, 5.0e5, d) @ \
+        O.rope_compact(O.select_pairs_adjacent(k, keep), tk, keep, 5.0e5, d).T
+    assert np.allclose(full, comp, rtol=0, atol=1e-12)
+
+
 def test_relative_position_invariance():
     """R(t)^T R(u) = R(u - t): the score depends on the offset only, also on the compact row."""
     rng = _rng(8)
