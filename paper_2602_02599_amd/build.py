@@ -49,5 +49,22 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
     return LIB
 
 
+HOST_TEST_SRC = os.path.join(os.path.dirname(HERE), "tests", "host", "rap_arith_host.hip")
+HOST_TEST_BIN = os.path.join(HERE, "_build", "rap_arith_host")
+
+
+def build_host_tests() -> str:
+    """Compile the CPU-side harness around csrc/rap_arith.h (host pass of hipcc only, address and
+    undefined-behaviour sanitizers on); returns the path of the program.  No GPU is involved."""
+    os.makedirs(os.path.dirname(HOST_TEST_BIN), exist_ok=True)
+    cmd = [hipcc(), "--offload-host-only", "-O1", "-g", "-std=c++17", "-Xarch_host", "-fsanitize=address",
+           "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-sanitize-recover=undefined",
+           HOST_TEST_SRC, "-o", HOST_TEST_BIN]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("host test build failed:\n%s\n%s" % (" ".join(cmd), r.stdout))
+    return HOST_TEST_BIN
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

@@ -1,0 +1,112 @@
+// The pieces of librap's arithmetic and indexing that are our own and can go wrong silently: the
+// rounding to bf16, the sine / cosine of the rotation angle, the first (software) half of the
+// rounding to E4M3, and the rule that says which 16-byte loads of a cache tile are issued.  They
+// are plain functions of their arguments, compiled for the device and for the host, so that the
+// CPU tests run the very code the kernels run (tests/host/rap_arith_host.hip, under the host
+// sanitizers).
+#ifndef RAP_ARITH_H_
+#define RAP_ARITH_H_
+
+#include <hip/hip_runtime.h>
+
+#include <math.h>
+#include <stdint.h>
+
+namespace rap {
+
+__host__ __device__ __forceinline__ uint32_t f32_bits(float f) { return __builtin_bit_cast(uint32_t, f); }
+__host__ __device__ __forceinline__ float bits_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
+
+// bf16 bit pattern -> fp32 (a bf16 is the upper half of a binary32)
+__host__ __device__ __forceinline__ float bf16_lo(uint32_t packed) { return bits_f32(packed << 16); }
+__host__ __device__ __forceinline__ float bf16_hi(uint32_t packed) { return bits_f32(packed & 0xffff0000u); }
+__host__ __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return bits_f32(static_cast<uint32_t>(b) << 16); }
+
+// fp64 -> bf16 with a single round-to-nearest-even.  The conversion to fp32 (nearest even) cannot
+// carry a value across a bf16 rounding boundary, because every such boundary is an fp32 number; it
+// can only land ON one (low half exactly 0x8000) from either side.  In that case the fp32 is
+// moved one step back towards the side x came from, after which rounding the fp32 to its upper 16
+// bits gives the correctly rounded result.
+__host__ __device__ __forceinline__ uint16_t f64_to_bf16_rne(double x) {
+  const float f = static_cast<float>(x);
+  const uint32_t u0 = f32_bits(f);
+  const double fd = static_cast<double>(f);
+  uint32_t u = u0 + ((fabs(x) > fabs(fd)) ? 1u : 0u);               // sign-magnitude: +1 is away from zero
+  u -= (fabs(x) < fabs(fd)) ? 1u : 0u;
+  u = (u0 & 0xffffu) == 0x8000u ? u : u0;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<uint16_t>(x != x ? (u0 >> 16) | 0x40u : u >> 16);   // NaN stays NaN
+}
+
+// sin and cos of an fp64 angle, both within about 1.5e-16 of the true values for |phi| up to 2^31:
+// the nearest multiple of pi/2 is taken off with two fused multiply-adds against a two-part pi/2
+// (a fused multiply-add rounds once, after the cancellation), then Taylor polynomials up to
+// r^15 / r^16 on |r| <= pi/4, whose first left-out terms are below 5e-17.  The library routine
+// costs several times as much because it also covers angles beyond 2^31 with a table-driven
+// reduction.  Only multiplications, fused multiply-adds and one rounding to integer: the host and
+// the device compute the same bits.
+__host__ __device__ __forceinline__ void sincos_f64(double phi, double* s, double* c) {
+  const double k = rint(phi * 0.63661977236758134308);
+  double r = fma(-k, 1.5707963267948965580e+00, phi);
+  r = fma(-k, 6.1232339957367660359e-17, r);
+  const double z = r * r;
+  double ps = -1.0 / 1307674368000.0;                 // -1/15!
+  ps = fma(ps, z, 1.0 / 6227020800.0);
+  ps = fma(ps, z, -1.0 / 39916800.0);
+  ps = fma(ps, z, 1.0 / 362880.0);
+  ps = fma(ps, z, -1.0 / 5040.0);
+  ps = fma(ps, z, 1.0 / 120.0);
+  ps = fma(ps, z, -1.0 / 6.0);
+  const double sr = fma(r * z, ps, r);
+  double pc = 1.0 / 20922789888000.0;                 // 1/16!
+  pc = fma(pc, z, -1.0 / 87178291200.0);
+  pc = fma(pc, z, 1.0 / 479001600.0);
+  pc = fma(pc, z, -1.0 / 3628800.0);
+  pc = fma(pc, z, 1.0 / 40320.0);
+  pc = fma(pc, z, -1.0 / 720.0);
+  pc = fma(pc, z, 1.0 / 24.0);
+  pc = fma(pc, z, -0.5);
+  const double cr = fma(z, pc, 1.0);
+  const long long n = static_cast<long long>(k) & 3;   // quadrant
+  const double a = (n & 1) ? cr : sr, b = (n & 1) ? sr : cr;
+  *s = (n & 2) ? -a : a;
+  *c = ((n + 1) & 2) ? -b : b;
+}
+
+// First half of fp64 -> E4M3: the value, clamped to the largest E4M3 magnitude 448, brought to
+// fp32 by ROUNDING TO ODD (truncate towards zero, then set the last mantissa bit if anything was
+// cut off).  A value rounded to odd keeps every fact a later nearest-even rounding to a format at
+// least two bits shorter needs, so the conversion instruction that follows on the device
+// (fp32 -> E4M3, nearest even) yields the single correct rounding of the fp64 value.  NaN must be
+// handled by the caller.
+__host__ __device__ __forceinline__ float f64_to_f32_odd_clamped448(double y) {
+  y = y > 448.0 ? 448.0 : (y < -448.0 ? -448.0 : y);
+  const float f = static_cast<float>(y);            // nearest-even; repaired to round-to-odd below
+  uint32_t bits = f32_bits(f);
+  const double d = static_cast<double>(f);
+  if (d != y) {
+    if (fabs(d) > fabs(y)) bits -= 1u;              // went away from zero: step back to the truncation
+    bits |= 1u;
+  }
+  return bits_f32(bits);
+}
+
+// Which loads of a cache tile the decode kernel issues.  A tile (32 rows of any width: a multiple
+// of 64 bytes for two-byte elements, of 32 for one-byte ones, 16-byte aligned) is fetched as n_ld
+// wave-wide loads of 1 KB, lane l of load j taking bytes [1024 j + 16 l, + 16).  n_ld is fixed at
+// compile time from the instantiation (KCH = ceil(d_k / 32) score steps, NT = ceil(d_v / 16)
+// output tiles) and is the number of loads the tile needs, except for bf16 K tiles, where it can
+// exceed that by one whole load (2 KCH against ceil(d_k / 16)).  The last n_trim loads are
+// therefore trimmed to the tile by lane, all earlier ones are issued whole.  In a partial tile
+// (the last rows of a sequence) every load is trimmed to the bytes of the rows that exist.
+constexpr int k_tile_loads(int kch, bool q8) { return q8 ? kch : 2 * kch; }
+constexpr int v_tile_loads(int nt, bool q8) { return q8 ? (nt + 1) / 2 : nt; }
+constexpr int k_tile_trimmed(bool q8) { return q8 ? 1 : 2; }
+constexpr int v_tile_trimmed(bool) { return 1; }
+__host__ __device__ __forceinline__ bool tile_load_issued(int j, int lane, int n_ld, int n_trim, int bytes, bool whole_tile) {
+  if (whole_tile && j < n_ld - n_trim) return true;
+  return 1024 * j + 16 * lane < bytes;
+}
+
+}  // namespace rap
+#endif  // RAP_ARITH_H_

@@ -206,8 +206,9 @@ constexpr int kMaxCols = 16;   // columns of the matrix instruction: query rows 
 // the two scales fold into the softmax scale and into the partial sums.
 template <int KCH, int NT, bool VPAIR, bool PAGED, bool Q8>
 __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(DecodeArgs a) {
-  constexpr int NLD_K = Q8 ? KCH : 2 * KCH;        // 1 KB wave-loads covering a K tile (d_k <= 32 KCH)
-  constexpr int NLD_V = Q8 ? (NT + 1) / 2 : NT;    // same for a V tile (d_v <= 16 NT)
+  constexpr int NLD_K = k_tile_loads(KCH, Q8);     // 1 KB wave-loads covering a K tile (d_k <= 32 KCH)
+  constexpr int NLD_V = v_tile_loads(NT, Q8);      // same for a V tile (d_v <= 16 NT)
+  constexpr int TRIM_K = k_tile_trimmed(Q8), TRIM_V = v_tile_trimmed(Q8);   // trailing loads trimmed by lane
   constexpr int EB = Q8 ? 1 : 2;                   // bytes per cache element
   extern __shared__ __align__(16) unsigned char smem[];
 
@@ -304,31 +305,35 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
 #pragma unroll
   for (int j = 0; j < NLD_V; ++j) vst[j] = make_uint4(0, 0, 0, 0);
 
-  // does this lane's share of the last whole-KB load belong to the tile?
-  const bool k_last = 1024 * (NLD_K - 1) + 16 * lane < kTileRows * pitch_k;
-  const bool v_last = 1024 * (NLD_V - 1) + 16 * lane < kTileRows * pitch_v;
+  // A full tile is fetched with whole-KB loads except the last one or two of each run, which are
+  // trimmed to the tile's own bytes (tile_load_issued): nothing is fetched twice, nothing beyond
+  // the tile is touched.
+  bool k_tail[TRIM_K], v_tail[TRIM_V];
+#pragma unroll
+  for (int u = 0; u < TRIM_K; ++u) k_tail[u] = tile_load_issued(NLD_K - TRIM_K + u, lane, NLD_K, TRIM_K, kTileRows * pitch_k, true);
+#pragma unroll
+  for (int u = 0; u < TRIM_V; ++u) v_tail[u] = tile_load_issued(NLD_V - TRIM_V + u, lane, NLD_V, TRIM_V, kTileRows * pitch_v, true);
   auto issue_loads = [&](int base, long long trow) {
     const unsigned char* kg = kslab + trow * pitch_k + 16 * lane;
     const unsigned char* vg = vslab + trow * pitch_v + 16 * lane;
     if (base + kTileRows <= len8) {
-      // common case, a full tile: whole-KB loads, the last one of each run trimmed to the tile's
-      // own bytes so that nothing is fetched twice and nothing beyond row len8 is touched
+      // common case, a full tile
 #pragma unroll
-      for (int j = 0; j < NLD_K - 1; ++j) kst[j] = ld_stream(kg + 1024 * j);
-      if (k_last) kst[NLD_K - 1] = ld_stream(kg + 1024 * (NLD_K - 1));
+      for (int j = 0; j < NLD_K; ++j)
+        if (j < NLD_K - TRIM_K || k_tail[j < NLD_K - TRIM_K ? 0 : j - (NLD_K - TRIM_K)]) kst[j] = ld_stream(kg + 1024 * j);
 #pragma unroll
-      for (int j = 0; j < NLD_V - 1; ++j) vst[j] = ld_stream(vg + 1024 * j);
-      if (v_last) vst[NLD_V - 1] = ld_stream(vg + 1024 * (NLD_V - 1));
+      for (int j = 0; j < NLD_V; ++j)
+        if (j < NLD_V - TRIM_V || v_tail[j < NLD_V - TRIM_V ? 0 : j - (NLD_V - TRIM_V)]) vst[j] = ld_stream(vg + 1024 * j);
     } else {
       // last tiles of a sequence: read only rows [base, len8), chunk by chunk
       const int rows = min(kTileRows, len8 - base);   // multiple of 8
       const int kval = rows * pitch_k, vval = rows * pitch_v;
 #pragma unroll
       for (int j = 0; j < NLD_K; ++j)
-        if (1024 * j + 16 * lane < kval) kst[j] = ld_stream(kg + 1024 * j);
+        if (tile_load_issued(j, lane, NLD_K, TRIM_K, kval, false)) kst[j] = ld_stream(kg + 1024 * j);
 #pragma unroll
       for (int j = 0; j < NLD_V; ++j)
-        if (1024 * j + 16 * lane < vval) vst[j] = ld_stream(vg + 1024 * j);
+        if (tile_load_issued(j, lane, NLD_V, TRIM_V, vval, false)) vst[j] = ld_stream(vg + 1024 * j);
     }
   };
 
@@ -485,11 +490,17 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
       }
     }
     const bf16x8 pa_hi = __builtin_bit_cast(bf16x8, p_hi), pa_lo = __builtin_bit_cast(bf16x8, p_lo);
+    // V rows: as laid out, unless the tile is partial or holds the row that is left out.  Rows
+    // beyond the valid ones read the last valid row, the left-out row reads a valid neighbour
+    // (there is one: a left-out LAST row has shortened the sequence instead): their
+    // probabilities are 0, and 0 x (whatever bits such a row holds) must not reach the sums.
+    const bool plain = nv == kTileRows && static_cast<unsigned>(skip_rel) >= static_cast<unsigned>(kTileRows);
     int vo[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const int row = min(16 * (j >> 2) + 4 * lg + (j & 3), nv - 1);
-      vo[j] = nv == kTileRows ? voff[j >> 2][j & 3] : row * pitch_v + (VPAIR ? 2 : 1) * EB * l16;
+      int row = min(16 * (j >> 2) + 4 * lg + (j & 3), nv - 1);
+      row = row == skip_rel ? (skip_rel == 0 ? min(1, nv - 1) : skip_rel - 1) : row;
+      vo[j] = plain ? voff[j >> 2][j & 3] : row * pitch_v + (VPAIR ? 2 : 1) * EB * l16;
     }
     if constexpr (VPAIR) {
 #pragma unroll

@@ -7,6 +7,8 @@
 #include <atomic>
 #include <stdint.h>
 
+#include "rap_arith.h"
+
 namespace rap {
 
 constexpr int kWave = 64;            // CDNA wavefront width
@@ -15,61 +17,6 @@ constexpr int kMaxDv = 128;
 constexpr int kMaxGroup = 8;         // query heads per KV head: vector-ALU kernel, fused query rotation, one-call step
 constexpr int kMaxGroupWide = 16;    // the same for the matrix-core attention kernels (16 columns per instruction)
 constexpr int kSplitQuantum = 128;   // rows_per_split granularity
-
-// bf16 bit pattern -> fp32 (a bf16 is the upper half of a binary32)
-__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
-__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
-
-// fp64 -> bf16 with a single round-to-nearest-even.  The hardware conversion to fp32 (nearest
-// even) cannot carry a value across a bf16 rounding boundary, because every such boundary is an
-// fp32 number; it can only land ON one (low half exactly 0x8000) from either side.  In that case
-// the fp32 is moved one step back towards the side x came from, after which rounding the fp32 to
-// its upper 16 bits gives the correctly rounded result.
-__device__ __forceinline__ uint16_t f64_to_bf16_rne(double x) {
-  const float f = static_cast<float>(x);
-  const uint32_t u0 = __float_as_uint(f);
-  const double fd = static_cast<double>(f);
-  uint32_t u = u0 + ((fabs(x) > fabs(fd)) ? 1u : 0u);               // sign-magnitude: +1 is away from zero
-  u -= (fabs(x) < fabs(fd)) ? 1u : 0u;
-  u = (u0 & 0xffffu) == 0x8000u ? u : u0;
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return static_cast<uint16_t>(x != x ? (u0 >> 16) | 0x40u : u >> 16);   // NaN stays NaN
-}
-
-// sin and cos of an fp64 angle, both within about 1.5e-16 of the true values for |phi| up to 2^31
-// (checked on the host against long-double sinl/cosl): the nearest multiple of pi/2 is taken off
-// with two fused multiply-adds against a two-part pi/2 (a fused multiply-add rounds once, after
-// the cancellation), then Taylor polynomials up to r^15 / r^16 on |r| <= pi/4, whose first left-out
-// terms are below 5e-17.  The library routine costs several times as much because it also covers
-// angles beyond 2^31 with a table-driven reduction.
-__device__ __forceinline__ void sincos_f64(double phi, double* s, double* c) {
-  const double k = rint(phi * 0.63661977236758134308);
-  double r = fma(-k, 1.5707963267948965580e+00, phi);
-  r = fma(-k, 6.1232339957367660359e-17, r);
-  const double z = r * r;
-  double ps = -1.0 / 1307674368000.0;                 // -1/15!
-  ps = fma(ps, z, 1.0 / 6227020800.0);
-  ps = fma(ps, z, -1.0 / 39916800.0);
-  ps = fma(ps, z, 1.0 / 362880.0);
-  ps = fma(ps, z, -1.0 / 5040.0);
-  ps = fma(ps, z, 1.0 / 120.0);
-  ps = fma(ps, z, -1.0 / 6.0);
-  const double sr = fma(r * z, ps, r);
-  double pc = 1.0 / 20922789888000.0;                 // 1/16!
-  pc = fma(pc, z, -1.0 / 87178291200.0);
-  pc = fma(pc, z, 1.0 / 479001600.0);
-  pc = fma(pc, z, -1.0 / 3628800.0);
-  pc = fma(pc, z, 1.0 / 40320.0);
-  pc = fma(pc, z, -1.0 / 720.0);
-  pc = fma(pc, z, 1.0 / 24.0);
-  pc = fma(pc, z, -0.5);
-  const double cr = fma(z, pc, 1.0);
-  const long long n = static_cast<long long>(k) & 3;   // quadrant
-  const double a = (n & 1) ? cr : sr, b = (n & 1) ? sr : cr;
-  *s = (n & 2) ? -a : a;
-  *c = ((n + 1) & 2) ? -b : b;
-}
 
 // Angular frequency of compact pair idx = h * P + c: from the caller's table when there is one
 // (every entry is valid, 0 means "do not rotate"), else theta^(-2j/D) = 2^(j * (-2 log2(theta) / D))
@@ -200,15 +147,7 @@ PrefillPlan prefill_plan(int batch, int n_kv, int group, int d_k, int d_v, int n
 // saturates, hence the clamp to 448 in front of it.
 __device__ __forceinline__ uint8_t f64_to_e4m3(double y) {
   if (y != y) return 0x7f;
-  y = y > 448.0 ? 448.0 : (y < -448.0 ? -448.0 : y);
-  const float f = static_cast<float>(y);            // nearest-even; repaired to round-to-odd below
-  uint32_t bits = __float_as_uint(f);
-  const double d = static_cast<double>(f);
-  if (d != y) {
-    if (fabs(d) > fabs(y)) bits -= 1u;              // went away from zero: step back to the truncation
-    bits |= 1u;
-  }
-  return static_cast<uint8_t>(__builtin_amdgcn_cvt_pk_fp8_f32(__uint_as_float(bits), 0.f, 0, false) & 0xff);
+  return static_cast<uint8_t>(__builtin_amdgcn_cvt_pk_fp8_f32(f64_to_f32_odd_clamped448(y), 0.f, 0, false) & 0xff);
 }
 
 // value of one E4M3 code
