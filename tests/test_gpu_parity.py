@@ -1580,6 +1580,29 @@ def _sampled(w, n, seed):
     return sorted(picks)
 
 
+def test_cfg3_full(rap):
+    """Every output element of cfg3 against the oracle, slab by slab (256 (b, h) slabs of 32768 rows)."""
+    _say("cfg3 full")
+    _append_then_decode(rap, I.make_case(I.WORKLOADS["cfg3"], device=DEV))
+
+
+def test_cfg4_full(rap):
+    """Every output element of cfg4 (32 slabs of 131072 rows, 32 row ranges each)."""
+    _say("cfg4 full")
+    _append_then_decode(rap, I.make_case(I.WORKLOADS["cfg4"], device=DEV))
+
+
+@pytest.mark.parametrize("name", ["cfg5", "cfg5_rho1"])
+def test_cfg5_full(rap, name):
+    """Every output element of the ragged batch and of its rho = 1 control (512 slabs, lengths 512
+    to 65540, cache offsets beyond 2^32 bytes)."""
+    _say(name + " full")
+    case = I.make_case(I.WORKLOADS[name], device=DEV)
+    _append_then_decode(rap, case)
+    del case
+    torch.cuda.empty_cache()
+
+
 def test_cfg3_sampled(rap):
     _say("cfg3 sampled")
     w = I.WORKLOADS["cfg3"]
