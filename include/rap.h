@@ -39,7 +39,9 @@ typedef enum rap_status {
   RAP_ERR_UNSUPPORTED = 3, /* consistent, but outside what the kernels are built for            */
   RAP_ERR_CAPACITY = 4,    /* max_seq_len exceeds cache_cap                                     */
   RAP_ERR_WORKSPACE = 5,   /* workspace missing or smaller than rap_decode_attn_workspace_bytes */
-  RAP_ERR_HIP = 6          /* the HIP runtime refused a launch                                  */
+  RAP_ERR_HIP = 6,         /* the HIP runtime refused a launch                                  */
+  RAP_ERR_STATIC_LIMIT = 7 /* rap_decode_attn_static: the shape needs more scratch than
+                              RAP_STATIC_SCRATCH_BYTES                                          */
 } rap_status_t;
 
 /* Geometry of one attention layer and its compact cache.  Plain data, passed by const pointer.
@@ -151,6 +153,28 @@ rap_status_t rap_decode_attn(const rap_shape_t* shape, const void* q,
                              void* out, float scale,
                              void* workspace, size_t workspace_bytes,
                              const rap_tuning_t* tuning, void* stream);
+
+/* rap_decode_attn for callers that cannot allocate device memory and have no workspace to hand
+ * over: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * per-range partials go to a fixed array of RAP_STATIC_SCRATCH_BYTES bytes that lives in the
+ * library's device image (every GPU the library runs on holds its own copy until the process
+ * ends); its address on the current device is looked up on the first call there
+ * (hipGetSymbolAddress: make that first call outside any stream capture).  The call allocates
+ * nothing and frees nothing.  Same kernels, same results, bit for bit, as rap_decode_attn with a
+ * workspace of rap_decode_attn_workspace_bytes(shape, max_seq_len, tuning) bytes.
+ *
+ * A shape whose partials need more than the array holds is refused with RAP_ERR_STATIC_LIMIT and
+ * nothing is launched (the five benchmark configurations need 0.8, 4.3, 1.4 and 13.5 MB).
+ * Nothing in the array has to be zero beforehand and nothing is cleared: every slot that is read
+ * was written by the same call.  All calls on one GPU share that GPU's array: two such calls
+ * that overlap in time on one device (different streams, different host threads) race; calls on
+ * one stream, or otherwise ordered, are fine.  Arguments as in rap_decode_attn. */
+#define RAP_STATIC_SCRATCH_BYTES (16u << 20)
+rap_status_t rap_decode_attn_static(const rap_shape_t* shape, const void* q,
+                                    const void* k_cache, const void* v_cache,
+                                    const int32_t* seq_lens, int64_t max_seq_len,
+                                    void* out, float scale,
+                                    const rap_tuning_t* tuning, void* stream);
 
 /* The same attention with the query-side rotation fused in: q arrives pruned but UN-rotated and
  * is rotated at q_pos[b] by the index-aware RoPE of its KV head's kept pairs before the scores

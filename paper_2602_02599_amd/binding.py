@@ -54,7 +54,7 @@ class RapTuning(C.Structure):
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 
 STATUS = {0: "RAP_OK", 1: "RAP_ERR_NULL", 2: "RAP_ERR_SHAPE", 3: "RAP_ERR_UNSUPPORTED", 4: "RAP_ERR_CAPACITY",
-          5: "RAP_ERR_WORKSPACE", 6: "RAP_ERR_HIP"}
+          5: "RAP_ERR_WORKSPACE", 6: "RAP_ERR_HIP", 7: "RAP_ERR_STATIC_LIMIT"}
 
 
 def _ptr(t: Optional[torch.Tensor], dtype=None, name="tensor") -> C.c_void_p:
@@ -95,6 +95,9 @@ class Rap:
         L.rap_decode_attn.restype = C.c_int
         L.rap_decode_attn.argtypes = [C.POINTER(RapShape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                       C.c_void_p, C.c_float, C.c_void_p, C.c_size_t, C.POINTER(RapTuning), C.c_void_p]
+        L.rap_decode_attn_static.restype = C.c_int
+        L.rap_decode_attn_static.argtypes = [C.POINTER(RapShape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                             C.c_void_p, C.c_float, C.POINTER(RapTuning), C.c_void_p]
         L.rap_decode_attn_rope.restype = C.c_int
         L.rap_decode_attn_rope.argtypes = [C.POINTER(RapShape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                            C.c_void_p, C.c_int64, C.c_void_p, C.c_float, C.c_void_p, C.c_size_t,
@@ -213,6 +216,16 @@ class Rap:
                                       _ptr(workspace, None, "workspace"),
                                       0 if workspace is None else workspace.numel() * workspace.element_size(),
                                       C.byref(tuning) if tuning is not None else None, _stream(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def rap_decode_attn_static(self, shape: RapShape, q, k_cache, v_cache, seq_lens, max_seq_len: int, out, scale: float,
+                               tuning: Optional[RapTuning] = None, stream=None, check=True) -> int:
+        st = self.lib.rap_decode_attn_static(C.byref(shape), _ptr(q, torch.bfloat16, "q"), _ptr(k_cache, torch.bfloat16, "k_cache"),
+                                             _ptr(v_cache, torch.bfloat16, "v_cache"), _ptr(seq_lens, torch.int32, "seq_lens"),
+                                             max_seq_len, _ptr(out, torch.float32, "out"), scale,
+                                             C.byref(tuning) if tuning is not None else None, _stream(stream))
         if check:
             self._check(st)
         return st

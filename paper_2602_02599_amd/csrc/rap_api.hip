@@ -1,7 +1,8 @@
 // C ABI of librap: host-side validation, split planning and kernel dispatch.  See include/rap.h
 // for the contract of every entry point.  Each exported function fills a request record and hands
 // it to one of the two shared bodies below (append_impl, decode_impl); nothing here allocates,
-// synchronises or keeps state between calls.
+// synchronises or keeps state between calls (rap_decode_attn_static remembers, per device, where
+// its scratch array lives).
 #include <math.h>
 #include <string.h>
 
@@ -329,6 +330,27 @@ rap_status_t decode_impl(const DecodeRequest& r) {
   return RAP_OK;
 }
 
+// ---- scratch for the entry point that allocates nothing ------------------------------------------
+// The array lives in the device image of the library: each GPU holds its own copy at its own
+// address.  On the host its name is only a handle for hipGetSymbolAddress, never a device address;
+// kernels get the looked-up pointer as an argument, like any caller's workspace.
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[RAP_STATIC_SCRATCH_BYTES];
+
+std::atomic<void*> g_scratch_ptr[rap::kMaxDevicesRemembered];
+
+// Address of `scratch` on the current device, looked up once per device.
+rap_status_t static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= rap::kMaxDevicesRemembered) return RAP_ERR_HIP;
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (ptr == nullptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return RAP_ERR_HIP;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);   // a lost race between host threads repeats the lookup
+  }
+  *out = ptr;
+  return RAP_OK;
+}
+
 // rap_decode_attn_rope and its relatives take q_pos and keep_pair_idx as a pair: an argument the
 // call needs and does not get is RAP_ERR_NULL, but only once the shape itself has passed.
 rap_status_t null_after_shape(const rap_shape_t* shape) {
@@ -555,6 +577,33 @@ rap_status_t rap_decode_attn(const rap_shape_t* shape, const void* q, const void
   r.workspace_bytes = workspace_bytes;
   r.tuning = tuning;
   r.stream = stream;
+  return decode_impl(r);
+}
+
+rap_status_t rap_decode_attn_static(const rap_shape_t* shape, const void* q, const void* k_cache, const void* v_cache,
+                                    const int32_t* seq_lens, int64_t max_seq_len, void* out, float scale,
+                                    const rap_tuning_t* tuning, void* stream) {
+  DecodeRequest r;
+  r.shape = shape;
+  r.q = q;
+  r.k_cache = k_cache;
+  r.v_cache = v_cache;
+  r.seq_lens = seq_lens;
+  r.max_seq_len = max_seq_len;
+  r.out = out;
+  r.scale = scale;
+  r.tuning = tuning;
+  r.stream = stream;
+  // an invalid shape, length or tuning gives 0 here and its own error from decode_impl below
+  const size_t need = rap_decode_attn_workspace_bytes(shape, max_seq_len, tuning);
+  if (need > RAP_STATIC_SCRATCH_BYTES) return RAP_ERR_STATIC_LIMIT;
+  if (need > 0 && shape->batch > 0) {
+    void* ptr = nullptr;
+    const rap_status_t st = static_scratch(&ptr);
+    if (st != RAP_OK) return st;
+    r.workspace = ptr;
+    r.workspace_bytes = RAP_STATIC_SCRATCH_BYTES;
+  }
   return decode_impl(r);
 }
 
@@ -840,10 +889,11 @@ const char* rap_status_str(rap_status_t status) {
     case RAP_ERR_CAPACITY: return "max_seq_len exceeds cache capacity";
     case RAP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case RAP_ERR_HIP: return "HIP runtime error";
+    case RAP_ERR_STATIC_LIMIT: return "shape needs more scratch than the static array of rap_decode_attn_static holds";
   }
   return "unknown status";
 }
 
-int32_t rap_version(void) { return 800; }
+int32_t rap_version(void) { return 900; }
 
 }  // extern "C"
