@@ -1,22 +1,28 @@
 #!/usr/bin/env python3
 """Benchmark of the librap hot path on one MI355X.
 
-A step is one pass of the whole path over one batch: rap_rope_append of one new token per
-sequence, then rap_decode_attn over the compact cache.  Workload: the Llama-3.1-8B-shaped
-configuration at rho = 0.7 (batch 16, 32/8 heads, 8192 rows, d_k = d_v = 90, 1 % of K rows x8),
-seeded synthetic bf16 data already resident in HBM.  Successive steps rotate over several
+A step is one pass of the whole path over one batch: rap_rope_append of the new token(s) of every
+sequence, then rap_decode_attn over the compact cache.  Headline workload: the Llama-3.1-8B-shaped
+configuration at rho = 0.7 (cfg2: batch 16, 32/8 heads, 8192 rows, d_k = d_v = 90, 1 % of K rows
+x8), seeded synthetic bf16 data already resident in HBM.  Successive steps rotate over several
 distinct copies of the cache so that the working set exceeds L2 + Infinity Cache and the bytes
 really come from HBM.
 
-Prints ONE JSON line: whole-job throughput in algorithmic GB/s (K and V bytes that a decode step
-must read once, divided by the step time), the roofline object of the dominant kernel measured
-with HIP events on the launch stream, the float64 oracle timed on the host cores, and the
-rho = 1.0 control from the same code.
+Every timed figure is the MEDIAN over REPS repetitions of a block of exactly --steps steps (device
+synchronised on both sides of each block), with the fastest and slowest block beside it.
+
+Prints ONE compact JSON line: whole-job throughput in algorithmic GB/s (K and V bytes that a decode
+step must read once, divided by the step time), the roofline object of the dominant kernel measured
+with HIP events on the launch stream, the other four configurations and the rho = 1.0 controls from
+the same code (`configs`), the follow-up calls (one-call step, fp8 caches, several tokens, prefill)
+and the float64 oracle timed on the host cores.  The same figures with every detail go to
+gpurun_out/bench_detail.json when that directory can be written.
 """
 from __future__ import annotations
 
 import argparse
 import ctypes as C
+import hashlib
 import json
 import os
 import sys
@@ -30,6 +36,7 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+REPS = 11                        # repetitions of the --steps block behind every median
 
 
 class HipEvents:
@@ -67,6 +74,25 @@ def kv_bytes(w, seq_lens) -> int:
     return int(np.sum(seq_lens)) * w.n_kv_heads * (w.d_k + w.d_v) * 2
 
 
+def blocks(fn, steps, warmup, sync, reps=REPS):
+    """Seconds per step of `reps` blocks of exactly `steps` calls of fn(i), after `warmup` calls:
+    (median, min, max)."""
+    i = 0
+    for _ in range(warmup):
+        fn(i)
+        i += 1
+    out = []
+    for _ in range(reps):
+        sync()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn(i)
+            i += 1
+        sync()
+        out.append((time.perf_counter() - t0) / steps)
+    return float(np.median(out)), float(np.min(out)), float(np.max(out))
+
+
 class Job:
     """One workload with n_buf distinct cache copies, ready to step."""
 
@@ -85,14 +111,15 @@ class Job:
         self.ws = rap.new_workspace(self.shape, self.max_len, None, device=device)
         self.out = torch.empty((w.batch, w.n_q_heads, w.d_v), dtype=torch.float32, device=device)
         self.bytes_per_step = float(np.mean([kv_bytes(w, c.seq_lens.cpu().numpy()) for c in self.cases]))
-        self.i = 0
+        for c in self.cases:
+            c.k_new1, c.v_new1 = c.k_new[:, -1].contiguous(), c.v_new[:, -1].contiguous()
+            c.pos1 = c.pos[:, -1].contiguous()
 
-    def step(self, tuning=None, mode="two"):
+    def step(self, i, tuning=None, mode="two"):
         """One decode step.  mode "step": one rap_decode_step call (query already rotated);
         "step_rope": the same with the query rotation fused in; "two": rap_rope_append then
         rap_decode_attn.  Workloads that append several tokens per step always take "two"."""
-        c = self.cases[self.i % len(self.cases)]
-        self.i += 1
+        c = self.cases[i % len(self.cases)]
         w = self.w
         if w.n_new != 1 or mode == "two":
             self.rap.rap_rope_append(self.shape, w.n_new, c.k_new, c.v_new, c.pos, c.keep, c.k_cache, c.v_cache)
@@ -103,31 +130,50 @@ class Job:
                                      c.v_cache, c.seq_lens, self.max_len, self.out, float(w.scale), self.ws, tuning)
 
     def timed(self, steps, warmup, mode="two"):
-        torch = self.torch
-        for c in self.cases:
-            c.k_new1, c.v_new1 = c.k_new[:, -1].contiguous(), c.v_new[:, -1].contiguous()
-            c.pos1 = c.pos[:, -1].contiguous()
-        for _ in range(warmup):
-            self.step(mode=mode)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            self.step(mode=mode)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / steps
+        return blocks(lambda i: self.step(i, mode=mode), steps, warmup, self.torch.cuda.synchronize)
 
     def kernel_ms(self, steps, ev):
-        """Average duration of the partial-attention kernel alone, HIP events recorded by librap
-        around that launch on the launch stream."""
+        """Duration of the partial-attention kernel alone (mean, min over `steps` launches), HIP
+        events recorded by librap around that launch on the launch stream."""
         pairs = [(ev.create(), ev.create()) for _ in range(steps)]
-        for a, b in pairs:
-            self.step(self.rap.tuning(ev_main_start=a, ev_main_stop=b))
+        for i, (a, b) in enumerate(pairs):
+            self.step(i, self.rap.tuning(ev_main_start=a, ev_main_stop=b))
         self.torch.cuda.synchronize()
         ms = [ev.elapsed_ms(a, b) for a, b in pairs]
         for a, b in pairs:
             ev.destroy(a)
             ev.destroy(b)
         return float(np.mean(ms)), float(np.min(ms))
+
+    def figures(self, steps, warmup, ev):
+        """Step time (median of REPS blocks, with spread) and kernel time of this workload."""
+        med, lo, hi = self.timed(steps, warmup)
+        k_mean, k_min = self.kernel_ms(max(steps, 10), ev)
+        gbps = self.bytes_per_step / med / 1e9
+        k_gbps = self.bytes_per_step / (k_mean * 1e-3) / 1e9
+        return {"ms": med * 1e3, "ms_min": lo * 1e3, "ms_max": hi * 1e3, "GBps": gbps, "frac": gbps / HBM_PEAK_GBPS,
+                "k_ms": k_mean, "k_ms_min": k_min, "k_GBps": k_gbps, "k_frac": k_gbps / HBM_PEAK_GBPS,
+                "kv_bytes": int(self.bytes_per_step), "tokens_per_s": self.w.batch / med}
+
+    def stream_read_gbps(self, reps=10):
+        """What a trivial read-only kernel reaches over this job's cache bytes, same run."""
+        torch = self.torch
+        flat = torch.cat([c.k_cache.view(-1) for c in self.cases] + [c.v_cache.view(-1) for c in self.cases]) \
+            if len(self.cases) > 1 else None
+        bufs = [flat.view(torch.uint8)] if flat is not None else [self.cases[0].k_cache.view(-1).view(torch.uint8),
+                                                                  self.cases[0].v_cache.view(-1).view(torch.uint8)]
+        bufs = [b[:b.numel() // 16 * 16] for b in bufs]
+        sink = torch.zeros(16, dtype=torch.uint8, device=self.out.device)
+        for _ in range(3):
+            for b in bufs:
+                self.rap.rap_stream_read(b, sink)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            for b in bufs:
+                self.rap.rap_stream_read(b, sink)
+        torch.cuda.synchronize()
+        return sum(b.numel() for b in bufs) * reps / (time.perf_counter() - t0) / 1e9
 
 
 def cpu_baseline(I, case, min_seconds=10.0):
@@ -154,16 +200,14 @@ def cpu_baseline(I, case, min_seconds=10.0):
         threads = 1
     threads = min(threads, len(os.sched_getaffinity(0)))
     return {"value": round(kv_bytes(w, lens) * n / dt / 1e9, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
-            "sample": "%d whole steps of the same workload (append + attention, %d sequences x %d KV heads x %d rows), "
-                      "NumPy float64, %.1f s" % (n, w.batch, w.n_kv_heads, w.ctx, dt),
-            "tokens_per_s": round(w.batch * n / dt, 3), "host_cpus": len(os.sched_getaffinity(0))}
+            "sample": "%d whole steps of %s (append + attention), NumPy float64, %.1f s" % (n, w.name, dt),
+            "tokens_per_s": round(w.batch * n / dt, 2)}
 
 
 def prefill_figure(rap, torch, w, dev, reps=5):
     """Causal prefill attention (rap_prefill_attn) at the workload's shape: every sequence prefilled
     from scratch, HIP-event timing on torch's stream (the call is issued there).  Algorithmic
-    flops: 2 (d_k + d_v) per (query token, visible row, query head)."""
-    import math
+    flops: 2 (d_k + d_v) per (query token, visible row, query head).  Returns (median ms, flops)."""
     B, S = w.batch, w.ctx
     gen = torch.Generator(device=dev)
     gen.manual_seed(w.seed)
@@ -182,7 +226,7 @@ def prefill_figure(rap, torch, w, dev, reps=5):
         rap.rap_prefill_attn(shp, S, q, kc, vc, sl, S, out, float(w.scale))
         b.record()
     torch.cuda.synchronize()
-    ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+    ms = float(np.median([a.elapsed_time(b) for a, b in evs]))
     flops = B * w.n_q_heads * (S * (S + 1) / 2) * 2 * (w.d_k + w.d_v)
     del kc, vc, q, out
     torch.cuda.empty_cache()
@@ -192,7 +236,7 @@ def prefill_figure(rap, torch, w, dev, reps=5):
 def chunk_figure(rap, torch, w, dev, n_new=64, reps=10):
     """A chunk of n_new tokens at the end of every sequence of the workload (chunked prefill,
     drafted tokens beyond what rap_decode_attn_multi takes): rap_prefill_attn_ex as one launch
-    against rap_prefill_attn_split, which also cuts the context into key ranges."""
+    against rap_prefill_attn_split, which also cuts the context into key ranges.  ms of each."""
     B, S = w.batch, w.ctx
     gen = torch.Generator(device=dev)
     gen.manual_seed(w.seed + 3)
@@ -221,13 +265,13 @@ def chunk_figure(rap, torch, w, dev, n_new=64, reps=10):
         ms.append(a.elapsed_time(b) / reps)
     del kc, vc, q, out, ws
     torch.cuda.empty_cache()
-    return {"call": "rap_prefill_attn_split", "tokens_per_sequence": n_new, "rows_per_sequence": S,
-            "ms_one_launch": round(ms[0], 4), "ms_key_ranges": round(ms[1], 4), "workspace_bytes": int(need)}
+    return ms
 
 
 def q8_figure(rap, torch, job, steps, warmup):
     """rap_decode_attn_q8 over fp8 (E4M3) caches of the same shape and lengths (random finite
-    codes), the attention call alone; bytes are the one-byte rows actually read."""
+    codes) and rap_decode_attn over the bf16 caches, each attention call alone: seconds per call
+    (medians), and the one-byte rows actually read."""
     w = job.w
     dev = job.out.device
     cap = (max(c.cap for c in job.cases) + 15) // 16 * 16
@@ -254,17 +298,11 @@ def q8_figure(rap, torch, job, steps, warmup):
         c = job.cases[i % n]
         rap.rap_decode_attn(job.shape, c.q, c.k_cache, c.v_cache, c.seq_lens, job.max_len, job.out, float(w.scale), job.ws, None)
 
-    res = []
-    for fn in (call, call16):
-        for i in range(warmup + 3 * n):
-            fn(i)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(steps):
-            fn(i)
-        torch.cuda.synchronize()
-        res.append((time.perf_counter() - t0) / steps)
-    return res[0], res[1], job.bytes_per_step / 2
+    s8 = blocks(call, steps, warmup + 3 * n, torch.cuda.synchronize)[0]
+    s16 = blocks(call16, steps, warmup + 3 * n, torch.cuda.synchronize)[0]
+    del pools
+    torch.cuda.empty_cache()
+    return s8, s16, job.bytes_per_step / 2
 
 
 def multi_figure(rap, torch, job, steps, warmup):
@@ -285,18 +323,25 @@ def multi_figure(rap, torch, job, steps, warmup):
         rap.rap_decode_attn_multi(job.shape, c.k_cache, c.v_cache, None, None, None, n_tok, q, c.seq_lens, job.max_len, out,
                                   float(w.scale), ws)
 
-    for i in range(warmup + 3 * n):
-        call(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(steps):
-        call(i)
-    torch.cuda.synchronize()
-    return n_tok, (time.perf_counter() - t0) / steps
+    return n_tok, blocks(call, steps, warmup + 3 * n, torch.cuda.synchronize)[0]
+
+
+KERNEL_SOURCES = ("rap_decode_mfma.hip", "rap_device.h", "rap_arith.h")
+
+
+def kernel_source_id():
+    """Short hash of the sources of the dominant kernel (what a committed counter summary was measured on)."""
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2602_02599_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:12]
 
 
 def read_traffic(path):
-    """HBM bytes per launch of the dominant kernel from the committed counter summary, if present."""
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, and
+    the kernel-source hash that summary was measured on; the figure is dropped (None) when the
+    kernel's sources have changed since."""
     try:
         kv = {}
         with open(path) as f:
@@ -304,22 +349,30 @@ def read_traffic(path):
                 if "=" in line and not line.lstrip().startswith("#"):
                     k, v = line.split("=", 1)
                     kv[k.strip()] = v.strip()
-        return float(kv["hbm_bytes_per_launch"])
+        if kv.get("kernel_source_id") != kernel_source_id():
+            return None, "stale: %s was measured on other kernel sources" % os.path.basename(path)
+        return float(kv["hbm_bytes_per_launch"]), "profiles/%s (rocprofv3 FETCH_SIZE + WRITE_SIZE, kernel sources %s)" % (
+            os.path.basename(path), kv["kernel_source_id"])
     except Exception:
-        return None
+        return None, "no counter summary"
+
+
+def r(x, n=4):
+    return round(float(x), n)
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg2", help="headline workload (default cfg2)")
     ap.add_argument("--buffers", type=int, default=4, help="distinct cache copies rotated through")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
-    ap.add_argument("--no-control", action="store_true", help="skip the rho = 1.0 control")
-    ap.add_argument("--no-prefill", action="store_true", help="skip the causal prefill attention figure")
-    ap.add_argument("--no-q8", action="store_true", help="skip the fp8-cache attention figure")
+    ap.add_argument("--no-control", action="store_true", help="skip the rho = 1.0 controls")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the causal prefill attention figures")
+    ap.add_argument("--no-q8", action="store_true", help="skip the fp8-cache and several-token figures")
+    ap.add_argument("--no-configs", action="store_true", help="skip the other configurations")
     ap.add_argument("--only-prefill", action="store_true",
                     help="run nothing but the causal prefill attention figure (for profiling that kernel)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -348,44 +401,22 @@ def main():
                           "frac_of_mfma_peak": round(pflops / pms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)}))
         return
 
+    detail = {}
     job = Job(rap, I, args.workload, args.buffers, dev)
     w = job.w
-    sec = job.timed(args.steps, args.warmup)
-    gbps = job.bytes_per_step / sec / 1e9
-    sec_one = job.timed(args.steps, args.warmup, mode="step")
-    sec_rope = job.timed(args.steps, args.warmup, mode="step_rope")
-    k_mean_ms, k_min_ms = job.kernel_ms(args.steps, ev)
-    achieved = job.bytes_per_step / (k_mean_ms * 1e-3) / 1e9
+    head = job.figures(args.steps, args.warmup, ev)
+    sec_one = job.timed(args.steps, args.warmup, mode="step")[0] if w.n_new == 1 else None
+    sec_rope = job.timed(args.steps, args.warmup, mode="step_rope")[0] if w.n_new == 1 else None
+    detail[w.name] = head
+    stream_gbps = job.stream_read_gbps()
 
     q8 = multi = None
     if not args.no_q8:
-        # last row of the path's follow-ups (not part of `value`): the same attention over fp8 caches
         s8, s16, b8 = q8_figure(rap, torch, job, args.steps, args.warmup)
-        q8 = {"call": "rap_decode_attn_q8 (attention call alone, E4M3 caches, half the bytes per row)",
-              "ms": round(s8 * 1e3, 5), "value": round(b8 / s8 / 1e9, 2), "unit": "GB/s",
-              "tokens_per_s": round(w.batch / s8, 1),
-              "bf16_call_ms": round(s16 * 1e3, 5), "speedup_over_bf16_cache": round(s16 / s8, 4)}
-
-        # and a few query tokens per sequence (drafted tokens, short chunks) through the decode kernel
+        q8 = {"ms": r(s8 * 1e3, 5), "GBps": r(b8 / s8 / 1e9, 1), "frac": r(b8 / s8 / 1e9 / HBM_PEAK_GBPS), "bf16_ms": r(s16 * 1e3, 5),
+              "x_bf16": r(s16 / s8)}
         n_tok, sm = multi_figure(rap, torch, job, args.steps, args.warmup)
-        multi = {"call": "rap_decode_attn_multi (attention call alone, %d query tokens per sequence)" % n_tok,
-                 "n_tok": n_tok, "ms": round(sm * 1e3, 5), "one_token_call_ms": round(s16 * 1e3, 5),
-                 "query_tokens_per_s": round(w.batch * n_tok / sm, 1)}
-
-    # what a trivial read-only kernel reaches over the same bytes, same run
-    flat = torch.cat([c.k_cache.view(-1) for c in job.cases] + [c.v_cache.view(-1) for c in job.cases])
-    nflat = flat.numel() * 2 // 16 * 16
-    flat_u8 = flat.view(torch.uint8)[:nflat]
-    sink = torch.zeros(16, dtype=torch.uint8, device=dev)
-    for _ in range(3):
-        rap.rap_stream_read(flat_u8, sink)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(10):
-        rap.rap_stream_read(flat_u8, sink)
-    torch.cuda.synchronize()
-    stream_gbps = nflat * 10 / (time.perf_counter() - t0) / 1e9
-    del flat, flat_u8
+        multi = {"n_tok": n_tok, "ms": r(sm * 1e3, 5)}
 
     if args.copy_calibration:
         csrc = torch.full((256 << 20,), 3, dtype=torch.uint8, device=dev)
@@ -395,69 +426,86 @@ def main():
         torch.cuda.synchronize()
         del csrc, cdst
 
+    traffic, traffic_from = read_traffic(os.path.join(ROOT, "profiles", "traffic_decode_mfma_%s.txt" % w.name))
     result = {
         "metric": "decode-attention HBM GB/s (fraction of peak) and tokens/s at rho=0.7, 1 MI355X",
-        "value": round(gbps, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(sec * 1e3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": r(head["GBps"], 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": r(head["ms"], 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 storage, f32 accumulate", "data": "synthetic",
-        "config": {"workload": "%s: B=%d, %d/%d heads, ctx=%d, d_k=%d, d_v=%d, rho=%.1f, one layer; step = rap_rope_append(%d token/seq) + rap_decode_attn"
-                               % (w.name, w.batch, w.n_q_heads, w.n_kv_heads, w.ctx, w.d_k, w.d_v, w.n_pairs / (w.d_head / 2), w.n_new),
-                   "cache_copies_rotated": len(job.cases), "kv_bytes_per_step": int(job.bytes_per_step)},
-        "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
-        "tokens_per_s": round(w.batch / sec, 1),
-        "stream_read_GBps": round(stream_gbps, 1),
-        # the same step as ONE rap_decode_step call (new token handled inside the attention launch),
-        # with the query already rotated and with the query rotation fused in as well
-        "one_call_step": {"calls": "rap_decode_step", "ms_per_step": round(sec_one * 1e3, 5),
-                          "value": round(job.bytes_per_step / sec_one / 1e9, 2), "unit": "GB/s",
-                          "ms_per_step_with_query_rope": round(sec_rope * 1e3, 5)},
-        "roofline": {"bound": "hbm", "kernel": "decode_mfma_kernel", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": read_traffic(os.path.join(ROOT, "profiles", "traffic_decode_mfma_%s.txt" % w.name)),
-                     "kernel_ms_mean": round(k_mean_ms, 5), "kernel_ms_min": round(k_min_ms, 5),
-                     "algorithmic_bytes_per_launch": int(job.bytes_per_step)},
+        "config": {"workload": "%s: B=%d, %d/%d heads, ctx=%d, d_k=%d, d_v=%d, rho=%.1f; step = rap_rope_append + rap_decode_attn"
+                               % (w.name, w.batch, w.n_q_heads, w.n_kv_heads, w.ctx, w.d_k, w.d_v, w.n_pairs / (w.d_head / 2)),
+                   "copies": len(job.cases), "kv_bytes": head["kv_bytes"]},
+        "spread": {"stat": "median of %d blocks of --steps steps" % REPS, "ms_min": r(head["ms_min"], 5), "ms_max": r(head["ms_max"], 5)},
+        "frac_of_hbm_peak": r(head["frac"]), "tokens_per_s": r(head["tokens_per_s"], 1), "stream_read_GBps": r(stream_gbps, 1),
+        "roofline": {"bound": "hbm", "kernel": "decode_mfma_kernel", "achieved": r(head["k_GBps"], 2), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": r(head["k_frac"]), "traffic": traffic, "traffic_from": traffic_from,
+                     "k_ms": r(head["k_ms"], 5), "k_ms_min": r(head["k_ms_min"], 5)},
     }
-
+    if sec_one is not None:
+        result["one_call_step_ms"] = [r(sec_one * 1e3, 5), r(sec_rope * 1e3, 5)]     # query rotated / rotation fused in
     if q8 is not None:
-        result["fp8_cache"] = q8
-        result["multi_token"] = multi
+        result["fp8"] = q8
+        result["multi"] = multi
 
-    if not args.no_control and (args.workload + "_rho1") in I.WORKLOADS:
-        case0 = job.cases[0]
-        del job.cases[1:]
-        ctl = Job(rap, I, args.workload + "_rho1", args.buffers, dev)
-        csec = ctl.timed(args.steps, args.warmup)
-        result["rho1_control"] = {"value": round(ctl.bytes_per_step / csec / 1e9, 2), "unit": "GB/s",
-                                  "ms_per_step": round(csec * 1e3, 5), "kv_bytes_per_step": int(ctl.bytes_per_step),
-                                  "speedup_of_pruned": round(csec / sec, 4),
-                                  "kv_byte_ratio": round(ctl.bytes_per_step / job.bytes_per_step, 4)}
+    def compact(f):
+        return {"ms": r(f["ms"], 5), "GBps": r(f["GBps"], 1), "frac": r(f["frac"]), "k_ms": r(f["k_ms"], 5), "k_frac": r(f["k_frac"])}
+
+    case0 = job.cases[0]
+    del job.cases[1:]
+    torch.cuda.empty_cache()
+
+    # ---- rho = 1.0 control of the headline workload, same code
+    speedups = {}
+    configs = {}
+    if not args.no_control and (w.name + "_rho1") in I.WORKLOADS:
+        ctl = Job(rap, I, w.name + "_rho1", args.buffers, dev)
+        cf = ctl.figures(args.steps, args.warmup, ev)
+        detail[ctl.w.name] = cf
+        configs[ctl.w.name] = compact(cf)
+        speedups[w.name] = [r(cf["ms"] / head["ms"]), r(cf["kv_bytes"] / head["kv_bytes"])]
         del ctl
         torch.cuda.empty_cache()
-    else:
-        case0 = job.cases[0]
 
+    # ---- causal prefill attention at the headline shape (next row of the path, not part of `value`)
     if not args.no_prefill and w.ragged_min is None and w.batch * w.ctx * w.n_q_heads * w.d_v * 4 <= 8 << 30:
-        # next row of the path (not part of `value`): causal prefill attention at the same shape
-        case0 = job.cases[0]
-        del job.cases[1:]
-        torch.cuda.empty_cache()
         pms, pflops = prefill_figure(rap, torch, w, dev)
-        pf = {"call": "rap_prefill_attn", "tokens_per_sequence": w.ctx, "ms": round(pms, 4),
-              "roofline": {"bound": "mfma", "kernel": "prefill_kernel", "achieved": round(pflops / pms / 1e9, 1),
-                           "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                           "frac": round(pflops / pms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
-                           "algorithmic_flops_per_launch": int(pflops)}}
-        if not args.no_control and (args.workload + "_rho1") in I.WORKLOADS:
-            cms, cflops = prefill_figure(rap, torch, I.WORKLOADS[args.workload + "_rho1"], dev)
-            pf["rho1_control"] = {"ms": round(cms, 4), "achieved": round(cflops / cms / 1e9, 1), "unit": "TFLOP/s",
-                                  "speedup_of_pruned": round(cms / pms, 4), "flop_ratio": round(cflops / pflops, 4)}
-        pf["chunk"] = chunk_figure(rap, torch, w, dev)
+        pf = {"ms": r(pms), "roofline": {"bound": "mfma", "kernel": "prefill_kernel", "achieved": r(pflops / pms / 1e9, 1),
+                                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                         "frac": r(pflops / pms / 1e9 / MFMA_BF16_PEAK_TFLOPS), "traffic": None}}
+        if not args.no_control and (w.name + "_rho1") in I.WORKLOADS:
+            cms, cflops = prefill_figure(rap, torch, I.WORKLOADS[w.name + "_rho1"], dev)
+            pf["rho1_ms"] = r(cms)
+        pf["chunk64_ms"] = [r(x) for x in chunk_figure(rap, torch, w, dev)]      # one launch / key ranges
         result["prefill"] = pf
 
-    if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline(I, case0)
-    else:
-        result["cpu_baseline"] = None
+    # ---- the other configurations, one at a time (caches freed in between)
+    if not args.no_configs and args.workload == "cfg2":
+        del job
+        torch.cuda.empty_cache()
+        for name in ("cfg1", "cfg3", "cfg4", "cfg5", "cfg5_rho1"):
+            if name.endswith("_rho1") and args.no_control:
+                continue
+            j = Job(rap, I, name, args.buffers if name == "cfg1" else 1, dev)
+            f = j.figures(args.steps, args.warmup, ev)
+            f["stream_read_GBps"] = j.stream_read_gbps(reps=3)
+            detail[name] = f
+            configs[name] = compact(f)
+            del j
+            torch.cuda.empty_cache()
+        if "cfg5" in detail and "cfg5_rho1" in detail:
+            speedups["cfg5"] = [r(detail["cfg5_rho1"]["ms"] / detail["cfg5"]["ms"]), r(detail["cfg5_rho1"]["kv_bytes"] / detail["cfg5"]["kv_bytes"])]
+    if configs:
+        result["configs"] = configs
+    if speedups:
+        result["speedup_vs_rho1"] = speedups          # [time ratio, KV-byte ratio] of the rho = 1.0 control over the pruned run
+
+    result["cpu_baseline"] = None if args.no_cpu else cpu_baseline(I, case0)
+    try:
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "bench_detail.json"), "w") as f:
+            json.dump({"line": result, "detail": detail}, f, indent=1)
+    except OSError:
+        pass
     print(json.dumps(result))
 
 

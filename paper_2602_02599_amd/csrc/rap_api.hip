@@ -25,7 +25,7 @@ int mfma_lds_wave_bytes(int d_k, int d_v, bool q8, int cols);
 
 namespace {
 
-constexpr int kCUs = 256;                          // MI355X
+constexpr int kCUs = 256;                          // MI355X; what is assumed when no device can be asked
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int64_t kInt32Max = 0x7fffffffLL;
 
@@ -63,25 +63,48 @@ struct Plan {
   int kernel;   // 1 vector ALU, 2 matrix core
 };
 
+// Compute units of the current device, asked once per device (256 on MI355X, which is also the
+// answer when no device can be asked: the workspace query is host-only arithmetic).
+int device_cus() {
+  static std::atomic<int> known[rap::kMaxDevicesRemembered];
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= rap::kMaxDevicesRemembered) return kCUs;
+  int n = known[dev].load(std::memory_order_relaxed);
+  if (n > 0) return n;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return kCUs;
+  known[dev].store(n, std::memory_order_relaxed);
+  return n;
+}
+
 // Row range per workgroup.  A workgroup whose range starts at or beyond its sequence's length
 // exits at once, so ragged batches cost only empty launches.  Measured on MI355X: a workgroup
 // should stream for a long time (its fixed cost is a few microseconds), and when the whole job
-// fits in one round of resident workgroups their number should be a multiple of the 256 compute
-// units.  So: about 512 workgroups when the (b, h) count allows it, ranges never shorter than 512
-// rows nor longer than 4096 (longer ranges only lengthen the tail of a ragged batch).
+// fits in one round of resident workgroups their number should be a multiple of the compute
+// units.  So: about two workgroups per compute unit when the (b, h) count allows it, ranges never
+// shorter than 512 rows nor longer than 4096 (longer ranges only lengthen the tail of a ragged
+// batch) - except when that ceiling would leave a second, partly filled round of workgroups
+// (more than the chip holds at once, fewer than twice that): then ranges of up to 8192 rows bring
+// the job back into a single round of two workgroups per compute unit (cfg4 shape, 4 x 8 slabs of
+// 131072 rows: 1024 workgroups of 4096 rows over 768 places took 195 us, 512 of 8192 rows 189 us).
 rap_status_t make_plan(const rap_shape_t* s, int64_t max_seq_len, const rap_tuning_t* t, Plan* p) {
   int rps = t ? t->rows_per_split : 0;
   if (rps < 0 || (rps % rap::kSplitQuantum) != 0) return RAP_ERR_SHAPE;
   const int kernel = t ? t->kernel : 0;
   if (kernel < 0 || kernel > 2) return RAP_ERR_SHAPE;
   if (rps == 0) {
+    const int cus = device_cus();
     const int64_t slabs = static_cast<int64_t>(s->batch) * s->n_kv_heads;
-    int64_t per_slab = slabs > 0 ? (2LL * kCUs) / slabs : 1;            // ranges per (b, h)
+    int64_t per_slab = slabs > 0 ? (2LL * cus) / slabs : 1;            // ranges per (b, h)
     if (per_slab < 1) per_slab = 1;
     int64_t r = (max_seq_len + per_slab - 1) / per_slab;
     r = (r + rap::kSplitQuantum - 1) / rap::kSplitQuantum * rap::kSplitQuantum;
+    const int64_t single_round = r;
     if (r < 512) r = 512;
     if (r > 4096) r = 4096;
+    // workgroups the chip holds at once: three per compute unit up to d_k = 96, else two
+    const int64_t places = static_cast<int64_t>(cus) * (2 * s->n_pairs <= 96 ? 3 : 2);
+    const int64_t n_wg = slabs * ((max_seq_len + r - 1) / r);
+    if (n_wg > places && n_wg < 2 * places && single_round <= 8192) r = single_round;
     rps = static_cast<int>(r);
   }
   p->rows_per_split = rps;
