@@ -326,7 +326,7 @@ def multi_figure(rap, torch, job, steps, warmup):
     return n_tok, blocks(call, steps, warmup + 3 * n, torch.cuda.synchronize)[0]
 
 
-KERNEL_SOURCES = ("rap_decode_mfma.hip", "rap_device.h", "rap_arith.h")
+KERNEL_SOURCES = ("rap_decode_kernel.h", "rap_decode_mfma.hip", "rap_device.h", "rap_arith.h")
 
 
 def kernel_source_id():

@@ -94,15 +94,17 @@ __host__ __device__ __forceinline__ float f64_to_f32_odd_clamped448(double y) {
 // Which loads of a cache tile the decode kernel issues.  A tile (32 rows of any width: a multiple
 // of 64 bytes for two-byte elements, of 32 for one-byte ones, 16-byte aligned) is fetched as n_ld
 // wave-wide loads of 1 KB, lane l of load j taking bytes [1024 j + 16 l, + 16).  n_ld is fixed at
-// compile time from the instantiation (KCH = ceil(d_k / 32) score steps, NT = ceil(d_v / 16)
-// output tiles) and is the number of loads the tile needs, except for bf16 K tiles, where it can
-// exceed that by one whole load (2 KCH against ceil(d_k / 16)).  The last n_trim loads are
-// therefore trimmed to the tile by lane, all earlier ones are issued whole.  In a partial tile
+// compile time from the instantiation (KCH = ceil(d_k / 32) score steps; NT output tiles of 16
+// channels: ceil(d_v / 16) for bf16 caches, blocks of 64 channels, i.e. 4 or 8 tiles, for one-byte
+// codes) and can exceed the number of loads the tile needs by one whole load (bf16 K tiles: 2 KCH
+// against ceil(d_k / 16); one-byte V tiles: NT / 2 against ceil(d_v / 32)).  The last n_trim loads
+// are therefore trimmed to the tile by lane, all earlier ones are issued whole.  In a partial tile
 // (the last rows of a sequence) every load is trimmed to the bytes of the rows that exist.
+constexpr int decode_v_tiles(int d_v, bool q8) { return q8 ? 4 * ((d_v + 63) / 64) : (d_v + 15) / 16; }
 constexpr int k_tile_loads(int kch, bool q8) { return q8 ? kch : 2 * kch; }
 constexpr int v_tile_loads(int nt, bool q8) { return q8 ? (nt + 1) / 2 : nt; }
 constexpr int k_tile_trimmed(bool q8) { return q8 ? 1 : 2; }
-constexpr int v_tile_trimmed(bool) { return 1; }
+constexpr int v_tile_trimmed(bool q8) { return q8 ? 2 : 1; }
 __host__ __device__ __forceinline__ bool tile_load_issued(int j, int lane, int n_ld, int n_trim, int bytes, bool whole_tile) {
   if (whole_tile && j < n_ld - n_trim) return true;
   return 1024 * j + 16 * lane < bytes;

@@ -37,7 +37,7 @@ int loadplan(bool trim_one_only) {
     const int eb = q8 ? 1 : 2, row_quantum = q8 ? 16 : 8;
     for (int kind = 0; kind < 2; ++kind) {            // 0: K tile (even widths), 1: V tile
       for (int d = kind == 0 ? 2 : 1; d <= 128; d += kind == 0 ? 2 : 1) {
-        const int n_ld = kind == 0 ? rap::k_tile_loads((d + 31) / 32, q8 != 0) : rap::v_tile_loads((d + 15) / 16, q8 != 0);
+        const int n_ld = kind == 0 ? rap::k_tile_loads((d + 31) / 32, q8 != 0) : rap::v_tile_loads(rap::decode_v_tiles(d, q8 != 0), q8 != 0);
         const int n_trim = trim_one_only ? 1 : (kind == 0 ? rap::k_tile_trimmed(q8 != 0) : rap::v_tile_trimmed(q8 != 0));
         const int pitch = eb * d;
         for (int rows = row_quantum; rows <= 32; rows += row_quantum) {
