@@ -144,7 +144,9 @@ size_t rap_decode_attn_workspace_bytes(const rap_shape_t* shape, int64_t max_seq
  *   max_seq_len host: upper bound on seq_lens, sizes the grid; 1 <= max_seq_len <= cache_cap
  *   out        dev  fp32  [batch, n_q_heads, d_v]
  *   workspace  dev, at least rap_decode_attn_workspace_bytes(shape, max_seq_len, tuning) bytes,
- *              256-byte aligned; contents before and after the call are unspecified
+ *              256-byte aligned; contents before and after the call are unspecified (the size
+ *              depends on the compute-unit count of the current device: ask on the device the
+ *              call will run on)
  * Cache rows at or beyond seq_lens[b] are never used in the result, whatever bits they hold.
  */
 rap_status_t rap_decode_attn(const rap_shape_t* shape, const void* q,
@@ -232,6 +234,9 @@ rap_status_t rap_prefill_attn(const rap_shape_t* shape, int32_t n_new, const voi
 /* One whole decode step of a layer in a single call: append the new token of every sequence
  * (the result of rap_rope_append with n_new = 1), rotate its query unless it already is, and
  * attend (the result of rap_decode_attn / rap_decode_attn_rope over the updated cache).
+ * Paper: Sec. "Background" (decode step t: the new K_t, V_t enter the cache, attention runs over
+ * the prefix 1:t), Eq. (rope) and Sec. "RAP" (index-aware rotation of the new K row and of the
+ * query), Eq. (latent-score) and Eq. (attn) (scores against K_latent, softmax, weighted V).
  * On the matrix-core kernel the append is not a launch of its own: the attention kernel scans
  * the cache without row pos[b], one extra workgroup per (sequence, KV head) rotates the new K
  * row, writes it and the V row into the caches and scores the token straight from registers, and
@@ -406,7 +411,10 @@ rap_status_t rap_decode_attn_multi(const rap_shape_t* shape, const rap_kv_cache_
                                    const rap_tuning_t* tuning, void* stream);
 
 /* A look at the device-side inputs whose values the host never sees, for callers who want to
- * know before trusting a result.  ORs into *flags (dev, one uint32 the caller has set to 0):
+ * know before trusting a result.  Not an operation of the paper: it checks the preconditions its
+ * formulas put on the inputs (Sec. "RAP": the rotation uses the ORIGINAL indices of the retained
+ * pairs, each in [0, D/2) and kept once; Sec. "Background": attention runs over a prefix that
+ * lies inside the cache).  ORs into *flags (dev, one uint32 the caller has set to 0):
  *   RAP_FLAG_POS        a pos[b][n] outside [0, cache_cap): rap_rope_append skips that token
  *   RAP_FLAG_PAIR       a keep_pair_idx entry outside [0, d_head / 2): that pair is left alone
  *   RAP_FLAG_PAIR_ORDER a row of keep_pair_idx that is not strictly ascending (a pair kept twice)

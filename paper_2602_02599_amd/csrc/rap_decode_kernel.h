@@ -42,27 +42,8 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 constexpr int kTileRows = 32;
-
-// two fp32 -> two bf16 (round to nearest even) in one dword, first argument in the low half
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  const f32x2 v = {lo, hi};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-}
-
-// eight E4M3 codes (c0: elements 0..3, c1: elements 4..7, lowest byte first) -> eight bf16, exact:
-// v_cvt_scalef32_pk_bf16_fp8 turns two codes into two bf16 in one instruction (with a scale of 1.0
-// it gives, for every pair of codes, the bits of the conversion to fp32 followed by the rounding
-// to bf16, NaN codes included: checked on the device over all 65536 pairs)
-__device__ __forceinline__ uint4 widen_e4m3x8(uint32_t c0, uint32_t c1) {
-  return make_uint4(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c0, 1.0f, false)),
-                    __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c0, 1.0f, true)),
-                    __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c1, 1.0f, false)),
-                    __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c1, 1.0f, true)));
-}
 
 // Rows of one-byte codes have any width, so a fragment in LDS starts at any byte.  Wide LDS reads
 // at such addresses are served, but slowly (the 8- and 4-byte reads below, issued unaligned, made

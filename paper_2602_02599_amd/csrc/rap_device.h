@@ -18,6 +18,26 @@ constexpr int kMaxGroup = 8;         // query heads per KV head: vector-ALU kern
 constexpr int kMaxGroupWide = 16;    // the same for the matrix-core attention kernels (16 columns per instruction)
 constexpr int kSplitQuantum = 128;   // rows_per_split granularity
 
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+// two fp32 -> two bf16 (round to nearest even) in one dword, first argument in the low half
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// eight E4M3 codes (c0: elements 0..3, c1: elements 4..7, lowest byte first) -> eight bf16, exact:
+// v_cvt_scalef32_pk_bf16_fp8 turns two codes into two bf16 in one instruction (with a scale of 1.0
+// it gives, for every pair of codes, the bits of the conversion to fp32 followed by the rounding
+// to bf16, NaN codes included: checked on the device over all 65536 pairs)
+__device__ __forceinline__ uint4 widen_e4m3x8(uint32_t c0, uint32_t c1) {
+  return make_uint4(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c0, 1.0f, false)),
+                    __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c0, 1.0f, true)),
+                    __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c1, 1.0f, false)),
+                    __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c1, 1.0f, true)));
+}
+
 // Angular frequency of compact pair idx = h * P + c: from the caller's table when there is one
 // (every entry is valid, 0 means "do not rotate"), else theta^(-2j/D) = 2^(j * (-2 log2(theta) / D))
 // at the pair's original index j; false when that index lies outside [0, D/2).

@@ -42,10 +42,18 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((address_space(1))) const void* global_ptr_t;
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+// maximum of three floats in one instruction.  Written as the instruction because the compiler,
+// asked for nested two-operand maxima of matrix-instruction results, first passes every operand
+// through a max(x, x) of its own to quiet a possible signalling NaN: eleven instructions where
+// three do (the instruction quiets NaNs by itself).
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
 
 constexpr int kKeysPerTile = 64;     // staged per barrier
 constexpr int kSub = 32;             // keys per matrix-instruction group (two 16-row fragments)
@@ -57,19 +65,6 @@ __device__ __forceinline__ void static_for(std::integer_sequence<int, Is...>, F&
 }
 
 constexpr float kHeadroomP = 64.f;   // log2 units a score may exceed the reference before a rescale
-
-// eight E4M3 codes (c0: elements 0..3, c1: elements 4..7, lowest byte first) -> eight bf16, exact
-__device__ __forceinline__ uint4 widen_codes(uint32_t c0, uint32_t c1) {
-  const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(c0), false), b = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(c0), true);
-  const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(c1), false), d = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(c1), true);
-  return make_uint4(__builtin_bit_cast(uint32_t, __builtin_convertvector(a, bf16x2)), __builtin_bit_cast(uint32_t, __builtin_convertvector(b, bf16x2)),
-                    __builtin_bit_cast(uint32_t, __builtin_convertvector(c, bf16x2)), __builtin_bit_cast(uint32_t, __builtin_convertvector(d, bf16x2)));
-}
-
-__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
-  const f32x2 v = {lo, hi};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-}
 
 // Q8: the caches hold one-byte E4M3 codes (value = code value x the scale of the KV head): rows and
 // tiles are half as long, a fragment is widened to bf16 (exactly) between LDS and the matrix
@@ -257,9 +252,11 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 
   f32x4 acc[NQ][NT];
   float m_run[NQ], l_run[NQ];
+  float nref[NQ];      // minus the reference as the exponent's addend: kept beside m_run, 0 while that is -inf
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) {
     m_run[nq] = -INFINITY;
+    nref[nq] = 0.f;
     l_run[nq] = 0.f;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[nq][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -339,7 +336,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
               c0 &= kmask8[0];
               c1 &= kmask8[1];
             }
-            w = widen_codes(c0, c1);
+            w = widen_e4m3x8(c0, c1);
           } else {
             const uint32_t* p = reinterpret_cast<const uint32_t*>(kt + koff[rt] + 64 * kk);
             w = make_uint4(p[0], p[1], p[2], p[3]);
@@ -377,8 +374,8 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
       float tmax[NQ];
 #pragma unroll
       for (int nq = 0; nq < NQ; ++nq) {
-        tmax[nq] = fmaxf(fmaxf(fmaxf(sc[nq][0][0], sc[nq][0][1]), fmaxf(sc[nq][0][2], sc[nq][0][3])),
-                         fmaxf(fmaxf(sc[nq][1][0], sc[nq][1][1]), fmaxf(sc[nq][1][2], sc[nq][1][3]))) * mul;
+        tmax[nq] = max3(max3(sc[nq][0][0], sc[nq][0][1], sc[nq][0][2]), max3(sc[nq][0][3], sc[nq][1][0], sc[nq][1][1]),
+                        max3(sc[nq][1][2], sc[nq][1][3], sc[nq][1][3])) * mul;
         grow = grow || tmax[nq] > m_run[nq] + kHeadroomP;
       }
       if (__any(grow)) {
@@ -397,6 +394,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
             for (int nt = 0; nt < NT; ++nt) acc[nq][nt][reg] *= at;
           }
           m_run[nq] = m_new;
+          nref[nq] = m_new > -INFINITY ? -m_new : 0.f;      // -inf - -inf would be NaN
         }
       }
 
@@ -413,12 +411,11 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
       const bf16x2 minus_hi = __builtin_bit_cast(bf16x2, sel_hi);   // (0, -1)
 #pragma unroll
       for (int nq = 0; nq < NQ; ++nq) {
-        const float mref = m_run[nq] > -INFINITY ? m_run[nq] : 0.f;   // -inf - -inf would be NaN
         float pr[2][4];
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-          for (int r = 0; r < 4; ++r) pr[rt][r] = __builtin_amdgcn_exp2f(fmaf(sc[nq][rt][r], mul, -mref));
+          for (int r = 0; r < 4; ++r) pr[rt][r] = __builtin_amdgcn_exp2f(fmaf(sc[nq][rt][r], mul, nref[nq]));
         if constexpr (!ONES)                         // otherwise the sum comes out of the P.V product
           l_run[nq] += ((pr[0][0] + pr[0][1]) + (pr[0][2] + pr[0][3])) + ((pr[1][0] + pr[1][1]) + (pr[1][2] + pr[1][3]));
         uint32_t* ph = reinterpret_cast<uint32_t*>(&p_hi[nq]);
@@ -426,10 +423,10 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
           const float a0 = pr[d >> 1][2 * (d & 1)], a1 = pr[d >> 1][2 * (d & 1) + 1];
-          const uint32_t hh = pack2(a0, a1);
+          const uint32_t hh = pack_bf16(a0, a1);
           const bf16x2 hv = __builtin_bit_cast(bf16x2, hh);
           ph[d] = hh;
-          pl[d] = pack2(__builtin_amdgcn_fdot2_f32_bf16(hv, minus_lo, a0, false),
+          pl[d] = pack_bf16(__builtin_amdgcn_fdot2_f32_bf16(hv, minus_lo, a0, false),
                         __builtin_amdgcn_fdot2_f32_bf16(hv, minus_hi, a1, false));
         }
       }
@@ -449,8 +446,8 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
             const uint32_t lo45 = __builtin_amdgcn_perm(hw[5], hw[4], 0x0c0c0400u), lo67 = __builtin_amdgcn_perm(hw[7], hw[6], 0x04000c0cu);
             const uint32_t hi01 = __builtin_amdgcn_perm(hw[1], hw[0], 0x0c0c0501u), hi23 = __builtin_amdgcn_perm(hw[3], hw[2], 0x05010c0cu);
             const uint32_t hi45 = __builtin_amdgcn_perm(hw[5], hw[4], 0x0c0c0501u), hi67 = __builtin_amdgcn_perm(hw[7], hw[6], 0x05010c0cu);
-            be = widen_codes(lo01 | lo23, lo45 | lo67);
-            bo = widen_codes(hi01 | hi23, hi45 | hi67);
+            be = widen_e4m3x8(lo01 | lo23, lo45 | lo67);
+            bo = widen_e4m3x8(hi01 | hi23, hi45 | hi67);
           } else {
             uint32_t w[8];
 #pragma unroll
@@ -483,7 +480,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
           if constexpr (Q8) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) u[j] = *reinterpret_cast<const uint8_t*>(vt + voff[j >> 2][j & 3] + 16 * nt);
-            bv = widen_codes(u[0] | (u[1] << 8) | (u[2] << 16) | (u[3] << 24), u[4] | (u[5] << 8) | (u[6] << 16) | (u[7] << 24));
+            bv = widen_e4m3x8(u[0] | (u[1] << 8) | (u[2] << 16) | (u[3] << 24), u[4] | (u[5] << 8) | (u[6] << 16) | (u[7] << 24));
           } else {
 #pragma unroll
             for (int j = 0; j < 8; ++j) u[j] = *reinterpret_cast<const uint16_t*>(vt + voff[j >> 2][j & 3] + 32 * nt);
