@@ -399,16 +399,14 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
       }
 
       // ---- C. numerators, packed straight into the P.V operand: a bf16 head and a bf16 remainder
-      // of every probability (16 significant bits); the remainder p - head comes from one
-      // two-term dot instruction per value (head . (-1, 0) + p, exact)
+      // of every probability (16 significant bits).  The remainder is p minus the head widened
+      // back (a shift or a mask, then a subtraction: exact).  A two-term dot instruction
+      // (head . (-1, 0) + p) does the same in one instruction instead of two, but it runs on the
+      // matrix pipeline: measured on this part, sixteen matrix instructions with two such dot
+      // instructions after each take 254 ns against 120 ns with two multiply-adds, conversions or
+      // permutes after each, which all hide completely; the one-instruction form made this kernel
+      // slower, not faster.
       uint4 p_hi[NQ], p_lo[NQ];
-      // The two selectors are kept in scalar registers behind an empty asm: as literals the
-      // compiler encodes (-1, 0) as the inline constant -1.0, which the hardware reads as the
-      // fp32 pattern 0xbf800000 = (0, -1) for this instruction (checked with a small probe).
-      uint32_t sel_lo = 0x0000bf80u, sel_hi = 0xbf800000u;
-      asm volatile("" : "+s"(sel_lo), "+s"(sel_hi));
-      const bf16x2 minus_lo = __builtin_bit_cast(bf16x2, sel_lo);   // (-1, 0)
-      const bf16x2 minus_hi = __builtin_bit_cast(bf16x2, sel_hi);   // (0, -1)
 #pragma unroll
       for (int nq = 0; nq < NQ; ++nq) {
         float pr[2][4];
@@ -424,10 +422,8 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
         for (int d = 0; d < 4; ++d) {
           const float a0 = pr[d >> 1][2 * (d & 1)], a1 = pr[d >> 1][2 * (d & 1) + 1];
           const uint32_t hh = pack_bf16(a0, a1);
-          const bf16x2 hv = __builtin_bit_cast(bf16x2, hh);
           ph[d] = hh;
-          pl[d] = pack_bf16(__builtin_amdgcn_fdot2_f32_bf16(hv, minus_lo, a0, false),
-                        __builtin_amdgcn_fdot2_f32_bf16(hv, minus_hi, a1, false));
+          pl[d] = pack_bf16(a0 - bf16_lo(hh), a1 - bf16_hi(hh));
         }
       }
 
@@ -463,11 +459,17 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
           }
           if (ONES && np == NT / 2 - 1 && l16 == 15) bo = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
           const bf16x8 vbe = __builtin_bit_cast(bf16x8, be), vbo = __builtin_bit_cast(bf16x8, bo);
+          // heads of all column blocks first, remainders after: an accumulator's two instructions
+          // then lie 2 NQ instructions apart, and the second never waits for the first
 #pragma unroll
           for (int nq = 0; nq < NQ; ++nq) {
-            const bf16x8 pa_hi = __builtin_bit_cast(bf16x8, p_hi[nq]), pa_lo = __builtin_bit_cast(bf16x8, p_lo[nq]);
+            const bf16x8 pa_hi = __builtin_bit_cast(bf16x8, p_hi[nq]);
             acc[nq][2 * np] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi, vbe, acc[nq][2 * np], 0, 0, 0);
             acc[nq][2 * np + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi, vbo, acc[nq][2 * np + 1], 0, 0, 0);
+          }
+#pragma unroll
+          for (int nq = 0; nq < NQ; ++nq) {
+            const bf16x8 pa_lo = __builtin_bit_cast(bf16x8, p_lo[nq]);
             acc[nq][2 * np] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_lo, vbe, acc[nq][2 * np], 0, 0, 0);
             acc[nq][2 * np + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_lo, vbo, acc[nq][2 * np + 1], 0, 0, 0);
           }
@@ -489,11 +491,11 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
           if (ONES && nt == NT - 1 && l16 == 15) bv = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
           const bf16x8 vb = __builtin_bit_cast(bf16x8, bv);
 #pragma unroll
-          for (int nq = 0; nq < NQ; ++nq) {
-            const bf16x8 pa_hi = __builtin_bit_cast(bf16x8, p_hi[nq]), pa_lo = __builtin_bit_cast(bf16x8, p_lo[nq]);
-            acc[nq][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi, vb, acc[nq][nt], 0, 0, 0);
-            acc[nq][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_lo, vb, acc[nq][nt], 0, 0, 0);
-          }
+          for (int nq = 0; nq < NQ; ++nq)
+            acc[nq][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, p_hi[nq]), vb, acc[nq][nt], 0, 0, 0);
+#pragma unroll
+          for (int nq = 0; nq < NQ; ++nq)
+            acc[nq][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, p_lo[nq]), vb, acc[nq][nt], 0, 0, 0);
         }
       }
     }
