@@ -373,6 +373,7 @@ def main():
     ap.add_argument("--no-prefill", action="store_true", help="skip the causal prefill attention figures")
     ap.add_argument("--no-q8", action="store_true", help="skip the fp8-cache and several-token figures")
     ap.add_argument("--no-configs", action="store_true", help="skip the other configurations")
+    ap.add_argument("--no-valu", action="store_true", help="skip the vector-ALU kernel comparison")
     ap.add_argument("--only-prefill", action="store_true",
                     help="run nothing but the causal prefill attention figure (for profiling that kernel)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -409,6 +410,12 @@ def main():
     sec_rope = job.timed(args.steps, args.warmup, mode="step_rope")[0] if w.n_new == 1 else None
     detail[w.name] = head
     stream_gbps = job.stream_read_gbps()
+    # the plain vector-ALU kernel on the same step (why the default kernel uses the matrix cores)
+    valu = None
+    if not args.no_valu and w.n_q_heads // w.n_kv_heads <= 8:
+        tun1 = rap.tuning(kernel=1)
+        vsec = blocks(lambda i: job.step(i, tuning=tun1), max(2, args.steps // 4), 2, torch.cuda.synchronize, reps=5)[0]
+        valu = {"ms": r(vsec * 1e3, 5), "GBps": r(job.bytes_per_step / vsec / 1e9, 1)}
 
     q8 = multi = None
     if not args.no_q8:
@@ -446,6 +453,8 @@ def main():
     if q8 is not None:
         result["fp8"] = q8
         result["multi"] = multi
+    if valu is not None:
+        result["valu_kernel"] = valu
 
     def compact(f):
         return {"ms": r(f["ms"], 5), "GBps": r(f["GBps"], 1), "frac": r(f["frac"]), "k_ms": r(f["k_ms"], 5), "k_frac": r(f["k_frac"])}

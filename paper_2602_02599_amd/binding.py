@@ -95,9 +95,10 @@ class Rap:
         L.rap_decode_attn.restype = C.c_int
         L.rap_decode_attn.argtypes = [C.POINTER(RapShape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                       C.c_void_p, C.c_float, C.c_void_p, C.c_size_t, C.POINTER(RapTuning), C.c_void_p]
-        L.rap_decode_attn_static.restype = C.c_int
-        L.rap_decode_attn_static.argtypes = [C.POINTER(RapShape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
-                                             C.c_void_p, C.c_float, C.POINTER(RapTuning), C.c_void_p]
+        if hasattr(L, "rap_decode_attn_static"):
+            L.rap_decode_attn_static.restype = C.c_int
+            L.rap_decode_attn_static.argtypes = [C.POINTER(RapShape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                                 C.c_void_p, C.c_float, C.POINTER(RapTuning), C.c_void_p]
         L.rap_decode_attn_rope.restype = C.c_int
         L.rap_decode_attn_rope.argtypes = [C.POINTER(RapShape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                            C.c_void_p, C.c_int64, C.c_void_p, C.c_float, C.c_void_p, C.c_size_t,
