@@ -31,6 +31,9 @@ Passages of the paper each function follows:
                            the query head's KV head.
   attn_full_masked_ref     App. "Method", Eq. (masked-logit-equivalence): the
                            full-width right-hand side with removed pairs zeroed.
+  mx4_*, append_mx4_ref,   the 4-bit (microscaling FP4) form of the cache: Sec. "Introduction" and
+  attn_mx4_ref             "Related Work" (KV quantisation composes with RAP); format and scale rule
+                           from the OCP Microscaling Formats specification.
   merge_partials_ref       log-sum-exp combination of row-partitioned softmax
                            partials (algebraic identity of Eq. (attn); the paper
                            itself has no split kernel).
@@ -485,6 +488,131 @@ def prefill_attn_q8_ref(q, k_cache8, v_cache8, k_scale, v_scale, seq_lens, scale
                 if p < 0:
                     continue
                 out[b, i, h * g:(h + 1) * g] = attn_rows_ref(qf[b, i, h * g:(h + 1) * g], kf[:p + 1], vf[:p + 1], scale)
+    return out
+
+
+# --------------------------------------------------------------------------
+# 4-bit cache: microscaling FP4 (the "MXFP4" of the OCP Microscaling Formats
+# specification): elements are E2M1 codes (1 sign, 2 exponent bits with bias 1,
+# 1 mantissa bit: +-{0, 0.5, 1, 1.5, 2, 3, 4, 6}), and every block of 32
+# consecutive elements of a row shares one E8M0 scale byte e standing for
+# 2^(e - 127).  As for fp8 the paper only says that KV quantisation composes
+# with RAP (Sec. "Introduction", "Related Work"); this is the 4-bit format
+# gfx950 converts natively.  A row of d elements is stored as ceil(d / 32)
+# blocks of 16 code bytes (element 2i of a block in the low nibble of byte i,
+# element 2i + 1 in the high nibble; elements at and beyond d are code 0) and
+# 4 scale bytes (those beyond the row's blocks hold 127).
+# --------------------------------------------------------------------------
+
+MX_BLOCK = 32
+MX_SCALE_BYTES = 4
+
+
+def mx_blocks(d: int) -> int:
+    return (d + MX_BLOCK - 1) // MX_BLOCK
+
+
+def e2m1_code_to_f64(code: np.ndarray) -> np.ndarray:
+    """4-bit codes (0..15) -> float64, from the bit layout S.EE.M: exponent field 0 is subnormal
+    (M * 0.5), else (1 + M / 2) * 2^(EE - 1); no infinity, no NaN."""
+    c = np.asarray(code).astype(np.int64)
+    sign = np.where(c & 0x8, -1.0, 1.0)
+    e = (c >> 1) & 0x3
+    m = (c & 0x1).astype(np.float64)
+    val = np.where(e == 0, 0.5 * m, (1.0 + 0.5 * m) * np.exp2((e - 1).astype(np.float64)))
+    return sign * val
+
+
+def f64_to_e2m1_code(y: np.ndarray) -> np.ndarray:
+    """float64 -> nearest E2M1 code, ties to the code with mantissa bit 0, magnitudes above 6
+    saturate to 6.  A search over the eight magnitudes, so that it is the definition."""
+    y = np.asarray(y, dtype=np.float64)
+    grid = e2m1_code_to_f64(np.arange(8))                           # ascending: 0 .. 6
+    a = np.minimum(np.abs(y), 6.0)
+    hi = np.clip(np.searchsorted(grid, a, side="left"), 0, 7)       # first magnitude >= a
+    lo = np.clip(hi - 1, 0, 7)
+    d_hi, d_lo = grid[hi] - a, a - grid[lo]
+    pick_lo = (d_lo < d_hi) | ((d_lo == d_hi) & (lo % 2 == 0))
+    code = np.where(pick_lo, lo, hi).astype(np.uint8)
+    return np.where(np.signbit(y), code | 0x8, code).astype(np.uint8)
+
+
+def mx_shared_exponent(amax: np.ndarray) -> np.ndarray:
+    """Scale exponent of a block whose largest magnitude is amax: floor(log2 amax) minus the
+    exponent of the largest E2M1 binade (2, since 4 <= 6 < 8), so that the block's largest element
+    lands in [4, 8) before rounding; limited to [-126, 127]; 0 for a block of zeros."""
+    amax = np.asarray(amax, dtype=np.float64)
+    with np.errstate(divide="ignore"):
+        fl = np.floor(np.log2(np.where(amax > 0, amax, 1.0)))
+    # log2 of a double is correctly rounded only near exact powers by luck: repair with exact tests
+    fl = np.where(np.exp2(fl) > amax, fl - 1, fl)
+    fl = np.where(np.exp2(fl + 1) <= amax, fl + 1, fl)
+    e = np.where(amax > 0, fl - 2, 0.0)
+    return np.clip(e, -126, 127).astype(np.int64)
+
+
+def mx4_quantize_rows(x: np.ndarray):
+    """x float64 [..., d] -> (codes uint8 [..., 16 * blocks], scales uint8 [..., 4])."""
+    x = np.asarray(x, dtype=np.float64)
+    d = x.shape[-1]
+    nb = mx_blocks(d)
+    pad = np.zeros(x.shape[:-1] + (nb * MX_BLOCK,), dtype=np.float64)
+    pad[..., :d] = x
+    blk = pad.reshape(x.shape[:-1] + (nb, MX_BLOCK))
+    e = mx_shared_exponent(np.abs(blk).max(axis=-1))                # [..., nb]
+    q = f64_to_e2m1_code(blk / np.exp2(e.astype(np.float64))[..., None])    # division by a power of two: exact
+    codes = (q[..., 0::2] | (q[..., 1::2] << 4)).astype(np.uint8).reshape(x.shape[:-1] + (nb * 16,))
+    scales = np.full(x.shape[:-1] + (MX_SCALE_BYTES,), 127, dtype=np.uint8)
+    scales[..., :nb] = (e + 127).astype(np.uint8)
+    return codes, scales
+
+
+def mx4_dequantize_rows(codes: np.ndarray, scales: np.ndarray, d: int) -> np.ndarray:
+    """Inverse layout walk: float64 [..., d]; a scale byte of 255 is NaN (the format's rule)."""
+    codes = np.asarray(codes)
+    nb = mx_blocks(d)
+    c = codes.reshape(codes.shape[:-1] + (nb, 16))
+    q = np.empty(codes.shape[:-1] + (nb, MX_BLOCK), dtype=np.uint8)
+    q[..., 0::2] = c & 0xF
+    q[..., 1::2] = c >> 4
+    sb = np.asarray(scales)[..., :nb].astype(np.int64)
+    sc = np.where(sb == 255, np.nan, np.exp2((sb - 127).astype(np.float64)))
+    val = e2m1_code_to_f64(q) * sc[..., None]
+    return val.reshape(codes.shape[:-1] + (nb * MX_BLOCK,))[..., :d]
+
+
+def append_mx4_ref(k_new, v_new, pos, keep, k_codes, k_scales, v_codes, v_scales, theta_base, d_head):
+    """append_ref into a 4-bit cache: the rotated K row (float64) and the V row are quantised block
+    by block, each block with the scale its own largest magnitude asks for.  k_codes / v_codes:
+    uint8 [B, H_kv, cap, 16 * blocks], k_scales / v_scales: uint8 [B, H_kv, cap, 4], in place."""
+    k_new = np.asarray(k_new)
+    v_new = np.asarray(v_new)
+    pos = np.asarray(pos)
+    bsz, n_new, n_kv, _ = k_new.shape
+    kf, vf = bf16_bits_to_f64(k_new), bf16_bits_to_f64(v_new)
+    for b in range(bsz):
+        for n in range(n_new):
+            t = int(pos[b, n])
+            for h in range(n_kv):
+                rot = rope_compact(kf[b, n, h], np.float64(t), np.asarray(keep)[h], theta_base, d_head)
+                k_codes[b, h, t], k_scales[b, h, t] = mx4_quantize_rows(rot)
+                v_codes[b, h, t], v_scales[b, h, t] = mx4_quantize_rows(vf[b, n, h])
+
+
+def attn_mx4_ref(q, k_codes, k_scales, v_codes, v_scales, seq_lens, scale, d_k: int, d_v: int) -> np.ndarray:
+    """attn_ref over a 4-bit cache: every element stands for its code's value times its block's scale."""
+    q = np.asarray(q)
+    bsz, n_q, _ = q.shape
+    n_kv = k_codes.shape[1]
+    g = n_q // n_kv
+    out = np.zeros((bsz, n_q, d_v), dtype=np.float64)
+    qf = bf16_bits_to_f64(q)
+    for b in range(bsz):
+        n = int(seq_lens[b])
+        for h in range(n_kv):
+            kf = mx4_dequantize_rows(k_codes[b, h, :n], k_scales[b, h, :n], d_k)
+            vf = mx4_dequantize_rows(v_codes[b, h, :n], v_scales[b, h, :n], d_v)
+            out[b, h * g:(h + 1) * g] = attn_rows_ref(qf[b, h * g:(h + 1) * g], kf, vf, scale)
     return out
 
 

@@ -741,6 +741,126 @@ def test_prefill_q8_pins():
     assert np.all(got[1, :2] == 0) and np.any(got[1, 2] != 0)      # positions -2, -1 do not exist; position 0 does
 
 
+# ---------------------------------------------------------------- 4-bit (microscaling FP4) cache
+
+
+def test_e2m1_codes_and_rounding():
+    """E2M1 as the microscaling formats specification lists it (exponent bias 1, largest normal 6,
+    smallest normal 1, subnormal 0.5, no infinity or NaN): the eight magnitudes, the sign bit,
+    nearest with ties to the even mantissa bit against exact rational arithmetic, saturation."""
+    listed = [0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0]
+    vals = O.e2m1_code_to_f64(np.arange(16))
+    assert list(vals[:8]) == listed and list(vals[8:]) == [-v for v in listed] and np.signbit(vals[8])
+    rng = _rng(21)
+    mids = [(a + b) / 2 for a, b in zip(listed[:-1], listed[1:])]
+    xs = np.concatenate([np.array(listed), np.array(mids), np.nextafter(mids, 0.0), np.nextafter(mids, 10.0),
+                         rng.uniform(0, 7, 4000), [6.0, 6.5, 7.99, 8.0, 1e9, np.inf, 2.0 ** -40]])
+    got = O.f64_to_e2m1_code(np.concatenate([xs, -xs]))
+    for x, c in zip(np.concatenate([xs, -xs]), got):
+        a = Fraction(min(abs(x), 6.0)) if np.isfinite(x) else Fraction(6)
+        dist = [abs(Fraction(v) - a) for v in listed]
+        best = min(dist)
+        cands = [k for k in range(8) if dist[k] == best]
+        want = cands[0] if len(cands) == 1 else [k for k in cands if k % 2 == 0][0]
+        assert int(c) & 7 == want and bool(int(c) & 8) == bool(np.signbit(x)), (x, c)
+    # ties: 0.25 -> 0, 0.75 -> 1, 1.25 -> 1, 1.75 -> 2, 2.5 -> 2, 3.5 -> 4, 5 -> 4
+    assert list(O.e2m1_code_to_f64(O.f64_to_e2m1_code(np.array(mids)))) == [0.0, 1.0, 1.0, 2.0, 2.0, 4.0, 4.0]
+
+
+def test_mx_shared_exponent_rule():
+    """Scale of a block: 2^(floor(log2 amax) - 2), so that amax / scale lies in [4, 8): the top
+    binade of E2M1.  Exact at and next to powers of two, limited to [-126, 127], 0 for zeros."""
+    for k in range(-120, 120, 7):
+        p = 2.0 ** k
+        for amax, fl in ((p, k), (np.nextafter(p, 0.0), k - 1), (np.nextafter(p, np.inf), k), (1.75 * p, k), (1.999999 * p, k)):
+            e = int(O.mx_shared_exponent(np.array(amax)))
+            assert e == fl - 2
+            assert 4.0 <= amax / 2.0 ** e < 8.0
+    assert int(O.mx_shared_exponent(np.array(0.0))) == 0
+    assert int(O.mx_shared_exponent(np.array(2.0 ** -200))) == -126 and int(O.mx_shared_exponent(np.array(1e300))) == 127
+
+
+def test_mx4_layout_and_round_trip():
+    """Where a code and a scale sit in a row (one non-zero element at a time), what the padding
+    holds, the error of a round trip, idempotence, and that every stored value is a bf16 number."""
+    d = 90
+    for i, val in ((0, 1.0), (1, -3.0), (31, 0.5), (32, 6.0), (63, -1.5), (64, 2.0), (89, 96.0)):
+        x = np.zeros(d)
+        x[i] = val
+        codes, scales = O.mx4_quantize_rows(x)
+        assert codes.shape == (48,) and scales.shape == (4,)
+        blk, within = divmod(i, 32)
+        byte = 16 * blk + within // 2
+        e = int(np.floor(np.log2(abs(val)))) - 2
+        nib = int(O.f64_to_e2m1_code(np.array(val / 2.0 ** e)))
+        assert int(codes[byte]) == (nib << 4 if within % 2 else nib), (i, hex(int(codes[byte])))
+        assert np.count_nonzero(codes) == 1
+        want_scales = [127, 127, 127, 127]
+        want_scales[blk] = 127 + e
+        assert list(scales) == want_scales
+        assert np.array_equal(O.mx4_dequantize_rows(codes, scales, d), x)     # a single element is always exact here
+    rng = _rng(22)
+    for d in (90, 115, 116, 64, 128, 6, 33):
+        x = rng.standard_normal((50, d)) * 10.0 ** rng.integers(-3, 4, (50, 1))
+        codes, scales = O.mx4_quantize_rows(x)
+        nb = O.mx_blocks(d)
+        assert codes.shape == (50, 16 * nb) and np.all(scales[:, nb:] == 127)
+        back = O.mx4_dequantize_rows(codes, scales, d)
+        full = O.mx4_dequantize_rows(codes, scales, 32 * nb)
+        assert np.all(full[:, d:] == 0)                                       # padding elements are code 0
+        for r in range(50):
+            for b in range(nb):
+                sl = slice(32 * b, min(32 * b + 32, d))
+                s = 2.0 ** (int(scales[r, b]) - 127)
+                y = np.abs(x[r, sl]) / s
+                assert 4.0 <= y.max() < 8.0
+                # half the spacing of the grid at y (0.5 below 2, 1 below 4, 2 above), 2 where 6 < y < 8 saturates
+                half = np.where(y < 2, 0.25, np.where(y < 4, 0.5, 1.0))
+                half = np.where(y > 6, 2.0, half)
+                assert np.all(np.abs(back[r, sl] - x[r, sl]) <= half * s)
+                assert np.abs(back[r, sl]).max() >= 4.0 * s                     # the largest element lands in the top binade
+        c2, s2 = O.mx4_quantize_rows(back)
+        assert np.array_equal(c2, codes) and np.array_equal(s2, scales)       # stored values are fixed points
+        assert np.array_equal(O.bf16_bits_to_f64(O.f64_to_bf16_bits_rne(back)), back)
+    assert np.isnan(O.mx4_dequantize_rows(np.full(16, 0x22, dtype=np.uint8), np.array([255, 127, 127, 127], dtype=np.uint8), 32)).all()
+
+
+def test_mx4_cache_pins():
+    """The 4-bit cache is the dense path on dequantised values: the appended rows are the quantised
+    rotated rows (position 0: the quantised input row itself), V rows the quantised inputs, other
+    rows untouched, and attention over the codes equals attn_ref over a bf16 cache that holds
+    exactly the dequantised values."""
+    rng = _rng(23)
+    B, n_new, H, P, dv, cap, D, theta = 2, 3, 2, 20, 35, 16, 64, 1.0e4
+    keep = np.stack([np.sort(rng.choice(D // 2, P, replace=False)) for _ in range(H)])
+    k_new = _bf16_of(rng.standard_normal((B, n_new, H, 2 * P)) * 3)
+    v_new = _bf16_of(rng.standard_normal((B, n_new, H, dv)))
+    pos = np.array([[0, 1, 2], [7, 3, 11]])
+    nbk, nbv = O.mx_blocks(2 * P), O.mx_blocks(dv)
+    kc = np.zeros((B, H, cap, 16 * nbk), dtype=np.uint8); ks = np.zeros((B, H, cap, 4), dtype=np.uint8)
+    vc = np.zeros((B, H, cap, 16 * nbv), dtype=np.uint8); vs = np.zeros((B, H, cap, 4), dtype=np.uint8)
+    O.append_mx4_ref(k_new, v_new, pos, keep, kc, ks, vc, vs, theta, D)
+    for b in range(B):
+        for n in range(n_new):
+            t = pos[b, n]
+            for h in range(H):
+                exact = O.rope_compact(O.bf16_bits_to_f64(k_new[b, n, h]), np.float64(t), keep[h], theta, D)
+                c, s = O.mx4_quantize_rows(exact)
+                assert np.array_equal(kc[b, h, t], c) and np.array_equal(ks[b, h, t], s)
+                c, s = O.mx4_quantize_rows(O.bf16_bits_to_f64(v_new[b, n, h]))
+                assert np.array_equal(vc[b, h, t], c) and np.array_equal(vs[b, h, t], s)
+    c0, s0 = O.mx4_quantize_rows(O.bf16_bits_to_f64(k_new[0, 0, 1]))
+    assert np.array_equal(kc[0, 1, 0], c0) and np.array_equal(ks[0, 1, 0], s0)      # position 0 does not rotate
+    assert np.all(kc[0, :, 3:] == 0) and np.all(vs[1, :, 0] == 0)                   # untouched rows
+    q = _bf16_of(rng.standard_normal((B, 2 * H, 2 * P)))
+    lens = np.array([3, 12])
+    # rows never appended hold scale byte 0 = 2^-127 and code 0: value 0
+    got = O.attn_mx4_ref(q, kc, ks, vc, vs, lens, 0.4, 2 * P, dv)
+    kb = _bf16_of(O.mx4_dequantize_rows(kc, ks, 2 * P))
+    vb = _bf16_of(O.mx4_dequantize_rows(vc, vs, dv))
+    assert np.array_equal(got, O.attn_ref(q, kb, vb, lens, 0.4))
+
+
 def test_split_merge_identity():
     """Merging (m, l, acc) partials over any partition of the rows gives the unsplit result."""
     rng = _rng(17)
