@@ -351,6 +351,46 @@ rap_status_t rap_decode_attn_paged_q8(const rap_shape_t* shape, const rap_paging
                                       void* workspace, size_t workspace_bytes,
                                       const rap_tuning_t* tuning, void* stream);
 
+/* 4-bit caches: the microscaling FP4 form of the compact cache.
+ *
+ * Paper: Sec. "Introduction" and Sec. "Related Work" (KV-cache quantisation composes with RAP; no
+ * format is fixed there).  Format: the "MXFP4" of the OCP Microscaling Formats specification,
+ * which gfx950 converts natively.  Elements are E2M1 codes (1 sign, 2 exponent bits with bias 1,
+ * 1 mantissa bit: +-{0, 0.5, 1, 1.5, 2, 3, 4, 6}); every block of 32 consecutive elements of a row
+ * shares one scale byte e standing for 2^(e - 127).  With nb(d) = ceil(d / 32):
+ *   k_codes  dev uint8 [batch, n_kv_heads, cache_cap, 16 * nb(2P)]   v_codes  [.., 16 * nb(d_v)]
+ *            block j of a row holds elements 32 j .. 32 j + 31, element 2 i of the block in the low
+ *            nibble of its byte i, element 2 i + 1 in the high nibble; elements at and beyond the
+ *            row's width are code 0
+ *   k_scales dev uint8 [batch, n_kv_heads, cache_cap, 4]             v_scales likewise
+ *            byte j = scale of block j; bytes beyond the row's blocks hold 127
+ * All four arrays 16-byte aligned (scales: 4).  A K row of d_k = 90 takes 48 + 4 bytes against 180
+ * as bf16.
+ *
+ * rap_rope_append_mx4: as rap_rope_append (same rotation, Eq. (rope) at the pair's original index,
+ * fp64), then each block of the rotated K row and of the V row gets the scale
+ * 2^(floor(log2(largest magnitude in the block)) - 2), limited to 2^-126 .. 2^127 and 2^0 for a
+ * block of zeros, and every element is divided by it and rounded once, from fp64, to the nearest
+ * code (ties to the code with mantissa bit 0, magnitudes above 6 saturate).  A pair whose index
+ * lies outside [0, D/2) counts as zero (a row is written as a whole); a token whose pos lies
+ * outside [0, cache_cap) is skipped.  Any n_new.
+ *
+ * rap_decode_attn_mx4: rap_decode_attn with every cache element standing for its code's value
+ * times its block's scale (all such values are bf16 numbers, so the arithmetic is that of the
+ * bf16 call on the dequantised cache).  Matrix-core kernel only (tuning->kernel = 1 is
+ * RAP_ERR_UNSUPPORTED); q arrives rotated.  Workspace and tuning as in rap_decode_attn.  Rows at
+ * or beyond seq_lens[b] may hold any codes and scale bytes. */
+rap_status_t rap_rope_append_mx4(const rap_shape_t* shape, int32_t n_new, const void* k_new, const void* v_new,
+                                 const int32_t* pos, const int32_t* keep_pair_idx,
+                                 void* k_codes, void* k_scales, void* v_codes, void* v_scales, void* stream);
+rap_status_t rap_decode_attn_mx4(const rap_shape_t* shape, const void* q,
+                                 const void* k_codes, const void* k_scales,
+                                 const void* v_codes, const void* v_scales,
+                                 const int32_t* seq_lens, int64_t max_seq_len,
+                                 void* out, float scale,
+                                 void* workspace, size_t workspace_bytes,
+                                 const rap_tuning_t* tuning, void* stream);
+
 /* The one-call decode step over any kind of cache.  k, v: the dense caches or, with paging, the
  * pools (dev, updated in place); k_scale, v_scale (dev fp32 [n_kv_heads]): both non-NULL when the
  * caches hold one-byte E4M3 codes, both NULL for bf16; paging: NULL for dense caches.  Everything

@@ -99,6 +99,12 @@ class Rap:
             L.rap_decode_attn_static.restype = C.c_int
             L.rap_decode_attn_static.argtypes = [C.POINTER(RapShape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                                  C.c_void_p, C.c_float, C.POINTER(RapTuning), C.c_void_p]
+        if hasattr(L, "rap_rope_append_mx4"):
+            L.rap_rope_append_mx4.restype = C.c_int
+            L.rap_rope_append_mx4.argtypes = [C.POINTER(RapShape), C.c_int32] + [C.c_void_p] * 9
+            L.rap_decode_attn_mx4.restype = C.c_int
+            L.rap_decode_attn_mx4.argtypes = [C.POINTER(RapShape)] + [C.c_void_p] * 6 + [C.c_int64, C.c_void_p, C.c_float,
+                                               C.c_void_p, C.c_size_t, C.POINTER(RapTuning), C.c_void_p]
         L.rap_decode_attn_rope.restype = C.c_int
         L.rap_decode_attn_rope.argtypes = [C.POINTER(RapShape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                            C.c_void_p, C.c_int64, C.c_void_p, C.c_float, C.c_void_p, C.c_size_t,
@@ -336,6 +342,31 @@ class Rap:
                                          scale, _ptr(workspace, None, "workspace"),
                                          0 if workspace is None else workspace.numel() * workspace.element_size(),
                                          C.byref(tuning) if tuning is not None else None, _stream(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def rap_rope_append_mx4(self, shape: RapShape, n_new: int, k_new, v_new, pos, keep_pair_idx, k_codes, k_scales,
+                            v_codes, v_scales, stream=None, check=True) -> int:
+        st = self.lib.rap_rope_append_mx4(C.byref(shape), n_new, _ptr(k_new, torch.bfloat16, "k_new"),
+                                          _ptr(v_new, torch.bfloat16, "v_new"), _ptr(pos, torch.int32, "pos"),
+                                          _ptr(keep_pair_idx, torch.int32, "keep_pair_idx"),
+                                          _ptr(k_codes, torch.uint8, "k_codes"), _ptr(k_scales, torch.uint8, "k_scales"),
+                                          _ptr(v_codes, torch.uint8, "v_codes"), _ptr(v_scales, torch.uint8, "v_scales"),
+                                          _stream(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def rap_decode_attn_mx4(self, shape: RapShape, q, k_codes, k_scales, v_codes, v_scales, seq_lens, max_seq_len: int, out,
+                            scale: float, workspace=None, tuning: Optional[RapTuning] = None, stream=None, check=True) -> int:
+        st = self.lib.rap_decode_attn_mx4(C.byref(shape), _ptr(q, torch.bfloat16, "q"),
+                                          _ptr(k_codes, torch.uint8, "k_codes"), _ptr(k_scales, torch.uint8, "k_scales"),
+                                          _ptr(v_codes, torch.uint8, "v_codes"), _ptr(v_scales, torch.uint8, "v_scales"),
+                                          _ptr(seq_lens, torch.int32, "seq_lens"), max_seq_len, _ptr(out, torch.float32, "out"),
+                                          scale, _ptr(workspace, None, "workspace"),
+                                          0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                          C.byref(tuning) if tuning is not None else None, _stream(stream))
         if check:
             self._check(st)
         return st

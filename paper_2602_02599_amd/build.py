@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librap.so")
-SOURCES = ["rap_api.hip", "rap_append.hip", "rap_decode_valu.hip", "rap_decode_mfma.hip", "rap_decode_mfma_q8.hip", "rap_merge.hip", "rap_stream.hip", "rap_prefill.hip",
+SOURCES = ["rap_api.hip", "rap_append.hip", "rap_decode_valu.hip", "rap_decode_mfma.hip", "rap_decode_mfma_q8.hip", "rap_decode_mfma_mx4.hip", "rap_merge.hip", "rap_stream.hip", "rap_prefill.hip",
            "rap_prefill_k1.hip", "rap_prefill_k2.hip", "rap_prefill_k3.hip", "rap_prefill_k4.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -20,7 +20,7 @@ hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStre
 hipError_t launch_stream_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 hipError_t launch_validate(const int32_t* pos, long long n_pos, long long cap, const int32_t* keep, int n_kv, int n_pairs,
                            int half, const int32_t* seq_lens, int batch, long long max_len, uint32_t* flags, hipStream_t stream);
-int mfma_lds_wave_bytes(int d_k, int d_v, bool q8, int cols);
+int mfma_lds_wave_bytes(int d_k, int d_v, bool q8, int cols, bool mx4);
 }  // namespace rap
 
 namespace {
@@ -157,10 +157,13 @@ struct AppendRequest {
   bool fp8 = false;                        // caches hold E4M3 codes, scales required
   const float* k_scale = nullptr;
   const float* v_scale = nullptr;
+  void* k_scales4 = nullptr;               // 4-bit caches: k_cache / v_cache hold the code blocks, these the scale bytes
+  void* v_scales4 = nullptr;
+  bool mx4 = false;
   void* stream = nullptr;
 };
 
-// Shared body of rap_rope_append and its paged and fp8 variants.
+// Shared body of rap_rope_append and its paged, fp8 and 4-bit variants.
 rap_status_t append_impl(const AppendRequest& r) {
   const rap_shape_t* shape = r.shape;
   rap_status_t st = check_shape(shape);
@@ -187,6 +190,14 @@ rap_status_t append_impl(const AppendRequest& r) {
     if (shape->cache_cap % 16 != 0) return RAP_ERR_SHAPE;
     a.k_scale = r.k_scale;
     a.v_scale = r.v_scale;
+  }
+  if (r.mx4) {
+    if (!r.k_scales4 || !r.v_scales4) return RAP_ERR_NULL;
+    if (r.paging || r.fp8) return RAP_ERR_UNSUPPORTED;
+    if (misaligned(r.k_cache, 16) || misaligned(r.v_cache, 16) || misaligned(r.k_scales4, 4) || misaligned(r.v_scales4, 4))
+      return RAP_ERR_SHAPE;
+    a.k_scales4 = static_cast<uint8_t*>(r.k_scales4);
+    a.v_scales4 = static_cast<uint8_t*>(r.v_scales4);
   }
   a.k_new = static_cast<const uint16_t*>(r.k_new);
   a.v_new = static_cast<const uint16_t*>(r.v_new);
@@ -220,6 +231,9 @@ struct DecodeRequest {
   bool fp8 = false;                        // caches hold E4M3 codes, scales required
   const float* k_scale = nullptr;
   const float* v_scale = nullptr;
+  const void* k_scales4 = nullptr;         // 4-bit caches: k_cache / v_cache hold the code blocks, these the scale bytes
+  const void* v_scales4 = nullptr;
+  bool mx4 = false;
   const void* k_new = nullptr;             // one-call step: the token to append first (with v_new, new_pos)
   const void* v_new = nullptr;
   const int32_t* new_pos = nullptr;
@@ -279,6 +293,12 @@ rap_status_t decode_impl(const DecodeRequest& r) {
     if (shape->cache_cap % 16 != 0) return RAP_ERR_SHAPE;
     if (!r.k_scale || !r.v_scale) return RAP_ERR_NULL;
   }
+  if (r.mx4) {
+    // 4-bit caches: the plain attention call on the matrix-core kernel over dense caches
+    if (!r.k_scales4 || !r.v_scales4) return RAP_ERR_NULL;
+    if (p.kernel != 2 || r.fp8 || r.paging || step || multi || r.q_pos) return RAP_ERR_UNSUPPORTED;
+    if (misaligned(r.k_scales4, 4) || misaligned(r.v_scales4, 4)) return RAP_ERR_SHAPE;
+  }
 
   rap::DecodeArgs a;
   memset(&a, 0, sizeof(a));
@@ -309,7 +329,9 @@ rap_status_t decode_impl(const DecodeRequest& r) {
   a.n_slots = fused_step ? p.n_split + 1 : p.n_split;
   a.cap = shape->cache_cap;
   a.scale_log2e = r.scale * kLog2e;
-  a.lds_wave_bytes = rap::mfma_lds_wave_bytes(a.d_k, a.d_v, r.fp8, r.n_tok * a.group);
+  a.lds_wave_bytes = rap::mfma_lds_wave_bytes(a.d_k, a.d_v, r.fp8, r.n_tok * a.group, r.mx4);
+  a.k_scales4 = r.mx4 ? static_cast<const uint8_t*>(r.k_scales4) : nullptr;
+  a.v_scales4 = r.mx4 ? static_cast<const uint8_t*>(r.v_scales4) : nullptr;
   a.k_scale = r.fp8 ? r.k_scale : nullptr;
   a.v_scale = r.fp8 ? r.v_scale : nullptr;
   if (r.paging) {
@@ -546,6 +568,48 @@ rap_status_t rap_rope_append_q8(const rap_shape_t* shape, int32_t n_new, const v
   r.v_scale = v_scale;
   r.stream = stream;
   return append_impl(r);
+}
+
+rap_status_t rap_rope_append_mx4(const rap_shape_t* shape, int32_t n_new, const void* k_new, const void* v_new,
+                                 const int32_t* pos, const int32_t* keep_pair_idx, void* k_codes, void* k_scales,
+                                 void* v_codes, void* v_scales, void* stream) {
+  AppendRequest r;
+  r.shape = shape;
+  r.n_new = n_new;
+  r.k_new = k_new;
+  r.v_new = v_new;
+  r.pos = pos;
+  r.keep_pair_idx = keep_pair_idx;
+  r.k_cache = k_codes;
+  r.v_cache = v_codes;
+  r.mx4 = true;
+  r.k_scales4 = k_scales;
+  r.v_scales4 = v_scales;
+  r.stream = stream;
+  return append_impl(r);
+}
+
+rap_status_t rap_decode_attn_mx4(const rap_shape_t* shape, const void* q, const void* k_codes, const void* k_scales,
+                                 const void* v_codes, const void* v_scales, const int32_t* seq_lens,
+                                 int64_t max_seq_len, void* out, float scale, void* workspace, size_t workspace_bytes,
+                                 const rap_tuning_t* tuning, void* stream) {
+  DecodeRequest r;
+  r.shape = shape;
+  r.q = q;
+  r.k_cache = k_codes;
+  r.v_cache = v_codes;
+  r.mx4 = true;
+  r.k_scales4 = k_scales;
+  r.v_scales4 = v_scales;
+  r.seq_lens = seq_lens;
+  r.max_seq_len = max_seq_len;
+  r.out = out;
+  r.scale = scale;
+  r.workspace = workspace;
+  r.workspace_bytes = workspace_bytes;
+  r.tuning = tuning;
+  r.stream = stream;
+  return decode_impl(r);
 }
 
 rap_status_t rap_rope_queries(const rap_shape_t* shape, int32_t n_new, const void* q, const int32_t* pos,
@@ -917,6 +981,6 @@ const char* rap_status_str(rap_status_t status) {
   return "unknown status";
 }
 
-int32_t rap_version(void) { return 900; }
+int32_t rap_version(void) { return 1000; }
 
 }  // extern "C"

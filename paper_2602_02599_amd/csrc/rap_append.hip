@@ -92,6 +92,82 @@ __global__ __launch_bounds__(256) void append_q8_kernel(AppendArgs a) {
   if (has_v1) v8[lane + kWave] = f64_to_e4m3(static_cast<double>(bf16_to_f32(v1)) / vs);
 }
 
+// The same append into a 4-bit cache (microscaling FP4).  A row is quantised block by block: the
+// 32 elements of a block share the scale their largest magnitude asks for (mx_shared_exponent),
+// every element is divided by it (a power of two: exact) and rounded once, from fp64, to the
+// nearest E2M1 code.  One wavefront per (token, KV head): lane c rotates pair c as above, the
+// rotated row (then the V row) is laid out in LDS, and lane e handles elements e and e + 64 of the
+// row, its block being the 32 lanes around it.  A pair whose index is out of range counts as zero
+// (the row is written as a whole).  Dense caches only.
+__global__ __launch_bounds__(256) void append_mx4_kernel(AppendArgs a) {
+  __shared__ double s_val[4][2 * kWave];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x >> 6;
+  const int h = blockIdx.y;
+  const long long tok = static_cast<long long>(blockIdx.x) * 4 + wave;   // b * n_new + n
+  const long long n_tok = static_cast<long long>(a.batch) * a.n_new;
+  if (tok >= n_tok) return;
+  const int b = static_cast<int>(tok / a.n_new);
+  const int P = a.n_pairs;
+  const bool has_pair = lane < P;
+  const bool has_v0 = lane < a.d_v, has_v1 = lane + kWave < a.d_v;
+  const uint16_t* ksrc = a.k_new + (tok * a.n_kv + h) * (2 * P);
+  const uint16_t* vsrc = a.v_new + (tok * a.n_kv + h) * a.d_v;
+  const int t = a.pos[tok];
+  double f = 0.0;
+  const bool rot = has_pair && pair_frequency(a.keep, a.pair_freq, a.neg2_log2_theta_over_d, a.d_head, h * P + lane, &f);
+  const uint16_t kx = has_pair ? ksrc[lane] : 0, ky = has_pair ? ksrc[lane + P] : 0;
+  const uint16_t v0 = has_v0 ? vsrc[lane] : 0, v1 = has_v1 ? vsrc[lane + kWave] : 0;
+  if (t < 0 || t >= a.cap) return;                                        // documented: skipped (the whole wavefront)
+  const long long row = (static_cast<long long>(b) * a.n_kv + h) * a.cap + t;
+  double* val = s_val[wave];
+
+  // one row in LDS -> code blocks and scale bytes of that row
+  auto quantise_row = [&](int n_blk, uint8_t* codes, uint8_t* scales) {
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int e = lane + kWave * half, blk = e >> 5;
+      const double v = val[e];
+      double amax = v < 0 ? -v : v;
+#pragma unroll
+      for (int o = 16; o >= 1; o >>= 1) {
+        const double other = __shfl_xor(amax, o);
+        amax = other > amax ? other : amax;
+      }
+      const int se = mx_shared_exponent(amax);
+      const uint32_t code = f64_to_e2m1(v * pow2_neg(se));
+      const uint32_t next = __shfl_down(code, 1);
+      if (blk < n_blk && (lane & 1) == 0) codes[16 * blk + ((e & 31) >> 1)] = static_cast<uint8_t>(code | (next << 4));
+      if ((lane & 31) == 0) scales[blk] = static_cast<uint8_t>(blk < n_blk ? se + 127 : 127);
+    }
+  };
+  auto wave_sync = [] {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  };
+
+  val[lane] = 0.0;
+  val[lane + kWave] = 0.0;
+  wave_sync();
+  if (rot) {
+    double sn, cs;
+    sincos_f64(static_cast<double>(t) * f, &sn, &cs);
+    const double x = static_cast<double>(bf16_to_f32(kx));
+    const double y = static_cast<double>(bf16_to_f32(ky));
+    val[lane] = x * cs - y * sn;
+    val[lane + P] = x * sn + y * cs;
+  }
+  wave_sync();
+  const int nbk = mx_blocks(2 * P), nbv = mx_blocks(a.d_v);
+  quantise_row(nbk, reinterpret_cast<uint8_t*>(a.k_cache) + row * 16 * nbk, a.k_scales4 + row * 4);
+  wave_sync();
+  val[lane] = has_v0 ? static_cast<double>(bf16_to_f32(v0)) : 0.0;
+  val[lane + kWave] = has_v1 ? static_cast<double>(bf16_to_f32(v1)) : 0.0;
+  wave_sync();
+  quantise_row(nbv, reinterpret_cast<uint8_t*>(a.v_cache) + row * 16 * nbv, a.v_scales4 + row * 4);
+}
+
 // Many tokens per sequence (prefill-sized appends).  The per-token kernel above spends its time in
 // fp64 exp2 and sincos (about 0.6 ms for 131072 tokens x 8 heads, four times the HBM time of the
 // same rows) and in one memory round trip per token.  Here a wavefront takes runs_per_wave runs of
@@ -308,6 +384,12 @@ __global__ __launch_bounds__(256) void append_bulk_kernel(AppendArgs a, int runs
 }
 
 hipError_t launch_append(const AppendArgs& a, hipStream_t stream) {
+  if (a.k_scales4 != nullptr) {
+    const long long n_tok4 = static_cast<long long>(a.batch) * a.n_new;
+    dim3 grid4(static_cast<unsigned>((n_tok4 + 3) / 4), static_cast<unsigned>(a.n_kv), 1);
+    hipLaunchKernelGGL(append_mx4_kernel, grid4, dim3(256), 0, stream, a);
+    return hipGetLastError();
+  }
   if (a.k_scale != nullptr && a.n_new >= kBulkRun) {
     const long long runs = static_cast<long long>((a.n_new + kBulkRun - 1) / kBulkRun) * a.n_kv * a.batch;
     const int rpw = runs >= 32768 ? 4 : runs >= 16384 ? 2 : 1;

@@ -100,6 +100,32 @@ __host__ __device__ __forceinline__ float f64_to_f32_odd_clamped448(double y) {
 // against ceil(d_k / 16); one-byte V tiles: NT / 2 against ceil(d_v / 32)).  The last n_trim loads
 // are therefore trimmed to the tile by lane, all earlier ones are issued whole.  In a partial tile
 // (the last rows of a sequence) every load is trimmed to the bytes of the rows that exist.
+// ---- 4-bit caches: microscaling FP4 (E2M1 elements, one E8M0 scale byte per block of 32) --------
+// E2M1 code (S.EE.M; magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6) nearest to y, ties to the code with
+// mantissa bit 0, magnitudes above 6 saturate.  The thresholds are the midpoints between
+// neighbouring magnitudes, each closed on the side of its even neighbour.
+__host__ __device__ __forceinline__ uint32_t f64_to_e2m1(double y) {
+  const double a = y < 0 ? -y : y;
+  const uint32_t c = a <= 0.25 ? 0u : a < 0.75 ? 1u : a <= 1.25 ? 2u : a < 1.75 ? 3u : a <= 2.5 ? 4u : a < 3.5 ? 5u : a <= 5.0 ? 6u : 7u;
+  return c | ((__builtin_bit_cast(uint64_t, y) >> 63) != 0 ? 8u : 0u);
+}
+
+// Scale exponent of a block whose largest magnitude is amax (finite, not subnormal as a double):
+// floor(log2 amax) - 2, so that amax / 2^e lies in [4, 8), the top binade of E2M1; limited to
+// [-126, 127]; 0 for a block of zeros.  The scale byte is e + 127.
+__host__ __device__ __forceinline__ int mx_shared_exponent(double amax) {
+  if (!(amax > 0.0)) return 0;
+  const int e = static_cast<int>((__builtin_bit_cast(uint64_t, amax) >> 52) & 0x7ff) - 1023 - 2;
+  return e < -126 ? -126 : (e > 127 ? 127 : e);
+}
+
+// 2^(-e) for e in [-126, 127], exact
+__host__ __device__ __forceinline__ double pow2_neg(int e) {
+  return __builtin_bit_cast(double, static_cast<uint64_t>(1023 - e) << 52);
+}
+
+constexpr int mx_blocks(int d) { return (d + 31) / 32; }
+
 constexpr int decode_v_tiles(int d_v, bool q8) { return q8 ? 4 * ((d_v + 63) / 64) : (d_v + 15) / 16; }
 constexpr int k_tile_loads(int kch, bool q8) { return q8 ? kch : 2 * kch; }
 constexpr int v_tile_loads(int nt, bool q8) { return q8 ? (nt + 1) / 2 : nt; }

@@ -216,10 +216,21 @@ constexpr int kMaxCols = 16;   // columns of the matrix instruction: query rows 
 // lane takes FOUR adjacent V channels of a row with two aligned dwords (NT is 4 or 8, tile nt
 // holds channels 64 (nt / 4) + 4 l16 + (nt & 3)) and sorts the bytes of eight rows into the four
 // operands with byte permutes.
-template <int KCH, int NT, bool VPAIR, bool PAGED, bool Q8, bool AL>
+// MX4: the caches hold 4-bit codes (microscaling FP4: E2M1 elements, one E8M0 scale byte per block
+// of 32 elements; a row is KCH, respectively NT / 2, blocks of 16 code bytes, its scale bytes sit in
+// a second array, four per row).  A tile of 32 rows is a flat run of 16-byte blocks: a lane
+// fetches whole blocks with the scale byte of each, widens a block to 32 bf16 (exactly:
+// v_cvt_scalef32_pk_bf16_fp4 multiplies the two codes of a byte by the scale it is given; compared
+// on the device with the format's table for every byte value and scales from 2^-126 to 2^127) on
+// the way into LDS, and from there on the tile is a bf16 tile of 32 KCH x 16 NT elements with rows
+// 16 bytes apart from a multiple of 64 (so that fragment reads of 16 rows spread over the banks):
+// scores, softmax and P.V are the bf16 path's, instruction for instruction.
+template <int KCH, int NT, bool VPAIR, bool PAGED, bool Q8, bool AL, bool MX4 = false>
 __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(DecodeArgs a) {
-  constexpr int NLD_K = k_tile_loads(KCH, Q8);     // 1 KB wave-loads covering a K tile (d_k <= 32 KCH)
-  constexpr int NLD_V = v_tile_loads(NT, Q8);      // same for a V tile (d_v <= 16 NT)
+  // 1 KB wave-loads covering a K tile (d_k <= 32 KCH); MX4: 16-byte blocks of the tile per lane
+  constexpr int NLD_K = MX4 ? (kTileRows * KCH + 63) / 64 : k_tile_loads(KCH, Q8);
+  constexpr int NLD_V = MX4 ? (kTileRows * (NT / 2) + 63) / 64 : v_tile_loads(NT, Q8);   // same for a V tile (d_v <= 16 NT)
+  static_assert(!MX4 || (VPAIR && !PAGED && !Q8 && !AL && NT % 2 == 0), "4-bit caches: dense, blocks of 32 channels");
   constexpr int TRIM_K = k_tile_trimmed(Q8), TRIM_V = v_tile_trimmed(Q8);   // trailing loads trimmed by lane
   constexpr int EB = Q8 ? 1 : 2;                   // bytes per cache element
   constexpr int VLANE = Q8 ? 4 : (VPAIR ? 4 : 2);  // bytes of a V row one lane slot stands for
@@ -288,10 +299,11 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
   const int G = a.group;
   const int cols = G * a.n_tok;                    // query rows of this (b, h): columns of the matrix instruction
   const int dk = a.d_k, dv = a.d_v;
-  const int pitch_k = EB * dk, pitch_v = EB * dv;  // bytes
+  const int pitch_k = MX4 ? 16 * KCH : EB * dk, pitch_v = MX4 ? 8 * NT : EB * dv;   // bytes of a cache row
+  const int lpk = MX4 ? 64 * KCH + 16 : pitch_k, lpv = MX4 ? 32 * NT + 16 : pitch_v;  // bytes of a row in LDS
   // LDS slice of this wavefront: K area and V area, each a whole number of 1 KB wave-stores
   unsigned char* kt = smem + wave * a.lds_wave_bytes;
-  unsigned char* vt = kt + 1024 * NLD_K;
+  unsigned char* vt = kt + (MX4 ? kTileRows * lpk : 1024 * NLD_K);
 
   const long long slab = static_cast<long long>(b) * a.n_kv + h;
   const unsigned char* kslab = reinterpret_cast<const unsigned char*>(a.k_cache) + (PAGED ? 0 : slab * a.cap * pitch_k);
@@ -319,6 +331,28 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
   for (int j = 0; j < NLD_K; ++j) kst[j] = make_uint4(0, 0, 0, 0);
 #pragma unroll
   for (int j = 0; j < NLD_V; ++j) vst[j] = make_uint4(0, 0, 0, 0);
+  // MX4: the scale byte that goes with each staged block, where the block lands in LDS, and the
+  // slabs of the scale bytes.  Block c = lane + 64 j of a tile is block c % KCH of row c / KCH.
+  uint32_t kss[MX4 ? NLD_K : 1], vss[MX4 ? NLD_V : 1];
+  int k_lds[MX4 ? NLD_K : 1], v_lds[MX4 ? NLD_V : 1];
+  const unsigned char* ksslab = nullptr;
+  const unsigned char* vsslab = nullptr;
+  if constexpr (MX4) {
+    ksslab = a.k_scales4 + slab * a.cap * 4;
+    vsslab = a.v_scales4 + slab * a.cap * 4;
+#pragma unroll
+    for (int j = 0; j < NLD_K; ++j) {
+      const int c = lane + 64 * j, row = c / KCH;
+      kss[j] = 127;
+      k_lds[j] = row * lpk + (c - row * KCH) * 64;
+    }
+#pragma unroll
+    for (int j = 0; j < NLD_V; ++j) {
+      const int c = lane + 64 * j, row = c / (NT / 2);
+      vss[j] = 127;
+      v_lds[j] = row * lpv + (c - row * (NT / 2)) * 64;
+    }
+  }
 
   // A full tile is fetched with whole-KB loads except the last one or two of each run, which are
   // trimmed to the tile's own bytes (tile_load_issued): nothing is fetched twice, nothing beyond
@@ -331,6 +365,28 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
   auto issue_loads = [&](int base, long long trow) {
     const unsigned char* kg = kslab + trow * pitch_k + 16 * lane;
     const unsigned char* vg = vslab + trow * pitch_v + 16 * lane;
+    if constexpr (MX4) {
+      // whole blocks of the rows below len8 (<= cache_cap), each with its scale byte: block c of the
+      // tile is 16 c bytes into it, its scale byte 4 (c / KCH) + c % KCH bytes into the tile's scales
+      const int rows = min(kTileRows, len8 - base);
+#pragma unroll
+      for (int j = 0; j < NLD_K; ++j) {
+        const int c = lane + 64 * j, row = c / KCH;
+        if (c < rows * KCH) {
+          kst[j] = ld_stream(kg + 1024 * j);
+          kss[j] = ksslab[(trow + row) * 4 + (c - row * KCH)];
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < NLD_V; ++j) {
+        const int c = lane + 64 * j, row = c / (NT / 2);
+        if (c < rows * (NT / 2)) {
+          vst[j] = ld_stream(vg + 1024 * j);
+          vss[j] = vsslab[(trow + row) * 4 + (c - row * (NT / 2))];
+        }
+      }
+      return;
+    }
     if (base + kTileRows <= len8) {
       // common case, a full tile
 #pragma unroll
@@ -400,19 +456,42 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
   // LDS byte offsets of this lane's operands inside a tile
   int koff[2];
 #pragma unroll
-  for (int rt = 0; rt < 2; ++rt) koff[rt] = (16 * rt + l16) * pitch_k + 8 * EB * lg;
+  for (int rt = 0; rt < 2; ++rt) koff[rt] = (16 * rt + l16) * lpk + 8 * EB * lg;
   int vo_laid[8];   // V rows of the lane's eight contraction slots as laid out: j = 4 rt + r is row 16 rt + 4 lg + r
 #pragma unroll
-  for (int j = 0; j < 8; ++j) vo_laid[j] = (16 * (j >> 2) + 4 * lg + (j & 3)) * pitch_v + VLANE * l16;
+  for (int j = 0; j < 8; ++j) vo_laid[j] = (16 * (j >> 2) + 4 * lg + (j & 3)) * lpv + VLANE * l16;
+  // MX4: a staged block of 32 codes becomes 32 bf16 (64 bytes) of its row in LDS
+  auto park_mx4 = [&](unsigned char* area, int off, const uint4& blk, uint32_t scale_byte) {
+    const float sc = bits_f32((scale_byte & 0xffu) << 23);       // 2^(e - 127), e >= 1
+    const uint32_t w[4] = {blk.x, blk.y, blk.z, blk.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint4 o;
+      o.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[i], sc, 0));
+      o.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[i], sc, 1));
+      o.z = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[i], sc, 2));
+      o.w = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[i], sc, 3));
+      *reinterpret_cast<uint4*>(area + off + 16 * i) = o;
+    }
+  };
 
 
   for (int base = first; base < r1; base += 4 * kTileRows) {
     // ---- park the staged tile in LDS, start fetching the next one
     wave_lds_sync();
+    if constexpr (MX4) {
 #pragma unroll
-    for (int j = 0; j < NLD_K; ++j) *reinterpret_cast<uint4*>(kt + 1024 * j + 16 * lane) = kst[j];
+      for (int j = 0; j < NLD_K; ++j)
+        if (lane + 64 * j < kTileRows * KCH) park_mx4(kt, k_lds[j], kst[j], kss[j]);
 #pragma unroll
-    for (int j = 0; j < NLD_V; ++j) *reinterpret_cast<uint4*>(vt + 1024 * j + 16 * lane) = vst[j];
+      for (int j = 0; j < NLD_V; ++j)
+        if (lane + 64 * j < kTileRows * (NT / 2)) park_mx4(vt, v_lds[j], vst[j], vss[j]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < NLD_K; ++j) *reinterpret_cast<uint4*>(kt + 1024 * j + 16 * lane) = kst[j];
+#pragma unroll
+      for (int j = 0; j < NLD_V; ++j) *reinterpret_cast<uint4*>(vt + 1024 * j + 16 * lane) = vst[j];
+    }
     wave_lds_sync();
     if (base + 4 * kTileRows < r1) issue_loads(base + 4 * kTileRows, PAGED ? trow1 : base + 4 * kTileRows);
     if (PAGED && base + 8 * kTileRows < r1) trow1 = tile_row(base + 8 * kTileRows);
@@ -537,7 +616,7 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
         for (int j = 0; j < 8; ++j) {
           int row = min(16 * (j >> 2) + 4 * lg + (j & 3), nv - 1);
           row = row == skip_rel ? (skip_rel == 0 ? min(1, nv - 1) : skip_rel - 1) : row;
-          vo_laid[j] = row * pitch_v + VLANE * l16;
+          vo_laid[j] = row * lpv + VLANE * l16;
         }
       }
 #pragma unroll
@@ -547,7 +626,7 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
       for (int j = 0; j < 8; ++j) {
         int row = min(16 * (j >> 2) + 4 * lg + (j & 3), nv - 1);
         row = row == skip_rel ? (skip_rel == 0 ? min(1, nv - 1) : skip_rel - 1) : row;
-        vo[j] = plain ? vo_laid[j] : row * pitch_v + VLANE * l16;
+        vo[j] = plain ? vo_laid[j] : row * lpv + VLANE * l16;
       }
     }
     if constexpr (Q8) {
@@ -612,7 +691,7 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
     }
     if (Q8 && !plain) {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) vo_laid[j] = (16 * (j >> 2) + 4 * lg + (j & 3)) * pitch_v + VLANE * l16;
+      for (int j = 0; j < 8; ++j) vo_laid[j] = (16 * (j >> 2) + 4 * lg + (j & 3)) * lpv + VLANE * l16;
     }
   }
 
@@ -668,17 +747,17 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
   }
 }
 
-template <int KCH, int NT, bool VPAIR, bool PAGED, bool Q8, bool AL = false>
+template <int KCH, int NT, bool VPAIR, bool PAGED, bool Q8, bool AL = false, bool MX4 = false>
 hipError_t launch_inst2(const DecodeArgs& a, hipStream_t stream) {
   // scanning workgroups, then (decode step: n_slots = n_split + 1) one per (b, h) for the new token
   dim3 grid(static_cast<unsigned>(a.n_slots) * a.n_kv * a.batch), block(256);
   const size_t lds = 4 * static_cast<size_t>(a.lds_wave_bytes);
   if (lds > 64 * 1024) {
     // more than the default dynamic-LDS limit: raise it once per kernel (gfx950 has 160 KB per CU)
-    const hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(&decode_mfma_kernel<KCH, NT, VPAIR, PAGED, Q8, AL>), static_cast<int>(lds));
+    const hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(&decode_mfma_kernel<KCH, NT, VPAIR, PAGED, Q8, AL, MX4>), static_cast<int>(lds));
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((decode_mfma_kernel<KCH, NT, VPAIR, PAGED, Q8, AL>), grid, block, lds, stream, a);
+  hipLaunchKernelGGL((decode_mfma_kernel<KCH, NT, VPAIR, PAGED, Q8, AL, MX4>), grid, block, lds, stream, a);
   return hipGetLastError();
 }
 

@@ -5,6 +5,7 @@
 namespace rap {
 
 hipError_t launch_decode_mfma_q8(const DecodeArgs& a, hipStream_t stream);   // rap_decode_mfma_q8.hip
+hipError_t launch_decode_mfma_mx4(const DecodeArgs& a, hipStream_t stream);  // rap_decode_mfma_mx4.hip
 
 namespace {
 
@@ -43,15 +44,18 @@ hipError_t launch_k(const DecodeArgs& a, hipStream_t stream) {
 
 // LDS bytes one wavefront needs: its K tile, its V tile and slack for the fragment reads that run
 // past the last row, or the hand-over area of the final fold, whichever is larger.
-int mfma_lds_wave_bytes(int d_k, int d_v, bool q8, int cols) {
-  const int nt = decode_v_tiles(d_v, q8);
-  const int tiles = 1024 * (k_tile_loads((d_k + 31) / 32, q8) + v_tile_loads(nt, q8)) + 128;
+// (4-bit caches: the tile is widened on its way into LDS, to rows of 32 bf16 per block plus 16 bytes.)
+int mfma_lds_wave_bytes(int d_k, int d_v, bool q8, int cols, bool mx4) {
+  const int nt = mx4 ? 2 * mx_blocks(d_v) : decode_v_tiles(d_v, q8);
+  const int tiles = mx4 ? 32 * (64 * mx_blocks(d_k) + 16 + 32 * nt + 16) + 128
+                        : 1024 * (k_tile_loads((d_k + 31) / 32, q8) + v_tile_loads(nt, q8)) + 128;
   const int fold = (32 + (cols > kMaxGroup ? kMaxCols : kMaxGroup) * 16 * nt) * 4;
   const int need = tiles > fold ? tiles : fold;
   return (need + 127) / 128 * 128;
 }
 
 hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t stream) {
+  if (a.k_scales4 != nullptr) return launch_decode_mfma_mx4(a, stream);
   if (a.k_scale != nullptr) return launch_decode_mfma_q8(a, stream);
   switch ((a.d_k + 31) / 32) {
     case 1: return launch_k<1>(a, stream);

@@ -62,6 +62,8 @@ struct AppendArgs {
   const int32_t* block_table;       // paged caches: [B, max_pages], or null
   const float* k_scale;             // fp8 caches: [H_kv] scales of the codes, or null
   const float* v_scale;
+  uint8_t* k_scales4;               // 4-bit caches: scale bytes [B, H_kv, cap, 4], or null
+  uint8_t* v_scales4;
   int32_t page_shift, n_pages, max_pages;
   uint16_t* k_cache;
   uint16_t* v_cache;
@@ -84,6 +86,10 @@ struct DecodeArgs {
   // fp8 caches (null otherwise): per-KV-head scales of the E4M3 codes
   const float* k_scale;
   const float* v_scale;
+  // 4-bit caches (null otherwise): k_cache / v_cache hold the code blocks, these the scale bytes,
+  // [B, H_kv, cap, 4] each
+  const uint8_t* k_scales4;
+  const uint8_t* v_scales4;
   // paged caches (block_table null otherwise): pools [n_pages, H_kv, 1 << page_shift, d]
   const int32_t* block_table;   // [B, max_pages]
   int32_t page_shift, n_pages, max_pages;

@@ -6,6 +6,8 @@
 //   rap_arith_host bf16      stdin: float64[n]  -> stdout: uint16[n]   f64_to_bf16_rne
 //   rap_arith_host sincos    stdin: float64[n]  -> stdout: float64[2n] sincos_f64 (sin, cos)
 //   rap_arith_host odd448    stdin: float64[n]  -> stdout: uint32[n]   bits of f64_to_f32_odd_clamped448
+//   rap_arith_host mx4       stdin: float64[32 n] (n blocks) -> stdout: per block one byte
+//                               mx_shared_exponent + 127 and 32 bytes f64_to_e2m1(x * pow2_neg(e))
 //   rap_arith_host loadplan  -> text, one line per (kind, width, element size): what the decode
 //                               kernel's tile loads touch; exit status 1 if any load leaves its tile,
 //                               or any tile byte is fetched twice or not at all
@@ -71,7 +73,7 @@ int loadplan(bool trim_one_only) {
 
 int main(int argc, char** argv) {
   if (argc != 2) {
-    fprintf(stderr, "usage: rap_arith_host bf16|sincos|odd448|loadplan|loadplan-trim1\n");
+    fprintf(stderr, "usage: rap_arith_host bf16|sincos|odd448|mx4|loadplan|loadplan-trim1\n");
     return 2;
   }
   if (strcmp(argv[1], "loadplan") == 0) return loadplan(false) == 0 ? 0 : 1;
@@ -89,6 +91,19 @@ int main(int argc, char** argv) {
     std::vector<uint32_t> out(in.size());
     for (size_t i = 0; i < in.size(); ++i) out[i] = rap::f32_bits(rap::f64_to_f32_odd_clamped448(in[i]));
     fwrite(out.data(), sizeof(uint32_t), out.size(), stdout);
+  } else if (strcmp(argv[1], "mx4") == 0) {
+    std::vector<uint8_t> out;
+    for (size_t b = 0; b + 32 <= in.size(); b += 32) {
+      double amax = 0.0;
+      for (int i = 0; i < 32; ++i) {
+        const double m = in[b + i] < 0 ? -in[b + i] : in[b + i];
+        amax = m > amax ? m : amax;
+      }
+      const int e = rap::mx_shared_exponent(amax);
+      out.push_back(static_cast<uint8_t>(e + 127));
+      for (int i = 0; i < 32; ++i) out.push_back(static_cast<uint8_t>(rap::f64_to_e2m1(in[b + i] * rap::pow2_neg(e))));
+    }
+    fwrite(out.data(), 1, out.size(), stdout);
   } else {
     fprintf(stderr, "unknown command %s\n", argv[1]);
     return 2;

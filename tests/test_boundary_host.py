@@ -125,6 +125,13 @@ def test_later_entry_points_reject_bad_arguments(rap):
     assert a8(shp) == 1 and d8(shp) == 1
     assert a8(_shape(rap, cache_cap=511)) == 2 and d8(_shape(rap, n_q_heads=7)) == 2
     assert a8(_shape(rap, batch=0)) == 0 and d8(_shape(rap, batch=0)) == 0
+    # 4-bit append / attention: everything null is a null pointer, bad shapes are seen first, empty batches are no-ops
+    a4 = lambda s: rap.rap_rope_append_mx4(s, 1, None, None, None, None, None, None, None, None, check=False)
+    d4 = lambda s, msl=8: rap.rap_decode_attn_mx4(s, None, None, None, None, None, None, msl, None, 0.1, None, None, check=False)
+    assert a4(shp) == 1 and d4(shp) == 1
+    assert a4(_shape(rap, cache_cap=511)) == 2 and d4(_shape(rap, n_q_heads=7)) == 2
+    assert a4(_shape(rap, batch=0)) == 0 and d4(_shape(rap, batch=0)) == 0
+    assert d4(shp, msl=513) == 4
     # paged fp8
     ap8 = lambda s, p: rap.rap_rope_append_paged_q8(s, p, 1, None, None, None, None, None, None, None, None, check=False)
     dp8 = lambda s, p: rap.rap_decode_attn_paged_q8(s, p, None, None, None, None, None, None, None, None, 512, None, 0.1, None,

@@ -142,6 +142,36 @@ def test_round_to_odd_then_nearest_even_is_one_rounding(harness):
     assert np.any(O.f64_to_e4m3_bits(plain) != O.f64_to_e4m3_bits(x))
 
 
+def test_mx4_block_quantiser_equals_oracle(harness):
+    """The 4-bit append's arithmetic (scale exponent of a block from its largest magnitude, division
+    by that power of two, rounding to E2M1): codes and scale bytes equal the oracle's for random
+    blocks over many magnitudes, blocks whose maximum sits at and next to a power of two, elements at
+    and next to every tie between neighbouring codes, zeros, signed zeros and the clamped extremes."""
+    rng = _rng(44)
+    blocks = [rng.standard_normal((4000, 32)) * 10.0 ** rng.integers(-30, 30, (4000, 1))]
+    grid = O.e2m1_code_to_f64(np.arange(8))
+    mids = (grid[:-1] + grid[1:]) / 2
+    ties = np.concatenate([mids, np.nextafter(mids, 0.0), np.nextafter(mids, 10.0), grid, [5.0, 5.5, 6.5, 7.99]])
+    for k in (-140, -126, -40, -1, 0, 3, 77, 127):
+        for top in (4.0, np.nextafter(4.0, 0.0), np.nextafter(8.0, 0.0), 6.0, 5.0):
+            b = np.zeros(32)
+            b[:ties.size] = ties[:32]
+            b[31] = top                                   # fixes the block's scale at 2^k (or the binade below)
+            b[1::2] *= -1
+            blocks.append((b * 2.0 ** k)[None, :])
+    blocks.append(np.zeros((1, 32)))
+    blocks.append(np.where(np.arange(32) % 2 == 0, 0.0, -0.0)[None, :])
+    blocks.append(np.full((1, 32), 3.0e38))
+    blocks.append(np.full((1, 32), 2.0 ** -133))
+    x = np.concatenate(blocks)
+    raw = _run(harness, "mx4", x.ravel(), np.uint8).reshape(-1, 33)
+    codes, scales = O.mx4_quantize_rows(x)
+    assert np.array_equal(raw[:, 0], scales[:, 0])
+    packed = (raw[:, 1::2] | (raw[:, 2::2] << 4)).astype(np.uint8)
+    bad = np.nonzero((packed != codes).any(axis=1))[0]
+    assert bad.size == 0, (bad[:5], x[bad[0]], raw[bad[0]], codes[bad[0]])
+
+
 def test_decode_tile_loads_stay_inside_the_tile(harness):
     """Every 16-byte load the decode kernel issues for a K or V tile, for every width the library
     accepts, both element sizes, full and partial tiles: inside the tile's bytes, every byte once."""
