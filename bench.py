@@ -305,6 +305,89 @@ def q8_figure(rap, torch, job, steps, warmup):
     return s8, s16, job.bytes_per_step / 2
 
 
+def mx4_figure(rap, torch, job, steps, warmup):
+    """rap_decode_attn_mx4 over 4-bit caches of the same shape and lengths (random codes, scale
+    bytes around 2^-2): seconds per attention call (median) and the code and scale bytes read."""
+    w = job.w
+    dev = job.out.device
+    cap = max(c.cap for c in job.cases)
+    shp = rap.shape(w.batch, w.n_q_heads, w.n_kv_heads, w.d_head, w.n_pairs, w.d_v, cap, w.rope_theta)
+    nbk, nbv = (w.d_k + 31) // 32, (w.d_v + 31) // 32
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed + 13)
+    pools = []
+    for _ in job.cases:
+        kc = torch.randint(0, 256, (w.batch, w.n_kv_heads, cap, 16 * nbk), generator=gen, device=dev, dtype=torch.uint8)
+        vc = torch.randint(0, 256, (w.batch, w.n_kv_heads, cap, 16 * nbv), generator=gen, device=dev, dtype=torch.uint8)
+        ks = torch.randint(123, 127, (w.batch, w.n_kv_heads, cap, 4), generator=gen, device=dev, dtype=torch.uint8)
+        vs = torch.randint(123, 127, (w.batch, w.n_kv_heads, cap, 4), generator=gen, device=dev, dtype=torch.uint8)
+        pools.append((kc, ks, vc, vs))
+    ws = rap.new_workspace(shp, job.max_len, None, device=dev)
+    n = len(job.cases)
+
+    def call(i):
+        c = job.cases[i % n]
+        kc, ks, vc, vs = pools[i % n]
+        rap.rap_decode_attn_mx4(shp, c.q, kc, ks, vc, vs, c.seq_lens, job.max_len, job.out, float(w.scale), ws, None)
+
+    s4 = blocks(call, steps, warmup + 3 * n, torch.cuda.synchronize)[0]
+    del pools
+    torch.cuda.empty_cache()
+    rows = job.bytes_per_step / (2 * (w.d_k + w.d_v))                 # cache rows read per step (K and V counted once each)
+    return s4, rows * (16 * (nbk + nbv) + nbk + nbv)
+
+
+def next_rows_figure(rap, torch, job, steps, warmup):
+    """The other calls of the path at the headline shape, each alone (medians): the attention with
+    the query rotation fused in, the attention over paged pools (pages of 128 rows behind a
+    shuffled table), and a prefill-sized append (every row of every sequence in one call; bytes
+    read + written)."""
+    w = job.w
+    c = job.cases[0]
+    dev = job.out.device
+    sync = torch.cuda.synchronize
+    qpos = (c.seq_lens - 1).clamp(min=0).to(torch.int32)
+    s_rope = blocks(lambda i: rap.rap_decode_attn_rope(job.shape, c.q, qpos, c.keep, c.k_cache, c.v_cache, c.seq_lens, job.max_len,
+                                                       job.out, float(w.scale), job.ws, None), steps, warmup, sync, reps=5)[0]
+    page_rows = 128
+    max_pages = (job.max_len + page_rows - 1) // page_rows
+    cap = max_pages * page_rows
+    n_pages = w.batch * max_pages
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed + 17)
+    perm = torch.randperm(n_pages, generator=gen, device=dev)
+
+    def to_pool(x, d):      # dense [B, H, cap_d, d] -> pool [n_pages, H, page_rows, d] through the table
+        xd = torch.zeros((w.batch, w.n_kv_heads, cap, d), dtype=x.dtype, device=dev)
+        n = min(cap, x.shape[2])
+        xd[:, :, :n] = x[:, :, :n]
+        xp = xd.reshape(w.batch, w.n_kv_heads, max_pages, page_rows, d).permute(0, 2, 1, 3, 4).reshape(n_pages, w.n_kv_heads, page_rows, d)
+        pool = torch.empty_like(xp)
+        pool[perm] = xp
+        return pool.contiguous()
+
+    kp, vp = to_pool(c.k_cache, w.d_k), to_pool(c.v_cache, w.d_v)
+    table = perm.reshape(w.batch, max_pages).to(torch.int32).contiguous()
+    shp = rap.shape(w.batch, w.n_q_heads, w.n_kv_heads, w.d_head, w.n_pairs, w.d_v, cap, w.rope_theta)
+    pg = rap.paging(page_rows, n_pages, table)
+    wsp = rap.new_workspace(shp, job.max_len, None, device=dev)
+    s_paged = blocks(lambda i: rap.rap_decode_attn_paged(shp, pg, c.q, None, None, kp, vp, c.seq_lens, job.max_len, job.out,
+                                                         float(w.scale), wsp, None), steps, warmup, sync, reps=5)[0]
+    del kp, vp
+    n_new = int(min(job.max_len, c.cap))
+    gen.manual_seed(w.seed + 19)
+    k_new = torch.randn((w.batch, n_new, w.n_kv_heads, w.d_k), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    v_new = torch.randn((w.batch, n_new, w.n_kv_heads, w.d_v), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    pos = torch.arange(n_new, dtype=torch.int32, device=dev).repeat(w.batch, 1).contiguous()
+    kc, vc = c.k_cache.clone(), c.v_cache.clone()
+    s_bulk = blocks(lambda i: rap.rap_rope_append(job.shape, n_new, k_new, v_new, pos, c.keep, kc, vc), 5, 2, sync, reps=5)[0]
+    nbytes = 2.0 * w.batch * n_new * w.n_kv_heads * (w.d_k + w.d_v) * 2
+    del k_new, v_new, kc, vc
+    torch.cuda.empty_cache()
+    return {"rope_ms": r(s_rope * 1e3, 5), "paged_ms": r(s_paged * 1e3, 5), "bulk_append_ms": r(s_bulk * 1e3, 4),
+            "bulk_append_GBps": r(nbytes / s_bulk / 1e9, 1)}
+
+
 def multi_figure(rap, torch, job, steps, warmup):
     """rap_decode_attn_multi over the job's caches: the causal attention of the last n_tok rows of
     every sequence, n_tok = 16 // G of them (the most one launch takes), the attention call alone."""
@@ -417,13 +500,16 @@ def main():
         vsec = blocks(lambda i: job.step(i, tuning=tun1), max(2, args.steps // 4), 2, torch.cuda.synchronize, reps=5)[0]
         valu = {"ms": r(vsec * 1e3, 5), "GBps": r(job.bytes_per_step / vsec / 1e9, 1)}
 
-    q8 = multi = None
+    q8 = multi = mx4 = others = None
     if not args.no_q8:
         s8, s16, b8 = q8_figure(rap, torch, job, args.steps, args.warmup)
         q8 = {"ms": r(s8 * 1e3, 5), "GBps": r(b8 / s8 / 1e9, 1), "frac": r(b8 / s8 / 1e9 / HBM_PEAK_GBPS), "bf16_ms": r(s16 * 1e3, 5),
               "x_bf16": r(s16 / s8)}
+        s4, b4 = mx4_figure(rap, torch, job, args.steps, args.warmup)
+        mx4 = {"ms": r(s4 * 1e3, 5), "GBps": r(b4 / s4 / 1e9, 1), "x_bf16": r(s16 / s4)}
         n_tok, sm = multi_figure(rap, torch, job, args.steps, args.warmup)
         multi = {"n_tok": n_tok, "ms": r(sm * 1e3, 5)}
+        others = next_rows_figure(rap, torch, job, args.steps, args.warmup) if w.ragged_min is None and w.n_new == 1 else None
 
     if args.copy_calibration:
         csrc = torch.full((256 << 20,), 3, dtype=torch.uint8, device=dev)
@@ -452,7 +538,9 @@ def main():
         result["one_call_step_ms"] = [r(sec_one * 1e3, 5), r(sec_rope * 1e3, 5)]     # query rotated / rotation fused in
     if q8 is not None:
         result["fp8"] = q8
+        result["mx4"] = mx4
         result["multi"] = multi
+        result["other_calls"] = others
     if valu is not None:
         result["valu_kernel"] = valu
 
