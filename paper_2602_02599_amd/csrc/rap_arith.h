@@ -125,6 +125,18 @@ __host__ __device__ __forceinline__ double pow2_neg(int e) {
 }
 
 constexpr int mx_blocks(int d) { return (d + 31) / 32; }
+// A widened 4-bit tile in LDS: 32 rows of nb blocks of 32 bf16 (64 bytes).  The layout is chosen so
+// that, with LDS serving 128 bytes per clock, neither the 16-byte stores that fill the tile (lane c
+// holds block c % nb of row c / nb) nor the 16-byte K fragment reads (16 rows, one column) nor the
+// 4-byte V reads fall on the same banks: rows 16 bytes past a multiple of 32 and blocks 64 bytes
+// apart for one, two and four blocks (with four, the upper two blocks of a row also store their
+// four 16-byte pieces in the order 2, 3, 0, 1: blocks 0 and 2 of a row are 128 bytes apart); three
+// blocks lie 80 bytes apart in rows of 240 bytes.  (One extra 16 bytes per row was measured against
+// none, 32 and 48 at the time the blocks were all 64 bytes apart: cfg3 shape 298 us against 733,
+// 326 and 298 us.)
+constexpr int mx4_block_stride(int nb) { return nb == 3 ? 80 : 64; }
+constexpr int mx4_row_pitch(int nb) { return nb == 3 ? 240 : 64 * nb + 16; }
+constexpr bool mx4_rotate_upper_blocks(int nb) { return nb == 4; }
 
 constexpr int decode_v_tiles(int d_v, bool q8) { return q8 ? 4 * ((d_v + 63) / 64) : (d_v + 15) / 16; }
 constexpr int k_tile_loads(int kch, bool q8) { return q8 ? kch : 2 * kch; }

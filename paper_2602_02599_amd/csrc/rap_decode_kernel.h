@@ -222,9 +222,9 @@ constexpr int kMaxCols = 16;   // columns of the matrix instruction: query rows 
 // fetches whole blocks with the scale byte of each, widens a block to 32 bf16 (exactly:
 // v_cvt_scalef32_pk_bf16_fp4 multiplies the two codes of a byte by the scale it is given; compared
 // on the device with the format's table for every byte value and scales from 2^-126 to 2^127) on
-// the way into LDS, and from there on the tile is a bf16 tile of 32 KCH x 16 NT elements with rows
-// 16 bytes apart from a multiple of 64 (so that fragment reads of 16 rows spread over the banks):
-// scores, softmax and P.V are the bf16 path's, instruction for instruction.
+// the way into LDS, and from there on the tile is a bf16 tile of 32 KCH x 16 NT elements (rows and
+// blocks placed so that neither the stores nor the fragment reads collide on LDS banks, see
+// mx4_row_pitch): scores, softmax and P.V are the bf16 path's, instruction for instruction.
 template <int KCH, int NT, bool VPAIR, bool PAGED, bool Q8, bool AL, bool MX4 = false>
 __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(DecodeArgs a) {
   // 1 KB wave-loads covering a K tile (d_k <= 32 KCH); MX4: 16-byte blocks of the tile per lane
@@ -300,7 +300,8 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
   const int cols = G * a.n_tok;                    // query rows of this (b, h): columns of the matrix instruction
   const int dk = a.d_k, dv = a.d_v;
   const int pitch_k = MX4 ? 16 * KCH : EB * dk, pitch_v = MX4 ? 8 * NT : EB * dv;   // bytes of a cache row
-  const int lpk = MX4 ? 64 * KCH + 16 : pitch_k, lpv = MX4 ? 32 * NT + 16 : pitch_v;  // bytes of a row in LDS
+  const int lpk = MX4 ? mx4_row_pitch(KCH) : pitch_k, lpv = MX4 ? mx4_row_pitch(NT / 2) : pitch_v;   // bytes of a row in LDS
+  constexpr int SK = MX4 ? mx4_block_stride(KCH) : 64, SV = MX4 ? mx4_block_stride(NT / 2) : 64;    // bytes from one 32-element block of a row to the next
   // LDS slice of this wavefront: K area and V area, each a whole number of 1 KB wave-stores
   unsigned char* kt = smem + wave * a.lds_wave_bytes;
   unsigned char* vt = kt + (MX4 ? kTileRows * lpk : 1024 * NLD_K);
@@ -335,6 +336,7 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
   // slabs of the scale bytes.  Block c = lane + 64 j of a tile is block c % KCH of row c / KCH.
   uint32_t kss[MX4 ? NLD_K : 1], vss[MX4 ? NLD_V : 1];
   int k_lds[MX4 ? NLD_K : 1], v_lds[MX4 ? NLD_V : 1];
+  bool k_rot[MX4 ? NLD_K : 1], v_rot[MX4 ? NLD_V : 1];     // this block stores its pieces in the order 2, 3, 0, 1
   const unsigned char* ksslab = nullptr;
   const unsigned char* vsslab = nullptr;
   if constexpr (MX4) {
@@ -344,13 +346,15 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
     for (int j = 0; j < NLD_K; ++j) {
       const int c = lane + 64 * j, row = c / KCH;
       kss[j] = 127;
-      k_lds[j] = row * lpk + (c - row * KCH) * 64;
+      k_lds[j] = row * lpk + (c - row * KCH) * SK;
+      k_rot[j] = mx4_rotate_upper_blocks(KCH) && ((c - row * KCH) & 2) != 0;
     }
 #pragma unroll
     for (int j = 0; j < NLD_V; ++j) {
       const int c = lane + 64 * j, row = c / (NT / 2);
       vss[j] = 127;
-      v_lds[j] = row * lpv + (c - row * (NT / 2)) * 64;
+      v_lds[j] = row * lpv + (c - row * (NT / 2)) * SV;
+      v_rot[j] = mx4_rotate_upper_blocks(NT / 2) && ((c - row * (NT / 2)) & 2) != 0;
     }
   }
 
@@ -461,17 +465,20 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
 #pragma unroll
   for (int j = 0; j < 8; ++j) vo_laid[j] = (16 * (j >> 2) + 4 * lg + (j & 3)) * lpv + VLANE * l16;
   // MX4: a staged block of 32 codes becomes 32 bf16 (64 bytes) of its row in LDS
-  auto park_mx4 = [&](unsigned char* area, int off, const uint4& blk, uint32_t scale_byte) {
+  // (rot: the block's 16-byte pieces are stored in the order 2, 3, 0, 1, each at its own place)
+  auto park_mx4 = [&](unsigned char* area, int off, const uint4& blk, uint32_t scale_byte, bool rot, bool may_rot) {
     const float sc = bits_f32((scale_byte & 0xffu) << 23);       // 2^(e - 127), e >= 1
     const uint32_t w[4] = {blk.x, blk.y, blk.z, blk.w};
+    const int off_lo = may_rot && rot ? off + 32 : off, off_hi = may_rot && rot ? off - 32 : off;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
+      const uint32_t src = may_rot && rot ? w[i ^ 2] : w[i];
       uint4 o;
-      o.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[i], sc, 0));
-      o.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[i], sc, 1));
-      o.z = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[i], sc, 2));
-      o.w = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[i], sc, 3));
-      *reinterpret_cast<uint4*>(area + off + 16 * i) = o;
+      o.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(src, sc, 0));
+      o.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(src, sc, 1));
+      o.z = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(src, sc, 2));
+      o.w = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(src, sc, 3));
+      *reinterpret_cast<uint4*>(area + (i < 2 ? off_lo : off_hi) + 16 * i) = o;
     }
   };
 
@@ -482,10 +489,10 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
     if constexpr (MX4) {
 #pragma unroll
       for (int j = 0; j < NLD_K; ++j)
-        if (lane + 64 * j < kTileRows * KCH) park_mx4(kt, k_lds[j], kst[j], kss[j]);
+        if (lane + 64 * j < kTileRows * KCH) park_mx4(kt, k_lds[j], kst[j], kss[j], k_rot[j], mx4_rotate_upper_blocks(KCH));
 #pragma unroll
       for (int j = 0; j < NLD_V; ++j)
-        if (lane + 64 * j < kTileRows * (NT / 2)) park_mx4(vt, v_lds[j], vst[j], vss[j]);
+        if (lane + 64 * j < kTileRows * (NT / 2)) park_mx4(vt, v_lds[j], vst[j], vss[j], v_rot[j], mx4_rotate_upper_blocks(NT / 2));
     } else {
 #pragma unroll
       for (int j = 0; j < NLD_K; ++j) *reinterpret_cast<uint4*>(kt + 1024 * j + 16 * lane) = kst[j];
@@ -520,7 +527,7 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
           }
           w = widen_e4m3x8(c0, c1);
         } else {
-          const uint32_t* p = reinterpret_cast<const uint32_t*>(kt + koff[rt] + 64 * kk);
+          const uint32_t* p = reinterpret_cast<const uint32_t*>(kt + koff[rt] + SK * kk);
           w = make_uint4(p[0], p[1], p[2], p[3]);
           if (kk == KCH - 1) {
             w.x &= kmask[0];
@@ -662,7 +669,7 @@ __global__ __launch_bounds__(256, (KCH <= 3 ? 3 : 2)) void decode_mfma_kernel(De
         uint4 be, bo;   // even / odd channel of the pair, rows packed two by two
         uint32_t w[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) w[j] = *reinterpret_cast<const uint32_t*>(vt + vo[j] + 64 * np);
+        for (int j = 0; j < 8; ++j) w[j] = *reinterpret_cast<const uint32_t*>(vt + vo[j] + SV * np);
         be.x = __builtin_amdgcn_perm(w[1], w[0], 0x05040100u);
         be.y = __builtin_amdgcn_perm(w[3], w[2], 0x05040100u);
         be.z = __builtin_amdgcn_perm(w[5], w[4], 0x05040100u);

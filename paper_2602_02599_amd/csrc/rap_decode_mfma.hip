@@ -47,7 +47,7 @@ hipError_t launch_k(const DecodeArgs& a, hipStream_t stream) {
 // (4-bit caches: the tile is widened on its way into LDS, to rows of 32 bf16 per block plus 16 bytes.)
 int mfma_lds_wave_bytes(int d_k, int d_v, bool q8, int cols, bool mx4) {
   const int nt = mx4 ? 2 * mx_blocks(d_v) : decode_v_tiles(d_v, q8);
-  const int tiles = mx4 ? 32 * (64 * mx_blocks(d_k) + 16 + 32 * nt + 16) + 128
+  const int tiles = mx4 ? 32 * (mx4_row_pitch(mx_blocks(d_k)) + mx4_row_pitch(nt / 2)) + 128
                         : 1024 * (k_tile_loads((d_k + 31) / 32, q8) + v_tile_loads(nt, q8)) + 128;
   const int fold = (32 + (cols > kMaxGroup ? kMaxCols : kMaxGroup) * 16 * nt) * 4;
   const int need = tiles > fold ? tiles : fold;
