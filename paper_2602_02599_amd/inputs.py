@@ -63,6 +63,10 @@ WORKLOADS = {
     "cfg5_rho1": Workload("cfg5_rho1", 64, 32, 8, 128, 5.0e5, 64, 128, 65536 + 4, 4, _S128, ragged_min=512, seed=1005),
     # rho = 1 control of the headline workload (same lengths, full head).
     "cfg2_rho1": Workload("cfg2_rho1", 16, 32, 8, 128, 5.0e5, 64, 128, 8192, 1, _S128, peaky_frac=0.01, seed=1002),
+    # The headline shape at two other budgets of Tab. (effsweep), rho = 0.8 and 0.6: K rows whose tile takes an odd
+    # number of 1 KB loads (used for one traffic-counter run; not part of the default benchmark).
+    "cfg2_rho08": Workload("cfg2_rho08", 16, 32, 8, 128, 5.0e5, 51, 102, 8192, 1, _S128, peaky_frac=0.01, seed=1002),
+    "cfg2_rho06": Workload("cfg2_rho06", 16, 32, 8, 128, 5.0e5, 38, 77, 8192, 1, _S128, peaky_frac=0.01, seed=1002),
 }
 
 
