@@ -219,3 +219,46 @@ def test_mx4_cfg2_size_sampled(rap):
         vf = O.mx4_dequantize_rows(vc[b, h, :n], vs[b, h, :n], dv)
         ref = O.attn_rows_ref(qf[b, h * g:(h + 1) * g], kf, vf, w.scale)
         H.assert_attn_close(got[b, h * g:(h + 1) * g], ref, "cfg2 shape slab (%d, %d)" % (b, h))
+
+
+def test_mx4_random_shapes(rap):
+    """Twelve seeded draws of widths, group size, heads, batch, context and range size: append of
+    one to five tokens per sequence, then attention over the GPU-written 4-bit cache against the
+    oracle on the same codes."""
+    rng = np.random.Generator(np.random.PCG64(4242))
+    for it in range(12):
+        P = int(rng.integers(1, 65))
+        dv = int(rng.integers(1, 129))
+        G = int(rng.choice([1, 2, 3, 4, 5, 8, 16]))
+        Hkv = int(rng.integers(1, 4))
+        B = int(rng.integers(1, 4))
+        ctx = int(rng.integers(40, 1500))
+        n_new = int(rng.integers(1, 6))
+        rps = int(rng.choice([0, 128, 256, 512]))
+        _say("random %d: P=%d dv=%d G=%d Hkv=%d B=%d ctx=%d n_new=%d rps=%d" % (it, P, dv, G, Hkv, B, ctx, n_new, rps))
+        w = I.scaled(I.WORKLOADS["cfg2"], batch=B, n_q_heads=G * Hkv, n_kv_heads=Hkv, n_pairs=P, d_v=dv, ctx=ctx, n_new=n_new,
+                     ragged_min=max(n_new + 1, ctx // 4), peaky_frac=0.0, seed=5000 + it)
+        case = I.make_case(w, device=DEV)
+        lens = case.seq_lens.cpu().numpy()
+        cap = (int(lens.max()) + 7) // 8 * 8
+        kc, ks, vc, vs = _quantised_caches(case, cap, case.prefill_lens)
+        kcd, ksd, vcd, vsd = _dev(kc, ks, vc, vs)
+        shp = rap.shape(B, G * Hkv, Hkv, w.d_head, P, dv, cap, w.rope_theta)
+        rap.rap_rope_append_mx4(shp, n_new, case.k_new, case.v_new, case.pos, case.keep, kcd, ksd, vcd, vsd)
+        torch.cuda.synchronize()
+        gkc, gks, gvc, gvs = (t.cpu().numpy() for t in (kcd, ksd, vcd, vsd))
+        ovc, ovs = vc.copy(), vs.copy()
+        okc, oks = kc.copy(), ks.copy()
+        O.append_mx4_ref(I.bits(case.k_new), I.bits(case.v_new), case.pos.cpu().numpy(), case.keep.cpu().numpy(),
+                         okc, oks, ovc, ovs, w.rope_theta, w.d_head)
+        assert np.array_equal(gvc, ovc) and np.array_equal(gvs, ovs)
+        assert (gks != oks).any(axis=-1).sum() <= 1 and (gkc != okc).sum() <= gkc.size // 5000 + 2
+        ref = O.attn_mx4_ref(I.bits(case.q), gkc, gks, gvc, gvs, lens, w.scale, 2 * P, dv)
+        tun = rap.tuning(rows_per_split=rps)
+        gw, ws = H.guarded_workspace(rap, shp, cap, tun, device=DEV)
+        go, out = H.guarded_out((B, G * Hkv, dv), DEV)
+        rap.rap_decode_attn_mx4(shp, case.q, kcd, ksd, vcd, vsd, case.seq_lens, cap, out, float(w.scale), ws, tun)
+        torch.cuda.synchronize()
+        gw.check("workspace")
+        go.check("out")
+        H.assert_attn_close(out.cpu().numpy(), ref, "random mx4 %d" % it)
