@@ -141,7 +141,6 @@ struct PrefillArgs {
   int32_t n_qblk;           // ceil(n_new / tok_per_wg)
   int32_t lds_buf_bytes;    // one K + V tile buffer
   int32_t pad_k, pad_v;     // LDS row padding in bytes (0 or 16)
-  int32_t shift_k, shift_v; // log2 of the cache row pitch when padded, else 31
   int64_t cap;
   float scale_log2e;
   // Key ranges (n_ksplit > 1, for launches whose query blocks alone would not fill the chip): a
@@ -160,6 +159,10 @@ struct PrefillArgs {
 struct PrefillPlan {
   int tok_per_wg, n_qblk, n_ksplit, tiles_per_split;
 };
+// Column blocks (of 16 query columns) per wavefront in the prefill kernel: four where the registers
+// hold their accumulators, three at d_k > 96 or d_v > 96.  The plan and the kernel's table of
+// instantiations both go by these.
+constexpr int kPrefillBlocks = 4, kPrefillBlocksWide = 3;
 PrefillPlan prefill_plan(int batch, int n_kv, int group, int d_k, int d_v, int n_new, int max_len);
 
 // fp64 -> E4M3 code (finite-only 8-bit float: 4 exponent bits, bias 7, 3 mantissa bits, no

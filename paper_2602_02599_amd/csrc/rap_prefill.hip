@@ -16,7 +16,7 @@ hipError_t launch_prefill_kch4(const PrefillArgs& a, hipStream_t stream);
 PrefillPlan prefill_plan(int batch, int n_kv, int group, int d_k, int d_v, int n_new, int max_len) {
   // column blocks per wavefront as the instantiation table (launch_prefill_k and the four callers) picks them
   const int kch = (d_k + 31) / 32, nt = (d_v + 15) / 16;
-  const int nq = (kch == 4 || nt >= 7) ? 2 : 4;
+  const int nq = (kch == 4 || nt >= 7) ? kPrefillBlocksWide : kPrefillBlocks;
   PrefillPlan p;
   p.tok_per_wg = (64 * nq) / group;
   p.n_qblk = (n_new + p.tok_per_wg - 1) / p.tok_per_wg;

@@ -3,6 +3,6 @@
 
 namespace rap {
 
-hipError_t launch_prefill_kch1(const PrefillArgs& a, hipStream_t stream) { return launch_prefill_k<1, 4>(a, stream); }
+hipError_t launch_prefill_kch1(const PrefillArgs& a, hipStream_t stream) { return launch_prefill_k<1, kPrefillBlocks>(a, stream); }
 
 }  // namespace rap

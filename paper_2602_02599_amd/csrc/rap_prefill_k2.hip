@@ -3,6 +3,6 @@
 
 namespace rap {
 
-hipError_t launch_prefill_kch2(const PrefillArgs& a, hipStream_t stream) { return launch_prefill_k<2, 4>(a, stream); }
+hipError_t launch_prefill_kch2(const PrefillArgs& a, hipStream_t stream) { return launch_prefill_k<2, kPrefillBlocks>(a, stream); }
 
 }  // namespace rap

@@ -3,6 +3,6 @@
 
 namespace rap {
 
-hipError_t launch_prefill_kch3(const PrefillArgs& a, hipStream_t stream) { return launch_prefill_k<3, 4>(a, stream); }
+hipError_t launch_prefill_kch3(const PrefillArgs& a, hipStream_t stream) { return launch_prefill_k<3, kPrefillBlocks>(a, stream); }
 
 }  // namespace rap

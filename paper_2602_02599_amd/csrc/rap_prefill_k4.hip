@@ -3,6 +3,6 @@
 
 namespace rap {
 
-hipError_t launch_prefill_kch4(const PrefillArgs& a, hipStream_t stream) { return launch_prefill_k<4, 2>(a, stream); }
+hipError_t launch_prefill_kch4(const PrefillArgs& a, hipStream_t stream) { return launch_prefill_k<4, kPrefillBlocksWide>(a, stream); }
 
 }  // namespace rap

@@ -16,8 +16,8 @@
 //    column, which are exactly the contraction slots of the P.V instruction when those are
 //    numbered accordingly, so probabilities never leave the lane.  A K fragment read from LDS is
 //    used for NQ column blocks, and so is the gathered V operand.
-//  * Tiles of 64 keys are staged by the whole workgroup (flat 16-byte loads into registers one
-//    tile ahead, parked into the other LDS buffer, one barrier per tile).
+//  * Tiles of 64 keys are staged by the whole workgroup: 16-byte loads that write LDS themselves,
+//    issued one tile ahead into the other buffer, one barrier per tile.
 //  * Online softmax in the log2 domain against a per-column reference that moves only when a
 //    score outgrows it by 2^64; the causal mask is applied only on the tiles that straddle the
 //    diagonal of the wavefront's columns, later tiles are skipped by the wavefront, earlier ones
@@ -69,11 +69,14 @@ constexpr float kHeadroomP = 64.f;   // log2 units a score may exceed the refere
 // Q8: the caches hold one-byte E4M3 codes (value = code value x the scale of the KV head): rows and
 // tiles are half as long, a fragment is widened to bf16 (exactly) between LDS and the matrix
 // instruction, k_scale folds into the softmax scale and v_scale into the final normalisation.
-template <int KCH, int NT, bool VPAIR, int NQ, bool DIRECT, bool ONES, bool Q8>
+template <int KCH, int NT, bool VPAIR, int NQ, bool ONES, bool Q8, bool PADL>
 __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   constexpr int EB = Q8 ? 1 : 2;                                      // bytes per cache element
   constexpr int NCK = (kKeysPerTile * 32 * EB * KCH + 4095) / 4096;   // 16-byte chunks per thread, K tile
   constexpr int NCV = (kKeysPerTile * 16 * EB * NT + 4095) / 4096;    // same, V tile
+  // the same when every row is followed by a 16-byte gap in LDS (direct loads of padded rows)
+  constexpr int NCKP = (kKeysPerTile * (32 * EB * KCH + 16) + 4095) / 4096;
+  constexpr int NCVP = (kKeysPerTile * (16 * EB * NT + 16) + 4095) / 4096;
   extern __shared__ __align__(16) unsigned char smem[];
 
   int tid = threadIdx.x;
@@ -190,44 +193,29 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   // rows below len8 are readable: <= cache_cap (a multiple of 8, of 16 for one-byte elements, which
   // keeps every such group of rows 16-byte aligned whatever the row width)
   const int len8 = Q8 ? (len + 15) & ~15 : (len + 7) & ~7;
-  const int kbytes = kKeysPerTile * pitch_k, vbytes = kKeysPerTile * pitch_v;   // bytes fetched per tile
   const int v_off = (kKeysPerTile * lpk + 64 + 127) & ~127;   // slack: the last K fragment read runs past the tile
 
-  uint4 kst[DIRECT ? 1 : NCK], vst[DIRECT ? 1 : NCV];
-  auto issue = [&](int t, long long trow) {
-    const int base = t * kKeysPerTile;
-    const int rows = min(kKeysPerTile, len8 - base);           // multiple of 8, >= 8
-    const int kval = rows * pitch_k, vval = rows * pitch_v;    // multiples of 16
-    const unsigned char* kg = kslab + trow * pitch_k;
-    const unsigned char* vg = vslab + trow * pitch_v;
+  // The 16-byte global loads write LDS themselves (lane i of a wavefront lands at the wavefront's
+  // LDS base + 16 i): no staging registers.  Without LDS padding the tile is a flat copy.  With
+  // padded rows (PADL) where a lane's 16 bytes land is just as fixed, but where they come from is
+  // not: the lane whose slot is piece p of padded row r loads piece p of cache row r, and the
+  // lanes whose slot is a gap load nothing.  Offsets into the cache tile per lane and load are
+  // worked out once (no load: an offset beyond any tile).
+  constexpr int NDK = PADL ? NCKP : NCK, NDV = PADL ? NCVP : NCV;
+  int kgo[PADL ? NCKP : 1], vgo[PADL ? NCVP : 1];
+  if constexpr (PADL) {
+    const int cprk = (pitch_k >> 4) + 1, cprv = (pitch_v >> 4) + 1;   // 16-byte slots per padded row
 #pragma unroll
-    for (int j = 0; j < NCK; ++j) {
-      const int off = (j * 256 + tid) * 16;
-      kst[j] = off < kval ? *reinterpret_cast<const uint4*>(kg + off) : make_uint4(0, 0, 0, 0);
+    for (int j = 0; j < NCKP; ++j) {
+      const int c = j * 256 + tid, row = c / cprk, piece = c - row * cprk;
+      kgo[j] = a.pad_k ? (piece < cprk - 1 ? row * pitch_k + piece * 16 : 0x7fffffff) : c * 16;
     }
 #pragma unroll
-    for (int j = 0; j < NCV; ++j) {
-      const int off = (j * 256 + tid) * 16;
-      vst[j] = off < vval ? *reinterpret_cast<const uint4*>(vg + off) : make_uint4(0, 0, 0, 0);
+    for (int j = 0; j < NCVP; ++j) {
+      const int c = j * 256 + tid, row = c / cprv, piece = c - row * cprv;
+      vgo[j] = a.pad_v ? (piece < cprv - 1 ? row * pitch_v + piece * 16 : 0x7fffffff) : c * 16;
     }
-  };
-  auto park = [&](int which) {
-    unsigned char* kt = smem + which * a.lds_buf_bytes;
-    unsigned char* vt = kt + v_off;
-#pragma unroll
-    for (int j = 0; j < NCK; ++j) {
-      const int off = (j * 256 + tid) * 16;
-      if (off < kbytes) *reinterpret_cast<uint4*>(kt + off + ((off >> a.shift_k) << 4)) = kst[j];
-    }
-#pragma unroll
-    for (int j = 0; j < NCV; ++j) {
-      const int off = (j * 256 + tid) * 16;
-      if (off < vbytes) *reinterpret_cast<uint4*>(vt + off + ((off >> a.shift_v) << 4)) = vst[j];
-    }
-  };
-
-  // Without LDS padding the tile is a flat copy, and the 16-byte loads can write LDS themselves
-  // (lane i of a wavefront lands at the wavefront's LDS base + 16 i): no staging registers.
+  }
   auto issue_direct = [&](int t, long long trow) {
     const int base = t * kKeysPerTile;
     const int rows = min(kKeysPerTile, len8 - base);
@@ -237,14 +225,14 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     unsigned char* kt = smem + (t & 1) * a.lds_buf_bytes;
     unsigned char* vt = kt + v_off;
 #pragma unroll
-    for (int j = 0; j < NCK; ++j) {
-      const int off = (j * 256 + tid) * 16;
+    for (int j = 0; j < NDK; ++j) {
+      const int off = PADL ? kgo[PADL ? j : 0] : (j * 256 + tid) * 16;
       if (off < kval)
         __builtin_amdgcn_global_load_lds((global_ptr_t)(kg + off), (lds_ptr_t)(kt + (j * 256 + wave * 64) * 16), 16, 0, 0);
     }
 #pragma unroll
-    for (int j = 0; j < NCV; ++j) {
-      const int off = (j * 256 + tid) * 16;
+    for (int j = 0; j < NDV; ++j) {
+      const int off = PADL ? vgo[PADL ? j : 0] : (j * 256 + tid) * 16;
       if (off < vval)
         __builtin_amdgcn_global_load_lds((global_ptr_t)(vg + off), (lds_ptr_t)(vt + (j * 256 + wave * 64) * 16), 16, 0, 0);
     }
@@ -284,26 +272,16 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   // start row of the tile whose loads are issued next, looked up (paged) one tile ahead of them
   long long trow_next;
   auto row_of_tile = [&](int t) -> long long { return t < n_tiles ? tile_row(t * kKeysPerTile) : 0; };
-  if constexpr (DIRECT) {
-    issue_direct(t_first, row_of_tile(t_first));
-    trow_next = row_of_tile(t_first + 1);
-  } else {
-    issue(t_first, row_of_tile(t_first));
-    park(t_first & 1);
-    __syncthreads();
-    if (t_first + 1 < n_tiles) issue(t_first + 1, row_of_tile(t_first + 1));
-    trow_next = row_of_tile(t_first + 2);
-  }
+  issue_direct(t_first, row_of_tile(t_first));
+  trow_next = row_of_tile(t_first + 1);
 
   for (int t = t_first; t < n_tiles; ++t) {
     unsigned char* kt0 = smem + (t & 1) * a.lds_buf_bytes;
     unsigned char* vt0 = kt0 + v_off;
-    if constexpr (DIRECT) {
-      __builtin_amdgcn_s_waitcnt(0);       // this wavefront's share of tile t has landed
-      __syncthreads();                     // everybody's has, and nobody still reads the other buffer
-      if (t + 1 < n_tiles) issue_direct(t + 1, trow_next);
-      trow_next = row_of_tile(t + 2);
-    }
+    __builtin_amdgcn_s_waitcnt(0);         // this wavefront's share of tile t has landed
+    __syncthreads();                       // everybody's has, and nobody still reads the other buffer
+    if (t + 1 < n_tiles) issue_direct(t + 1, trow_next);
+    trow_next = row_of_tile(t + 2);
     if ((t + 1) * kKeysPerTile > len) {
       // The V rows at or beyond the sequence length may hold anything (NaN included) and a zero
       // probability does not silence a NaN: in the one tile that holds the end of the sequence
@@ -499,14 +477,6 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
         }
       }
     }
-
-    if constexpr (!DIRECT) {
-      // ---- next tile into the other buffer (its last readers passed the previous barrier)
-      if (t + 1 < n_tiles) park((t + 1) & 1);
-      __syncthreads();
-      if (t + 2 < n_tiles) issue(t + 2, trow_next);
-      trow_next = row_of_tile(t + 3);
-    }
   }
 
   // ---- normalise and store: accumulator register reg of lane (l16, lg) is column 4 lg + reg
@@ -554,27 +524,27 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   }
 }
 
-template <int KCH, int NT, bool VPAIR, int NQ, bool DIRECT, bool ONES, bool Q8>
+template <int KCH, int NT, bool VPAIR, int NQ, bool ONES, bool Q8, bool PADL>
 hipError_t launch_prefill_go3(const PrefillArgs& a, size_t lds, long long n_wg, hipStream_t stream) {
   if (lds > 64 * 1024) {
-    const hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(&prefill_kernel<KCH, NT, VPAIR, NQ, DIRECT, ONES, Q8>), static_cast<int>(lds));
+    const hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(&prefill_kernel<KCH, NT, VPAIR, NQ, ONES, Q8, PADL>), static_cast<int>(lds));
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((prefill_kernel<KCH, NT, VPAIR, NQ, DIRECT, ONES, Q8>), dim3(static_cast<unsigned>(n_wg)), dim3(256), lds, stream, a);
+  hipLaunchKernelGGL((prefill_kernel<KCH, NT, VPAIR, NQ, ONES, Q8, PADL>), dim3(static_cast<unsigned>(n_wg)), dim3(256), lds, stream, a);
   return hipGetLastError();
 }
 
-template <int KCH, int NT, bool VPAIR, int NQ, bool DIRECT, bool ONES>
+template <int KCH, int NT, bool VPAIR, int NQ, bool ONES, bool PADL>
 hipError_t launch_prefill_go2(const PrefillArgs& a, size_t lds, long long n_wg, hipStream_t stream) {
-  if (a.k_scale != nullptr) return launch_prefill_go3<KCH, NT, VPAIR, NQ, DIRECT, ONES, true>(a, lds, n_wg, stream);
-  return launch_prefill_go3<KCH, NT, VPAIR, NQ, DIRECT, ONES, false>(a, lds, n_wg, stream);
+  if (a.k_scale != nullptr) return launch_prefill_go3<KCH, NT, VPAIR, NQ, ONES, true, PADL>(a, lds, n_wg, stream);
+  return launch_prefill_go3<KCH, NT, VPAIR, NQ, ONES, false, PADL>(a, lds, n_wg, stream);
 }
 
 // a spare channel slot exists exactly when d_v is not a multiple of 16
-template <int KCH, int NT, bool VPAIR, int NQ, bool DIRECT>
+template <int KCH, int NT, bool VPAIR, int NQ, bool PADL>
 hipError_t launch_prefill_go(const PrefillArgs& a, size_t lds, long long n_wg, hipStream_t stream) {
-  if ((a.d_v & 15) != 0) return launch_prefill_go2<KCH, NT, VPAIR, NQ, DIRECT, true>(a, lds, n_wg, stream);
-  return launch_prefill_go2<KCH, NT, VPAIR, NQ, DIRECT, false>(a, lds, n_wg, stream);
+  if ((a.d_v & 15) != 0) return launch_prefill_go2<KCH, NT, VPAIR, NQ, true, PADL>(a, lds, n_wg, stream);
+  return launch_prefill_go2<KCH, NT, VPAIR, NQ, false, PADL>(a, lds, n_wg, stream);
 }
 
 template <int KCH, int NT, bool VPAIR, int NQ>
@@ -583,30 +553,27 @@ hipError_t launch_prefill_inst(PrefillArgs a, hipStream_t stream) {
   if (a.n_ksplit > 1 && a.tok_per_wg != (64 * NQ) / a.group) return hipErrorInvalidValue;
   a.tok_per_wg = (64 * NQ) / a.group;
   a.n_qblk = (a.n_new + a.tok_per_wg - 1) / a.tok_per_wg;
-  // padded LDS rows for pitches of 128 or 256 bytes (the shift turns a byte offset into its row)
+  // padded LDS rows for pitches of 128 or 256 bytes
   const int eb = a.k_scale != nullptr ? 1 : 2;        // bytes per cache element
   const int pk = eb * a.d_k, pv = eb * a.d_v;
   a.pad_k = (pk % 128 == 0) ? 16 : 0;
   a.pad_v = (pv % 128 == 0) ? 16 : 0;
-  a.shift_k = a.pad_k ? (pk == 128 ? 7 : 8) : 31;
-  a.shift_v = a.pad_v ? (pv == 128 ? 7 : 8) : 31;
   const int kbytes = kKeysPerTile * (pk + a.pad_k), vbytes = kKeysPerTile * (pv + a.pad_v);
   a.lds_buf_bytes = ((kbytes + 64 + 127) & ~127) + ((vbytes + 64 + 127) & ~127);
   const size_t lds = 2 * static_cast<size_t>(a.lds_buf_bytes);
   const long long n_wg = static_cast<long long>(a.n_qblk) * a.n_kv * a.batch * (a.n_ksplit > 1 ? a.n_ksplit : 1);
   if (n_wg > 0x7fffffffLL) return hipErrorInvalidValue;
-  // padded rows only occur at 128- and 256-byte pitches (d = 64, 128), where the kernel also has
-  // registers to spare for staging
+  // padded rows only occur at 128- and 256-byte pitches (d = 64, 128; one-byte codes: d = 128)
   if constexpr ((KCH == 2 || KCH == 4) || (NT == 4 || NT == 8)) {
-    if (a.pad_k || a.pad_v) return launch_prefill_go<KCH, NT, VPAIR, NQ, false>(a, lds, n_wg, stream);
+    if (a.pad_k || a.pad_v) return launch_prefill_go<KCH, NT, VPAIR, NQ, true>(a, lds, n_wg, stream);
   }
-  return launch_prefill_go<KCH, NT, VPAIR, NQ, true>(a, lds, n_wg, stream);
+  return launch_prefill_go<KCH, NT, VPAIR, NQ, false>(a, lds, n_wg, stream);
 }
 
 template <int KCH, int NQ>
 hipError_t launch_prefill_k(const PrefillArgs& a, hipStream_t stream) {
   const int nt = (a.d_v + 15) / 16;
-  constexpr int NQW = NQ > 2 ? 2 : NQ;   // d_v > 96: four column blocks of accumulators do not fit the registers
+  constexpr int NQW = NQ > kPrefillBlocksWide ? kPrefillBlocksWide : NQ;   // d_v > 96: four column blocks of accumulators do not fit the registers
   if ((a.d_v & 1) == 0 && (nt & 1) == 0) {
     switch (nt) {
       case 2: return launch_prefill_inst<KCH, 2, true, NQ>(a, stream);

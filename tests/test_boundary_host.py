@@ -198,7 +198,7 @@ def test_prefill_split_plan_from_the_outside(rap):
     two or more ranges of partials (d_v + 2 floats per query row and range)."""
     for batch, hq, hkv, n_pairs, dv in [(1, 32, 8, 45, 90), (2, 8, 2, 58, 115), (16, 32, 8, 64, 128), (3, 5, 1, 3, 5)]:
         group = hq // hkv
-        nq = 2 if (2 * n_pairs > 96 or dv > 96) else 4            # column blocks per wavefront at these widths
+        nq = 3 if (2 * n_pairs > 96 or dv > 96) else 4            # column blocks per wavefront at these widths
         tok_per_wg = 64 * nq // group
         for n_new in (1, 16, 100, 512, 5000):
             for max_len in (64, 448, 449, 512, 4096, 65536):

@@ -317,7 +317,7 @@ PREFILL_CASES = [
     # name, fp8, page_rows, P, dv, Hkv, G, n_new, split
     ("bf16 d90/90", False, 0, 45, 90, 2, 4, 70, False),
     ("bf16 d116/115 (row sums from a spare channel)", False, 0, 58, 115, 1, 4, 70, False),
-    ("bf16 d128/128 (padded LDS rows, two column blocks)", False, 0, 64, 128, 1, 2, 70, False),
+    ("bf16 d128/128 (padded LDS rows, three column blocks)", False, 0, 64, 128, 1, 2, 70, False),
     ("bf16 d64/64 G5", False, 0, 32, 64, 1, 5, 70, False),
     ("fp8 d90/90", True, 0, 45, 90, 2, 4, 70, False),
     ("fp8 paged d116/115", True, 64, 58, 115, 1, 4, 70, False),
