@@ -414,6 +414,9 @@ def _prefill_case(P, dv, Hq, Hkv, n_new, lens, seed, scale=None, nan_beyond=Fals
     (3, 5, 3, 1, 33, [33, 40, 5]),
     (45, 90, 8, 8, 300, [300]),                    # no grouping: 256 tokens per workgroup
     (45, 90, 8, 1, 40, [40, 1000]),                # group of 8
+    (64, 128, 10, 2, 97, [97, 300]),               # three column blocks: 192 columns over groups of 5 (38 tokens, 2 columns idle)
+    (58, 116, 7, 1, 50, [50, 131, 27]),            # ... of 7 (27 tokens, 3 columns idle), blocks that end inside n_new
+    (45, 128, 8, 2, 130, [130, 190]),              # narrow scores with wide values: three blocks, only V padded in LDS
 ])
 def test_prefill_small(rap, P, dv, Hq, Hkv, n_new, lens):
     """rap_prefill_attn against the oracle, element by element: several key tiles, ragged tails,
@@ -785,7 +788,7 @@ def test_decode_multi_one_token_and_rejections(rap):
 @pytest.mark.parametrize("P,dv,Hkv,G,n_new,lens,page_rows", [
     (45, 90, 2, 4, 100, [3000, 700, 40], 0),          # 12 key ranges; a short and a too-short sequence
     (58, 115, 1, 4, 33, [5000, 4999], 64),            # odd d_v, pages of 64 rows
-    (64, 128, 2, 2, 300, [2500, 2100], 128),          # padded LDS rows, two column blocks
+    (64, 128, 2, 2, 300, [2500, 2100], 128),          # padded LDS rows, three column blocks
     (32, 64, 1, 5, 17, [1100, 1], 0), (3, 5, 1, 1, 70, [777, 650, 0], 0),
     (45, 90, 8, 4, 512, [4096], 0)])                  # a chunk at the end of one long sequence
 def test_prefill_split(rap, fp8, P, dv, Hkv, G, n_new, lens, page_rows):
