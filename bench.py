@@ -468,7 +468,7 @@ def main():
 
     import torch
     import paper_2602_02599_amd as pkg
-    from paper_2602_02599_amd import inputs as I
+    import rap_inputs as I
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)

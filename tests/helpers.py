@@ -5,7 +5,7 @@ import numpy as np
 import torch
 
 from oracle import rap_oracle as O
-from paper_2602_02599_amd import inputs as I
+import rap_inputs as I
 
 # spec tolerances for attention outputs (fp32 accumulation against the float64 oracle)
 MAX_ABS = 1e-2

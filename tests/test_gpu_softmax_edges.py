@@ -31,7 +31,7 @@ import pytest
 import torch
 
 from oracle import rap_oracle as O
-from paper_2602_02599_amd import inputs as I
+import rap_inputs as I
 from tests import helpers as H
 
 pytestmark = pytest.mark.gpu
